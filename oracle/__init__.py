@@ -1,0 +1,188 @@
+"""CPU oracle for the STS hot path -- TEST INFRASTRUCTURE ONLY.
+
+ctypes wrapper around ``sts_oracle.c`` (plain C, fp64 accumulation). Only tests, the smoke
+check and the benchmark's ``cpu_baseline`` leg may import this package; the product path
+never does. It shares no code with the HIP library.
+
+Arrays are numpy (host). bf16 tensors are passed as ``uint16`` bit patterns; use
+:func:`bf16_bits` to get them from a torch bf16 tensor.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sts_oracle.c")
+_LIB = os.path.join(_HERE, "libsts_oracle.so")
+
+PROBS, LOGITS_LSE = 0, 1
+SUM, MAX = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2 -fopenmp, no fast-math). Returns the library path."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(os.path.join(_HERE, "sts_oracle.h"))):
+        return _LIB
+    cmd = ["gcc", "-std=c11", "-O2", "-fopenmp", "-fno-fast-math", "-ffp-contract=off", "-fPIC",
+           "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+    subprocess.run(cmd, check=True, cwd=_HERE)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.oracle_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def bf16_bits(t) -> np.ndarray:
+    """uint16 bit patterns of a (CPU, contiguous or strided) torch bf16 tensor, same shape/strides."""
+    import torch
+
+    assert t.dtype == torch.bfloat16 and t.device.type == "cpu"
+    return t.view(torch.int16).numpy().view(np.uint16)
+
+
+def _p(a: Optional[np.ndarray], ty):
+    if a is None:
+        return None
+    return a.ctypes.data_as(ctypes.POINTER(ty))
+
+
+def _c(a, dtype) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise ValueError(f"{what} failed with oracle status {rc}")
+
+
+def aggregate(scores: np.ndarray, lse: Optional[np.ndarray] = None, kind: int = PROBS,
+              reduce: int = SUM) -> np.ndarray:
+    """scores [B,Hd,Tq,N] fp32 (+ lse [B,Hd,Tq]) -> A [B,Hd,N] fp32. See oracle_aggregate."""
+    scores = _c(scores, np.float32)
+    B, Hd, Tq, N = scores.shape
+    if lse is not None:
+        lse = _c(lse, np.float32)
+        assert lse.shape == (B, Hd, Tq)
+    A = np.empty((B, Hd, N), np.float32)
+    rc = _load().oracle_aggregate(_p(scores, ctypes.c_float), _p(lse, ctypes.c_float), B, Hd, Tq, N,
+                                  kind, reduce, _p(A, ctypes.c_float))
+    _check(rc, "oracle_aggregate")
+    return A
+
+
+def select(A: np.ndarray, k: int, seq_lens: Optional[np.ndarray] = None):
+    """A [B,Hd,N] fp32 -> (sel [B,Hd,k] int32 ascending, -1 padded ; cnt [B,Hd]). See oracle_select."""
+    A = _c(A, np.float32)
+    B, Hd, N = A.shape
+    if seq_lens is not None:
+        seq_lens = _c(seq_lens, np.int32)
+        assert seq_lens.shape == (B,)
+    sel = np.empty((B, Hd, k), np.int32)
+    cnt = np.empty((B, Hd), np.int32)
+    rc = _load().oracle_select(_p(A, ctypes.c_float), B, Hd, N, _p(seq_lens, ctypes.c_int32), int(k),
+                               _p(sel, ctypes.c_int32), _p(cnt, ctypes.c_int32))
+    _check(rc, "oracle_select")
+    return sel, cnt
+
+
+def remap(sel: np.ndarray, cnt: np.ndarray, head_map: np.ndarray):
+    """sel [B,Hd,k], cnt [B,Hd], head_map [Hq] -> (indices [B,Hq,k], counts [B,Hq]). See oracle_remap."""
+    sel = _c(sel, np.int32)
+    cnt = _c(cnt, np.int32)
+    head_map = _c(head_map, np.int32)
+    B, Hd, k = sel.shape
+    Hq = head_map.shape[0]
+    indices = np.empty((B, Hq, k), np.int32)
+    counts = np.empty((B, Hq), np.int32)
+    rc = _load().oracle_remap(_p(sel, ctypes.c_int32), _p(cnt, ctypes.c_int32), B, Hd, Hq, k,
+                              _p(head_map, ctypes.c_int32), _p(indices, ctypes.c_int32),
+                              _p(counts, ctypes.c_int32))
+    _check(rc, "oracle_remap")
+    return indices, counts
+
+
+def select_indices(scores, head_map, k, lse=None, kind=PROBS, reduce=SUM, seq_lens=None):
+    """The whole selection half: aggregate -> select -> remap. Returns (indices, counts, A)."""
+    A = aggregate(scores, lse, kind, reduce)
+    sel, cnt = select(A, k, seq_lens)
+    indices, counts = remap(sel, cnt, head_map)
+    return indices, counts, A
+
+
+def attn(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float,
+         indices: Optional[np.ndarray] = None, counts: Optional[np.ndarray] = None,
+         seq_lens: Optional[np.ndarray] = None, want_logits: bool = False,
+         batches: Optional[range] = None, heads: Optional[range] = None):
+    """Sparse (indices given) or dense (indices None) softmax attention. See oracle_attn.
+
+    q [B,Tq,Hq,d] uint16 (bf16 bits); k, v [B,Hkv,N,d] uint16, any strides with unit stride on d.
+    Returns dict(out [B,Tq,Hq,d] fp32, lse [B,Hq,Tq] fp32, logits [B,Hq,Tq,N] or None).
+    ``batches``/``heads`` (contiguous ranges) restrict which outputs are computed; the others
+    stay zero (lse NaN).
+    """
+    assert q.dtype == np.uint16 and k.dtype == np.uint16 and v.dtype == np.uint16
+    q = np.ascontiguousarray(q)
+    B, Tq, Hq, d = q.shape
+    Bk, Hkv, N, dk = k.shape
+    assert (Bk, dk) == (B, d) and v.shape == k.shape and v.strides == k.strides
+    assert k.strides[3] == 2
+    sb, sh, sn = (s // 2 for s in k.strides[:3])
+    kmax = 0
+    if indices is not None:
+        indices = _c(indices, np.int32)
+        assert indices.shape[:2] == (B, Hq)
+        kmax = indices.shape[2]
+        if counts is not None:
+            counts = _c(counts, np.int32)
+            assert counts.shape == (B, Hq)
+    if seq_lens is not None:
+        seq_lens = _c(seq_lens, np.int32)
+    out = np.zeros((B, Tq, Hq, d), np.float32)
+    lse = np.full((B, Hq, Tq), np.nan, np.float32)
+    logits = np.zeros((B, Hq, Tq, N), np.float32) if want_logits else None
+    bb, be = (batches.start, batches.stop) if batches is not None else (0, B)
+    hb, he = (heads.start, heads.stop) if heads is not None else (0, Hq)
+    lib = _load()
+    rc = lib.oracle_attn(_p(q, ctypes.c_uint16), _p(k, ctypes.c_uint16), _p(v, ctypes.c_uint16),
+                         B, Tq, Hq, Hkv, d, N, ctypes.c_int64(sb), ctypes.c_int64(sh),
+                         ctypes.c_int64(sn), _p(indices, ctypes.c_int32), _p(counts, ctypes.c_int32),
+                         kmax, _p(seq_lens, ctypes.c_int32), ctypes.c_float(scale),
+                         _p(out, ctypes.c_float), _p(lse, ctypes.c_float), _p(logits, ctypes.c_float),
+                         bb, be, hb, he)
+    _check(rc, "oracle_attn")
+    return {"out": out, "lse": lse, "logits": logits}
+
+
+def head_mapping(a_d: np.ndarray, a_t: np.ndarray, k: int):
+    """Algorithm 1. a_d [S,Hd,R,N], a_t [S,Ht,R,N] fp32 -> (map [Ht] int32, overlap [Ht,Hd] int64)."""
+    a_d = _c(a_d, np.float32)
+    a_t = _c(a_t, np.float32)
+    S, Hd, R, N = a_d.shape
+    St, Ht, Rt, Nt = a_t.shape
+    assert (St, Rt, Nt) == (S, R, N)
+    mp = np.empty((Ht,), np.int32)
+    ov = np.empty((Ht, Hd), np.int64)
+    rc = _load().oracle_head_mapping(_p(a_d, ctypes.c_float), _p(a_t, ctypes.c_float), S, Hd, Ht, R,
+                                     N, int(k), _p(mp, ctypes.c_int32), _p(ov, ctypes.c_int64))
+    _check(rc, "oracle_head_mapping")
+    return mp, ov

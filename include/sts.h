@@ -1,0 +1,161 @@
+/*
+ * sts.h -- C ABI of the MI355X (gfx950) library for the hot path of STS, Speculative Token
+ * Sparsity: draft attention scores -> per-target-head top-k index sets -> verification
+ * attention over the gathered rows of a full, never-pruned KV cache.
+ *
+ * Conventions
+ *  - C11, no C++ types cross the ABI. Pointers marked [dev] are DEVICE pointers owned by the
+ *    caller (e.g. torch allocations); pointers marked [host] are HOST pointers read during
+ *    the call and not retained.
+ *  - The entry points never allocate, free or synchronise: each call validates its arguments
+ *    on the host and enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = the
+ *    default stream). Scratch memory comes from the caller as `workspace`; query its size
+ *    with the *_workspace_bytes functions (the size depends only on the integer shape
+ *    fields, `sparse`/flags and pointer NULL-ness, never on device data).
+ *  - Inputs are never written. Outputs and workspace must not alias inputs or each other.
+ *  - Return value: STS_OK (0) or a negative sts_status. On error nothing has been enqueued
+ *    (except STS_EHIP, a failed launch, after which earlier kernels of the call may have
+ *    been enqueued). No exceptions, no errno, no logging.
+ *  - Results are deterministic run to run: the split count depends only on the shape and the
+ *    partial results are combined in a fixed order; selection uses integer arithmetic only.
+ *  - bf16 tensors are raw 16-bit patterns. All accumulation is fp32.
+ */
+#ifndef STS_H
+#define STS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  STS_OK = 0,
+  STS_EINVAL = -1,       /* NULL where data is required, negative size, bad enum, bad head map */
+  STS_EUNSUPPORTED = -2, /* shape outside what the kernels cover (see each call) */
+  STS_EWORKSPACE = -3,   /* workspace NULL or smaller than *_workspace_bytes */
+  STS_EHIP = -4          /* the HIP runtime reported an error at launch */
+} sts_status;
+
+typedef enum { STS_SCORES_PROBS = 0, STS_SCORES_LOGITS_LSE = 1 } sts_score_kind;
+typedef enum { STS_REDUCE_SUM = 0, STS_REDUCE_MAX = 1 } sts_reduce;
+typedef enum { STS_BF16 = 0, STS_F32 = 1 } sts_dtype;
+
+/* ----------------------------------------------------------------------------------------
+ * sts_select -- online mask generation (paper Section 4.2: top-k over each draft head's
+ * attention weights, remapped to the target heads through the offline head-mapping
+ * dictionary of Section 4.1; Section 4.3: one mask per speculative batch).
+ *
+ * For every batch b and draft head j the draft attention weights of the Tq query rows of
+ * the speculative block are reduced to one score per cached token,
+ *     A[b,j,n] = ((P[b,j,0,n] + P[b,j,1,n]) + P[b,j,2,n]) + ...   (fp32, left to right)
+ * (or their maximum), the c = min(k, N_b) tokens with the largest A are kept, ties going to
+ * the lower token index, and written in ascending token order to every target head t with
+ * head_map[t] == j. With kind == STS_SCORES_LOGITS_LSE the input holds scaled logits s and
+ * P = exp(s - lse[b,j,i]) is formed on the fly. -0 and +0 compare equal. NaN scores are a
+ * caller error (they are ordered above +inf, deterministically, but that order is not part
+ * of the contract).
+ *
+ * Supported: 1 <= Tq <= 64, 1 <= Hq <= 256, 1 <= Hd <= 256, N < 2^31 - 2^16. B, N or k-free rows of
+ * size zero are handled (nothing is read; counts are written as 0).
+ */
+typedef struct {
+  int32_t B, Hd, Tq, N, Hq;
+  int32_t k;                /* token budget per head, >= 1; k >= N_b selects everything */
+  const float *scores;      /* [dev] [B,Hd,Tq,N] fp32 contiguous: probabilities or scaled logits */
+  const float *lse;         /* [dev] [B,Hd,Tq] natural-log normalisers; LOGITS_LSE only, else NULL */
+  const int32_t *head_map;  /* [host] [Hq] target head -> draft head, values in [0,Hd) */
+  const int32_t *seq_lens;  /* [dev] [B] valid lengths N_b <= N, or NULL (N_b = N) */
+  int32_t *indices;         /* [dev] out [B,Hq,k] ascending token ids; positions >= c hold -1 */
+  int32_t *counts;          /* [dev] out [B,Hq] c = min(k, N_b); may be NULL */
+  float *agg_out;           /* [dev] out [B,Hd,N] the aggregated scores A; may be NULL */
+  int32_t kind;             /* sts_score_kind */
+  int32_t reduce;           /* sts_reduce */
+  void *workspace;          /* [dev] 256-byte aligned scratch */
+  size_t workspace_bytes;
+} sts_select_params;
+
+/* ----------------------------------------------------------------------------------------
+ * sts_sparse_attn -- sparse verification attention (paper Section 4.2: the target's
+ * attention layers attend only to the key-value pairs named by the provided indices;
+ * Section 2.3: the full cache is kept; Section 5: per-head KV sets, split-K).
+ * sts_dense_attn -- the same kernel family over all N_b cached tokens (the dense baseline
+ * of Section 6.1, and the draft-side attention that also dumps QK^T, Section 5).
+ *
+ * For each batch b, query head t (KV head g = t / (Hq/Hkv)) and query row i:
+ *     s_c = scale * <Q[b,i,t,:], K[b,g,I_c,:]>,   p_c = exp(s_c - max_c s_c),
+ *     out[b,i,t,:] = sum_c p_c V[b,g,I_c,:] / sum_c p_c,   lse[b,t,i] = max_c s_c + ln sum_c p_c
+ * where I = indices[b,t,0:counts[b,t]] (sparse) or 0..N_b-1 (dense). The N cached tokens
+ * are the prefix before the speculative block, so every query row sees all of them; the
+ * block's own causal part is merged by the caller using lse_out. A row with no key gives
+ * out = 0 and lse = -inf. Index values must lie in [0,N); they are clamped into range for
+ * memory safety, never checked. A repeated index is counted once per occurrence.
+ *
+ * Supported: d in {64,128}; Hq % Hkv == 0; Hq/Hkv <= 16; 1 <= Tq <= 16; Hq <= 256;
+ * kv strides with kv_stride_n*2 bytes a multiple of 16 and bases 16-byte aligned.
+ */
+typedef struct {
+  int32_t B, Tq, Hq, Hkv, d, N;
+  const void *q;            /* [dev] bf16 [B,Tq,Hq,d] contiguous */
+  const void *k, *v;        /* [dev] bf16 [B,Hkv,N,d], element strides below, unit stride on d */
+  int64_t kv_stride_b, kv_stride_h, kv_stride_n;   /* in elements, shared by k and v */
+  const int32_t *indices;   /* [dev] [B,Hq,kmax] (sparse); must be NULL for dense */
+  const int32_t *counts;    /* [dev] [B,Hq] valid entries per row, or NULL (= kmax) */
+  int32_t kmax;
+  const int32_t *head_map;  /* [host] optional hint [Hq]: heads of one KV group with equal
+                               values have identical index rows and are processed together
+                               over one gathered tile. NULL = every head on its own. */
+  const int32_t *seq_lens;  /* [dev] [B] (dense only) or NULL */
+  float scale;              /* usually 1/sqrt(d) */
+  void *out;                /* [dev] [B,Tq,Hq,d] of out_dtype */
+  int32_t out_dtype;        /* sts_dtype */
+  float *lse_out;           /* [dev] optional [B,Hq,Tq], natural log */
+  float *logits_out;        /* [dev] dense only, optional [B,Hq,Tq,N] scaled logits s_c */
+  void *workspace;          /* [dev] 256-byte aligned scratch */
+  size_t workspace_bytes;
+} sts_attn_params;
+
+size_t sts_select_workspace_bytes(const sts_select_params *p);
+size_t sts_attn_workspace_bytes(const sts_attn_params *p, int sparse);
+
+sts_status sts_select(const sts_select_params *p, void *stream);
+sts_status sts_sparse_attn(const sts_attn_params *p, void *stream);
+sts_status sts_dense_attn(const sts_attn_params *p, void *stream);
+
+const char *sts_strerror(sts_status s);
+int sts_version(void);
+
+/* ----------------------------------------------------------------------------------------
+ * Measurement aid (not on the hot path): when enabled, every kernel launch of the calls
+ * above is bracketed by HIP events on the call's stream. sts_prof_read synchronises those
+ * events and returns, per kernel kind, the number of launches and their summed duration
+ * since the last sts_prof_reset. Enabling allocates events lazily; at most STS_PROF_MAX
+ * launches are kept per reset, later ones are not recorded.
+ */
+typedef enum {
+  STS_K_SELECT_CLEAR = 0,  /* zero histograms */
+  STS_K_SELECT_AGG = 1,    /* aggregation + first-digit histogram */
+  STS_K_SELECT_HIST = 2,   /* refinement histograms */
+  STS_K_SELECT_COUNT = 3,  /* per-chunk counts against the threshold */
+  STS_K_SELECT_WRITE = 4,  /* ordered compaction + head remap */
+  STS_K_ATTN_SPARSE = 5,   /* split sparse gather flash-decode */
+  STS_K_ATTN_DENSE = 6,    /* split dense flash-decode */
+  STS_K_ATTN_COMBINE = 7,  /* split combine */
+  STS_K_COUNT_ = 8
+} sts_kernel_kind;
+#define STS_PROF_MAX 4096
+
+void sts_prof_enable(int on);
+void sts_prof_reset(void);
+sts_status sts_prof_read(int kernel_kind, int32_t *launches, double *total_ms);
+
+/* Launch geometry chosen for a shape (for reports): number of context splits and of
+ * (head-set) work units per batch element. Returns STS_OK or the validation error. */
+sts_status sts_attn_plan(const sts_attn_params *p, int sparse, int32_t *num_splits,
+                         int32_t *units_per_batch, int32_t *query_tiles);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

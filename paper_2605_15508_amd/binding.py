@@ -1,0 +1,264 @@
+"""ctypes binding of include/sts.h. Argument marshalling only.
+
+torch is used for device memory (outputs, workspace) and for the current HIP stream.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsts.so")
+
+STS_SCORES_PROBS, STS_SCORES_LOGITS_LSE = 0, 1
+STS_REDUCE_SUM, STS_REDUCE_MAX = 0, 1
+STS_BF16, STS_F32 = 0, 1
+KERNEL_KINDS = {"select_clear": 0, "select_agg": 1, "select_hist": 2, "select_count": 3,
+                "select_write": 4, "attn_sparse": 5, "attn_dense": 6, "attn_combine": 7}
+
+# every symbol include/sts.h declares
+EXPORTS = ["sts_select_workspace_bytes", "sts_attn_workspace_bytes", "sts_select", "sts_sparse_attn",
+           "sts_dense_attn", "sts_strerror", "sts_version", "sts_prof_enable", "sts_prof_reset",
+           "sts_prof_read", "sts_attn_plan"]
+
+
+class StsError(RuntimeError):
+    pass
+
+
+class SelectParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("Hd", ctypes.c_int32), ("Tq", ctypes.c_int32),
+                ("N", ctypes.c_int32), ("Hq", ctypes.c_int32), ("k", ctypes.c_int32),
+                ("scores", ctypes.c_void_p), ("lse", ctypes.c_void_p), ("head_map", ctypes.c_void_p),
+                ("seq_lens", ctypes.c_void_p), ("indices", ctypes.c_void_p), ("counts", ctypes.c_void_p),
+                ("agg_out", ctypes.c_void_p), ("kind", ctypes.c_int32), ("reduce", ctypes.c_int32),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+
+
+class AttnParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("Tq", ctypes.c_int32), ("Hq", ctypes.c_int32),
+                ("Hkv", ctypes.c_int32), ("d", ctypes.c_int32), ("N", ctypes.c_int32),
+                ("q", ctypes.c_void_p), ("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("kv_stride_b", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64),
+                ("kv_stride_n", ctypes.c_int64), ("indices", ctypes.c_void_p),
+                ("counts", ctypes.c_void_p), ("kmax", ctypes.c_int32), ("head_map", ctypes.c_void_p),
+                ("seq_lens", ctypes.c_void_p), ("scale", ctypes.c_float), ("out", ctypes.c_void_p),
+                ("out_dtype", ctypes.c_int32), ("lse_out", ctypes.c_void_p),
+                ("logits_out", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
+                ("workspace_bytes", ctypes.c_size_t)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libsts.so built in-tree. Fails loudly if it is missing (no fallback path exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise StsError(f"{_LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = ctypes.CDLL(_LIB_PATH)
+    lib.sts_select_workspace_bytes.restype = ctypes.c_size_t
+    lib.sts_select_workspace_bytes.argtypes = [ctypes.POINTER(SelectParams)]
+    lib.sts_attn_workspace_bytes.restype = ctypes.c_size_t
+    lib.sts_attn_workspace_bytes.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_int]
+    lib.sts_select.restype = ctypes.c_int
+    lib.sts_select.argtypes = [ctypes.POINTER(SelectParams), ctypes.c_void_p]
+    for f in (lib.sts_sparse_attn, lib.sts_dense_attn):
+        f.restype = ctypes.c_int
+        f.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
+    lib.sts_strerror.restype = ctypes.c_char_p
+    lib.sts_strerror.argtypes = [ctypes.c_int]
+    lib.sts_version.restype = ctypes.c_int
+    lib.sts_prof_enable.argtypes = [ctypes.c_int]
+    lib.sts_prof_enable.restype = None
+    lib.sts_prof_reset.restype = None
+    lib.sts_prof_read.restype = ctypes.c_int
+    lib.sts_prof_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double)]
+    lib.sts_attn_plan.restype = ctypes.c_int
+    lib.sts_attn_plan.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_int] + [ctypes.POINTER(ctypes.c_int32)] * 3
+    _lib = lib
+    return lib
+
+
+def exported_symbols() -> Dict[str, bool]:
+    lib = load_library()
+    return {name: hasattr(lib, name) for name in EXPORTS}
+
+
+def sts_version() -> int:
+    return int(load_library().sts_version())
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        msg = load_library().sts_strerror(rc).decode()
+        raise StsError(f"{what}: {msg} ({rc})")
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+
+    return torch.cuda.current_stream().cuda_stream
+
+
+_ws_cache: Dict[Tuple[str, int], "object"] = {}
+
+
+def _workspace(tag: str, nbytes: int, device):
+    """A cached device scratch buffer (256-byte aligned by the torch allocator)."""
+    import torch
+
+    key = (tag, device.index if device.index is not None else torch.cuda.current_device())
+    buf = _ws_cache.get(key)
+    if buf is None or buf.numel() < nbytes:
+        buf = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+        _ws_cache[key] = buf
+    return buf
+
+
+def _host_i32(seq) -> ctypes.Array:
+    vals = [int(x) for x in (seq.tolist() if hasattr(seq, "tolist") else seq)]
+    return (ctypes.c_int32 * len(vals))(*vals)
+
+
+def sts_select(scores, head_map, k: int, lse=None, seq_lens=None, kind: int = STS_SCORES_PROBS,
+               reduce: int = STS_REDUCE_SUM, want_agg: bool = False, out=None, workspace=None):
+    """scores [B,Hd,Tq,N] fp32 (device), head_map [Hq] (host ints) -> (indices [B,Hq,k] int32,
+    counts [B,Hq] int32, agg [B,Hd,N] fp32 or None). See sts_select in include/sts.h."""
+    import torch
+
+    lib = load_library()
+    assert scores.is_cuda and scores.dtype == torch.float32 and scores.is_contiguous()
+    B, Hd, Tq, N = scores.shape
+    hm = _host_i32(head_map)
+    Hq = len(hm)
+    dev = scores.device
+    if out is None:
+        indices = torch.empty(B, Hq, k, dtype=torch.int32, device=dev)
+        counts = torch.empty(B, Hq, dtype=torch.int32, device=dev)
+    else:
+        indices, counts = out
+    agg = torch.empty(B, Hd, N, dtype=torch.float32, device=dev) if want_agg else None
+    if lse is not None:
+        assert lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous() and lse.shape == (B, Hd, Tq)
+    if seq_lens is not None:
+        assert seq_lens.is_cuda and seq_lens.dtype == torch.int32 and seq_lens.shape == (B,)
+    p = SelectParams(B=B, Hd=Hd, Tq=Tq, N=N, Hq=Hq, k=int(k), scores=_ptr(scores), lse=_ptr(lse),
+                     head_map=ctypes.cast(hm, ctypes.c_void_p), seq_lens=_ptr(seq_lens),
+                     indices=_ptr(indices), counts=_ptr(counts), agg_out=_ptr(agg), kind=kind,
+                     reduce=reduce, workspace=None, workspace_bytes=0)
+    need = lib.sts_select_workspace_bytes(ctypes.byref(p))
+    ws = workspace if workspace is not None else _workspace("select", need, dev)
+    p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()
+    _check(lib.sts_select(ctypes.byref(p), _stream()), "sts_select")
+    return indices, counts, agg
+
+
+def _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse_out, logits_out):
+    import torch
+
+    assert q.is_cuda and q.dtype == torch.bfloat16 and q.is_contiguous()
+    assert k.dtype == torch.bfloat16 and v.dtype == torch.bfloat16 and k.is_cuda and v.is_cuda
+    B, Tq, Hq, d = q.shape
+    Bk, Hkv, N, dk = k.shape
+    assert (Bk, dk) == (B, d) and v.shape == k.shape and v.stride() == k.stride() and k.stride(3) == 1
+    kmax = 0
+    if indices is not None:
+        assert indices.is_cuda and indices.dtype == torch.int32 and indices.is_contiguous()
+        assert indices.shape[:2] == (B, Hq)
+        kmax = indices.shape[2]
+    if counts is not None:
+        assert counts.is_cuda and counts.dtype == torch.int32 and counts.is_contiguous() and counts.shape == (B, Hq)
+    if seq_lens is not None:
+        assert seq_lens.is_cuda and seq_lens.dtype == torch.int32 and seq_lens.shape == (B,)
+    hm = _host_i32(head_map) if head_map is not None else None
+    out_dtype = STS_BF16 if out.dtype == torch.bfloat16 else STS_F32
+    p = AttnParams(B=B, Tq=Tq, Hq=Hq, Hkv=Hkv, d=d, N=N, q=_ptr(q), k=_ptr(k), v=_ptr(v),
+                   kv_stride_b=k.stride(0), kv_stride_h=k.stride(1), kv_stride_n=k.stride(2),
+                   indices=_ptr(indices), counts=_ptr(counts), kmax=kmax,
+                   head_map=ctypes.cast(hm, ctypes.c_void_p) if hm is not None else None,
+                   seq_lens=_ptr(seq_lens), scale=float(scale), out=_ptr(out), out_dtype=out_dtype,
+                   lse_out=_ptr(lse_out), logits_out=_ptr(logits_out), workspace=None, workspace_bytes=0)
+    return p, hm
+
+
+def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=None, seq_lens=None,
+              out=None, out_dtype=None, want_lse=True, want_logits=False, workspace=None):
+    import torch
+
+    lib = load_library()
+    B, Tq, Hq, d = q.shape
+    N = k.shape[2]
+    dev = q.device
+    if out is None:
+        out = torch.empty(B, Tq, Hq, d, dtype=out_dtype or torch.bfloat16, device=dev)
+    lse = torch.empty(B, Hq, Tq, dtype=torch.float32, device=dev) if want_lse else None
+    logits = torch.empty(B, Hq, Tq, N, dtype=torch.float32, device=dev) if want_logits else None
+    p, _keep = _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse, logits)
+    need = lib.sts_attn_workspace_bytes(ctypes.byref(p), 1 if sparse else 0)
+    ws = workspace if workspace is not None else _workspace("attn", need, dev)
+    p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()
+    fn = lib.sts_sparse_attn if sparse else lib.sts_dense_attn
+    _check(fn(ctypes.byref(p), _stream()), "sts_sparse_attn" if sparse else "sts_dense_attn")
+    return out, lse, logits
+
+
+def sts_sparse_attn(q, k, v, indices, scale, counts=None, head_map=None, out=None, out_dtype=None,
+                    want_lse=True, workspace=None):
+    """Attention over the gathered rows indices[b,t,:counts[b,t]] of the full cache.
+    q [B,Tq,Hq,d] bf16, k/v [B,Hkv,N,d] bf16 (strided ok) -> (out [B,Tq,Hq,d], lse [B,Hq,Tq])."""
+    out, lse, _ = _run_attn(True, q, k, v, scale, indices=indices, counts=counts, head_map=head_map,
+                            out=out, out_dtype=out_dtype, want_lse=want_lse, workspace=workspace)
+    return out, lse
+
+
+def sts_dense_attn(q, k, v, scale, seq_lens=None, out=None, out_dtype=None, want_lse=True,
+                   want_logits=False, workspace=None):
+    """Dense attention of the same kernel family -> (out, lse, logits [B,Hq,Tq,N] or None)."""
+    return _run_attn(False, q, k, v, scale, seq_lens=seq_lens, out=out, out_dtype=out_dtype,
+                     want_lse=want_lse, want_logits=want_logits, workspace=workspace)
+
+
+def attn_plan(q, k, sparse: bool, kmax: int = 0, head_map=None) -> Dict[str, int]:
+    """Launch geometry the library picks for a shape (reports only)."""
+    lib = load_library()
+    B, Tq, Hq, d = q.shape
+    _, Hkv, N, _ = k.shape
+    hm = _host_i32(head_map) if head_map is not None else None
+    p = AttnParams(B=B, Tq=Tq, Hq=Hq, Hkv=Hkv, d=d, N=N, kv_stride_b=k.stride(0), kv_stride_h=k.stride(1),
+                   kv_stride_n=k.stride(2), kmax=kmax, scale=1.0,
+                   head_map=ctypes.cast(hm, ctypes.c_void_p) if hm is not None else None)
+    s, u, nq = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    _check(lib.sts_attn_plan(ctypes.byref(p), 1 if sparse else 0, ctypes.byref(s), ctypes.byref(u),
+                             ctypes.byref(nq)), "sts_attn_plan")
+    return {"num_splits": s.value, "units_per_batch": u.value, "query_tiles": nq.value}
+
+
+def prof_enable(on: bool = True):
+    load_library().sts_prof_enable(1 if on else 0)
+
+
+def prof_reset():
+    load_library().sts_prof_reset()
+
+
+def prof_read() -> Dict[str, Tuple[int, float]]:
+    """Per kernel kind: (launches, total milliseconds) since the last reset (synchronises)."""
+    lib = load_library()
+    res = {}
+    for name, kind in KERNEL_KINDS.items():
+        n, ms = ctypes.c_int32(), ctypes.c_double()
+        _check(lib.sts_prof_read(kind, ctypes.byref(n), ctypes.byref(ms)), "sts_prof_read")
+        res[name] = (n.value, ms.value)
+    return res

@@ -1,0 +1,350 @@
+// Host side of the C ABI declared in include/sts.h: argument validation, launch planning,
+// workspace carving, kernel enqueue, and the optional per-kernel event timing.
+#include <math.h>
+#include <string.h>
+
+#include <mutex>
+#include <vector>
+
+#include "common.h"
+
+namespace {
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// ------------------------------------------------------------------------- profiling aid
+struct ProfEvent {
+  hipEvent_t start, stop;
+  int kind;
+};
+std::mutex g_prof_mu;
+bool g_prof_on = false;
+std::vector<ProfEvent> g_prof_pool;   // created lazily, reused after reset
+size_t g_prof_used = 0;
+
+template <class F>
+hipError_t run_kernel(int kind, hipStream_t s, F &&launch) {
+  if (!g_prof_on) return launch();
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (g_prof_used >= STS_PROF_MAX) return launch();
+  if (g_prof_used == g_prof_pool.size()) {
+    ProfEvent e;
+    if (hipEventCreate(&e.start) != hipSuccess) return launch();
+    if (hipEventCreate(&e.stop) != hipSuccess) {
+      (void)hipEventDestroy(e.start);
+      return launch();
+    }
+    g_prof_pool.push_back(e);
+  }
+  ProfEvent &e = g_prof_pool[g_prof_used];
+  e.kind = kind;
+  (void)hipEventRecord(e.start, s);
+  const hipError_t rc = launch();
+  (void)hipEventRecord(e.stop, s);
+  ++g_prof_used;
+  return rc;
+}
+
+int cu_count() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cus = n;
+    else
+      cus = 256;
+  }
+  return cus;
+}
+
+// ------------------------------------------------------------------------ attention plan
+sts_status validate_attn(const sts_attn_params *p, int sparse) {
+  if (!p) return STS_EINVAL;
+  if (p->B < 0 || p->Tq < 1 || p->Hq < 1 || p->Hkv < 1 || p->N < 0) return STS_EINVAL;
+  if (p->Hq % p->Hkv != 0) return STS_EINVAL;
+  if (p->d != 64 && p->d != 128) return STS_EUNSUPPORTED;
+  if (p->Tq > 16 || p->Hq > STS_MAX_HEADS || p->Hq / p->Hkv > STS_MAX_GROUP) return STS_EUNSUPPORTED;
+  if (p->out_dtype != STS_BF16 && p->out_dtype != STS_F32) return STS_EINVAL;
+  if (!isfinite(p->scale)) return STS_EINVAL;
+  if (sparse) {
+    if (p->kmax < 0) return STS_EINVAL;
+    if (p->logits_out || p->seq_lens) return STS_EINVAL;
+    if (p->head_map)
+      for (int t = 0; t < p->Hq; ++t)
+        if (p->head_map[t] < 0) return STS_EINVAL;
+  } else {
+    if (p->indices || p->counts) return STS_EINVAL;
+  }
+  if (p->kv_stride_n < p->d || (p->kv_stride_n * 2) % 16 != 0 || (p->kv_stride_h * 2) % 16 != 0 ||
+      (p->kv_stride_b * 2) % 16 != 0)
+    return STS_EUNSUPPORTED;
+  return STS_OK;
+}
+
+// Group query heads into units and pick the split count. Uses only host data.
+sts_status plan_attn(const sts_attn_params *p, int sparse, AttnPlan &pl) {
+  const sts_status v = validate_attn(p, sparse);
+  if (v != STS_OK) return v;
+  const int G = p->Hq / p->Hkv;
+  int max_heads = 64 / p->Tq;   // at most 4 query tiles of 16 rows
+  if (max_heads > STS_MAX_GROUP) max_heads = STS_MAX_GROUP;
+  int nu = 0, max_rows = 0;
+  memset(&pl.units, 0, sizeof(pl.units));
+  for (int g = 0; g < p->Hkv; ++g) {
+    bool done[STS_MAX_GROUP] = {false};
+    for (int i = 0; i < G; ++i) {
+      if (done[i]) continue;
+      // members of the set led by head i, in head order
+      int members[STS_MAX_GROUP], nm = 0;
+      for (int j2 = i; j2 < G; ++j2) {
+        if (done[j2]) continue;
+        const bool same = !sparse || j2 == i ||
+                          (p->head_map && p->head_map[g * G + j2] == p->head_map[g * G + i]);
+        if (same) {
+          members[nm++] = j2;
+          done[j2] = true;
+        }
+      }
+      for (int s0 = 0; s0 < nm; s0 += max_heads) {
+        const int cnt = (nm - s0 < max_heads) ? nm - s0 : max_heads;
+        uint32_t mask = 0;
+        for (int m = 0; m < cnt; ++m) mask |= 1u << members[s0 + m];
+        if (nu >= STS_MAX_HEADS) return STS_EUNSUPPORTED;
+        pl.units.unit[nu++] = (uint32_t)g | (mask << 8) | ((uint32_t)cnt << 24);
+        if (cnt * p->Tq > max_rows) max_rows = cnt * p->Tq;
+      }
+    }
+  }
+  pl.num_units = nu;
+  pl.nq = max_rows <= 16 ? 1 : (max_rows <= 32 ? 2 : 4);
+  const int64_t len = sparse ? p->kmax : p->N;
+  const int64_t tiles = (len + STS_TILE_KEYS - 1) / STS_TILE_KEYS;
+  const int64_t resident = (int64_t)cu_count() * (pl.nq == 4 ? 1 : 2);
+  const int64_t units_total = (int64_t)p->B * nu;
+  int64_t S = units_total > 0 ? resident / units_total : 1;
+  const int64_t s_cap = (tiles + STS_WG_WAVES - 1) / STS_WG_WAVES;   // >= 1 tile per wave
+  if (S > s_cap) S = s_cap;
+  if (S > 256) S = 256;
+  if (S < 1) S = 1;
+  pl.num_splits = (int)S;
+  const size_t parts = (size_t)units_total * (size_t)S;
+  if ((size_t)units_total * (size_t)S > 0x7fffffffull) return STS_EUNSUPPORTED;
+  pl.part_o_bytes = align256(parts * (size_t)pl.nq * 16 * p->d * sizeof(float));
+  pl.part_ml_bytes = align256(parts * (size_t)pl.nq * 16 * 2 * sizeof(float));
+  return STS_OK;
+}
+
+sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
+  AttnPlan pl;
+  const sts_status v = plan_attn(p, sparse, pl);
+  if (v != STS_OK) return v;
+  if (p->B == 0) return STS_OK;
+  if (!p->q || !p->out) return STS_EINVAL;
+  if (p->N > 0 && (!p->k || !p->v)) return STS_EINVAL;
+  if (sparse && p->kmax > 0 && !p->indices) return STS_EINVAL;
+  if (sparse && p->kmax > 0 && p->N == 0) return STS_EINVAL;
+  const size_t need = pl.part_o_bytes + pl.part_ml_bytes;
+  if (!p->workspace || p->workspace_bytes < need) return STS_EWORKSPACE;
+  if (reinterpret_cast<uintptr_t>(p->workspace) % 256 != 0) return STS_EWORKSPACE;
+  if (reinterpret_cast<uintptr_t>(p->k) % 16 != 0 || reinterpret_cast<uintptr_t>(p->v) % 16 != 0 ||
+      reinterpret_cast<uintptr_t>(p->q) % 16 != 0 || reinterpret_cast<uintptr_t>(p->out) % 16 != 0)
+    return STS_EUNSUPPORTED;
+
+  AttnArgs a;
+  memset(&a, 0, sizeof(a));
+  a.q = static_cast<const uint16_t *>(p->q);
+  a.k = static_cast<const uint16_t *>(p->k);
+  a.v = static_cast<const uint16_t *>(p->v);
+  a.indices = sparse ? p->indices : nullptr;
+  a.counts = sparse ? p->counts : nullptr;
+  a.seq_lens = sparse ? nullptr : p->seq_lens;
+  a.stride_b = p->kv_stride_b;
+  a.stride_h = p->kv_stride_h;
+  a.stride_n = p->kv_stride_n;
+  a.B = p->B; a.Tq = p->Tq; a.Hq = p->Hq; a.Hkv = p->Hkv; a.G = p->Hq / p->Hkv; a.N = p->N;
+  a.kmax = sparse ? p->kmax : 0;
+  a.num_units = pl.num_units;
+  a.num_splits = pl.num_splits;
+  a.scale = p->scale;
+  a.scale_log2 = p->scale * 1.44269504088896340736f;
+  a.part_o = static_cast<float *>(p->workspace);
+  a.part_ml = reinterpret_cast<float *>(static_cast<unsigned char *>(p->workspace) + pl.part_o_bytes);
+  a.logits_out = sparse ? nullptr : p->logits_out;
+  a.out = p->out;
+  a.lse_out = p->lse_out;
+  a.out_dtype = p->out_dtype;
+  a.units = pl.units;
+
+  hipError_t rc = run_kernel(sparse ? STS_K_ATTN_SPARSE : STS_K_ATTN_DENSE, s,
+                             [&] { return launch_attn_split(a, p->d, pl.nq, sparse != 0, s); });
+  if (rc != hipSuccess) return STS_EHIP;
+  rc = run_kernel(STS_K_ATTN_COMBINE, s, [&] { return launch_attn_combine(a, p->d, pl.nq, s); });
+  return rc == hipSuccess ? STS_OK : STS_EHIP;
+}
+
+// --------------------------------------------------------------------------- select plan
+struct SelectPlan {
+  int nchunks;
+  size_t agg_bytes, hist_bytes, state_bytes, chunk_bytes;
+};
+
+sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
+  if (!p) return STS_EINVAL;
+  if (p->B < 0 || p->Hd < 1 || p->Tq < 1 || p->N < 0 || p->Hq < 1 || p->k < 1) return STS_EINVAL;
+  if (p->kind != STS_SCORES_PROBS && p->kind != STS_SCORES_LOGITS_LSE) return STS_EINVAL;
+  if (p->reduce != STS_REDUCE_SUM && p->reduce != STS_REDUCE_MAX) return STS_EINVAL;
+  if (p->Tq > 64 || p->Hq > STS_MAX_HEADS || p->Hd > STS_MAX_HEADS) return STS_EUNSUPPORTED;
+  if ((int64_t)p->N > 0x7fffffffll - 65536) return STS_EUNSUPPORTED;
+  if ((int64_t)p->B * p->Hd > 65535) return STS_EUNSUPPORTED;   // grid.y
+  pl.nchunks = (p->N + SEL_CHUNK - 1) / SEL_CHUNK;
+  const size_t rows = (size_t)p->B * p->Hd;
+  pl.agg_bytes = p->agg_out ? 0 : align256(rows * (size_t)p->N * sizeof(float));
+  pl.hist_bytes = align256(rows * 3 * SEL_BINS * sizeof(uint32_t));
+  pl.state_bytes = align256(rows * 8 * sizeof(uint32_t));
+  pl.chunk_bytes = align256(rows * (size_t)pl.nchunks * 2 * sizeof(uint32_t));
+  return STS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t sts_attn_workspace_bytes(const sts_attn_params *p, int sparse) {
+  AttnPlan pl;
+  if (plan_attn(p, sparse, pl) != STS_OK) return 0;
+  const size_t n = pl.part_o_bytes + pl.part_ml_bytes;
+  return n ? n : 256;
+}
+
+sts_status sts_attn_plan(const sts_attn_params *p, int sparse, int32_t *num_splits,
+                         int32_t *units_per_batch, int32_t *query_tiles) {
+  AttnPlan pl;
+  const sts_status v = plan_attn(p, sparse, pl);
+  if (v != STS_OK) return v;
+  if (num_splits) *num_splits = pl.num_splits;
+  if (units_per_batch) *units_per_batch = pl.num_units;
+  if (query_tiles) *query_tiles = pl.nq;
+  return STS_OK;
+}
+
+sts_status sts_sparse_attn(const sts_attn_params *p, void *stream) {
+  return run_attn(p, 1, static_cast<hipStream_t>(stream));
+}
+
+sts_status sts_dense_attn(const sts_attn_params *p, void *stream) {
+  return run_attn(p, 0, static_cast<hipStream_t>(stream));
+}
+
+size_t sts_select_workspace_bytes(const sts_select_params *p) {
+  SelectPlan pl;
+  if (plan_select(p, pl) != STS_OK) return 0;
+  const size_t n = pl.agg_bytes + pl.hist_bytes + pl.state_bytes + pl.chunk_bytes;
+  return n ? n : 256;
+}
+
+sts_status sts_select(const sts_select_params *p, void *stream) {
+  SelectPlan pl;
+  const sts_status v = plan_select(p, pl);
+  if (v != STS_OK) return v;
+  if (!p->head_map || !p->indices) return STS_EINVAL;
+  for (int t = 0; t < p->Hq; ++t)
+    if (p->head_map[t] < 0 || p->head_map[t] >= p->Hd) return STS_EINVAL;
+  if (p->B == 0) return STS_OK;
+  if (p->N > 0 && !p->scores) return STS_EINVAL;
+  if (p->kind == STS_SCORES_LOGITS_LSE && !p->lse) return STS_EINVAL;
+  const size_t need = pl.agg_bytes + pl.hist_bytes + pl.state_bytes + pl.chunk_bytes;
+  if (!p->workspace || p->workspace_bytes < need) return STS_EWORKSPACE;
+  if (reinterpret_cast<uintptr_t>(p->workspace) % 256 != 0) return STS_EWORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  SelectArgs a;
+  memset(&a, 0, sizeof(a));
+  a.scores = p->scores;
+  a.lse = p->kind == STS_SCORES_LOGITS_LSE ? p->lse : nullptr;
+  a.seq_lens = p->seq_lens;
+  a.indices = p->indices;
+  a.counts = p->counts;
+  unsigned char *w = static_cast<unsigned char *>(p->workspace);
+  a.agg = p->agg_out ? p->agg_out : reinterpret_cast<float *>(w);
+  w += pl.agg_bytes;
+  a.hist = reinterpret_cast<uint32_t *>(w);
+  w += pl.hist_bytes;
+  a.state = reinterpret_cast<uint32_t *>(w);
+  w += pl.state_bytes;
+  a.chunk_cnt = reinterpret_cast<uint32_t *>(w);
+  a.B = p->B; a.Hd = p->Hd; a.Tq = p->Tq; a.N = p->N; a.Hq = p->Hq; a.k = p->k;
+  a.kind = p->kind; a.reduce = p->reduce; a.nchunks = pl.nchunks;
+  // inverse of the head map: the target heads fed by each draft head, in head order
+  {
+    int cnt[STS_MAX_HEADS + 1] = {0};
+    for (int t = 0; t < p->Hq; ++t) ++cnt[p->head_map[t] + 1];
+    for (int j = 0; j < p->Hd; ++j) cnt[j + 1] += cnt[j];
+    for (int j = 0; j <= p->Hd; ++j) a.targets.off[j] = (uint16_t)cnt[j];
+    int fill[STS_MAX_HEADS] = {0};
+    for (int t = 0; t < p->Hq; ++t) {
+      const int j = p->head_map[t];
+      a.targets.tgt[cnt[j] + fill[j]++] = (uint8_t)t;
+    }
+  }
+
+  hipError_t rc;
+  if (pl.nchunks > 0) {
+    rc = run_kernel(STS_K_SELECT_CLEAR, s, [&] { return launch_select_clear(a, s); });
+    if (rc != hipSuccess) return STS_EHIP;
+    rc = run_kernel(STS_K_SELECT_AGG, s, [&] { return launch_select_agg(a, s); });
+    if (rc != hipSuccess) return STS_EHIP;
+    rc = run_kernel(STS_K_SELECT_HIST, s, [&] { return launch_select_hist(a, 1, s); });
+    if (rc != hipSuccess) return STS_EHIP;
+    rc = run_kernel(STS_K_SELECT_HIST, s, [&] { return launch_select_hist(a, 2, s); });
+    if (rc != hipSuccess) return STS_EHIP;
+    rc = run_kernel(STS_K_SELECT_COUNT, s, [&] { return launch_select_count(a, s); });
+    if (rc != hipSuccess) return STS_EHIP;
+  }
+  rc = run_kernel(STS_K_SELECT_WRITE, s, [&] { return launch_select_write(a, s); });
+  return rc == hipSuccess ? STS_OK : STS_EHIP;
+}
+
+const char *sts_strerror(sts_status s) {
+  switch (s) {
+    case STS_OK: return "ok";
+    case STS_EINVAL: return "invalid argument";
+    case STS_EUNSUPPORTED: return "unsupported shape";
+    case STS_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case STS_EHIP: return "HIP launch error";
+  }
+  return "unknown status";
+}
+
+int sts_version(void) { return 100; }
+
+void sts_prof_enable(int on) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  g_prof_on = on != 0;
+}
+
+void sts_prof_reset(void) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  g_prof_used = 0;
+}
+
+sts_status sts_prof_read(int kernel_kind, int32_t *launches, double *total_ms) {
+  if (kernel_kind < 0 || kernel_kind >= STS_K_COUNT_) return STS_EINVAL;
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  int n = 0;
+  double ms = 0.0;
+  for (size_t i = 0; i < g_prof_used; ++i) {
+    const ProfEvent &e = g_prof_pool[i];
+    if (e.kind != kernel_kind) continue;
+    if (hipEventSynchronize(e.stop) != hipSuccess) return STS_EHIP;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, e.start, e.stop) != hipSuccess) return STS_EHIP;
+    ms += t;
+    ++n;
+  }
+  if (launches) *launches = n;
+  if (total_ms) *total_ms = ms;
+  return STS_OK;
+}
+
+}  // extern "C"

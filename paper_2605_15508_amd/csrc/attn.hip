@@ -1,0 +1,461 @@
+// Split flash-decode attention for the STS verification step (gfx950).
+//
+// One kernel family serves sparse attention over gathered KV rows (paper Section 4.2: attend
+// only to the key-value pairs named by the indices; Section 5: per-head KV sets, scattered
+// rows staged in on-chip memory, split-K) and the dense baseline (identity index row).
+//
+// Work decomposition. A unit is the set of query heads of one KV group that share one index
+// row; its nheads*Tq query rows are padded to NQ tiles of 16. The unit's index row is cut
+// into num_splits contiguous pieces; one workgroup of 4 waves owns one (batch, unit, split)
+// and its waves take alternating 32-key tiles. Each wave keeps its own online-softmax state
+// (fp32), the 4 waves are merged through LDS and one partial (max, sum, O) per workgroup goes
+// to the workspace; a second kernel combines the splits in fixed order.
+//
+// Tile arithmetic, all in the transposed orientation so that nothing but K needs LDS:
+//   S^T[key, query] = K[key, :] . Q[query, :]      v_mfma_f32_16x16x32_bf16, A = K tile
+//   O^T[d,  query] += V^T[d, key] P^T[key, query]                            A = V^T tile
+// Lane (a, b) = (lane / 16, lane % 16). The MFMA output S^T gives lane (a, b) the keys
+// {4a..4a+3, 16+4a..16+4a+3} of query b: exactly the 8 contraction elements lane (a, b) must
+// supply as the B operand of the second product, so P never moves between lanes. The
+// contraction order over d (first product) and the d-column owned by a lane (second product)
+// are free, so they are chosen to make every global load a full coalesced row read:
+//   - 16 consecutive lanes load the 16 chunks of one K or V row (256 B at d = 128);
+//   - V^T's A operand for output tile nt is element nt of each of the lane's 8 loaded V
+//     chunks (lane b owns d = NT*b + nt), two v_perm_b32 per register pair;
+//   - K is written to a wave-private, XOR-swizzled LDS tile and read back as ds_read_b128 in
+//     MFMA A layout (the only cross-lane transpose on the path).
+// Loads for tile t+1 are issued before tile t is consumed (registers are the staging
+// buffer), indices one tile further ahead.
+#include "common.h"
+
+namespace {
+
+template <int D> struct Chunk;
+template <> struct Chunk<128> { typedef u32x4 type; };
+template <> struct Chunk<64> { typedef u32x2 type; };
+
+__device__ __forceinline__ int nth_member(uint32_t mask, int n) {
+  // position of the n-th set bit (n < popcount)
+  int pos = 0;
+#pragma unroll
+  for (int i = 0; i < STS_MAX_GROUP; ++i) {
+    const bool set = (mask >> i) & 1u;
+    if (set && n == 0) pos = i;
+    n -= set ? 1 : 0;
+  }
+  return pos;
+}
+
+__device__ __forceinline__ float xor_max(float x, int lanemask) {
+  return fmaxf(x, __shfl_xor(x, lanemask, 64));
+}
+
+template <int D, int NQ, bool SPARSE, bool LOGITS>
+__global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_split_kernel(const AttnArgs A) {
+  typedef typename Chunk<D>::type chunk_t;
+  constexpr int NT = D / 16;         // output tiles of the PV product == elements per lane chunk
+  constexpr int KK = D / 32;         // contraction steps of the QK product
+  constexpr int CHB = D / 8;         // bytes per lane chunk
+  constexpr int ROWB = D * 2;        // bytes per K/V row
+  constexpr int NSLOT = D / 8;       // 16-byte slots per LDS row
+  constexpr int OPITCH = D + 4;      // floats per row of the merge buffer
+  constexpr int KTILE_BYTES = STS_TILE_KEYS * ROWB;
+  constexpr int MERGE_BYTES = STS_WG_WAVES * 16 * OPITCH * 4;
+  constexpr int LDS_MAIN = (STS_WG_WAVES * KTILE_BYTES > MERGE_BYTES) ? STS_WG_WAVES * KTILE_BYTES : MERGE_BYTES;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_MAIN];
+  __shared__ float lds_ml[STS_WG_WAVES][NQ * 16][2];
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int a = lane >> 4, b = lane & 15;
+
+  const int S = A.num_splits, U = A.num_units;
+  const int split = blockIdx.x % S;
+  const int u = (blockIdx.x / S) % U;
+  const int bt = blockIdx.x / (S * U);
+  const uint32_t unit = A.units.unit[u];
+  const int g = unit & 0xff;
+  const uint32_t mask = (unit >> 8) & 0xffff;
+  const int nheads = (unit >> 24) & 0x1f;
+  const int rows_valid = nheads * A.Tq;
+  const int head0 = g * A.G + nth_member(mask, 0);
+
+  // number of keys this unit attends to
+  int c;
+  if (SPARSE) {
+    c = A.counts ? A.counts[bt * A.Hq + head0] : A.kmax;
+    c = min(max(c, 0), A.kmax);
+  } else {
+    c = A.seq_lens ? A.seq_lens[bt] : A.N;
+    c = min(max(c, 0), A.N);
+  }
+  const int tiles_total = (c + STS_TILE_KEYS - 1) / STS_TILE_KEYS;
+  const int tps = (tiles_total + S - 1) / S;
+  const int t_begin = split * tps;
+  const int t_end = min(t_begin + tps, tiles_total);
+
+  // query rows owned by this lane: row nq*16 + b
+  int q_head[NQ], q_tq[NQ];
+  bool q_ok[NQ];
+  bf16x8 Q[NQ][KK];
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq) {
+    const int r = nq * 16 + b;
+    q_ok[nq] = r < rows_valid;
+    const int hsel = q_ok[nq] ? r / A.Tq : 0;
+    q_tq[nq] = q_ok[nq] ? r - hsel * A.Tq : 0;
+    q_head[nq] = g * A.G + nth_member(mask, hsel);
+    const uint16_t *qp = A.q + (((size_t)bt * A.Tq + q_tq[nq]) * A.Hq + q_head[nq]) * D;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      u32x4 w = {0u, 0u, 0u, 0u};
+      if (q_ok[nq]) w = *reinterpret_cast<const u32x4 *>(qp + 8 * (a + 4 * kk));
+      Q[nq][kk] = __builtin_bit_cast(bf16x8, w);
+    }
+  }
+
+  const unsigned char *kbase = reinterpret_cast<const unsigned char *>(A.k) +
+                               ((int64_t)bt * A.stride_b + (int64_t)g * A.stride_h) * 2 + b * CHB;
+  const unsigned char *vbase = reinterpret_cast<const unsigned char *>(A.v) +
+                               ((int64_t)bt * A.stride_b + (int64_t)g * A.stride_h) * 2 + b * CHB;
+  const int64_t row_bytes = A.stride_n * 2;
+  const int32_t *idx_row = SPARSE ? A.indices + ((size_t)bt * A.Hq + head0) * A.kmax : nullptr;
+  unsigned char *ldsK = lds + wave * KTILE_BYTES;
+
+  // row slot of load m for this lane: 16*(m/4) + 4a + m%4 (the keys the MFMA output hands
+  // to lane group a)
+  auto slot_of = [&](int m) { return 16 * (m >> 2) + 4 * a + (m & 3); };
+
+  // token row feeding slot (lane & 31) of tile t; tiles past the end read row `safe_row`
+  auto fetch_rows = [&](int t, int safe_row) -> int {
+    const int pos = t * STS_TILE_KEYS + (lane & 31);
+    int row;
+    if (t >= t_end) {
+      row = safe_row;
+    } else if (SPARSE) {
+      row = idx_row[min(pos, c - 1)];
+      row = min(max(row, 0), A.N - 1);
+    } else {
+      row = min(pos, c - 1);
+    }
+    return row;
+  };
+
+  auto issue_loads = [&](int rows, chunk_t (&Kr)[8], chunk_t (&Vr)[8]) {
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      const int row = __shfl(rows, slot_of(m), 64);
+      const int64_t off = (int64_t)row * row_bytes;
+      Kr[m] = *reinterpret_cast<const chunk_t *>(kbase + off);
+      Vr[m] = *reinterpret_cast<const chunk_t *>(vbase + off);
+    }
+  };
+
+  float m_run[NQ], l_run[NQ];
+  f32x4 acc[NQ][NT];
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq) {
+    m_run[nq] = -INFINITY;
+    l_run[nq] = 0.f;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[nq][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  auto consume = [&](int t, const chunk_t (&Kr)[8], const chunk_t (&Vr)[8]) {
+    const int pos0 = t * STS_TILE_KEYS;
+    // ---- K: registers -> swizzled LDS tile (row = slot, 16-byte slot index XOR row)
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      const int row = slot_of(m);
+      if (D == 128) {
+        const int sl = b ^ (row & (NSLOT - 1));
+        *reinterpret_cast<chunk_t *>(ldsK + row * ROWB + sl * 16) = Kr[m];
+      } else {
+        const int sl = (b >> 1) ^ (row & (NSLOT - 1));
+        *reinterpret_cast<chunk_t *>(ldsK + row * ROWB + sl * 16 + (b & 1) * 8) = Kr[m];
+      }
+    }
+    // ---- S^T = K Q^T
+    f32x4 St[NQ][2];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) St[nq][0] = St[nq][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const int row = 16 * ks + b;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const int sl = (a + 4 * kk) ^ (row & (NSLOT - 1));
+        const bf16x8 Ka = *reinterpret_cast<const bf16x8 *>(ldsK + row * ROWB + sl * 16);
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq)
+          St[nq][ks] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Ka, Q[nq][kk], St[nq][ks], 0, 0, 0);
+      }
+    }
+    if (LOGITS) {
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq) {
+        if (!q_ok[nq]) continue;
+        float *lp = A.logits_out + (((size_t)bt * A.Hq + q_head[nq]) * A.Tq + q_tq[nq]) * (size_t)A.N;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+          const int p = pos0 + 16 * ks + 4 * a;
+          if (p + 3 < c && (A.N & 3) == 0) {
+            *reinterpret_cast<f32x4 *>(lp + p) = St[nq][ks] * A.scale;
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (p + r < c) lp[p + r] = St[nq][ks][r] * A.scale;
+          }
+        }
+      }
+    }
+    // ---- online softmax (log2 domain) and P^T as bf16 B operands
+    bf16x8 Pb[NQ];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+      float s[8];
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const bool ok = pos0 + 16 * ks + 4 * a + r < c;
+          s[4 * ks + r] = ok ? St[nq][ks][r] * A.scale_log2 : -INFINITY;
+        }
+      float mt = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+      mt = xor_max(mt, 16);
+      mt = xor_max(mt, 32);
+      const float m_new = fmaxf(m_run[nq], mt);          // finite: every consumed tile has a valid key
+      const float alpha = __builtin_amdgcn_exp2f(m_run[nq] - m_new);
+      float p[8], psum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        p[i] = __builtin_amdgcn_exp2f(s[i] - m_new);
+        psum += p[i];
+      }
+      l_run[nq] = l_run[nq] * alpha + psum;
+      m_run[nq] = m_new;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) acc[nq][nt] *= alpha;
+      u32x4 pw;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const f32x2 pr = {p[2 * i], p[2 * i + 1]};
+        pw[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+      }
+      Pb[nq] = __builtin_bit_cast(bf16x8, pw);
+    }
+    // ---- O^T += V^T P^T
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const uint32_t sel = (nt & 1) ? 0x07060302u : 0x05040100u;
+      u32x4 vw;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        vw[j] = __builtin_amdgcn_perm(Vr[2 * j + 1][nt >> 1], Vr[2 * j][nt >> 1], sel);
+      const bf16x8 Va = __builtin_bit_cast(bf16x8, vw);
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq)
+        acc[nq][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Va, Pb[nq], acc[nq][nt], 0, 0, 0);
+    }
+  };
+
+  // ---- main loop over this wave's tiles: t_begin + wave, step 4
+  if (t_begin + wave < t_end) {   // wave-uniform; a wave without tiles touches no memory
+    chunk_t K0[8], V0[8], K1[8], V1[8];
+    int t = t_begin + wave;
+    int rows_cur = fetch_rows(t, 0);
+    const int safe_row = __shfl(rows_cur, 0, 64);
+    int rows_nxt = fetch_rows(t + STS_WG_WAVES, safe_row);
+    issue_loads(rows_cur, K0, V0);
+    while (t < t_end) {
+      int rows_fut = fetch_rows(t + 2 * STS_WG_WAVES, safe_row);
+      issue_loads(rows_nxt, K1, V1);
+      consume(t, K0, V0);
+      t += STS_WG_WAVES;
+      if (t >= t_end) break;
+      rows_nxt = fetch_rows(t + 2 * STS_WG_WAVES, safe_row);
+      issue_loads(rows_fut, K0, V0);
+      consume(t, K1, V1);
+      t += STS_WG_WAVES;
+    }
+  }
+
+  // ---- merge the 4 waves, write one partial per workgroup
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq) {
+    float l = l_run[nq];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    l_run[nq] = l;
+    if (a == 0) {
+      lds_ml[wave][nq * 16 + b][0] = m_run[nq];
+      lds_ml[wave][nq * 16 + b][1] = l;
+    }
+  }
+  __syncthreads();   // K staging is dead from here on; lds_ml visible
+  float *Om = reinterpret_cast<float *>(lds);
+  const size_t pidx = ((size_t)bt * U + u) * S + split;
+  float *po = A.part_o + pidx * (size_t)(NQ * 16 * D);
+  float *pml = A.part_ml + pidx * (size_t)(NQ * 16 * 2);
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq) {
+    float mstar = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < STS_WG_WAVES; ++w) mstar = fmaxf(mstar, lds_ml[w][nq * 16 + b][0]);
+    const float f = (m_run[nq] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_run[nq] - mstar);
+    float *orow = Om + (wave * 16 + b) * OPITCH;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int d0 = NT * (4 * a + r);
+#pragma unroll
+      for (int v4 = 0; v4 < NT / 4; ++v4) {
+        f32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = acc[nq][4 * v4 + e][r] * f;
+        *reinterpret_cast<f32x4 *>(orow + d0 + 4 * v4) = o;
+      }
+    }
+    __syncthreads();
+    {
+      // 256 threads: row = tid / 16, D/16 consecutive floats each
+      const int row = threadIdx.x >> 4, seg = threadIdx.x & 15;
+      constexpr int SEGF = D / 16;
+      float sum[SEGF];
+#pragma unroll
+      for (int e = 0; e < SEGF; ++e) sum[e] = 0.f;
+#pragma unroll
+      for (int w = 0; w < STS_WG_WAVES; ++w) {
+        const float *src = Om + (w * 16 + row) * OPITCH + seg * SEGF;
+#pragma unroll
+        for (int e = 0; e < SEGF; e += 4) {
+          const f32x4 x = *reinterpret_cast<const f32x4 *>(src + e);
+          sum[e] += x[0]; sum[e + 1] += x[1]; sum[e + 2] += x[2]; sum[e + 3] += x[3];
+        }
+      }
+      float *dst = po + (size_t)(nq * 16 + row) * D + seg * SEGF;
+#pragma unroll
+      for (int e = 0; e < SEGF; e += 4)
+        *reinterpret_cast<f32x4 *>(dst + e) = f32x4{sum[e], sum[e + 1], sum[e + 2], sum[e + 3]};
+      if (threadIdx.x < 16) {
+        const int r = nq * 16 + threadIdx.x;
+        float ms = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < STS_WG_WAVES; ++w) ms = fmaxf(ms, lds_ml[w][r][0]);
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < STS_WG_WAVES; ++w) {
+          const float mw = lds_ml[w][r][0];
+          L += (mw == -INFINITY) ? 0.f : lds_ml[w][r][1] * __builtin_amdgcn_exp2f(mw - ms);
+        }
+        pml[r * 2 + 0] = ms;
+        pml[r * 2 + 1] = L;
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// Combine the per-split partials of one (batch, unit, query tile) in split order and write
+// the final rows. One workgroup of 256 threads: row = tid / 16, D/16 floats per thread.
+template <int D>
+__global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs A, const int NQ) {
+  constexpr int SEGF = D / 16;
+  const int S = A.num_splits, U = A.num_units;
+  const int nq = blockIdx.x % NQ;
+  const int u = (blockIdx.x / NQ) % U;
+  const int bt = blockIdx.x / (NQ * U);
+  const uint32_t unit = A.units.unit[u];
+  const int g = unit & 0xff;
+  const uint32_t mask = (unit >> 8) & 0xffff;
+  const int nheads = (unit >> 24) & 0x1f;
+  const int row = threadIdx.x >> 4, seg = threadIdx.x & 15;
+  const int r = nq * 16 + row;
+  if (r >= nheads * A.Tq) return;
+  const int hsel = r / A.Tq, tq = r - hsel * A.Tq;
+  const int head = g * A.G + nth_member(mask, hsel);
+  const size_t p0 = ((size_t)bt * U + u) * S;
+  const size_t rows_per = (size_t)NQ * 16;
+
+  float mstar = -INFINITY;
+  for (int s = 0; s < S; ++s) mstar = fmaxf(mstar, A.part_ml[((p0 + s) * rows_per + r) * 2]);
+  float L = 0.f;
+  float o[SEGF];
+#pragma unroll
+  for (int e = 0; e < SEGF; ++e) o[e] = 0.f;
+  for (int s = 0; s < S; ++s) {
+    const float ms = A.part_ml[((p0 + s) * rows_per + r) * 2];
+    const float ls = A.part_ml[((p0 + s) * rows_per + r) * 2 + 1];
+    if (ms == -INFINITY) continue;
+    const float f = __builtin_amdgcn_exp2f(ms - mstar);
+    L += ls * f;
+    const float *src = A.part_o + ((p0 + s) * rows_per + r) * D + seg * SEGF;
+#pragma unroll
+    for (int e = 0; e < SEGF; e += 4) {
+      const f32x4 x = *reinterpret_cast<const f32x4 *>(src + e);
+      o[e] += x[0] * f; o[e + 1] += x[1] * f; o[e + 2] += x[2] * f; o[e + 3] += x[3] * f;
+    }
+  }
+  const float inv = (L > 0.f) ? 1.f / L : 0.f;
+  const size_t orow = (((size_t)bt * A.Tq + tq) * A.Hq + head) * D + seg * SEGF;
+  if (A.out_dtype == STS_F32) {
+    float *dst = reinterpret_cast<float *>(A.out) + orow;
+#pragma unroll
+    for (int e = 0; e < SEGF; e += 4)
+      *reinterpret_cast<f32x4 *>(dst + e) = f32x4{o[e] * inv, o[e + 1] * inv, o[e + 2] * inv, o[e + 3] * inv};
+  } else {
+    uint32_t *dst = reinterpret_cast<uint32_t *>(reinterpret_cast<uint16_t *>(A.out) + orow);
+#pragma unroll
+    for (int e = 0; e < SEGF; e += 2) {
+      const f32x2 pr = {o[e] * inv, o[e + 1] * inv};
+      dst[e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+    }
+  }
+  if (A.lse_out && seg == 0) {
+    const float ln2 = 0.69314718055994530942f;
+    A.lse_out[((size_t)bt * A.Hq + head) * A.Tq + tq] =
+        (L > 0.f) ? (mstar + __builtin_amdgcn_logf(L)) * ln2 : -INFINITY;
+  }
+}
+
+template <int D, int NQ>
+hipError_t launch_split_dn(const AttnArgs &a, bool sparse, hipStream_t s) {
+  const dim3 grid((unsigned)((size_t)a.B * a.num_units * a.num_splits)), block(64 * STS_WG_WAVES);
+  if (sparse)
+    hipLaunchKernelGGL((attn_split_kernel<D, NQ, true, false>), grid, block, 0, s, a);
+  else if (a.logits_out)
+    hipLaunchKernelGGL((attn_split_kernel<D, NQ, false, true>), grid, block, 0, s, a);
+  else
+    hipLaunchKernelGGL((attn_split_kernel<D, NQ, false, false>), grid, block, 0, s, a);
+  return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_split_d(const AttnArgs &a, int nq, bool sparse, hipStream_t s) {
+  switch (nq) {
+    case 1: return launch_split_dn<D, 1>(a, sparse, s);
+    case 2: return launch_split_dn<D, 2>(a, sparse, s);
+    case 4: return launch_split_dn<D, 4>(a, sparse, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+hipError_t launch_attn_split(const AttnArgs &a, int d, int nq, bool sparse, hipStream_t s) {
+  if ((size_t)a.B * a.num_units * a.num_splits == 0) return hipSuccess;
+  if (d == 128) return launch_split_d<128>(a, nq, sparse, s);
+  if (d == 64) return launch_split_d<64>(a, nq, sparse, s);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_attn_combine(const AttnArgs &a, int d, int nq, hipStream_t s) {
+  const size_t blocks = (size_t)a.B * a.num_units * nq;
+  if (blocks == 0) return hipSuccess;
+  const dim3 grid((unsigned)blocks), block(256);
+  if (d == 128)
+    hipLaunchKernelGGL((attn_combine_kernel<128>), grid, block, 0, s, a, nq);
+  else if (d == 64)
+    hipLaunchKernelGGL((attn_combine_kernel<64>), grid, block, 0, s, a, nq);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}

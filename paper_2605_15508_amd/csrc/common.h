@@ -1,0 +1,86 @@
+// Shared declarations of the STS HIP library (gfx950 only). Internal: the public surface is
+// include/sts.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/sts.h"
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int STS_MAX_HEADS = 256;   // Hq, Hd upper bound (tables travel as kernel arguments)
+constexpr int STS_MAX_GROUP = 16;    // query heads per KV head
+constexpr int STS_TILE_KEYS = 32;    // keys per wave tile
+constexpr int STS_WG_WAVES = 4;      // waves per attention workgroup
+
+// A work unit of the attention kernels: the query heads of one KV group that share one index
+// row (sparse) or all heads of the group (dense). Packed: bits 0-7 KV head, 8-23 mask of the
+// member heads within the group, 24-28 number of member heads.
+struct AttnUnitTable {
+  uint32_t unit[STS_MAX_HEADS];
+};
+
+struct AttnArgs {
+  const uint16_t *q, *k, *v;
+  const int32_t *indices, *counts, *seq_lens;
+  int64_t stride_b, stride_h, stride_n;   // elements
+  int32_t B, Tq, Hq, Hkv, G, N, kmax;
+  int32_t num_units, num_splits;
+  float scale_log2;                       // scale * log2(e)
+  float scale;
+  float *part_o;                          // [B*U*S][NQ*16][D]
+  float *part_ml;                         // [B*U*S][NQ*16][2]  (max in log2 domain, sum)
+  float *logits_out;
+  void *out;
+  float *lse_out;
+  int32_t out_dtype;
+  AttnUnitTable units;
+};
+
+struct AttnPlan {
+  int32_t nq;          // query tiles of 16 rows per unit (1, 2 or 4)
+  int32_t num_units;   // per batch element
+  int32_t num_splits;
+  size_t part_o_bytes, part_ml_bytes;
+  AttnUnitTable units;
+};
+
+// select ------------------------------------------------------------------------------------
+
+constexpr int SEL_BITS0 = 11, SEL_BITS1 = 11, SEL_BITS2 = 10;
+constexpr int SEL_BINS = 2048;          // bins of the widest digit
+constexpr int SEL_CHUNK = 8192;         // tokens per workgroup in the scan kernels
+constexpr int SEL_THREADS = 256;
+
+struct SelectTargets {
+  // targets of draft head j: tgt[off[j] .. off[j+1])
+  uint16_t off[STS_MAX_HEADS + 1];
+  uint8_t tgt[STS_MAX_HEADS];
+};
+
+struct SelectArgs {
+  const float *scores, *lse;
+  const int32_t *seq_lens;
+  int32_t *indices, *counts;
+  float *agg;                 // [B,Hd,N] (agg_out or workspace)
+  uint32_t *hist;             // [rows][3][SEL_BINS]
+  uint32_t *state;            // [rows][8]: prefix key, remaining k per pass, threshold, ties
+  uint32_t *chunk_cnt;        // [rows][nchunks][2]
+  int32_t B, Hd, Tq, N, Hq, k, kind, reduce, nchunks;
+  SelectTargets targets;
+};
+
+// launches (defined in the .hip files); each returns hipGetLastError() of its launch
+hipError_t launch_attn_split(const AttnArgs &a, int d, int nq, bool sparse, hipStream_t s);
+hipError_t launch_attn_combine(const AttnArgs &a, int d, int nq, hipStream_t s);
+hipError_t launch_select_clear(const SelectArgs &a, hipStream_t s);
+hipError_t launch_select_agg(const SelectArgs &a, hipStream_t s);
+hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t s);
+hipError_t launch_select_count(const SelectArgs &a, hipStream_t s);
+hipError_t launch_select_write(const SelectArgs &a, hipStream_t s);

@@ -1,0 +1,411 @@
+// Online mask generation for STS (gfx950): draft attention scores -> per-head top-k token
+// index sets, remapped to the target heads (paper Section 4.2; Section 4.3: one mask per
+// speculative batch).
+//
+// Pipeline, one row = one (batch, draft head), every kernel on a (chunk, row) grid:
+//   clear  zero the three digit histograms of every row
+//   agg    A[n] = ((P[0,n] + P[1,n]) + ...) in fp32, stored; histogram of the top 11 key bits
+//   hist1  find the first digit of the k-th largest key, histogram the next 11 bits of the
+//          keys that share it
+//   hist2  same for the last 10 bits
+//   count  the k-th largest key T is now known, with r = how many keys equal to T are kept;
+//          per-chunk counts of keys > T and == T
+//   write  ordered compaction: token n is kept iff key > T, or key == T and fewer than r equal
+//          keys precede it; its output position is (#greater before n) + min(#equal before n, r).
+//          The list is written to every target head mapped to this draft head.
+// Keys are the usual order-preserving map of fp32 to uint32 (with -0 folded onto +0), so the
+// whole selection is integer arithmetic: the index sets are exact, ties go to the lower token.
+// Histograms use LDS atomics per workgroup and integer global atomics to merge (order-free).
+#include "common.h"
+
+namespace {
+
+__device__ __forceinline__ uint32_t key_of(float x) {
+  uint32_t u = __builtin_bit_cast(uint32_t, x);
+  if (u == 0x80000000u) u = 0u;                       // -0 == +0
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // ascending with the float order
+}
+
+__device__ __forceinline__ int row_len(const SelectArgs &A, int bt) {
+  int nb = A.seq_lens ? A.seq_lens[bt] : A.N;
+  return min(max(nb, 0), A.N);
+}
+
+// exclusive prefix sum of one value per thread over a 256-thread block; also returns the total
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *lds_wave_tot, uint32_t &total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t incl = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t o = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += o;
+  }
+  if (lane == 63) lds_wave_tot[wave] = incl;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < SEL_THREADS / 64; ++w) {
+    const uint32_t t = lds_wave_tot[w];
+    if (w < wave) base += t;
+    tot += t;
+  }
+  __syncthreads();
+  total = tot;
+  return base + incl - v;
+}
+
+// Walk a digit histogram from the top: the digit holding the krem-th largest key of the
+// candidates, and how many keys of that digit are still wanted. Requires 1 <= krem <= total.
+template <int NBINS>
+__device__ __forceinline__ void find_digit(const uint32_t *hist, uint32_t krem, uint32_t *lds_tmp,
+                                           uint32_t &digit, uint32_t &krem_next) {
+  constexpr int PER = NBINS / SEL_THREADS;
+  uint32_t loc[PER], sum = 0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    loc[i] = hist[threadIdx.x * PER + i];
+    sum += loc[i];
+  }
+  uint32_t total;
+  const uint32_t excl = block_excl_scan(sum, lds_tmp, total);
+  uint32_t above = total - excl - sum;   // keys in bins owned by higher threads
+#pragma unroll
+  for (int i = PER - 1; i >= 0; --i) {
+    if (above < krem && above + loc[i] >= krem) {
+      lds_tmp[8] = threadIdx.x * PER + i;
+      lds_tmp[9] = krem - above;
+    }
+    above += loc[i];
+  }
+  __syncthreads();
+  digit = lds_tmp[8];
+  krem_next = lds_tmp[9];
+  __syncthreads();
+}
+
+__global__ void __launch_bounds__(SEL_THREADS) select_clear_kernel(uint32_t *p, size_t n) {
+  const size_t i = (size_t)blockIdx.x * SEL_THREADS + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+// --------------------------------------------------------------------------- aggregation
+template <bool VEC4>
+__global__ void __launch_bounds__(SEL_THREADS) select_agg_kernel(const SelectArgs A) {
+  __shared__ uint32_t h[SEL_BINS];
+  const int row = blockIdx.y, chunk = blockIdx.x;
+  const int bt = row / A.Hd;
+  const int nb = row_len(A, bt);
+  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) h[i] = 0u;
+  __syncthreads();
+  const float *P = A.scores + (size_t)row * A.Tq * A.N;
+  const float *L = A.lse ? A.lse + (size_t)row * A.Tq : nullptr;
+  float *out = A.agg + (size_t)row * A.N;
+  const int n0 = chunk * SEL_CHUNK;
+  const int n1 = min(n0 + SEL_CHUNK, A.N);
+  const bool logits = A.kind == STS_SCORES_LOGITS_LSE;
+  const bool use_max = A.reduce == STS_REDUCE_MAX;
+
+  auto reduce1 = [&](float acc, float p, int i) -> float {
+    if (i == 0) return p;
+    return use_max ? fmaxf(acc, p) : acc + p;
+  };
+
+  if (VEC4) {
+    for (int n = n0 + threadIdx.x * 4; n < n1; n += SEL_THREADS * 4) {
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      for (int i = 0; i < A.Tq; ++i) {
+        f32x4 p = *reinterpret_cast<const f32x4 *>(P + (size_t)i * A.N + n);
+        if (logits) {
+          const float l = L[i];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) p[e] = expf(p[e] - l);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] = reduce1(acc[e], p[e], i);
+      }
+      *reinterpret_cast<f32x4 *>(out + n) = acc;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (n + e < nb) atomicAdd(&h[key_of(acc[e]) >> (32 - SEL_BITS0)], 1u);
+    }
+  } else {
+    for (int n = n0 + threadIdx.x; n < n1; n += SEL_THREADS) {
+      float acc = 0.f;
+      for (int i = 0; i < A.Tq; ++i) {
+        float p = P[(size_t)i * A.N + n];
+        if (logits) p = expf(p - L[i]);
+        acc = reduce1(acc, p, i);
+      }
+      out[n] = acc;
+      if (n < nb) atomicAdd(&h[key_of(acc) >> (32 - SEL_BITS0)], 1u);
+    }
+  }
+  __syncthreads();
+  uint32_t *gh = A.hist + (size_t)row * 3 * SEL_BINS;
+  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS)
+    if (h[i]) atomicAdd(&gh[i], h[i]);
+}
+
+// ------------------------------------------------------------------ refinement histograms
+// PASS 1: digit 1 (bits 20..10) of keys whose digit 0 matches; PASS 2: digit 2 (bits 9..0)
+// of keys whose digits 0 and 1 match.
+template <int PASS, bool VEC4>
+__global__ void __launch_bounds__(SEL_THREADS) select_hist_kernel(const SelectArgs A) {
+  __shared__ uint32_t h[SEL_BINS];
+  __shared__ uint32_t tmp[16];
+  const int row = blockIdx.y, chunk = blockIdx.x;
+  const int bt = row / A.Hd;
+  const int nb = row_len(A, bt);
+  const uint32_t c = (uint32_t)min(A.k, nb);
+  if (c == 0) return;
+  uint32_t *st = A.state + (size_t)row * 8;
+  const uint32_t *gh = A.hist + (size_t)row * 3 * SEL_BINS;
+  uint32_t prefix, shift, dmask;
+  if (PASS == 1) {
+    uint32_t d0, k1;
+    find_digit<(1 << SEL_BITS0)>(gh, c, tmp, d0, k1);
+    if (chunk == 0 && threadIdx.x == 0) { st[0] = d0; st[1] = k1; st[6] = c; }
+    prefix = d0;
+    shift = SEL_BITS1 + SEL_BITS2;
+    dmask = (1u << SEL_BITS1) - 1;
+  } else {
+    const uint32_t d0 = st[0], k1 = st[1];
+    uint32_t d1, k2;
+    find_digit<(1 << SEL_BITS1)>(gh + SEL_BINS, k1, tmp, d1, k2);
+    if (chunk == 0 && threadIdx.x == 0) { st[2] = d1; st[3] = k2; }
+    prefix = (d0 << SEL_BITS1) | d1;
+    shift = SEL_BITS2;
+    dmask = (1u << SEL_BITS2) - 1;
+  }
+  const uint32_t dshift = (PASS == 1) ? SEL_BITS2 : 0;
+  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) h[i] = 0u;
+  __syncthreads();
+  const float *a = A.agg + (size_t)row * A.N;
+  const int n0 = chunk * SEL_CHUNK;
+  const int n1 = min(min(n0 + SEL_CHUNK, A.N), nb);
+  if (VEC4) {
+    for (int n = n0 + threadIdx.x * 4; n < n1; n += SEL_THREADS * 4) {
+      const f32x4 x = *reinterpret_cast<const f32x4 *>(a + n);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t key = key_of(x[e]);
+        if (n + e < n1 && (key >> shift) == prefix) atomicAdd(&h[(key >> dshift) & dmask], 1u);
+      }
+    }
+  } else {
+    for (int n = n0 + threadIdx.x; n < n1; n += SEL_THREADS) {
+      const uint32_t key = key_of(a[n]);
+      if ((key >> shift) == prefix) atomicAdd(&h[(key >> dshift) & dmask], 1u);
+    }
+  }
+  __syncthreads();
+  uint32_t *go = A.hist + ((size_t)row * 3 + PASS) * SEL_BINS;
+  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS)
+    if (h[i]) atomicAdd(&go[i], h[i]);
+}
+
+// --------------------------------------------------------------------- per-chunk counts
+template <bool VEC4>
+__global__ void __launch_bounds__(SEL_THREADS) select_count_kernel(const SelectArgs A) {
+  __shared__ uint32_t tmp[16];
+  const int row = blockIdx.y, chunk = blockIdx.x;
+  const int bt = row / A.Hd;
+  const int nb = row_len(A, bt);
+  const uint32_t c = (uint32_t)min(A.k, nb);
+  if (c == 0) return;
+  uint32_t *st = A.state + (size_t)row * 8;
+  const uint32_t *gh = A.hist + (size_t)row * 3 * SEL_BINS;
+  uint32_t d2, r;
+  find_digit<(1 << SEL_BITS2)>(gh + 2 * SEL_BINS, st[3], tmp, d2, r);
+  const uint32_t T = (st[0] << (SEL_BITS1 + SEL_BITS2)) | (st[2] << SEL_BITS2) | d2;
+  if (chunk == 0 && threadIdx.x == 0) { st[4] = T; st[5] = r; }
+  const float *a = A.agg + (size_t)row * A.N;
+  const int n0 = chunk * SEL_CHUNK;
+  const int n1 = min(min(n0 + SEL_CHUNK, A.N), nb);
+  uint32_t packed = 0;   // greater in the low half, equal in the high half (<= 8192 each)
+  if (VEC4) {
+    for (int n = n0 + threadIdx.x * 4; n < n1; n += SEL_THREADS * 4) {
+      const f32x4 x = *reinterpret_cast<const f32x4 *>(a + n);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t key = key_of(x[e]);
+        if (n + e < n1) packed += (key > T ? 1u : 0u) + (key == T ? 0x10000u : 0u);
+      }
+    }
+  } else {
+    for (int n = n0 + threadIdx.x; n < n1; n += SEL_THREADS) {
+      const uint32_t key = key_of(a[n]);
+      packed += (key > T ? 1u : 0u) + (key == T ? 0x10000u : 0u);
+    }
+  }
+  uint32_t total;
+  (void)block_excl_scan(packed, tmp, total);
+  if (threadIdx.x == 0) {
+    uint32_t *cc = A.chunk_cnt + ((size_t)row * A.nchunks + chunk) * 2;
+    cc[0] = total & 0xffffu;
+    cc[1] = total >> 16;
+  }
+}
+
+// ------------------------------------------------------ ordered compaction + head remap
+// Each wave owns a contiguous quarter of the chunk and walks it in 8 rows of 256 tokens
+// (lane l holds tokens 4l..4l+3 of the row), so prefix counts follow token order.
+__global__ void __launch_bounds__(SEL_THREADS) select_write_kernel(const SelectArgs A) {
+  __shared__ uint32_t tmp[16];
+  __shared__ uint32_t wave_gt[SEL_THREADS / 64], wave_eq[SEL_THREADS / 64];
+  const int row = blockIdx.y, chunk = blockIdx.x;
+  const int bt = row / A.Hd, j = row % A.Hd;
+  const int nb = row_len(A, bt);
+  const uint32_t c = (uint32_t)min(A.k, nb);
+  const int t0 = A.targets.off[j], t1 = A.targets.off[j + 1];
+  if (chunk == 0) {
+    // tail padding and counts for every target head of this draft head
+    for (int ti = t0; ti < t1; ++ti) {
+      const int tgt = A.targets.tgt[ti];
+      int32_t *dst = A.indices + ((size_t)bt * A.Hq + tgt) * A.k;
+      for (uint32_t p = c + threadIdx.x; p < (uint32_t)A.k; p += SEL_THREADS) dst[p] = -1;
+      if (A.counts && threadIdx.x == 0) A.counts[(size_t)bt * A.Hq + tgt] = (int32_t)c;
+    }
+  }
+  if (c == 0 || t0 == t1) return;
+  const int n0 = chunk * SEL_CHUNK;
+  if (n0 >= nb) return;
+  const uint32_t *st = A.state + (size_t)row * 8;
+  const uint32_t T = st[4], r = st[5];
+
+  // keys greater / equal in the chunks before this one
+  uint32_t pre = 0, pre_eq = 0;
+  {
+    const uint32_t *cc = A.chunk_cnt + (size_t)row * A.nchunks * 2;
+    uint32_t g = 0, e = 0;
+    for (int ch = threadIdx.x; ch < chunk; ch += SEL_THREADS) {
+      g += cc[ch * 2];
+      e += cc[ch * 2 + 1];
+    }
+    uint32_t tg, te;
+    (void)block_excl_scan(g, tmp, tg);
+    (void)block_excl_scan(e, tmp, te);
+    pre = tg;
+    pre_eq = te;
+  }
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const float *a = A.agg + (size_t)row * A.N;
+  constexpr int WAVE_TOK = SEL_CHUNK / (SEL_THREADS / 64);   // 2048
+  constexpr int ROWS = WAVE_TOK / 256;                        // 8
+  const int w0 = n0 + wave * WAVE_TOK;
+  uint32_t keys[ROWS][4];
+  uint32_t ex_gt[ROWS], ex_eq[ROWS];
+  uint32_t run_gt = 0, run_eq = 0;
+#pragma unroll
+  for (int i = 0; i < ROWS; ++i) {
+    const int n = w0 + i * 256 + lane * 4;
+    uint32_t cg = 0, ce = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      // out-of-range tokens get key 0 only as a placeholder; they are excluded by the test
+      const bool in = n + e < nb;
+      keys[i][e] = in ? key_of(a[n + e]) : 0u;
+      cg += (in && keys[i][e] > T) ? 1u : 0u;
+      ce += (in && keys[i][e] == T) ? 1u : 0u;
+    }
+    uint32_t v = cg | (ce << 16);
+    uint32_t incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t o = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += o;
+    }
+    const uint32_t tot = __shfl(incl, 63, 64);
+    const uint32_t excl = incl - v;
+    ex_gt[i] = run_gt + (excl & 0xffffu);
+    ex_eq[i] = run_eq + (excl >> 16);
+    run_gt += tot & 0xffffu;
+    run_eq += tot >> 16;
+  }
+  if (lane == 0) {
+    wave_gt[wave] = run_gt;
+    wave_eq[wave] = run_eq;
+  }
+  __syncthreads();
+  uint32_t base_gt = pre, base_eq = pre_eq;
+  for (int w = 0; w < wave; ++w) {
+    base_gt += wave_gt[w];
+    base_eq += wave_eq[w];
+  }
+#pragma unroll
+  for (int i = 0; i < ROWS; ++i) {
+    uint32_t g = base_gt + ex_gt[i], q = base_eq + ex_eq[i];
+    const int n = w0 + i * 256 + lane * 4;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const bool in = n + e < nb;
+      const bool is_gt = in && keys[i][e] > T;
+      const bool is_eq = in && keys[i][e] == T;
+      if (is_gt || (is_eq && q < r)) {
+        const uint32_t pos = g + min(q, r);
+        if (pos < c)   // always true for a consistent threshold; keeps a bad state in bounds
+          for (int ti = t0; ti < t1; ++ti)
+          A.indices[((size_t)bt * A.Hq + A.targets.tgt[ti]) * A.k + pos] = n + e;
+      }
+      g += is_gt ? 1u : 0u;
+      q += is_eq ? 1u : 0u;
+    }
+  }
+}
+
+}  // namespace
+
+static inline bool vec_ok(const SelectArgs &a) {
+  return (a.N % 4) == 0 && (reinterpret_cast<uintptr_t>(a.scores) % 16) == 0 &&
+         (reinterpret_cast<uintptr_t>(a.agg) % 16) == 0;
+}
+
+hipError_t launch_select_clear(const SelectArgs &a, hipStream_t s) {
+  const size_t n = (size_t)a.B * a.Hd * 3 * SEL_BINS;
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(select_clear_kernel, dim3((unsigned)((n + SEL_THREADS - 1) / SEL_THREADS)),
+                     dim3(SEL_THREADS), 0, s, a.hist, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_select_agg(const SelectArgs &a, hipStream_t s) {
+  if ((size_t)a.B * a.Hd == 0 || a.nchunks == 0) return hipSuccess;
+  const dim3 grid(a.nchunks, a.B * a.Hd), block(SEL_THREADS);
+  if (vec_ok(a))
+    hipLaunchKernelGGL(select_agg_kernel<true>, grid, block, 0, s, a);
+  else
+    hipLaunchKernelGGL(select_agg_kernel<false>, grid, block, 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t s) {
+  if ((size_t)a.B * a.Hd == 0 || a.nchunks == 0) return hipSuccess;
+  const dim3 grid(a.nchunks, a.B * a.Hd), block(SEL_THREADS);
+  const bool v = vec_ok(a);
+  if (pass == 1) {
+    if (v) hipLaunchKernelGGL((select_hist_kernel<1, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((select_hist_kernel<1, false>), grid, block, 0, s, a);
+  } else {
+    if (v) hipLaunchKernelGGL((select_hist_kernel<2, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((select_hist_kernel<2, false>), grid, block, 0, s, a);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_select_count(const SelectArgs &a, hipStream_t s) {
+  if ((size_t)a.B * a.Hd == 0 || a.nchunks == 0) return hipSuccess;
+  const dim3 grid(a.nchunks, a.B * a.Hd), block(SEL_THREADS);
+  if (vec_ok(a))
+    hipLaunchKernelGGL(select_count_kernel<true>, grid, block, 0, s, a);
+  else
+    hipLaunchKernelGGL(select_count_kernel<false>, grid, block, 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_select_write(const SelectArgs &a, hipStream_t s) {
+  if ((size_t)a.B * a.Hd == 0) return hipSuccess;
+  const dim3 grid(a.nchunks > 0 ? a.nchunks : 1, a.B * a.Hd), block(SEL_THREADS);
+  hipLaunchKernelGGL(select_write_kernel, grid, block, 0, s, a);
+  return hipGetLastError();
+}

@@ -1,0 +1,43 @@
+"""Helpers shared by the GPU parity tests: tolerances and oracle calls on device tensors."""
+import numpy as np
+import torch
+
+import oracle
+
+# bf16 inputs, fp32 accumulation, against the fp64 oracle (the bar the benchmark spec fixes)
+MAX_ABS = 1e-2
+MEAN_ABS = 1e-3
+LSE_ABS = 1e-3
+
+
+def bits(t: torch.Tensor) -> np.ndarray:
+    return oracle.bf16_bits(t.detach().cpu())
+
+
+def oracle_attn(q, k, v, scale, indices=None, counts=None, seq_lens=None, want_logits=False,
+                batches=None, heads=None):
+    return oracle.attn(bits(q), bits(k), bits(v), scale,
+                       None if indices is None else indices.cpu().numpy(),
+                       None if counts is None else counts.cpu().numpy(),
+                       None if seq_lens is None else seq_lens.cpu().numpy(),
+                       want_logits=want_logits, batches=batches, heads=heads)
+
+
+def check_attn(out, lse, ref, sel=None, what=""):
+    """Compare a GPU result with the oracle's within the stated tolerances. `sel` optionally
+    restricts to (batch slice, head slice)."""
+    o = out.float().cpu().numpy()
+    l = lse.cpu().numpy()
+    ro, rl = ref["out"], ref["lse"]
+    if sel is not None:
+        bs, hs = sel
+        o, ro = o[bs][:, :, hs], ro[bs][:, :, hs]
+        l, rl = l[bs][:, hs], rl[bs][:, hs]
+    err = np.abs(o - ro)
+    assert np.isfinite(o).all(), what
+    assert err.max() <= MAX_ABS, f"{what}: max-abs {err.max():.3e}"
+    assert err.mean() <= MEAN_ABS, f"{what}: mean-abs {err.mean():.3e}"
+    fin = np.isfinite(rl)
+    assert (np.isneginf(l) == np.isneginf(rl)).all(), what
+    assert np.abs(l[fin] - rl[fin]).max(initial=0.0) <= LSE_ABS, f"{what}: lse {np.abs(l[fin] - rl[fin]).max():.3e}"
+    return float(err.max()), float(err.mean())

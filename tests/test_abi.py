@@ -1,0 +1,101 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, and validates arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_15508_amd as sts
+from paper_2605_15508_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(sts.library_path()):
+        from paper_2605_15508_amd.build import build
+
+        build(force=True)
+    return sts.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sts.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sts_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"sts_select", "sts_sparse_attn", "sts_dense_attn"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/sts.h but not exported"
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_version_and_strerror(lib):
+    assert sts.sts_version() >= 100
+    assert lib.sts_strerror(0) == b"ok"
+    assert b"workspace" in lib.sts_strerror(-3)
+
+
+def attn_params(**kw):
+    base = dict(B=1, Tq=5, Hq=32, Hkv=8, d=128, N=4096, kv_stride_b=8 * 4096 * 128, kv_stride_h=4096 * 128,
+                kv_stride_n=128, kmax=410, scale=0.088, out_dtype=0)
+    base.update(kw)
+    return binding.AttnParams(**base)
+
+
+def test_attn_argument_validation(lib):
+    ok = attn_params()
+    assert lib.sts_attn_workspace_bytes(ctypes.byref(ok), 1) > 0
+    for bad in (attn_params(d=96), attn_params(Tq=17), attn_params(Hq=30), attn_params(kv_stride_n=100),
+                attn_params(Hq=512, Hkv=8)):
+        assert lib.sts_attn_workspace_bytes(ctypes.byref(bad), 1) == 0
+        assert lib.sts_sparse_attn(ctypes.byref(bad), None) < 0
+    # valid shape but no workspace / no data: refused before any launch
+    assert lib.sts_sparse_attn(ctypes.byref(ok), None) == -1
+
+
+def test_attn_plan_groups_heads_by_head_map(lib):
+    p = attn_params()
+    s, u, nq = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    assert lib.sts_attn_plan(ctypes.byref(p), 1, ctypes.byref(s), ctypes.byref(u), ctypes.byref(nq)) == 0
+    assert (u.value, nq.value) == (32, 1)            # no hint: one unit per query head
+    hm = (ctypes.c_int32 * 32)(*[t // 2 for t in range(32)])
+    p.head_map = ctypes.cast(hm, ctypes.c_void_p)
+    assert lib.sts_attn_plan(ctypes.byref(p), 1, ctypes.byref(s), ctypes.byref(u), ctypes.byref(nq)) == 0
+    assert (u.value, nq.value) == (16, 1)            # pairs share a gathered tile: 10 rows
+    assert s.value >= 1
+    hm2 = (ctypes.c_int32 * 32)(*[0] * 32)
+    p.head_map = ctypes.cast(hm2, ctypes.c_void_p)
+    assert lib.sts_attn_plan(ctypes.byref(p), 1, ctypes.byref(s), ctypes.byref(u), ctypes.byref(nq)) == 0
+    assert (u.value, nq.value) == (8, 2)             # whole KV group: 20 rows -> 2 query tiles
+    p.head_map = None
+    assert lib.sts_attn_plan(ctypes.byref(p), 0, ctypes.byref(s), ctypes.byref(u), ctypes.byref(nq)) == 0
+    assert (u.value, nq.value) == (8, 2)             # dense: one unit per KV head
+
+
+def test_select_argument_validation(lib):
+    hm = (ctypes.c_int32 * 4)(0, 1, 1, 0)
+    p = binding.SelectParams(B=1, Hd=2, Tq=5, N=1000, Hq=4, k=10, head_map=ctypes.cast(hm, ctypes.c_void_p))
+    assert lib.sts_select_workspace_bytes(ctypes.byref(p)) > 0
+    assert lib.sts_select(ctypes.byref(p), None) == -1          # indices missing
+    p.k = 0
+    assert lib.sts_select_workspace_bytes(ctypes.byref(p)) == 0
+    p.k = 10
+    bad = (ctypes.c_int32 * 4)(0, 2, 1, 0)                      # draft head 2 does not exist
+    p.head_map = ctypes.cast(bad, ctypes.c_void_p)
+    p.indices = 256                                             # never dereferenced: map is checked first
+    assert lib.sts_select(ctypes.byref(p), None) == -1
+
+
+def test_product_path_has_no_oracle_import():
+    pkg = os.path.join(ROOT, "paper_2605_15508_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "sts_oracle" not in text

@@ -1,0 +1,174 @@
+"""GPU parity: sts_sparse_attn / sts_dense_attn (through the C ABI) against the CPU oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_15508_amd as sts
+from gpu_util import check_attn, oracle_attn
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def make_qkv(seed, B, Tq, Hq, Hkv, d, N, kv_std=0.5):
+    g = torch.Generator().manual_seed(seed)
+    q = torch.randn(B, Tq, Hq, d, generator=g).to(torch.bfloat16)
+    k = (torch.randn(B, Hkv, N, d, generator=g) * kv_std).to(torch.bfloat16)
+    v = (torch.randn(B, Hkv, N, d, generator=g) * kv_std).to(torch.bfloat16)
+    return q.to(DEV), k.to(DEV), v.to(DEV)
+
+
+def make_indices(seed, B, Hq, N, kk, head_map=None):
+    rng = np.random.default_rng(seed)
+    idx = np.empty((B, Hq, kk), np.int32)
+    for b in range(B):
+        rows = {}
+        for t in range(Hq):
+            key = t if head_map is None else int(head_map[t])
+            if key not in rows:
+                rows[key] = np.sort(rng.choice(N, kk, replace=False))
+            idx[b, t] = rows[key]
+    return torch.from_numpy(idx).to(DEV)
+
+
+@pytest.mark.parametrize("B,Tq,Hq,Hkv,d,N", [
+    (2, 5, 8, 2, 128, 1000),     # GQA 4, several tiles, ragged tail
+    (1, 1, 4, 4, 128, 37),       # MHA, single query row, less than two tiles
+    (1, 8, 16, 2, 128, 2500),    # GQA 8 x 8 rows = 64 query rows (4 query tiles)
+    (2, 5, 8, 2, 64, 777),       # head dim 64
+    (1, 16, 4, 2, 128, 300),     # 16 query rows per head
+    (1, 3, 6, 2, 64, 31),        # GQA 3, less than one tile
+])
+def test_dense_matches_oracle(B, Tq, Hq, Hkv, d, N):
+    q, k, v = make_qkv(1, B, Tq, Hq, Hkv, d, N)
+    scale = 1.0 / math.sqrt(d)
+    out, lse, _ = sts.sts_dense_attn(q, k, v, scale, out_dtype=torch.float32)
+    ref = oracle_attn(q, k, v, scale)
+    check_attn(out, lse, ref, what="dense f32")
+    out16, lse16, _ = sts.sts_dense_attn(q, k, v, scale)
+    assert out16.dtype == torch.bfloat16
+    check_attn(out16, lse16, ref, what="dense bf16")
+
+
+@pytest.mark.parametrize("B,Tq,Hq,Hkv,d,N,kk,shared", [
+    (2, 5, 8, 2, 128, 1000, 100, 2),    # pairs of heads share a draft head
+    (1, 5, 8, 2, 128, 1000, 333, 1),    # every head on its own
+    (1, 5, 8, 2, 128, 1000, 45, 4),     # whole KV group shares (20 rows, 2 query tiles)
+    (1, 8, 16, 2, 128, 3000, 700, 2),   # 16 rows per unit
+    (2, 5, 8, 2, 64, 512, 64, 2),       # head dim 64
+    (1, 1, 4, 2, 128, 64, 1, 1),        # a single key per head
+    (1, 5, 8, 1, 128, 600, 77, 8),      # 8 heads x 5 rows = 40 rows (4 query tiles)
+])
+def test_sparse_matches_oracle(B, Tq, Hq, Hkv, d, N, kk, shared):
+    q, k, v = make_qkv(2, B, Tq, Hq, Hkv, d, N)
+    head_map = [t // shared for t in range(Hq)]
+    idx = make_indices(3, B, Hq, N, kk, head_map)
+    scale = 1.0 / math.sqrt(d)
+    ref = oracle_attn(q, k, v, scale, idx)
+    out, lse = sts.sts_sparse_attn(q, k, v, idx, scale, head_map=head_map, out_dtype=torch.float32)
+    check_attn(out, lse, ref, what="sparse hinted")
+    # without the hint every head is processed alone: same answer
+    out2, lse2 = sts.sts_sparse_attn(q, k, v, idx, scale, out_dtype=torch.float32)
+    check_attn(out2, lse2, ref, what="sparse unhinted")
+
+
+def test_sparse_scattered_head_map_and_counts():
+    B, Tq, Hq, Hkv, d, N, kk = 2, 5, 16, 2, 128, 2000, 150
+    q, k, v = make_qkv(4, B, Tq, Hq, Hkv, d, N)
+    rng = np.random.default_rng(0)
+    head_map = rng.integers(0, 5, size=Hq).tolist()        # sets are not contiguous head ranges
+    idx = make_indices(5, B, Hq, N, kk, head_map)
+    by_key = {}
+    counts = np.empty((B, Hq), np.int32)
+    for b in range(B):
+        for t in range(Hq):
+            counts[b, t] = by_key.setdefault((b, head_map[t]), int(rng.integers(0, kk + 1)))
+    counts[0, [t for t in range(Hq) if head_map[t] == head_map[0]]] = 0      # an empty row
+    counts_d = torch.from_numpy(counts).to(DEV)
+    # entries past the count are padding (-1) and must never be read as rows
+    idx_pad = idx.clone()
+    for b in range(B):
+        for t in range(Hq):
+            idx_pad[b, t, counts[b, t]:] = -1
+    ref = oracle_attn(q, k, v, 0.09, idx, counts_d)
+    out, lse = sts.sts_sparse_attn(q, k, v, idx_pad, 0.09, counts=counts_d, head_map=head_map,
+                                   out_dtype=torch.float32)
+    check_attn(out, lse, ref, what="scattered map + counts")
+    empty = counts == 0
+    assert (out.cpu().numpy().transpose(0, 2, 1, 3)[empty] == 0).all()
+
+
+def test_full_budget_equals_dense_kernel():
+    B, Tq, Hq, Hkv, d, N = 1, 5, 8, 2, 128, 500
+    q, k, v = make_qkv(6, B, Tq, Hq, Hkv, d, N)
+    idx = torch.arange(N, dtype=torch.int32, device=DEV).expand(B, Hq, N).contiguous()
+    o_s, l_s = sts.sts_sparse_attn(q, k, v, idx, 0.1, head_map=[0] * Hq, out_dtype=torch.float32)
+    o_d, l_d, _ = sts.sts_dense_attn(q, k, v, 0.1, out_dtype=torch.float32)
+    ref = oracle_attn(q, k, v, 0.1)
+    check_attn(o_s, l_s, ref, what="k = N sparse")
+    check_attn(o_d, l_d, ref, what="dense")
+    assert (o_s - o_d).abs().max().item() < 1e-5
+
+
+def test_dense_seq_lens_strided_cache_and_logits():
+    B, Tq, Hq, Hkv, d, N = 3, 5, 8, 2, 128, 640
+    q, k, v = make_qkv(7, B, Tq, Hq, Hkv, d, N)
+    kv = torch.stack([k, v], dim=3).contiguous()       # interleaved cache [B,Hkv,N,2,d]
+    ks, vs = kv[:, :, :, 0], kv[:, :, :, 1]
+    lens = torch.tensor([640, 129, 0], dtype=torch.int32, device=DEV)
+    out, lse, logits = sts.sts_dense_attn(q, ks, vs, 0.09, seq_lens=lens, out_dtype=torch.float32,
+                                          want_logits=True)
+    ref = oracle_attn(q, k, v, 0.09, seq_lens=lens, want_logits=True)
+    check_attn(out, lse, ref, what="dense seq_lens strided")
+    lg, rl = logits.cpu().numpy(), ref["logits"]
+    for b, n in enumerate(lens.tolist()):
+        assert np.abs(lg[b, :, :, :n] - rl[b, :, :, :n]).max(initial=0.0) < 2e-3
+    assert (out[2] == 0).all() and torch.isneginf(lse[2]).all()
+
+
+def test_logits_dump_head_dim_64_unaligned_n():
+    B, Tq, Hq, Hkv, d, N = 1, 8, 8, 2, 64, 301       # N % 4 != 0: scalar store path
+    q, k, v = make_qkv(8, B, Tq, Hq, Hkv, d, N)
+    out, lse, logits = sts.sts_dense_attn(q, k, v, 0.125, out_dtype=torch.float32, want_logits=True)
+    ref = oracle_attn(q, k, v, 0.125, want_logits=True)
+    check_attn(out, lse, ref, what="dense d64 logits")
+    assert np.abs(logits.cpu().numpy() - ref["logits"]).max() < 2e-3
+
+
+def test_results_are_deterministic_run_to_run():
+    B, Tq, Hq, Hkv, d, N, kk = 2, 5, 8, 2, 128, 4000, 400
+    q, k, v = make_qkv(9, B, Tq, Hq, Hkv, d, N)
+    hm = [t // 2 for t in range(Hq)]
+    idx = make_indices(10, B, Hq, N, kk, hm)
+    a, la = sts.sts_sparse_attn(q, k, v, idx, 0.09, head_map=hm, out_dtype=torch.float32)
+    a, la = a.clone(), la.clone()
+    b, lb = sts.sts_sparse_attn(q, k, v, idx, 0.09, head_map=hm, out_dtype=torch.float32)
+    assert torch.equal(a, b) and torch.equal(la, lb)
+
+
+def test_out_of_range_indices_are_clamped_not_faulting():
+    B, Tq, Hq, Hkv, d, N, kk = 1, 5, 4, 2, 128, 100, 10
+    q, k, v = make_qkv(11, B, Tq, Hq, Hkv, d, N)
+    idx = make_indices(12, B, Hq, N, kk)
+    bad = idx.clone()
+    bad[0, 0, 0] = -5
+    bad[0, 1, 3] = 10 ** 6
+    out, _ = sts.sts_sparse_attn(q, k, v, bad, 0.09, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    fixed = idx.clone()
+    fixed[0, 0, 0] = 0
+    fixed[0, 1, 3] = N - 1
+    ref = oracle_attn(q, k, v, 0.09, fixed)
+    assert np.abs(out.cpu().numpy() - ref["out"]).max() < 1e-2
+
+
+def test_empty_batch_and_workspace_errors():
+    q, k, v = make_qkv(13, 1, 5, 8, 2, 128, 256)
+    tiny = torch.empty(256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(sts.StsError):
+        sts.sts_dense_attn(q, k, v, 0.09, workspace=tiny)
+    q0 = q[:0].contiguous()
+    out, lse, _ = sts.sts_dense_attn(q0, k[:0].contiguous(), v[:0].contiguous(), 0.09)
+    assert out.shape[0] == 0

@@ -1,0 +1,134 @@
+"""GPU parity: sts_select (through the C ABI) against the CPU oracle. Index sets, counts and
+the aggregated scores must match bit for bit on identical score tensors."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_15508_amd as sts
+from workload import CONFIGS, make_workload
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def run_both(scores, head_map, k, lse=None, seq_lens=None, kind=0, reduce=0):
+    sd = scores.to(DEV)
+    idx, cnt, agg = sts.sts_select(sd, head_map, k, lse=None if lse is None else lse.to(DEV),
+                                   seq_lens=None if seq_lens is None else seq_lens.to(DEV),
+                                   kind=kind, reduce=reduce, want_agg=True)
+    torch.cuda.synchronize()
+    o_idx, o_cnt, o_agg = oracle.select_indices(
+        scores.numpy(), np.asarray(head_map, np.int32), k, lse=None if lse is None else lse.numpy(),
+        kind=kind, reduce=reduce, seq_lens=None if seq_lens is None else seq_lens.numpy())
+    return (idx.cpu().numpy(), cnt.cpu().numpy(), agg.cpu().numpy()), (o_idx, o_cnt, o_agg)
+
+
+def softmax_scores(seed, B, Hd, Tq, N, temp=2.0):
+    g = torch.Generator().manual_seed(seed)
+    return torch.softmax(torch.randn(B, Hd, Tq, N, generator=g) * temp, dim=-1)
+
+
+@pytest.mark.parametrize("B,Hd,Tq,N,Hq,k", [
+    (1, 16, 5, 4096, 32, 410),        # the 4K configuration's shape
+    (2, 3, 5, 20000, 6, 2000),        # several chunks per row, ragged last chunk
+    (1, 2, 1, 8192, 4, 1),            # single query row, k = 1
+    (2, 4, 8, 1001, 8, 100),          # N % 4 != 0: scalar path
+    (1, 2, 5, 50, 2, 50),             # k = N
+    (1, 2, 5, 50, 3, 80),             # k > N: tail padded with -1
+    (1, 1, 64, 300, 1, 7),            # many query rows
+])
+def test_select_bit_exact_random(B, Hd, Tq, N, Hq, k):
+    scores = softmax_scores(1, B, Hd, Tq, N)
+    hm = [(t * Hd) // Hq for t in range(Hq)]
+    (idx, cnt, agg), (o_idx, o_cnt, o_agg) = run_both(scores, hm, k)
+    np.testing.assert_array_equal(agg.view(np.uint32), o_agg.view(np.uint32))
+    np.testing.assert_array_equal(cnt, o_cnt)
+    np.testing.assert_array_equal(idx, o_idx)
+
+
+@pytest.mark.parametrize("levels", [1, 2, 4, 37])
+def test_select_heavy_ties(levels):
+    g = torch.Generator().manual_seed(levels)
+    B, Hd, Tq, N, Hq = 2, 4, 3, 30000, 8
+    scores = torch.randint(0, levels, (B, Hd, Tq, N), generator=g).float() / 8.0
+    hm = [3, 3, 0, 1, 2, 2, 0, 1]
+    for k in (1, 999, 8192, 29999):
+        (idx, cnt, _), (o_idx, o_cnt, _) = run_both(scores, hm, k)
+        np.testing.assert_array_equal(idx, o_idx)
+        np.testing.assert_array_equal(cnt, o_cnt)
+
+
+def test_select_signed_zero_negative_denormal_inf():
+    N = 5000
+    g = torch.Generator().manual_seed(5)
+    base = torch.randn(1, 2, 1, N, generator=g)
+    base[0, 0, 0, ::7] = 0.0
+    base[0, 0, 0, 3::7] = -0.0
+    base[0, 0, 0, 5::11] = 1e-42
+    base[0, 0, 0, 6::13] = -1e-42
+    base[0, 1, 0, 100] = float("inf")
+    base[0, 1, 0, 200] = float("-inf")
+    for k in (1, 700, 2500, 4999):
+        (idx, _, agg), (o_idx, _, o_agg) = run_both(base, [0, 1], k)
+        np.testing.assert_array_equal(agg.view(np.uint32), o_agg.view(np.uint32))
+        np.testing.assert_array_equal(idx, o_idx)
+
+
+def test_select_seq_lens_and_unmapped_draft_heads():
+    B, Hd, Tq, N, Hq, k = 3, 4, 5, 9000, 5, 600
+    scores = softmax_scores(6, B, Hd, Tq, N)
+    lens = torch.tensor([9000, 333, 0], dtype=torch.int32)
+    hm = [0, 0, 3, 3, 0]                      # draft heads 1 and 2 feed nobody
+    (idx, cnt, _), (o_idx, o_cnt, _) = run_both(scores, hm, k, seq_lens=lens)
+    np.testing.assert_array_equal(cnt, o_cnt)
+    np.testing.assert_array_equal(idx, o_idx)
+    assert (idx[2] == -1).all() and (cnt[1] == 333).all()
+
+
+def test_select_max_reduction():
+    scores = softmax_scores(7, 1, 4, 5, 6000)
+    hm = [0, 1, 2, 3]
+    (idx, _, agg), (o_idx, _, o_agg) = run_both(scores, hm, 512, reduce=sts.STS_REDUCE_MAX)
+    np.testing.assert_array_equal(agg.view(np.uint32), o_agg.view(np.uint32))
+    np.testing.assert_array_equal(idx, o_idx)
+
+
+def test_select_logits_lse_stagewise():
+    """expf differs between libm and the device, so the aggregate is compared within a
+    relative tolerance and the selection is then checked bit-exact on the GPU's own
+    aggregate fed to the oracle (identical score tensors on both sides)."""
+    g = torch.Generator().manual_seed(8)
+    B, Hd, Tq, N, Hq, k = 2, 4, 5, 12000, 8, 1200
+    logits = torch.randn(B, Hd, Tq, N, generator=g) * 2.0
+    lse = torch.logsumexp(logits.double(), dim=-1).float()
+    hm = [t // 2 for t in range(Hq)]
+    (idx, cnt, agg), (_, _, o_agg) = run_both(logits, hm, k, lse=lse, kind=sts.STS_SCORES_LOGITS_LSE)
+    np.testing.assert_allclose(agg, o_agg, rtol=1e-5, atol=1e-12)
+    sel, c = oracle.select(agg, k)
+    o_idx, o_cnt = oracle.remap(sel, c, np.asarray(hm, np.int32))
+    np.testing.assert_array_equal(idx, o_idx)
+    np.testing.assert_array_equal(cnt, o_cnt)
+
+
+def test_select_then_sparse_attention_on_the_4k_configuration():
+    """The whole path on the small configuration: planted workload, selection bit-exact,
+    sparse attention within tolerance, everything against the oracle."""
+    from gpu_util import check_attn, oracle_attn
+
+    w = make_workload(CONFIGS["c1"], seed=20251127)
+    q, k, v, scores = w.q.to(DEV), w.k.to(DEV), w.v.to(DEV), w.scores.to(DEV)
+    idx, cnt, _ = sts.sts_select(scores, w.head_map, w.k_budget)
+    out, lse = sts.sts_sparse_attn(q, k, v, idx, w.scale, counts=cnt, head_map=w.head_map,
+                                   out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    o_idx, o_cnt, _ = oracle.select_indices(w.scores.numpy(), w.head_map.numpy(), w.k_budget)
+    np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
+    np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
+    assert w.k_budget == 410 and (o_cnt == 410).all()
+    ref = oracle_attn(q, k, v, w.scale, torch.from_numpy(o_idx), torch.from_numpy(o_cnt))
+    check_attn(out, lse, ref, what="c1 chain")
+    # planted sinks are selected by every head
+    assert (o_idx[:, :, :4] == np.arange(4)).all()

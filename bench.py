@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the STS hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input, all of it
+resident in HBM before the timed region: sts_select (draft scores -> index sets),
+sts_sparse_attn (verification attention over the gathered rows) and sts_dense_attn (the
+same-family dense baseline on the same inputs). The headline value is the sparse
+verification attention time per layer; selection and dense times, the speedup over dense and
+the achieved HBM bandwidth on gathered KV bytes are reported beside it.
+
+Prints ONE JSON line. `python bench.py` defaults to the 128K-context, batch-4, 10%-budget
+configuration and finishes within a couple of minutes including the CPU-oracle baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "sparse verify-attn µs/layer + HBM GB/s at 90% sparsity, 128K ctx, vs dense"
+HBM_PEAK_GBS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c5"])
+    ap.add_argument("--budget", type=float, default=None, help="fraction of N kept per head")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true", help="leave the dense baseline out of the step")
+    ap.add_argument("--seed", type=int, default=20251127)
+    return ap.parse_args()
+
+
+def read_traffic(kernel: str, workload: str):
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary
+    (profiles/traffic_<kernel>_<workload>.txt holds a line `hbm_bytes_per_launch: <int>`)."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{kernel}_{workload}.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("hbm_bytes_per_launch:"):
+                    return int(float(line.split(":", 1)[1]))
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(w, idx, cnt, budget_s=25.0):
+    """Time the CPU oracle (as it stands, untuned) on this machine's host cores on a bounded sample
+    of the same workload. Returns the cpu_baseline object."""
+    import numpy as np
+
+    import oracle
+
+    cfg = w.cfg
+    threads = oracle.num_threads()
+    qb = oracle.bf16_bits(w.q.cpu())
+    # sample: as many whole batch elements as fit the time budget, estimated from one head
+    kb = oracle.bf16_bits(w.k[:1].cpu())
+    vb = oracle.bf16_bits(w.v[:1].cpu())
+    idx0 = idx[:1].cpu().numpy()
+    cnt0 = cnt[:1].cpu().numpy()
+    t0 = time.perf_counter()
+    oracle.attn(qb[:1], kb, vb, w.scale, idx0, cnt0, heads=range(0, min(threads, cfg.Hq)))
+    probe = time.perf_counter() - t0
+    per_batch = probe * cfg.Hq / min(threads, cfg.Hq)
+    nb = int(max(1, min(cfg.B, budget_s // max(per_batch, 1e-3))))
+    kb = oracle.bf16_bits(w.k[:nb].cpu())
+    vb = oracle.bf16_bits(w.v[:nb].cpu())
+    idxn = idx[:nb].cpu().numpy()
+    cntn = cnt[:nb].cpu().numpy()
+    best = float("inf")
+    for _ in range(2):
+        t0 = time.perf_counter()
+        oracle.attn(qb[:nb], kb, vb, w.scale, idxn, cntn)
+        best = min(best, time.perf_counter() - t0)
+    sparse_us_layer = best / nb * cfg.B * 1e6
+    # selection on one batch element
+    sc = w.scores[:1].cpu().numpy()
+    t0 = time.perf_counter()
+    oracle.select_indices(sc, w.head_map.numpy(), w.k_budget)
+    sel_us_layer = (time.perf_counter() - t0) * cfg.B * 1e6
+    # dense on one KV group of batch 0 (extrapolated linearly)
+    G = cfg.Hq // cfg.Hkv
+    t0 = time.perf_counter()
+    oracle.attn(qb[:1], kb[:1], vb[:1], w.scale, heads=range(0, G))
+    dense_us_layer = (time.perf_counter() - t0) * cfg.Hkv * cfg.B * 1e6
+    return {
+        "value": round(sparse_us_layer, 1), "unit": "us/layer", "cores": threads, "kind": "oracle",
+        "sample": (f"sts_sparse_attn oracle on {nb} of {cfg.B} batch elements (all {cfg.Hq} heads, "
+                   f"k={w.k_budget}), best of 2, scaled to the batch; select timed on 1 batch element, "
+                   f"dense on 1 KV group of 1 batch element, both scaled linearly"),
+        "select_us_layer": round(sel_us_layer, 1),
+        "dense_us_layer_extrapolated": round(dense_us_layer, 1),
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              f"--gpus {args.gpus} is not supported.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2605_15508_amd as sts
+    from workload import CONFIGS, budget_tokens, make_draft_layer, make_workload
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    sts.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = CONFIGS[args.config]
+    w = make_workload(cfg, seed=args.seed, device=dev, budget=args.budget, with_scores=not cfg.draft_d)
+    kb = w.k_budget
+    B, N, Hq, Hkv, d, Tq, Hd = cfg.B, cfg.N, cfg.Hq, cfg.Hkv, cfg.d, cfg.Tq, cfg.Hd
+    draft = make_draft_layer(w) if cfg.draft_d else None
+    torch.cuda.synchronize()
+
+    # persistent outputs so the timed region allocates nothing
+    idx = torch.empty(B, Hq, kb, dtype=torch.int32, device=dev)
+    cnt = torch.empty(B, Hq, dtype=torch.int32, device=dev)
+    out_s = torch.empty(B, Tq, Hq, d, dtype=torch.bfloat16, device=dev)
+    out_d = torch.empty_like(out_s)
+    d_out = d_lse = d_logits = None
+    if draft is not None:
+        d_out = torch.empty(B, Tq, Hd, cfg.draft_d, dtype=torch.bfloat16, device=dev)
+
+    def step(ev=None):
+        if ev: ev[0].record()
+        if draft is not None:
+            _, lse_d, logits_d = sts.sts_dense_attn(draft["q"], draft["k"], draft["v"], draft["scale"],
+                                                    out=d_out, want_logits=True)
+            if ev: ev[1].record()
+            sts.sts_select(logits_d, w.head_map, kb, lse=lse_d, kind=sts.STS_SCORES_LOGITS_LSE, out=(idx, cnt))
+        else:
+            if ev: ev[1].record()
+            sts.sts_select(w.scores, w.head_map, kb, out=(idx, cnt))
+        if ev: ev[2].record()
+        sts.sts_sparse_attn(w.q, w.k, w.v, idx, w.scale, counts=cnt, head_map=w.head_map, out=out_s,
+                            want_lse=False)
+        if ev: ev[3].record()
+        if not args.no_dense:
+            sts.sts_dense_attn(w.q, w.k, w.v, w.scale, out=out_d, want_lse=False)
+        if ev: ev[4].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    sts.prof_enable(True)
+    sts.prof_reset()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof = sts.prof_read()
+    sts.prof_enable(False)
+
+    def stage(i):
+        xs = [ev[i].elapsed_time(ev[i + 1]) * 1e3 for ev in events]      # microseconds
+        return statistics.fmean(xs), statistics.median(xs), min(xs)
+
+    draft_us, select_us, sparse_us, dense_us = stage(0), stage(1), stage(2), stage(3)
+    K = args.steps
+    split_n, split_ms = prof["attn_sparse"]
+    split_us = split_ms * 1e3 / max(split_n, 1)
+    dsplit_n, dsplit_ms = prof["attn_dense"]
+    plan = sts.attn_plan(w.q, w.k, True, kmax=kb, head_map=w.head_map)
+    units = plan["units_per_batch"]
+    row_bytes = 2 * d * 2                                   # one K row + one V row, bf16
+    b_set = B * units * kb * row_bytes                      # gathered once per distinct index row
+    b_req = B * Hq * kb * row_bytes                         # gathered per query head
+    b_dense = B * Hkv * N * row_bytes
+    achieved = b_set / (split_us * 1e-6) / 1e9 if split_us > 0 else 0.0
+    workload = (f"{cfg.name}: B{B} N{N} Hq{Hq}/Hkv{Hkv} d{d} Tq{Tq} Hd{Hd} budget "
+                f"{kb} tokens ({kb / N:.1%})")
+    result = {
+        "metric": METRIC,
+        "value": round(sparse_us[0], 2),
+        "unit": "us/layer",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall / K * 1e3, 4),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": workload, "context": N, "batch": B, "budget_tokens": kb,
+                   "head_map": "t*Hd//Hq", "step": "select + sparse_attn" + ("" if args.no_dense else " + dense_attn")
+                   + (" (+ draft dense attn with logits dump)" if draft is not None else "")},
+        "sparse_attn_us": {"mean": round(sparse_us[0], 2), "median": round(sparse_us[1], 2), "min": round(sparse_us[2], 2)},
+        "dense_attn_us": {"mean": round(dense_us[0], 2), "median": round(dense_us[1], 2), "min": round(dense_us[2], 2)},
+        "select_us": {"mean": round(select_us[0], 2), "median": round(select_us[1], 2), "min": round(select_us[2], 2)},
+        "speedup_vs_dense": round(dense_us[0] / sparse_us[0], 3) if not args.no_dense and sparse_us[0] > 0 else None,
+        "gathered_kv_gbs": {"b_set": round(b_set / (sparse_us[0] * 1e-6) / 1e9, 1),
+                            "b_req": round(b_req / (sparse_us[0] * 1e-6) / 1e9, 1)},
+        "dense_kv_gbs": round(b_dense / (dense_us[0] * 1e-6) / 1e9, 1) if not args.no_dense else None,
+        "kernel_us": {k: round(ms * 1e3 / n, 2) for k, (n, ms) in prof.items() if n},
+        "launch": plan,
+        "roofline": {
+            "bound": "hbm", "kernel": "attn_split_kernel<sparse>", "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "algorithmic_bytes_per_launch": b_set, "avg_launch_us": round(split_us, 2), "launches": split_n,
+            "traffic": read_traffic("attn_sparse_split", cfg.name),
+        },
+        "paper_context": "2.67x end-to-end speedup at ~90% sparsity on NVIDIA H20 (other hardware, whole serving stack)",
+    }
+    if draft is not None:
+        result["draft_attn_us"] = {"mean": round(draft_us[0], 2), "median": round(draft_us[1], 2)}
+    if dsplit_n:
+        result["roofline_dense"] = {"achieved": round(b_dense / (dsplit_ms * 1e-3 / dsplit_n) / 1e9, 1),
+                                    "frac": round(b_dense / (dsplit_ms * 1e-3 / dsplit_n) / 1e9 / HBM_PEAK_GBS, 4)}
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, idx, cnt)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -130,5 +130,6 @@ def test_select_then_sparse_attention_on_the_4k_configuration():
     assert w.k_budget == 410 and (o_cnt == 410).all()
     ref = oracle_attn(q, k, v, w.scale, torch.from_numpy(o_idx), torch.from_numpy(o_cnt))
     check_attn(out, lse, ref, what="c1 chain")
-    # planted sinks are selected by every head
-    assert (o_idx[:, :, :4] == np.arange(4)).all()
+    # planted sink / recent positions are kept far more often than the 10% base rate
+    planted = np.concatenate([np.arange(4), np.arange(4096 - 64, 4096)])
+    assert min(np.isin(planted, o_idx[0, t]).mean() for t in range(32)) > 0.4

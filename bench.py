@@ -38,6 +38,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true", help="leave the dense baseline out of the step")
     ap.add_argument("--seed", type=int, default=20251127)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (scales rocprofv3 --pmc byte counters)")
     return ap.parse_args()
 
 
@@ -171,6 +173,14 @@ def main():
     wall = time.perf_counter() - t0
     prof = sts.prof_read()
     sts.prof_enable(False)
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)          # one kernel reading 1 GiB and writing 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     def stage(i):
         xs = [ev[i].elapsed_time(ev[i + 1]) * 1e3 for ev in events]      # microseconds

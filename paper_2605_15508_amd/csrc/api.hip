@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/sts.h: argument validation, launch planning,
 // workspace carving, kernel enqueue, and the optional per-kernel event timing.
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <mutex>
@@ -120,7 +121,11 @@ sts_status plan_attn(const sts_attn_params *p, int sparse, AttnPlan &pl) {
   pl.nq = max_rows <= 16 ? 1 : (max_rows <= 32 ? 2 : 4);
   const int64_t len = sparse ? p->kmax : p->N;
   const int64_t tiles = (len + STS_TILE_KEYS - 1) / STS_TILE_KEYS;
-  const int64_t resident = (int64_t)cu_count() * (pl.nq == 4 ? 1 : 2);
+  int64_t resident = (int64_t)cu_count() * (pl.nq == 4 ? 1 : 2);
+  if (const char *e = getenv("STS_ATTN_WGS_PER_CU")) {   // tuning knob: target workgroups per CU
+    const double f = atof(e);
+    if (f > 0.0) resident = (int64_t)(cu_count() * f);
+  }
   const int64_t units_total = (int64_t)p->B * nu;
   int64_t S = units_total > 0 ? resident / units_total : 1;
   const int64_t s_cap = (tiles + STS_WG_WAVES - 1) / STS_WG_WAVES;   // >= 1 tile per wave

@@ -145,8 +145,9 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
     for (int m = 0; m < 8; ++m) {
       const int row = __shfl(rows, slot_of(m), 64);
       const int64_t off = (int64_t)row * row_bytes;
-      Kr[m] = *reinterpret_cast<const chunk_t *>(kbase + off);
-      Vr[m] = *reinterpret_cast<const chunk_t *>(vbase + off);
+      // every K/V row is consumed once per launch: stream it past the caches
+      Kr[m] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t *>(kbase + off));
+      Vr[m] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t *>(vbase + off));
     }
   };
 
@@ -375,23 +376,38 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs A, con
   const size_t p0 = ((size_t)bt * U + u) * S;
   const size_t rows_per = (size_t)NQ * 16;
 
-  float mstar = -INFINITY;
-  for (int s = 0; s < S; ++s) mstar = fmaxf(mstar, A.part_ml[((p0 + s) * rows_per + r) * 2]);
-  float L = 0.f;
+  // Splits are merged in split order with a running maximum (same arithmetic every run);
+  // loads are issued in independent batches of 8 so their latencies overlap.
+  constexpr int BATCH = 8;
+  float mstar = -INFINITY, L = 0.f;
   float o[SEGF];
 #pragma unroll
   for (int e = 0; e < SEGF; ++e) o[e] = 0.f;
-  for (int s = 0; s < S; ++s) {
-    const float ms = A.part_ml[((p0 + s) * rows_per + r) * 2];
-    const float ls = A.part_ml[((p0 + s) * rows_per + r) * 2 + 1];
-    if (ms == -INFINITY) continue;
-    const float f = __builtin_amdgcn_exp2f(ms - mstar);
-    L += ls * f;
-    const float *src = A.part_o + ((p0 + s) * rows_per + r) * D + seg * SEGF;
+  for (int s0 = 0; s0 < S; s0 += BATCH) {
+    float ms[BATCH], ls[BATCH];
+    f32x4 x[BATCH][SEGF / 4];
 #pragma unroll
-    for (int e = 0; e < SEGF; e += 4) {
-      const f32x4 x = *reinterpret_cast<const f32x4 *>(src + e);
-      o[e] += x[0] * f; o[e + 1] += x[1] * f; o[e + 2] += x[2] * f; o[e + 3] += x[3] * f;
+    for (int j = 0; j < BATCH; ++j) {
+      const int sj = min(s0 + j, S - 1);
+      const size_t pr = (p0 + sj) * rows_per + r;
+      ms[j] = (s0 + j < S) ? A.part_ml[pr * 2] : -INFINITY;
+      ls[j] = A.part_ml[pr * 2 + 1];
+      const float *src = A.part_o + pr * D + seg * SEGF;
+#pragma unroll
+      for (int e = 0; e < SEGF / 4; ++e) x[j][e] = *reinterpret_cast<const f32x4 *>(src + 4 * e);
+    }
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j) {
+      if (ms[j] == -INFINITY) continue;
+      const float mnew = fmaxf(mstar, ms[j]);
+      const float fo = __builtin_amdgcn_exp2f(mstar - mnew);   // 0 while nothing is accumulated
+      const float fn = __builtin_amdgcn_exp2f(ms[j] - mnew);
+      L = L * fo + ls[j] * fn;
+#pragma unroll
+      for (int e = 0; e < SEGF / 4; ++e)
+#pragma unroll
+        for (int c4 = 0; c4 < 4; ++c4) o[4 * e + c4] = o[4 * e + c4] * fo + x[j][e][c4] * fn;
+      mstar = mnew;
     }
   }
   const float inv = (L > 0.f) ? 1.f / L : 0.f;

@@ -139,14 +139,16 @@ def main():
     d_out = d_lse = d_logits = None
     if draft is not None:
         d_out = torch.empty(B, Tq, Hd, cfg.draft_d, dtype=torch.bfloat16, device=dev)
+        d_lse = torch.empty(B, Hd, Tq, dtype=torch.float32, device=dev)
+        d_logits = torch.empty(B, Hd, Tq, N, dtype=torch.float32, device=dev)
 
     def step(ev=None):
         if ev: ev[0].record()
         if draft is not None:
-            _, lse_d, logits_d = sts.sts_dense_attn(draft["q"], draft["k"], draft["v"], draft["scale"],
-                                                    out=d_out, want_logits=True)
+            sts.sts_dense_attn(draft["q"], draft["k"], draft["v"], draft["scale"], out=d_out,
+                               lse_out=d_lse, logits_out=d_logits)
             if ev: ev[1].record()
-            sts.sts_select(logits_d, w.head_map, kb, lse=lse_d, kind=sts.STS_SCORES_LOGITS_LSE, out=(idx, cnt))
+            sts.sts_select(d_logits, w.head_map, kb, lse=d_lse, kind=sts.STS_SCORES_LOGITS_LSE, out=(idx, cnt))
         else:
             if ev: ev[1].record()
             sts.sts_select(w.scores, w.head_map, kb, out=(idx, cnt))

@@ -194,7 +194,8 @@ def _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse_o
 
 
 def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=None, seq_lens=None,
-              out=None, out_dtype=None, want_lse=True, want_logits=False, workspace=None):
+              out=None, out_dtype=None, want_lse=True, want_logits=False, workspace=None,
+              lse_out=None, logits_out=None):
     import torch
 
     lib = load_library()
@@ -203,8 +204,14 @@ def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=
     dev = q.device
     if out is None:
         out = torch.empty(B, Tq, Hq, d, dtype=out_dtype or torch.bfloat16, device=dev)
-    lse = torch.empty(B, Hq, Tq, dtype=torch.float32, device=dev) if want_lse else None
-    logits = torch.empty(B, Hq, Tq, N, dtype=torch.float32, device=dev) if want_logits else None
+    lse = lse_out
+    if lse is None and want_lse:
+        lse = torch.empty(B, Hq, Tq, dtype=torch.float32, device=dev)
+    logits = logits_out
+    if logits is None and want_logits:
+        logits = torch.empty(B, Hq, Tq, N, dtype=torch.float32, device=dev)
+    for t, shape in ((lse, (B, Hq, Tq)), (logits, (B, Hq, Tq, N))):
+        assert t is None or (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == shape)
     p, _keep = _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse, logits)
     need = lib.sts_attn_workspace_bytes(ctypes.byref(p), 1 if sparse else 0)
     ws = workspace if workspace is not None else _workspace("attn", need, dev)
@@ -215,19 +222,21 @@ def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=
 
 
 def sts_sparse_attn(q, k, v, indices, scale, counts=None, head_map=None, out=None, out_dtype=None,
-                    want_lse=True, workspace=None):
+                    want_lse=True, workspace=None, lse_out=None):
     """Attention over the gathered rows indices[b,t,:counts[b,t]] of the full cache.
     q [B,Tq,Hq,d] bf16, k/v [B,Hkv,N,d] bf16 (strided ok) -> (out [B,Tq,Hq,d], lse [B,Hq,Tq])."""
     out, lse, _ = _run_attn(True, q, k, v, scale, indices=indices, counts=counts, head_map=head_map,
-                            out=out, out_dtype=out_dtype, want_lse=want_lse, workspace=workspace)
+                            out=out, out_dtype=out_dtype, want_lse=want_lse, workspace=workspace,
+                            lse_out=lse_out)
     return out, lse
 
 
 def sts_dense_attn(q, k, v, scale, seq_lens=None, out=None, out_dtype=None, want_lse=True,
-                   want_logits=False, workspace=None):
+                   want_logits=False, workspace=None, lse_out=None, logits_out=None):
     """Dense attention of the same kernel family -> (out, lse, logits [B,Hq,Tq,N] or None)."""
     return _run_attn(False, q, k, v, scale, seq_lens=seq_lens, out=out, out_dtype=out_dtype,
-                     want_lse=want_lse, want_logits=want_logits, workspace=workspace)
+                     want_lse=want_lse, want_logits=want_logits, workspace=workspace,
+                     lse_out=lse_out, logits_out=logits_out)
 
 
 def attn_plan(q, k, sparse: bool, kmax: int = 0, head_map=None) -> Dict[str, int]:

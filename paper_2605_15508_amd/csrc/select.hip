@@ -249,10 +249,14 @@ __global__ void __launch_bounds__(SEL_THREADS) select_count_kernel(const SelectA
 
 // ------------------------------------------------------ ordered compaction + head remap
 // Each wave owns a contiguous quarter of the chunk and walks it in 8 rows of 256 tokens
-// (lane l holds tokens 4l..4l+3 of the row), so prefix counts follow token order.
+// (lane l holds tokens 4l..4l+3 of the row), so prefix counts follow token order. The kept
+// tokens of a chunk occupy one contiguous range of the output list: they are staged in LDS at
+// their local rank and then copied out with coalesced stores, once per target head.
+template <bool VEC4>
 __global__ void __launch_bounds__(SEL_THREADS) select_write_kernel(const SelectArgs A) {
   __shared__ uint32_t tmp[16];
   __shared__ uint32_t wave_gt[SEL_THREADS / 64], wave_eq[SEL_THREADS / 64];
+  __shared__ int32_t staged[SEL_CHUNK];
   const int row = blockIdx.y, chunk = blockIdx.x;
   const int bt = row / A.Hd, j = row % A.Hd;
   const int nb = row_len(A, bt);
@@ -300,12 +304,24 @@ __global__ void __launch_bounds__(SEL_THREADS) select_write_kernel(const SelectA
 #pragma unroll
   for (int i = 0; i < ROWS; ++i) {
     const int n = w0 + i * 256 + lane * 4;
+    float x[4] = {0.f, 0.f, 0.f, 0.f};
+    if (VEC4) {
+      // N % 4 == 0 and n % 4 == 0: the whole quad is inside the row whenever n < N
+      if (n < A.N) {
+        const f32x4 q = *reinterpret_cast<const f32x4 *>(a + n);
+        x[0] = q[0]; x[1] = q[1]; x[2] = q[2]; x[3] = q[3];
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (n + e < nb) x[e] = a[n + e];
+    }
     uint32_t cg = 0, ce = 0;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      // out-of-range tokens get key 0 only as a placeholder; they are excluded by the test
+      // tokens past the valid length carry a placeholder key and are excluded by `in`
       const bool in = n + e < nb;
-      keys[i][e] = in ? key_of(a[n + e]) : 0u;
+      keys[i][e] = in ? key_of(x[e]) : 0u;
       cg += (in && keys[i][e] > T) ? 1u : 0u;
       ce += (in && keys[i][e] == T) ? 1u : 0u;
     }
@@ -328,11 +344,19 @@ __global__ void __launch_bounds__(SEL_THREADS) select_write_kernel(const SelectA
     wave_eq[wave] = run_eq;
   }
   __syncthreads();
-  uint32_t base_gt = pre, base_eq = pre_eq;
-  for (int w = 0; w < wave; ++w) {
-    base_gt += wave_gt[w];
-    base_eq += wave_eq[w];
+  uint32_t base_gt = pre, base_eq = pre_eq, chunk_gt = 0, chunk_eq = 0;
+#pragma unroll
+  for (int w = 0; w < SEL_THREADS / 64; ++w) {
+    if (w < wave) {
+      base_gt += wave_gt[w];
+      base_eq += wave_eq[w];
+    }
+    chunk_gt += wave_gt[w];
+    chunk_eq += wave_eq[w];
   }
+  // output range of this chunk: [first, last)
+  const uint32_t first = pre + min(pre_eq, r);
+  const uint32_t last = min((pre + chunk_gt) + min(pre_eq + chunk_eq, r), c);
 #pragma unroll
   for (int i = 0; i < ROWS; ++i) {
     uint32_t g = base_gt + ex_gt[i], q = base_eq + ex_eq[i];
@@ -344,12 +368,20 @@ __global__ void __launch_bounds__(SEL_THREADS) select_write_kernel(const SelectA
       const bool is_eq = in && keys[i][e] == T;
       if (is_gt || (is_eq && q < r)) {
         const uint32_t pos = g + min(q, r);
-        if (pos < c)   // always true for a consistent threshold; keeps a bad state in bounds
-          for (int ti = t0; ti < t1; ++ti)
-          A.indices[((size_t)bt * A.Hq + A.targets.tgt[ti]) * A.k + pos] = n + e;
+        // always inside [first, last) for a consistent threshold; the test keeps a bad
+        // state inside the staging buffer
+        if (pos >= first && pos - first < (uint32_t)SEL_CHUNK) staged[pos - first] = n + e;
       }
       g += is_gt ? 1u : 0u;
       q += is_eq ? 1u : 0u;
+    }
+  }
+  __syncthreads();
+  if (last > first) {
+    const uint32_t cnt = min(last - first, (uint32_t)SEL_CHUNK);
+    for (int ti = t0; ti < t1; ++ti) {
+      int32_t *dst = A.indices + ((size_t)bt * A.Hq + A.targets.tgt[ti]) * A.k + first;
+      for (uint32_t p = threadIdx.x; p < cnt; p += SEL_THREADS) dst[p] = staged[p];
     }
   }
 }
@@ -406,6 +438,9 @@ hipError_t launch_select_count(const SelectArgs &a, hipStream_t s) {
 hipError_t launch_select_write(const SelectArgs &a, hipStream_t s) {
   if ((size_t)a.B * a.Hd == 0) return hipSuccess;
   const dim3 grid(a.nchunks > 0 ? a.nchunks : 1, a.B * a.Hd), block(SEL_THREADS);
-  hipLaunchKernelGGL(select_write_kernel, grid, block, 0, s, a);
+  if (vec_ok(a))
+    hipLaunchKernelGGL(select_write_kernel<true>, grid, block, 0, s, a);
+  else
+    hipLaunchKernelGGL(select_write_kernel<false>, grid, block, 0, s, a);
   return hipGetLastError();
 }

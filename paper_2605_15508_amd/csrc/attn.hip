@@ -79,7 +79,9 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
   const int rows_valid = nheads * A.Tq;
   const int head0 = g * A.G + nth_member(mask, 0);
 
-  // number of keys this unit attends to
+  // Number of keys this unit attends to. The split boundaries come from the static upper
+  // bound (kmax or N), so the first index load below does not wait for this value; a unit
+  // with fewer keys simply leaves its last splits empty (the longest unit sets the makespan).
   int c;
   if (SPARSE) {
     c = A.counts ? A.counts[bt * A.Hq + head0] : A.kmax;
@@ -88,9 +90,17 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
     c = A.seq_lens ? A.seq_lens[bt] : A.N;
     c = min(max(c, 0), A.N);
   }
-  const int tiles_total = (c + STS_TILE_KEYS - 1) / STS_TILE_KEYS;
-  const int tps = (tiles_total + S - 1) / S;
+  const int len_max = SPARSE ? A.kmax : A.N;
+  const int tiles_max = (len_max + STS_TILE_KEYS - 1) / STS_TILE_KEYS;
+  const int tps = (tiles_max + S - 1) / S;
   const int t_begin = split * tps;
+  const int32_t *idx_row = SPARSE ? A.indices + ((size_t)bt * A.Hq + head0) * A.kmax : nullptr;
+  // first tile's index row, issued before anything depends on c (kmax >= 1 whenever a
+  // sparse grid is launched with tiles to do; the clamp keeps the address inside the row)
+  int rows_first = 0;
+  if (SPARSE && len_max > 0)
+    rows_first = idx_row[min((t_begin + wave) * STS_TILE_KEYS + (lane & 31), len_max - 1)];
+  const int tiles_total = (c + STS_TILE_KEYS - 1) / STS_TILE_KEYS;
   const int t_end = min(t_begin + tps, tiles_total);
 
   // query rows owned by this lane: row nq*16 + b
@@ -118,7 +128,6 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
   const unsigned char *vbase = reinterpret_cast<const unsigned char *>(A.v) +
                                ((int64_t)bt * A.stride_b + (int64_t)g * A.stride_h) * 2 + b * CHB;
   const int64_t row_bytes = A.stride_n * 2;
-  const int32_t *idx_row = SPARSE ? A.indices + ((size_t)bt * A.Hq + head0) * A.kmax : nullptr;
   unsigned char *ldsK = lds + wave * KTILE_BYTES;
 
   // row slot of load m for this lane: 16*(m/4) + 4a + m%4 (the keys the MFMA output hands
@@ -263,7 +272,15 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
   if (t_begin + wave < t_end) {   // wave-uniform; a wave without tiles touches no memory
     chunk_t K0[8], V0[8], K1[8], V1[8];
     int t = t_begin + wave;
-    int rows_cur = fetch_rows(t, 0);
+    int rows_cur;
+    if (SPARSE) {
+      // positions at or past c (last tile only) fall back to the last valid entry
+      const int pos = t * STS_TILE_KEYS + (lane & 31);
+      rows_cur = (pos < c) ? rows_first : idx_row[c - 1];
+      rows_cur = min(max(rows_cur, 0), A.N - 1);
+    } else {
+      rows_cur = fetch_rows(t, 0);
+    }
     const int safe_row = __shfl(rows_cur, 0, 64);
     int rows_nxt = fetch_rows(t + STS_WG_WAVES, safe_row);
     issue_loads(rows_cur, K0, V0);

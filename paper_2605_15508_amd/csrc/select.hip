@@ -26,6 +26,12 @@ __device__ __forceinline__ uint32_t key_of(float x) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // ascending with the float order
 }
 
+// exp(s - lse) through the hardware base-2 exponential (about 1 ulp; the product with log2(e)
+// adds a relative error below 1e-6 for |s - lse| < 40, far inside the stage-wise tolerance)
+__device__ __forceinline__ float prob_of(float s, float lse) {
+  return __builtin_amdgcn_exp2f((s - lse) * 1.44269504088896340736f);
+}
+
 __device__ __forceinline__ int row_len(const SelectArgs &A, int bt) {
   int nb = A.seq_lens ? A.seq_lens[bt] : A.N;
   return min(max(nb, 0), A.N);
@@ -110,18 +116,33 @@ __global__ void __launch_bounds__(SEL_THREADS) select_agg_kernel(const SelectArg
     return use_max ? fmaxf(acc, p) : acc + p;
   };
 
+  // The Tq rows are loaded in independent batches of AGG_BATCH so their latencies overlap;
+  // the reduction itself stays strictly in row order.
+  constexpr int AGG_BATCH = 8;
   if (VEC4) {
     for (int n = n0 + threadIdx.x * 4; n < n1; n += SEL_THREADS * 4) {
       f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-      for (int i = 0; i < A.Tq; ++i) {
-        f32x4 p = *reinterpret_cast<const f32x4 *>(P + (size_t)i * A.N + n);
-        if (logits) {
-          const float l = L[i];
+      for (int i0 = 0; i0 < A.Tq; i0 += AGG_BATCH) {
+        f32x4 p[AGG_BATCH];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) p[e] = expf(p[e] - l);
+        for (int u = 0; u < AGG_BATCH; ++u) {
+          p[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+          if (i0 + u < A.Tq)   // uniform: no load is issued for rows that do not exist
+            p[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(P + (size_t)(i0 + u) * A.N + n));
         }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[e] = reduce1(acc[e], p[e], i);
+        for (int u = 0; u < AGG_BATCH; ++u) {
+          const int i = i0 + u;
+          if (i < A.Tq) {
+            if (logits) {
+              const float l = L[i];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) p[u][e] = prob_of(p[u][e], l);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] = reduce1(acc[e], p[u][e], i);
+          }
+        }
       }
       *reinterpret_cast<f32x4 *>(out + n) = acc;
 #pragma unroll
@@ -131,10 +152,18 @@ __global__ void __launch_bounds__(SEL_THREADS) select_agg_kernel(const SelectArg
   } else {
     for (int n = n0 + threadIdx.x; n < n1; n += SEL_THREADS) {
       float acc = 0.f;
-      for (int i = 0; i < A.Tq; ++i) {
-        float p = P[(size_t)i * A.N + n];
-        if (logits) p = expf(p - L[i]);
-        acc = reduce1(acc, p, i);
+      for (int i0 = 0; i0 < A.Tq; i0 += AGG_BATCH) {
+        float p[AGG_BATCH];
+#pragma unroll
+        for (int u = 0; u < AGG_BATCH; ++u) p[u] = (i0 + u < A.Tq) ? P[(size_t)(i0 + u) * A.N + n] : 0.f;
+#pragma unroll
+        for (int u = 0; u < AGG_BATCH; ++u) {
+          const int i = i0 + u;
+          if (i < A.Tq) {
+            const float x = logits ? prob_of(p[u], L[i]) : p[u];
+            acc = reduce1(acc, x, i);
+          }
+        }
       }
       out[n] = acc;
       if (n < nb) atomicAdd(&h[key_of(acc) >> (32 - SEL_BITS0)], 1u);
@@ -248,15 +277,16 @@ __global__ void __launch_bounds__(SEL_THREADS) select_count_kernel(const SelectA
 }
 
 // ------------------------------------------------------ ordered compaction + head remap
-// Each wave owns a contiguous quarter of the chunk and walks it in 8 rows of 256 tokens
-// (lane l holds tokens 4l..4l+3 of the row), so prefix counts follow token order. The kept
-// tokens of a chunk occupy one contiguous range of the output list: they are staged in LDS at
-// their local rank and then copied out with coalesced stores, once per target head.
+// The chunk's scores are loaded coalesced into LDS, then every thread takes 32 consecutive
+// tokens, so one block scan of (greater, equal) counts gives every token its rank in token
+// order. The kept tokens of a chunk occupy one contiguous range of the output list: they are
+// staged in LDS at their local rank and copied out with coalesced stores, once per target.
 template <bool VEC4>
 __global__ void __launch_bounds__(SEL_THREADS) select_write_kernel(const SelectArgs A) {
+  constexpr int PER = SEL_CHUNK / SEL_THREADS;   // 32 tokens per thread
+  constexpr int PITCH = PER + 1;                 // odd pitch: conflict-free per-thread rows
   __shared__ uint32_t tmp[16];
-  __shared__ uint32_t wave_gt[SEL_THREADS / 64], wave_eq[SEL_THREADS / 64];
-  __shared__ int32_t staged[SEL_CHUNK];
+  __shared__ uint32_t buf[SEL_THREADS * PITCH];  // keys first, then the staged token ids
   const int row = blockIdx.y, chunk = blockIdx.x;
   const int bt = row / A.Hd, j = row % A.Hd;
   const int nb = row_len(A, bt);
@@ -276,6 +306,20 @@ __global__ void __launch_bounds__(SEL_THREADS) select_write_kernel(const SelectA
   if (n0 >= nb) return;
   const uint32_t *st = A.state + (size_t)row * 8;
   const uint32_t T = st[4], r = st[5];
+  const float *a = A.agg + (size_t)row * A.N;
+
+  // coalesced load of the chunk; token n0 + i lands at buf[(i / PER) * PITCH + i % PER]
+  if (VEC4) {
+    for (int i = threadIdx.x * 4; i < SEL_CHUNK; i += SEL_THREADS * 4) {
+      f32x4 x = {0.f, 0.f, 0.f, 0.f};
+      if (n0 + i < A.N) x = *reinterpret_cast<const f32x4 *>(a + n0 + i);   // N % 4 == 0
+#pragma unroll
+      for (int e = 0; e < 4; ++e) buf[((i + e) / PER) * PITCH + (i + e) % PER] = key_of(x[e]);
+    }
+  } else {
+    for (int i = threadIdx.x; i < SEL_CHUNK; i += SEL_THREADS)
+      buf[(i / PER) * PITCH + i % PER] = (n0 + i < nb) ? key_of(a[n0 + i]) : 0u;
+  }
 
   // keys greater / equal in the chunks before this one
   uint32_t pre = 0, pre_eq = 0;
@@ -287,94 +331,43 @@ __global__ void __launch_bounds__(SEL_THREADS) select_write_kernel(const SelectA
       e += cc[ch * 2 + 1];
     }
     uint32_t tg, te;
-    (void)block_excl_scan(g, tmp, tg);
+    (void)block_excl_scan(g, tmp, tg);    // contains the barrier that publishes buf
     (void)block_excl_scan(e, tmp, te);
     pre = tg;
     pre_eq = te;
   }
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const float *a = A.agg + (size_t)row * A.N;
-  constexpr int WAVE_TOK = SEL_CHUNK / (SEL_THREADS / 64);   // 2048
-  constexpr int ROWS = WAVE_TOK / 256;                        // 8
-  const int w0 = n0 + wave * WAVE_TOK;
-  uint32_t keys[ROWS][4];
-  uint32_t ex_gt[ROWS], ex_eq[ROWS];
-  uint32_t run_gt = 0, run_eq = 0;
+  const int base_n = n0 + threadIdx.x * PER;
+  uint32_t keys[PER];
+  uint32_t cg = 0, ce = 0;
 #pragma unroll
-  for (int i = 0; i < ROWS; ++i) {
-    const int n = w0 + i * 256 + lane * 4;
-    float x[4] = {0.f, 0.f, 0.f, 0.f};
-    if (VEC4) {
-      // N % 4 == 0 and n % 4 == 0: the whole quad is inside the row whenever n < N
-      if (n < A.N) {
-        const f32x4 q = *reinterpret_cast<const f32x4 *>(a + n);
-        x[0] = q[0]; x[1] = q[1]; x[2] = q[2]; x[3] = q[3];
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if (n + e < nb) x[e] = a[n + e];
-    }
-    uint32_t cg = 0, ce = 0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      // tokens past the valid length carry a placeholder key and are excluded by `in`
-      const bool in = n + e < nb;
-      keys[i][e] = in ? key_of(x[e]) : 0u;
-      cg += (in && keys[i][e] > T) ? 1u : 0u;
-      ce += (in && keys[i][e] == T) ? 1u : 0u;
-    }
-    uint32_t v = cg | (ce << 16);
-    uint32_t incl = v;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t o = __shfl_up(incl, off, 64);
-      if (lane >= off) incl += o;
-    }
-    const uint32_t tot = __shfl(incl, 63, 64);
-    const uint32_t excl = incl - v;
-    ex_gt[i] = run_gt + (excl & 0xffffu);
-    ex_eq[i] = run_eq + (excl >> 16);
-    run_gt += tot & 0xffffu;
-    run_eq += tot >> 16;
+  for (int i = 0; i < PER; ++i) {
+    keys[i] = buf[threadIdx.x * PITCH + i];
+    const bool in = base_n + i < nb;        // tokens past the valid length never count
+    cg += (in && keys[i] > T) ? 1u : 0u;
+    ce += (in && keys[i] == T) ? 1u : 0u;
   }
-  if (lane == 0) {
-    wave_gt[wave] = run_gt;
-    wave_eq[wave] = run_eq;
-  }
-  __syncthreads();
-  uint32_t base_gt = pre, base_eq = pre_eq, chunk_gt = 0, chunk_eq = 0;
-#pragma unroll
-  for (int w = 0; w < SEL_THREADS / 64; ++w) {
-    if (w < wave) {
-      base_gt += wave_gt[w];
-      base_eq += wave_eq[w];
-    }
-    chunk_gt += wave_gt[w];
-    chunk_eq += wave_eq[w];
-  }
+  uint32_t total;
+  const uint32_t excl = block_excl_scan(cg | (ce << 16), tmp, total);   // barriers: buf is free
+  uint32_t g = pre + (excl & 0xffffu), q = pre_eq + (excl >> 16);
+  const uint32_t chunk_gt = total & 0xffffu, chunk_eq = total >> 16;
   // output range of this chunk: [first, last)
   const uint32_t first = pre + min(pre_eq, r);
   const uint32_t last = min((pre + chunk_gt) + min(pre_eq + chunk_eq, r), c);
+  int32_t *staged = reinterpret_cast<int32_t *>(buf);
 #pragma unroll
-  for (int i = 0; i < ROWS; ++i) {
-    uint32_t g = base_gt + ex_gt[i], q = base_eq + ex_eq[i];
-    const int n = w0 + i * 256 + lane * 4;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const bool in = n + e < nb;
-      const bool is_gt = in && keys[i][e] > T;
-      const bool is_eq = in && keys[i][e] == T;
-      if (is_gt || (is_eq && q < r)) {
-        const uint32_t pos = g + min(q, r);
-        // always inside [first, last) for a consistent threshold; the test keeps a bad
-        // state inside the staging buffer
-        if (pos >= first && pos - first < (uint32_t)SEL_CHUNK) staged[pos - first] = n + e;
-      }
-      g += is_gt ? 1u : 0u;
-      q += is_eq ? 1u : 0u;
+  for (int i = 0; i < PER; ++i) {
+    const bool in = base_n + i < nb;
+    const bool is_gt = in && keys[i] > T;
+    const bool is_eq = in && keys[i] == T;
+    if (is_gt || (is_eq && q < r)) {
+      const uint32_t pos = g + min(q, r);
+      // always inside [first, last) for a consistent threshold; the test keeps a bad state
+      // inside the staging buffer
+      if (pos >= first && pos - first < (uint32_t)SEL_CHUNK) staged[pos - first] = base_n + i;
     }
+    g += is_gt ? 1u : 0u;
+    q += is_eq ? 1u : 0u;
   }
   __syncthreads();
   if (last > first) {

@@ -26,6 +26,7 @@ if ROOT not in sys.path:
 
 METRIC = "sparse verify-attn µs/layer + HBM GB/s at 90% sparsity, 128K ctx, vs dense"
 HBM_PEAK_GBS = 8000.0
+STS_PROF_BUDGET = 4096      # launches the library's event pool keeps per reset
 
 
 def parse_args():
@@ -33,7 +34,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c5"])
+    ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--budget", type=float, default=None, help="fraction of N kept per head")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true", help="leave the dense baseline out of the step")
@@ -129,6 +130,13 @@ def main():
     kb = w.k_budget
     B, N, Hq, Hkv, d, Tq, Hd = cfg.B, cfg.N, cfg.Hq, cfg.Hkv, cfg.d, cfg.Tq, cfg.Hd
     draft = make_draft_layer(w) if cfg.draft_d else None
+    # distinct resident layers (1M-context configuration: 32 x 4 GiB of KV); the draft scores
+    # are shared by the layers, the KV caches are not
+    layers = [(w.k, w.v)]
+    for l in range(1, cfg.layers):
+        wl = make_workload(cfg, seed=args.seed + l, device=dev, budget=args.budget, with_scores=False)
+        layers.append((wl.k, wl.v))
+        del wl
     torch.cuda.synchronize()
 
     # persistent outputs so the timed region allocates nothing
@@ -142,7 +150,8 @@ def main():
         d_lse = torch.empty(B, Hd, Tq, dtype=torch.float32, device=dev)
         d_logits = torch.empty(B, Hd, Tq, N, dtype=torch.float32, device=dev)
 
-    def step(ev=None):
+    def step(ev=None, layer=0):
+        lk, lv = layers[layer]
         if ev: ev[0].record()
         if draft is not None:
             sts.sts_dense_attn(draft["q"], draft["k"], draft["v"], draft["scale"], out=d_out,
@@ -153,24 +162,27 @@ def main():
             if ev: ev[1].record()
             sts.sts_select(w.scores, w.head_map, kb, out=(idx, cnt))
         if ev: ev[2].record()
-        sts.sts_sparse_attn(w.q, w.k, w.v, idx, w.scale, counts=cnt, head_map=w.head_map, out=out_s,
+        sts.sts_sparse_attn(w.q, lk, lv, idx, w.scale, counts=cnt, head_map=w.head_map, out=out_s,
                             want_lse=False)
         if ev: ev[3].record()
         if not args.no_dense:
-            sts.sts_dense_attn(w.q, w.k, w.v, w.scale, out=out_d, want_lse=False)
+            sts.sts_dense_attn(w.q, lk, lv, w.scale, out=out_d, want_lse=False)
         if ev: ev[4].record()
 
+    L = len(layers)
     for _ in range(args.warmup):
-        step()
+        for l in range(L):
+            step(layer=l)
     torch.cuda.synchronize()
 
     # timed region: exactly K steps, sync on both sides; per-call times from events recorded on
     # the stream the library launches on (torch's current stream)
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps * L)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(events[i])
+        for l in range(L):
+            step(events[i * L + l], layer=l)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
@@ -178,8 +190,9 @@ def main():
     # few microseconds per launch, so they stay out of the region that gives `value`)
     sts.prof_enable(True)
     sts.prof_reset()
-    for i in range(args.steps):
-        step()
+    for i in range(min(args.steps, max(1, STS_PROF_BUDGET // (8 * L)))):
+        for l in range(L):
+            step(layer=l)
     torch.cuda.synchronize()
     prof = sts.prof_read()
     sts.prof_enable(False)
@@ -224,8 +237,8 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": workload, "context": N, "batch": B, "budget_tokens": kb,
-                   "head_map": "t*Hd//Hq", "step": "select + sparse_attn" + ("" if args.no_dense else " + dense_attn")
-                   + (" (+ draft dense attn with logits dump)" if draft is not None else "")},
+                   "layers": L, "head_map": "t*Hd//Hq", "step": ("%d layers x (" % L if L > 1 else "(") + "select + sparse_attn" + ("" if args.no_dense else " + dense_attn")
+                   + (" + draft dense attn with logits dump" if draft is not None else "") + ")"},
         "sparse_attn_us": {"mean": round(sparse_us[0], 2), "median": round(sparse_us[1], 2), "min": round(sparse_us[2], 2)},
         "dense_attn_us": {"mean": round(dense_us[0], 2), "median": round(dense_us[1], 2), "min": round(dense_us[2], 2)},
         "select_us": {"mean": round(select_us[0], 2), "median": round(select_us[1], 2), "min": round(select_us[2], 2)},

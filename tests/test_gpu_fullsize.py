@@ -68,3 +68,80 @@ def test_c3_sparse_and_dense_sampled_heads(c3):
                    what=f"c3 dense b{b} h{t}")
     # the sparse result approximates the dense one because the planted heavy tokens are kept
     assert torch.isfinite(out.float()).all() and torch.isfinite(dout.float()).all()
+
+
+def _sample_heads(w, idx, cnt, out, lse, samples, tag, dense=None):
+    G = w.cfg.Hq // w.cfg.Hkv
+    for b, t in samples:
+        g = t // G
+        qg = w.q[b:b + 1, :, g * G:(g + 1) * G].contiguous().cpu()
+        kb, vb = w.k[b:b + 1, g:g + 1].cpu(), w.v[b:b + 1, g:g + 1].cpu()
+        hs = range(t - g * G, t - g * G + 1)
+        sl = (slice(0, 1), slice(t - g * G, t - g * G + 1))
+        if idx is not None:
+            ig = idx[b:b + 1, g * G:(g + 1) * G].cpu().contiguous()
+            cg = cnt[b:b + 1, g * G:(g + 1) * G].cpu().contiguous()
+            ref = oracle_attn(qg, kb, vb, w.scale, ig, cg, heads=hs)
+            check_attn(out[b:b + 1, :, g * G:(g + 1) * G], lse[b:b + 1, g * G:(g + 1) * G], ref, sel=sl,
+                       what=f"{tag} sparse b{b} h{t}")
+        if dense is not None:
+            dref = oracle_attn(qg, kb, vb, w.scale, heads=hs)
+            check_attn(dense[0][b:b + 1, :, g * G:(g + 1) * G], dense[1][b:b + 1, g * G:(g + 1) * G], dref,
+                       sel=sl, what=f"{tag} dense b{b} h{t}")
+
+
+def test_c4_one_layer_of_the_1m_context_configuration():
+    """One full layer of the 1M-token configuration (4 GiB of KV): byte offsets beyond 2^32,
+    selection bit-exact on whole rows at both budgets, attention on sampled heads."""
+    w = make_workload(CONFIGS["c4"], seed=4, device=DEV)
+    torch.cuda.synchronize()
+    for frac, want_k in ((0.02, 20972), (0.10, 104858)):
+        from workload import budget_tokens
+        kb = budget_tokens(w.cfg, frac)
+        assert kb == want_k
+        idx, cnt, agg = sts.sts_select(w.scores, w.head_map, kb, want_agg=True)
+        out, lse = sts.sts_sparse_attn(w.q, w.k, w.v, idx, w.scale, counts=cnt, head_map=w.head_map)
+        torch.cuda.synchronize()
+        o_idx, o_cnt, o_agg = oracle.select_indices(w.scores.cpu().numpy(), w.head_map.numpy(), kb)
+        np.testing.assert_array_equal(agg.cpu().numpy().view(np.uint32), o_agg.view(np.uint32))
+        np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
+        np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
+        _sample_heads(w, idx, cnt, out, lse, [(0, 5), (0, 30)], f"c4 {frac:.0%}")
+    dout, dlse, _ = sts.sts_dense_attn(w.q, w.k, w.v, w.scale)
+    torch.cuda.synchronize()
+    _sample_heads(w, None, None, None, None, [(0, 31)], "c4", dense=(dout, dlse))
+
+
+def test_c5_two_batch_elements_of_the_70b_shaped_chain():
+    """The 70B-shaped configuration at full context (128K), two batch elements: draft dense
+    attention with logits dump -> selection -> sparse target attention."""
+    from dataclasses import replace
+    from workload import make_draft_layer
+
+    cfg = replace(CONFIGS["c5"], B=2)
+    w = make_workload(cfg, seed=5, device=DEV, with_scores=False)
+    dl = make_draft_layer(w)
+    kb = w.k_budget
+    d_out, d_lse, d_logits = sts.sts_dense_attn(dl["q"], dl["k"], dl["v"], dl["scale"], want_logits=True)
+    idx, cnt, agg = sts.sts_select(d_logits, w.head_map, kb, lse=d_lse, kind=sts.STS_SCORES_LOGITS_LSE,
+                                   want_agg=True)
+    out, lse = sts.sts_sparse_attn(w.q, w.k, w.v, idx, w.scale, counts=cnt, head_map=w.head_map)
+    torch.cuda.synchronize()
+    # draft logits of one sampled draft head against the oracle (the QK^T dump)
+    j, b = 9, 1
+    gd = j // (cfg.Hd // cfg.draft_Hkv)
+    Gd = cfg.Hd // cfg.draft_Hkv
+    ref_d = oracle_attn(dl["q"][b:b + 1, :, gd * Gd:(gd + 1) * Gd].contiguous().cpu(), dl["k"][b:b + 1, gd:gd + 1].cpu(),
+                        dl["v"][b:b + 1, gd:gd + 1].cpu(), dl["scale"], want_logits=True,
+                        heads=range(j - gd * Gd, j - gd * Gd + 1))
+    got = d_logits[b, j].cpu().numpy()
+    assert np.abs(got - ref_d["logits"][0, j - gd * Gd]).max() < 2e-3
+    # selection: bit-exact on the GPU's own aggregate
+    a = agg.cpu().numpy()
+    sel, c = oracle.select(a, kb)
+    o_idx, o_cnt = oracle.remap(sel, c, w.head_map.numpy())
+    np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
+    np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
+    o_agg = oracle.aggregate(d_logits[:1, :4].cpu().numpy(), d_lse[:1, :4].cpu().numpy(), kind=oracle.LOGITS_LSE)
+    np.testing.assert_allclose(a[:1, :4], o_agg, rtol=1e-5, atol=1e-12)
+    _sample_heads(w, idx, cnt, out, lse, [(0, 3), (1, 40), (1, 63)], "c5")

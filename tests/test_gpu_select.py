@@ -133,3 +133,44 @@ def test_select_then_sparse_attention_on_the_4k_configuration():
     # planted sink / recent positions are kept far more often than the 10% base rate
     planted = np.concatenate([np.arange(4), np.arange(4096 - 64, 4096)])
     assert min(np.isin(planted, o_idx[0, t]).mean() for t in range(32)) > 0.4
+
+
+def test_draft_attention_to_selection_to_sparse_attention_chain():
+    """70B-shaped chain at a small context: the draft layer's dense attention dumps scaled
+    logits and LSE, selection consumes them (LOGITS_LSE), the target attends sparsely.
+    Checked stage by stage against the oracle."""
+    from dataclasses import replace
+
+    from gpu_util import check_attn, oracle_attn
+    from workload import make_draft_layer
+
+    cfg = replace(CONFIGS["c5"], B=2, N=3000)
+    w = make_workload(cfg, seed=11, with_scores=False)
+    dl = make_draft_layer(w)
+    q, k, v = w.q.to(DEV), w.k.to(DEV), w.v.to(DEV)
+    qd, kd, vd = dl["q"].to(DEV), dl["k"].to(DEV), dl["v"].to(DEV)
+    kb = w.k_budget
+    # stage a0: draft dense attention with logits + LSE
+    d_out, d_lse, d_logits = sts.sts_dense_attn(qd, kd, vd, dl["scale"], want_logits=True, out_dtype=torch.float32)
+    ref_d = oracle_attn(qd, kd, vd, dl["scale"], want_logits=True)
+    check_attn(d_out, d_lse, ref_d, what="draft dense")
+    assert np.abs(d_logits.cpu().numpy() - ref_d["logits"]).max() < 2e-3
+    # stage a1-a3 on the GPU's own logits (identical score tensors on both sides)
+    idx, cnt, agg = sts.sts_select(d_logits, w.head_map, kb, lse=d_lse, kind=sts.STS_SCORES_LOGITS_LSE,
+                                   want_agg=True)
+    torch.cuda.synchronize()
+    o_agg = oracle.aggregate(d_logits.cpu().numpy(), d_lse.cpu().numpy(), kind=oracle.LOGITS_LSE)
+    np.testing.assert_allclose(agg.cpu().numpy(), o_agg, rtol=1e-5, atol=1e-12)
+    sel, c = oracle.select(agg.cpu().numpy(), kb)
+    o_idx, o_cnt = oracle.remap(sel, c, w.head_map.numpy())
+    np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
+    np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
+    # stage a4-a5
+    out, lse = sts.sts_sparse_attn(q, k, v, idx, w.scale, counts=cnt, head_map=w.head_map,
+                                   out_dtype=torch.float32)
+    ref = oracle_attn(q, k, v, w.scale, idx, cnt)
+    check_attn(out, lse, ref, what="c5 chain sparse")
+    # the draft's selection captures more of the target's attention mass than a random set
+    dense = oracle_attn(q, k, v, w.scale)
+    mass = np.exp(ref["lse"].astype(np.float64) - dense["lse"].astype(np.float64))
+    assert mass.mean() > 1.1 * kb / cfg.N

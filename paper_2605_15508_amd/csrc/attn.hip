@@ -134,25 +134,22 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
   // to lane group a)
   auto slot_of = [&](int m) { return 16 * (m >> 2) + 4 * a + (m & 3); };
 
-  // token row feeding slot (lane & 31) of tile t; tiles past the end read row `safe_row`
-  auto fetch_rows = [&](int t, int safe_row) -> int {
+  // Raw token row feeding slot (lane & 31) of tile t. Branch-free on purpose: the load is
+  // unconditional (tiles past the end re-read the wave's first entry) and nothing touches the
+  // loaded value until issue_loads clamps it, so the wait for it lands right before its use
+  // instead of draining the K/V loads that are in flight.
+  const int safe_pos = (t_begin + wave) * STS_TILE_KEYS;
+  auto fetch_rows = [&](int t) -> int {
     const int pos = t * STS_TILE_KEYS + (lane & 31);
-    int row;
-    if (t >= t_end) {
-      row = safe_row;
-    } else if (SPARSE) {
-      row = idx_row[min(pos, c - 1)];
-      row = min(max(row, 0), A.N - 1);
-    } else {
-      row = min(pos, c - 1);
-    }
-    return row;
+    const int p = (t < t_end) ? min(pos, c - 1) : safe_pos;
+    return SPARSE ? idx_row[p] : p;
   };
 
   auto issue_loads = [&](int rows, chunk_t (&Kr)[8], chunk_t (&Vr)[8]) {
 #pragma unroll
     for (int m = 0; m < 8; ++m) {
-      const int row = __shfl(rows, slot_of(m), 64);
+      int row = __shfl(rows, slot_of(m), 64);
+      row = min(max(row, 0), A.N - 1);     // memory safety for arbitrary index values
       const int64_t off = (int64_t)row * row_bytes;
       // every K/V row is consumed once per launch: stream it past the caches
       Kr[m] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t *>(kbase + off));
@@ -272,28 +269,27 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
   if (t_begin + wave < t_end) {   // wave-uniform; a wave without tiles touches no memory
     chunk_t K0[8], V0[8], K1[8], V1[8];
     int t = t_begin + wave;
-    int rows_cur;
-    if (SPARSE) {
-      // positions at or past c (last tile only) fall back to the last valid entry
-      const int pos = t * STS_TILE_KEYS + (lane & 31);
-      rows_cur = (pos < c) ? rows_first : idx_row[c - 1];
-      rows_cur = min(max(rows_cur, 0), A.N - 1);
-    } else {
-      rows_cur = fetch_rows(t, 0);
-    }
-    const int safe_row = __shfl(rows_cur, 0, 64);
-    int rows_nxt = fetch_rows(t + STS_WG_WAVES, safe_row);
-    issue_loads(rows_cur, K0, V0);
-    while (t < t_end) {
-      int rows_fut = fetch_rows(t + 2 * STS_WG_WAVES, safe_row);
-      issue_loads(rows_nxt, K1, V1);
+    // entries at or past c (last tile only) are padding: any in-range row will do, they are
+    // masked out of the softmax
+    int rows_a = SPARSE ? rows_first : fetch_rows(t);
+    int rows_b = fetch_rows(t + STS_WG_WAVES);
+    issue_loads(rows_a, K0, V0);
+    if (SPARSE) __builtin_amdgcn_sched_barrier(0);
+    for (;;) {
+      rows_a = fetch_rows(t + 2 * STS_WG_WAVES);
+      if (SPARSE) __builtin_amdgcn_sched_barrier(0);   // index fetch stays ahead of the K/V loads below
+      issue_loads(rows_b, K1, V1);
+      if (SPARSE) __builtin_amdgcn_sched_barrier(0);   // ... and the loads are in flight before the tile is consumed
       consume(t, K0, V0);
       t += STS_WG_WAVES;
       if (t >= t_end) break;
-      rows_nxt = fetch_rows(t + 2 * STS_WG_WAVES, safe_row);
-      issue_loads(rows_fut, K0, V0);
+      rows_b = fetch_rows(t + 2 * STS_WG_WAVES);
+      if (SPARSE) __builtin_amdgcn_sched_barrier(0);
+      issue_loads(rows_a, K0, V0);
+      if (SPARSE) __builtin_amdgcn_sched_barrier(0);
       consume(t, K1, V1);
       t += STS_WG_WAVES;
+      if (t >= t_end) break;
     }
   }
 

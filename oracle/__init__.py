@@ -105,6 +105,52 @@ def select(A: np.ndarray, k: int, seq_lens: Optional[np.ndarray] = None):
     return sel, cnt
 
 
+def block_scores(A: np.ndarray, page: int, seq_lens: Optional[np.ndarray] = None) -> np.ndarray:
+    """A [B,Hd,N] -> per-block sums [B,Hd,ceil(N/page)]. See oracle_block_scores."""
+    A = _c(A, np.float32)
+    B, Hd, N = A.shape
+    if seq_lens is not None:
+        seq_lens = _c(seq_lens, np.int32)
+    NB = (N + page - 1) // page
+    blk = np.empty((B, Hd, NB), np.float32)
+    rc = _load().oracle_block_scores(_p(A, ctypes.c_float), B, Hd, N, _p(seq_lens, ctypes.c_int32),
+                                     int(page), _p(blk, ctypes.c_float))
+    _check(rc, "oracle_block_scores")
+    return blk
+
+
+def expand_blocks(indices: np.ndarray, counts: Optional[np.ndarray], page: int, N: int):
+    """Block ids [B,Hq,kb] (+counts in blocks) -> token ids [B,Hq,kb*page] and token counts:
+    block m stands for tokens m*page .. min((m+1)*page, N)-1, in order. Rows are left-packed."""
+    indices = _c(indices, np.int32)
+    B, Hq, kb = indices.shape
+    tok = np.full((B, Hq, kb * page), -1, np.int32)
+    cnt = np.zeros((B, Hq), np.int32)
+    for b in range(B):
+        for t in range(Hq):
+            c = kb if counts is None else int(counts[b, t])
+            row = []
+            for m in indices[b, t, :c]:
+                row.extend(range(int(m) * page, min((int(m) + 1) * page, N)))
+            tok[b, t, :len(row)] = row
+            cnt[b, t] = len(row)
+    return tok, cnt
+
+
+def select_indices(scores, head_map, k, lse=None, kind=PROBS, reduce=SUM, seq_lens=None, page=1):
+    """The whole selection half: aggregate -> [block scores] -> select -> remap. With page > 1
+    the result holds block ids (k counts blocks). Returns (indices, counts, A)."""
+    A = aggregate(scores, lse, kind, reduce)
+    if page > 1:
+        src = block_scores(A, page, seq_lens)
+        lens = None if seq_lens is None else (np.asarray(seq_lens, np.int64) + page - 1) // page
+        sel, cnt = select(src, k, None if lens is None else lens.astype(np.int32))
+    else:
+        sel, cnt = select(A, k, seq_lens)
+    indices, counts = remap(sel, cnt, head_map)
+    return indices, counts, A
+
+
 def remap(sel: np.ndarray, cnt: np.ndarray, head_map: np.ndarray):
     """sel [B,Hd,k], cnt [B,Hd], head_map [Hq] -> (indices [B,Hq,k], counts [B,Hq]). See oracle_remap."""
     sel = _c(sel, np.int32)
@@ -119,14 +165,6 @@ def remap(sel: np.ndarray, cnt: np.ndarray, head_map: np.ndarray):
                               _p(counts, ctypes.c_int32))
     _check(rc, "oracle_remap")
     return indices, counts
-
-
-def select_indices(scores, head_map, k, lse=None, kind=PROBS, reduce=SUM, seq_lens=None):
-    """The whole selection half: aggregate -> select -> remap. Returns (indices, counts, A)."""
-    A = aggregate(scores, lse, kind, reduce)
-    sel, cnt = select(A, k, seq_lens)
-    indices, counts = remap(sel, cnt, head_map)
-    return indices, counts, A
 
 
 def attn(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float,

@@ -124,6 +124,35 @@ int oracle_select(const float *A, int B, int Hd, int N, const int32_t *seq_lens,
   return status;
 }
 
+int oracle_block_scores(const float *A, int B, int Hd, int N, const int32_t *seq_lens, int page,
+                        float *blk) {
+  if (!A || !blk || B < 0 || Hd < 0 || N < 0 || page < 1) return -1;
+  const int NB = (N + page - 1) / page;
+  for (int b = 0; b < B; ++b) {
+    const int nb = seq_lens ? seq_lens[b] : N;
+    if (nb < 0 || nb > N) return -1;
+    for (int j = 0; j < Hd; ++j) {
+      const float *a = A + ((size_t)b * Hd + j) * N;
+      float *o = blk + ((size_t)b * Hd + j) * NB;
+      for (int m = 0; m < NB; ++m) {
+        float acc = 0.0f;
+        int first = 1;
+        for (int n = m * page; n < (m + 1) * page && n < nb; ++n) {
+          if (first) {
+            acc = a[n];
+            first = 0;
+          } else {
+            volatile float s = acc + a[n];   /* one fp32 rounding per add */
+            acc = s;
+          }
+        }
+        o[m] = acc;
+      }
+    }
+  }
+  return 0;
+}
+
 int oracle_remap(const int32_t *sel, const int32_t *cnt, int B, int Hd, int Hq, int k,
                  const int32_t *head_map, int32_t *indices, int32_t *counts) {
   if (!sel || !cnt || !head_map || !indices || B < 0 || Hd < 1 || Hq < 0 || k < 1) return -1;

@@ -53,6 +53,14 @@ int oracle_aggregate(const float *scores, const float *lse, int B, int Hd, int T
 int oracle_select(const float *A, int B, int Hd, int N, const int32_t *seq_lens, int k,
                   int32_t *sel, int32_t *cnt);
 
+/* Section 4.2 (top-k over blocks instead of individual tokens) / Section 6.3 (page size p_s):
+ * score of block m = A[m*p] + A[m*p+1] + ... over the tokens of the block that lie below the
+ * valid length, added left to right in fp32 (the paper does not name the operator; summing
+ * keeps "attention mass captured" as the criterion). NB = ceil(N / page) blocks per row.
+ *   A [B,Hd,N] ; seq_lens [B] or NULL ; blk [B,Hd,NB] out (blocks past the length get 0) */
+int oracle_block_scores(const float *A, int B, int Hd, int N, const int32_t *seq_lens, int page,
+                        float *blk);
+
 /* Section 4.2 (remap masks through the offline mapping dictionary):
  *   indices[b,t,:] = sel[b, head_map[t], :], counts[b,t] = cnt[b, head_map[t]]. */
 int oracle_remap(const int32_t *sel, const int32_t *cnt, int B, int Hd, int Hq, int k,

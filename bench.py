@@ -39,6 +39,10 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true", help="leave the dense baseline out of the step")
     ap.add_argument("--seed", type=int, default=20251127)
+    ap.add_argument("--page-size", type=int, default=1,
+                    help="selection / attention granularity in tokens (1 = token-wise, 8 = the paper's p_s=8)")
+    ap.add_argument("--paged", action="store_true",
+                    help="keep K/V in a pool of pages behind a random page table (needs --page-size)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (scales rocprofv3 --pmc byte counters)")
     return ap.parse_args()
@@ -58,7 +62,7 @@ def read_traffic(kernel: str, workload: str):
     return None
 
 
-def cpu_baseline(w, idx, cnt, budget_s=25.0):
+def cpu_baseline(w, idx, cnt, page=1, budget_s=25.0):
     """Time the CPU oracle (as it stands, untuned) on this machine's host cores on a bounded sample
     of the same workload. Returns the cpu_baseline object."""
     import numpy as np
@@ -71,8 +75,12 @@ def cpu_baseline(w, idx, cnt, budget_s=25.0):
     # sample: as many whole batch elements as fit the time budget, estimated from one head
     kb = oracle.bf16_bits(w.k[:1].cpu())
     vb = oracle.bf16_bits(w.v[:1].cpu())
-    idx0 = idx[:1].cpu().numpy()
-    cnt0 = cnt[:1].cpu().numpy()
+    def tokens(i, c):
+        # the oracle attends over token ids: expand block ids when the selection is block-wise
+        i, c = i.cpu().numpy(), c.cpu().numpy()
+        return oracle.expand_blocks(i, c, page, cfg.N) if page > 1 else (i, c)
+
+    idx0, cnt0 = tokens(idx[:1], cnt[:1])
     t0 = time.perf_counter()
     oracle.attn(qb[:1], kb, vb, w.scale, idx0, cnt0, heads=range(0, min(threads, cfg.Hq)))
     probe = time.perf_counter() - t0
@@ -80,8 +88,7 @@ def cpu_baseline(w, idx, cnt, budget_s=25.0):
     nb = int(max(1, min(cfg.B, budget_s // max(per_batch, 1e-3))))
     kb = oracle.bf16_bits(w.k[:nb].cpu())
     vb = oracle.bf16_bits(w.v[:nb].cpu())
-    idxn = idx[:nb].cpu().numpy()
-    cntn = cnt[:nb].cpu().numpy()
+    idxn, cntn = tokens(idx[:nb], cnt[:nb])
     best = float("inf")
     for _ in range(2):
         t0 = time.perf_counter()
@@ -91,7 +98,7 @@ def cpu_baseline(w, idx, cnt, budget_s=25.0):
     # selection on one batch element
     sc = w.scores[:1].cpu().numpy()
     t0 = time.perf_counter()
-    oracle.select_indices(sc, w.head_map.numpy(), w.k_budget)
+    oracle.select_indices(sc, w.head_map.numpy(), idx.shape[2], page=page)
     sel_us_layer = (time.perf_counter() - t0) * cfg.B * 1e6
     # dense on one KV group of batch 0 (extrapolated linearly)
     G = cfg.Hq // cfg.Hkv
@@ -101,7 +108,7 @@ def cpu_baseline(w, idx, cnt, budget_s=25.0):
     return {
         "value": round(sparse_us_layer, 1), "unit": "us/layer", "cores": threads, "kind": "oracle",
         "sample": (f"sts_sparse_attn oracle on {nb} of {cfg.B} batch elements (all {cfg.Hq} heads, "
-                   f"k={w.k_budget}), best of 2, scaled to the batch; select timed on 1 batch element, "
+                   f"k={idx.shape[2]}{' blocks of %d' % page if page > 1 else ''}), best of 2, scaled to the batch; select timed on 1 batch element, "
                    f"dense on 1 KV group of 1 batch element, both scaled linearly"),
         "select_us_layer": round(sel_us_layer, 1),
         "dense_us_layer_extrapolated": round(dense_us_layer, 1),
@@ -127,7 +134,8 @@ def main():
     torch.cuda.set_device(dev)
     cfg = CONFIGS[args.config]
     w = make_workload(cfg, seed=args.seed, device=dev, budget=args.budget, with_scores=not cfg.draft_d)
-    kb = w.k_budget
+    page = max(1, args.page_size)
+    kb = -(-w.k_budget // page)          # same token budget, counted in blocks of `page` tokens
     B, N, Hq, Hkv, d, Tq, Hd = cfg.B, cfg.N, cfg.Hq, cfg.Hkv, cfg.d, cfg.Tq, cfg.Hd
     draft = make_draft_layer(w) if cfg.draft_d else None
     # distinct resident layers (1M-context configuration: 32 x 4 GiB of KV); the draft scores
@@ -137,6 +145,24 @@ def main():
         wl = make_workload(cfg, seed=args.seed + l, device=dev, budget=args.budget, with_scores=False)
         layers.append((wl.k, wl.v))
         del wl
+    table = None
+    if args.paged:
+        # scatter every layer's cache into a pool [pages, Hkv, page, d] behind one random table
+        assert N % page == 0, "--paged needs N divisible by the page size"
+        nblk = N // page
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(args.seed + 999)
+        table = torch.randperm(B * nblk, generator=gen, device=dev).to(torch.int32).view(B, nblk)
+        inv = table.view(-1).long()
+        pooled = []
+        for (lk, lv) in layers:
+            pk = torch.empty(B * nblk, Hkv, page, d, dtype=torch.bfloat16, device=dev)
+            pv = torch.empty_like(pk)
+            pk[inv] = lk.view(B, Hkv, nblk, page, d).permute(0, 2, 1, 3, 4).reshape(B * nblk, Hkv, page, d)
+            pv[inv] = lv.view(B, Hkv, nblk, page, d).permute(0, 2, 1, 3, 4).reshape(B * nblk, Hkv, page, d)
+            pooled.append((pk, pv))
+        layers = pooled      # w.k / w.v keep the logical layer-0 cache for the CPU baseline
+    pg = dict(page_size=page, block_table=table, N=N) if table is not None else dict(page_size=page)
     torch.cuda.synchronize()
 
     # persistent outputs so the timed region allocates nothing
@@ -157,16 +183,17 @@ def main():
             sts.sts_dense_attn(draft["q"], draft["k"], draft["v"], draft["scale"], out=d_out,
                                lse_out=d_lse, logits_out=d_logits)
             if ev: ev[1].record()
-            sts.sts_select(d_logits, w.head_map, kb, lse=d_lse, kind=sts.STS_SCORES_LOGITS_LSE, out=(idx, cnt))
+            sts.sts_select(d_logits, w.head_map, kb, lse=d_lse, kind=sts.STS_SCORES_LOGITS_LSE, out=(idx, cnt),
+                           page_size=page)
         else:
             if ev: ev[1].record()
-            sts.sts_select(w.scores, w.head_map, kb, out=(idx, cnt))
+            sts.sts_select(w.scores, w.head_map, kb, out=(idx, cnt), page_size=page)
         if ev: ev[2].record()
         sts.sts_sparse_attn(w.q, lk, lv, idx, w.scale, counts=cnt, head_map=w.head_map, out=out_s,
-                            want_lse=False)
+                            want_lse=False, **pg)
         if ev: ev[3].record()
         if not args.no_dense:
-            sts.sts_dense_attn(w.q, lk, lv, w.scale, out=out_d, want_lse=False)
+            sts.sts_dense_attn(w.q, lk, lv, w.scale, out=out_d, want_lse=False, **pg)
         if ev: ev[4].record()
 
     L = len(layers)
@@ -214,15 +241,17 @@ def main():
     split_n, split_ms = prof["attn_sparse"]
     split_us = split_ms * 1e3 / max(split_n, 1)
     dsplit_n, dsplit_ms = prof["attn_dense"]
-    plan = sts.attn_plan(w.q, w.k, True, kmax=kb, head_map=w.head_map)
+    plan = sts.attn_plan(w.q, layers[0][0] if table is None else torch.empty(B, Hkv, N, d, device="meta"), True,
+                         kmax=kb, head_map=w.head_map, page_size=page)
     units = plan["units_per_batch"]
     row_bytes = 2 * d * 2                                   # one K row + one V row, bf16
-    b_set = B * units * kb * row_bytes                      # gathered once per distinct index row
-    b_req = B * Hq * kb * row_bytes                         # gathered per query head
+    b_set = B * units * kb * page * row_bytes               # gathered once per distinct index row
+    b_req = B * Hq * kb * page * row_bytes                  # gathered per query head
     b_dense = B * Hkv * N * row_bytes
     achieved = b_set / (split_us * 1e-6) / 1e9 if split_us > 0 else 0.0
     workload = (f"{cfg.name}: B{B} N{N} Hq{Hq}/Hkv{Hkv} d{d} Tq{Tq} Hd{Hd} budget "
-                f"{kb} tokens ({kb / N:.1%})")
+                f"{kb * page} tokens ({kb * page / N:.1%})"
+                + (f" as {kb} blocks of {page}" if page > 1 else "") + (" paged KV" if args.paged else ""))
     result = {
         "metric": METRIC,
         "value": round(sparse_us[0], 2),
@@ -236,7 +265,7 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": workload, "context": N, "batch": B, "budget_tokens": kb,
+        "config": {"workload": workload, "context": N, "batch": B, "budget_tokens": kb * page, "page_size": page, "paged_kv": bool(args.paged),
                    "layers": L, "head_map": "t*Hd//Hq", "step": ("%d layers x (" % L if L > 1 else "(") + "select + sparse_attn" + ("" if args.no_dense else " + dense_attn")
                    + (" + draft dense attn with logits dump" if draft is not None else "") + ")"},
         "sparse_attn_us": {"mean": round(sparse_us[0], 2), "median": round(sparse_us[1], 2), "min": round(sparse_us[2], 2)},
@@ -262,7 +291,7 @@ def main():
         result["roofline_dense"] = {"achieved": round(b_dense / (dsplit_ms * 1e-3 / dsplit_n) / 1e9, 1),
                                     "frac": round(b_dense / (dsplit_ms * 1e-3 / dsplit_n) / 1e9 / HBM_PEAK_GBS, 4)}
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, idx, cnt)
+        result["cpu_baseline"] = cpu_baseline(w, idx, cnt, page=page)
     print(json.dumps(result))
 
 

@@ -57,8 +57,14 @@ typedef enum { STS_BF16 = 0, STS_F32 = 1 } sts_dtype;
  * caller error (they are ordered above +inf, deterministically, but that order is not part
  * of the contract).
  *
- * Supported: 1 <= Tq <= 64, 1 <= Hq <= 256, 1 <= Hd <= 256, N < 2^31 - 2^16. B, N or k-free rows of
- * size zero are handled (nothing is read; counts are written as 0).
+ * Block granularity (paper Section 4.2: top-k over blocks instead of tokens; Section 6.3:
+ * page size p_s). With page_size = p > 1 the aggregated scores of the tokens of block m,
+ * A[m*p] + A[m*p+1] + ... (fp32, left to right, tokens below N_b only), rank the
+ * ceil(N_b / p) blocks; k then counts blocks and `indices` holds ascending block ids.
+ * agg_out stays per token.
+ *
+ * Supported: 1 <= Tq <= 64, 1 <= Hq <= 256, 1 <= Hd <= 256, N < 2^31 - 2^16,
+ * page_size <= 4096. Rows of size zero are handled (nothing is read; counts are 0).
  */
 typedef struct {
   int32_t B, Hd, Tq, N, Hq;
@@ -72,6 +78,7 @@ typedef struct {
   float *agg_out;           /* [dev] out [B,Hd,N] the aggregated scores A; may be NULL */
   int32_t kind;             /* sts_score_kind */
   int32_t reduce;           /* sts_reduce */
+  int32_t page_size;        /* 0 or 1: token granularity. p > 1: block granularity (see below) */
   void *workspace;          /* [dev] 256-byte aligned scratch */
   size_t workspace_bytes;
 } sts_select_params;
@@ -91,6 +98,15 @@ typedef struct {
  * block's own causal part is merged by the caller using lse_out. A row with no key gives
  * out = 0 and lse = -inf. Index values must lie in [0,N); they are clamped into range for
  * memory safety, never checked. A repeated index is counted once per occurrence.
+ *
+ * Block granularity and paged caches (paper Section 5: sparsity at block granularity over
+ * KV blocks scattered in memory; Section 6.3: page size p_s). With page_size = p in
+ * {2,4,8,16,32} an index entry m stands for the tokens m*p .. min((m+1)*p, N)-1, in order,
+ * and counts/kmax count entries. With block_table != NULL the cache is a pool of pages of
+ * p tokens shared by the batch: token n of batch b lives in page block_table[b, n / p] at
+ * slot n % p, i.e. at element offset page*kv_stride_page + g*kv_stride_h + (n % p)*kv_stride_n
+ * of k and v (kv_stride_b is ignored). N stays the logical length bound; table entries are
+ * clamped into [0, num_pages) for memory safety. Both options apply to sparse and dense.
  *
  * Supported: d in {64,128}; Hq % Hkv == 0; Hq/Hkv <= 16; 1 <= Tq <= 16; Hq <= 256;
  * kv strides with kv_stride_n*2 bytes a multiple of 16 and bases 16-byte aligned.
@@ -112,6 +128,11 @@ typedef struct {
   int32_t out_dtype;        /* sts_dtype */
   float *lse_out;           /* [dev] optional [B,Hq,Tq], natural log */
   float *logits_out;        /* [dev] dense only, optional [B,Hq,Tq,N] scaled logits s_c */
+  int32_t page_size;        /* 0 or 1: entries are tokens; else tokens per entry / per page */
+  const int32_t *block_table; /* [dev] [B, table_stride] logical block -> physical page, or NULL */
+  int32_t table_stride;     /* entries per batch row of block_table, >= ceil(N / page_size) */
+  int32_t num_pages;        /* pages in the pool (paged only) */
+  int64_t kv_stride_page;   /* elements between consecutive pages of the pool (paged only) */
   void *workspace;          /* [dev] 256-byte aligned scratch */
   size_t workspace_bytes;
 } sts_attn_params;
@@ -142,7 +163,8 @@ typedef enum {
   STS_K_ATTN_SPARSE = 5,   /* split sparse gather flash-decode */
   STS_K_ATTN_DENSE = 6,    /* split dense flash-decode */
   STS_K_ATTN_COMBINE = 7,  /* split combine */
-  STS_K_COUNT_ = 8
+  STS_K_SELECT_BLOCK = 8,  /* per-block score sums + first-digit histogram (page_size > 1) */
+  STS_K_COUNT_ = 9
 } sts_kernel_kind;
 #define STS_PROF_MAX 4096
 

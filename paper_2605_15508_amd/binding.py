@@ -15,7 +15,7 @@ STS_SCORES_PROBS, STS_SCORES_LOGITS_LSE = 0, 1
 STS_REDUCE_SUM, STS_REDUCE_MAX = 0, 1
 STS_BF16, STS_F32 = 0, 1
 KERNEL_KINDS = {"select_clear": 0, "select_agg": 1, "select_hist": 2, "select_count": 3,
-                "select_write": 4, "attn_sparse": 5, "attn_dense": 6, "attn_combine": 7}
+                "select_write": 4, "attn_sparse": 5, "attn_dense": 6, "attn_combine": 7, "select_block": 8}
 
 # every symbol include/sts.h declares
 EXPORTS = ["sts_select_workspace_bytes", "sts_attn_workspace_bytes", "sts_select", "sts_sparse_attn",
@@ -33,6 +33,7 @@ class SelectParams(ctypes.Structure):
                 ("scores", ctypes.c_void_p), ("lse", ctypes.c_void_p), ("head_map", ctypes.c_void_p),
                 ("seq_lens", ctypes.c_void_p), ("indices", ctypes.c_void_p), ("counts", ctypes.c_void_p),
                 ("agg_out", ctypes.c_void_p), ("kind", ctypes.c_int32), ("reduce", ctypes.c_int32),
+                ("page_size", ctypes.c_int32),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
 
 
@@ -45,8 +46,10 @@ class AttnParams(ctypes.Structure):
                 ("counts", ctypes.c_void_p), ("kmax", ctypes.c_int32), ("head_map", ctypes.c_void_p),
                 ("seq_lens", ctypes.c_void_p), ("scale", ctypes.c_float), ("out", ctypes.c_void_p),
                 ("out_dtype", ctypes.c_int32), ("lse_out", ctypes.c_void_p),
-                ("logits_out", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
-                ("workspace_bytes", ctypes.c_size_t)]
+                ("logits_out", ctypes.c_void_p), ("page_size", ctypes.c_int32),
+                ("block_table", ctypes.c_void_p), ("table_stride", ctypes.c_int32),
+                ("num_pages", ctypes.c_int32), ("kv_stride_page", ctypes.c_int64),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
 
 
 _lib = None
@@ -133,9 +136,11 @@ def _host_i32(seq) -> ctypes.Array:
 
 
 def sts_select(scores, head_map, k: int, lse=None, seq_lens=None, kind: int = STS_SCORES_PROBS,
-               reduce: int = STS_REDUCE_SUM, want_agg: bool = False, out=None, workspace=None):
+               reduce: int = STS_REDUCE_SUM, want_agg: bool = False, out=None, workspace=None,
+               page_size: int = 1):
     """scores [B,Hd,Tq,N] fp32 (device), head_map [Hq] (host ints) -> (indices [B,Hq,k] int32,
-    counts [B,Hq] int32, agg [B,Hd,N] fp32 or None). See sts_select in include/sts.h."""
+    counts [B,Hq] int32, agg [B,Hd,N] fp32 or None). With page_size > 1, k counts blocks and the
+    indices are block ids. See sts_select in include/sts.h."""
     import torch
 
     lib = load_library()
@@ -157,7 +162,7 @@ def sts_select(scores, head_map, k: int, lse=None, seq_lens=None, kind: int = ST
     p = SelectParams(B=B, Hd=Hd, Tq=Tq, N=N, Hq=Hq, k=int(k), scores=_ptr(scores), lse=_ptr(lse),
                      head_map=ctypes.cast(hm, ctypes.c_void_p), seq_lens=_ptr(seq_lens),
                      indices=_ptr(indices), counts=_ptr(counts), agg_out=_ptr(agg), kind=kind,
-                     reduce=reduce, workspace=None, workspace_bytes=0)
+                     reduce=reduce, page_size=int(page_size), workspace=None, workspace_bytes=0)
     need = lib.sts_select_workspace_bytes(ctypes.byref(p))
     ws = workspace if workspace is not None else _workspace("select", need, dev)
     p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()
@@ -165,14 +170,27 @@ def sts_select(scores, head_map, k: int, lse=None, seq_lens=None, kind: int = ST
     return indices, counts, agg
 
 
-def _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse_out, logits_out):
+def _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse_out, logits_out,
+                 page_size=1, block_table=None, N=None):
     import torch
 
     assert q.is_cuda and q.dtype == torch.bfloat16 and q.is_contiguous()
     assert k.dtype == torch.bfloat16 and v.dtype == torch.bfloat16 and k.is_cuda and v.is_cuda
     B, Tq, Hq, d = q.shape
-    Bk, Hkv, N, dk = k.shape
-    assert (Bk, dk) == (B, d) and v.shape == k.shape and v.stride() == k.stride() and k.stride(3) == 1
+    assert v.shape == k.shape and v.stride() == k.stride() and k.stride(3) == 1 and k.shape[3] == d
+    if block_table is None:
+        # contiguous-per-sequence cache [B,Hkv,N,d] (any strides on the first three dims)
+        Bk, Hkv, Nk, _ = k.shape
+        assert Bk == B
+        N = Nk if N is None else N
+        sb, sh, sn, sp, npages, tstride = k.stride(0), k.stride(1), k.stride(2), 0, 0, 0
+    else:
+        # pool of pages [num_pages,Hkv,page,d] + table [B,T] of physical page ids
+        npages, Hkv, pg, _ = k.shape
+        assert pg == page_size and N is not None
+        assert block_table.is_cuda and block_table.dtype == torch.int32 and block_table.is_contiguous()
+        assert block_table.shape[0] == B
+        sb, sh, sn, sp, tstride = 0, k.stride(1), k.stride(2), k.stride(0), block_table.shape[1]
     kmax = 0
     if indices is not None:
         assert indices.is_cuda and indices.dtype == torch.int32 and indices.is_contiguous()
@@ -185,22 +203,26 @@ def _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse_o
     hm = _host_i32(head_map) if head_map is not None else None
     out_dtype = STS_BF16 if out.dtype == torch.bfloat16 else STS_F32
     p = AttnParams(B=B, Tq=Tq, Hq=Hq, Hkv=Hkv, d=d, N=N, q=_ptr(q), k=_ptr(k), v=_ptr(v),
-                   kv_stride_b=k.stride(0), kv_stride_h=k.stride(1), kv_stride_n=k.stride(2),
+                   kv_stride_b=sb, kv_stride_h=sh, kv_stride_n=sn,
                    indices=_ptr(indices), counts=_ptr(counts), kmax=kmax,
                    head_map=ctypes.cast(hm, ctypes.c_void_p) if hm is not None else None,
                    seq_lens=_ptr(seq_lens), scale=float(scale), out=_ptr(out), out_dtype=out_dtype,
-                   lse_out=_ptr(lse_out), logits_out=_ptr(logits_out), workspace=None, workspace_bytes=0)
+                   lse_out=_ptr(lse_out), logits_out=_ptr(logits_out), page_size=int(page_size),
+                   block_table=_ptr(block_table), table_stride=tstride, num_pages=npages,
+                   kv_stride_page=sp, workspace=None, workspace_bytes=0)
     return p, hm
 
 
 def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=None, seq_lens=None,
               out=None, out_dtype=None, want_lse=True, want_logits=False, workspace=None,
-              lse_out=None, logits_out=None):
+              lse_out=None, logits_out=None, page_size=1, block_table=None, N=None):
     import torch
 
     lib = load_library()
     B, Tq, Hq, d = q.shape
-    N = k.shape[2]
+    if N is None:
+        assert block_table is None, "a paged cache needs the logical length bound N"
+        N = k.shape[2]
     dev = q.device
     if out is None:
         out = torch.empty(B, Tq, Hq, d, dtype=out_dtype or torch.bfloat16, device=dev)
@@ -212,7 +234,8 @@ def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=
         logits = torch.empty(B, Hq, Tq, N, dtype=torch.float32, device=dev)
     for t, shape in ((lse, (B, Hq, Tq)), (logits, (B, Hq, Tq, N))):
         assert t is None or (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == shape)
-    p, _keep = _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse, logits)
+    p, _keep = _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse, logits,
+                            page_size=page_size, block_table=block_table, N=N)
     need = lib.sts_attn_workspace_bytes(ctypes.byref(p), 1 if sparse else 0)
     ws = workspace if workspace is not None else _workspace("attn", need, dev)
     p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()
@@ -222,31 +245,33 @@ def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=
 
 
 def sts_sparse_attn(q, k, v, indices, scale, counts=None, head_map=None, out=None, out_dtype=None,
-                    want_lse=True, workspace=None, lse_out=None):
+                    want_lse=True, workspace=None, lse_out=None, page_size=1, block_table=None, N=None):
     """Attention over the gathered rows indices[b,t,:counts[b,t]] of the full cache.
     q [B,Tq,Hq,d] bf16, k/v [B,Hkv,N,d] bf16 (strided ok) -> (out [B,Tq,Hq,d], lse [B,Hq,Tq])."""
     out, lse, _ = _run_attn(True, q, k, v, scale, indices=indices, counts=counts, head_map=head_map,
                             out=out, out_dtype=out_dtype, want_lse=want_lse, workspace=workspace,
-                            lse_out=lse_out)
+                            lse_out=lse_out, page_size=page_size, block_table=block_table, N=N)
     return out, lse
 
 
 def sts_dense_attn(q, k, v, scale, seq_lens=None, out=None, out_dtype=None, want_lse=True,
-                   want_logits=False, workspace=None, lse_out=None, logits_out=None):
+                   want_logits=False, workspace=None, lse_out=None, logits_out=None, page_size=1,
+                   block_table=None, N=None):
     """Dense attention of the same kernel family -> (out, lse, logits [B,Hq,Tq,N] or None)."""
     return _run_attn(False, q, k, v, scale, seq_lens=seq_lens, out=out, out_dtype=out_dtype,
                      want_lse=want_lse, want_logits=want_logits, workspace=workspace,
-                     lse_out=lse_out, logits_out=logits_out)
+                     lse_out=lse_out, logits_out=logits_out, page_size=page_size,
+                     block_table=block_table, N=N)
 
 
-def attn_plan(q, k, sparse: bool, kmax: int = 0, head_map=None) -> Dict[str, int]:
+def attn_plan(q, k, sparse: bool, kmax: int = 0, head_map=None, page_size: int = 1) -> Dict[str, int]:
     """Launch geometry the library picks for a shape (reports only)."""
     lib = load_library()
     B, Tq, Hq, d = q.shape
     _, Hkv, N, _ = k.shape
     hm = _host_i32(head_map) if head_map is not None else None
     p = AttnParams(B=B, Tq=Tq, Hq=Hq, Hkv=Hkv, d=d, N=N, kv_stride_b=k.stride(0), kv_stride_h=k.stride(1),
-                   kv_stride_n=k.stride(2), kmax=kmax, scale=1.0,
+                   kv_stride_n=k.stride(2), kmax=kmax, scale=1.0, page_size=int(page_size),
                    head_map=ctypes.cast(hm, ctypes.c_void_p) if hm is not None else None)
     s, u, nq = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
     _check(lib.sts_attn_plan(ctypes.byref(p), 1 if sparse else 0, ctypes.byref(s), ctypes.byref(u),

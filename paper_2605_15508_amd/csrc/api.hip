@@ -80,8 +80,17 @@ sts_status validate_attn(const sts_attn_params *p, int sparse) {
   if (p->kv_stride_n < p->d || (p->kv_stride_n * 2) % 16 != 0 || (p->kv_stride_h * 2) % 16 != 0 ||
       (p->kv_stride_b * 2) % 16 != 0)
     return STS_EUNSUPPORTED;
+  const int page = p->page_size <= 1 ? 1 : p->page_size;
+  if (page != 1 && page != 2 && page != 4 && page != 8 && page != 16 && page != 32) return STS_EUNSUPPORTED;
+  if (p->block_table) {
+    if (p->num_pages < 1 || p->kv_stride_page < 1 || (p->kv_stride_page * 2) % 16 != 0) return STS_EINVAL;
+    if ((int64_t)p->table_stride * page < p->N) return STS_EINVAL;
+  }
+  if (sparse && (int64_t)p->kmax * page > 0x7fffffffll - 65536) return STS_EUNSUPPORTED;
   return STS_OK;
 }
+
+int page_of(const sts_attn_params *p) { return p->page_size <= 1 ? 1 : p->page_size; }
 
 // Group query heads into units and pick the split count. Uses only host data.
 sts_status plan_attn(const sts_attn_params *p, int sparse, AttnPlan &pl) {
@@ -119,7 +128,7 @@ sts_status plan_attn(const sts_attn_params *p, int sparse, AttnPlan &pl) {
   }
   pl.num_units = nu;
   pl.nq = max_rows <= 16 ? 1 : (max_rows <= 32 ? 2 : 4);
-  const int64_t len = sparse ? p->kmax : p->N;
+  const int64_t len = sparse ? (int64_t)p->kmax * page_of(p) : p->N;
   const int64_t tiles = (len + STS_TILE_KEYS - 1) / STS_TILE_KEYS;
   int64_t resident = (int64_t)cu_count() * (pl.nq == 4 ? 1 : 2);
   if (const char *e = getenv("STS_ATTN_WGS_PER_CU")) {   // tuning knob: target workgroups per CU
@@ -169,6 +178,13 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
   a.stride_n = p->kv_stride_n;
   a.B = p->B; a.Tq = p->Tq; a.Hq = p->Hq; a.Hkv = p->Hkv; a.G = p->Hq / p->Hkv; a.N = p->N;
   a.kmax = sparse ? p->kmax : 0;
+  a.page = page_of(p);
+  a.page_shift = 0;
+  while ((1 << a.page_shift) < a.page) ++a.page_shift;
+  a.block_table = p->block_table;
+  a.table_stride = p->table_stride;
+  a.num_pages = p->num_pages;
+  a.stride_page = p->kv_stride_page;
   a.num_units = pl.num_units;
   a.num_splits = pl.num_splits;
   a.scale = p->scale;
@@ -190,8 +206,8 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
 
 // --------------------------------------------------------------------------- select plan
 struct SelectPlan {
-  int nchunks;
-  size_t agg_bytes, hist_bytes, state_bytes, chunk_bytes;
+  int nchunks, page, srcN;
+  size_t agg_bytes, blk_bytes, hist_bytes, state_bytes, chunk_bytes;
 };
 
 sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
@@ -202,9 +218,13 @@ sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
   if (p->Tq > 64 || p->Hq > STS_MAX_HEADS || p->Hd > STS_MAX_HEADS) return STS_EUNSUPPORTED;
   if ((int64_t)p->N > 0x7fffffffll - 65536) return STS_EUNSUPPORTED;
   if ((int64_t)p->B * p->Hd > 65535) return STS_EUNSUPPORTED;   // grid.y
-  pl.nchunks = (p->N + SEL_CHUNK - 1) / SEL_CHUNK;
+  if (p->page_size < 0 || p->page_size > 4096) return STS_EUNSUPPORTED;
+  pl.page = p->page_size <= 1 ? 1 : p->page_size;
+  pl.srcN = (p->N + pl.page - 1) / pl.page;
+  pl.nchunks = (pl.srcN + SEL_CHUNK - 1) / SEL_CHUNK;
   const size_t rows = (size_t)p->B * p->Hd;
   pl.agg_bytes = p->agg_out ? 0 : align256(rows * (size_t)p->N * sizeof(float));
+  pl.blk_bytes = pl.page > 1 ? align256(rows * (size_t)pl.srcN * sizeof(float)) : 0;
   pl.hist_bytes = align256(rows * 3 * SEL_BINS * sizeof(uint32_t));
   pl.state_bytes = align256(rows * 8 * sizeof(uint32_t));
   pl.chunk_bytes = align256(rows * (size_t)pl.nchunks * 2 * sizeof(uint32_t));
@@ -244,7 +264,7 @@ sts_status sts_dense_attn(const sts_attn_params *p, void *stream) {
 size_t sts_select_workspace_bytes(const sts_select_params *p) {
   SelectPlan pl;
   if (plan_select(p, pl) != STS_OK) return 0;
-  const size_t n = pl.agg_bytes + pl.hist_bytes + pl.state_bytes + pl.chunk_bytes;
+  const size_t n = pl.agg_bytes + pl.blk_bytes + pl.hist_bytes + pl.state_bytes + pl.chunk_bytes;
   return n ? n : 256;
 }
 
@@ -258,7 +278,7 @@ sts_status sts_select(const sts_select_params *p, void *stream) {
   if (p->B == 0) return STS_OK;
   if (p->N > 0 && !p->scores) return STS_EINVAL;
   if (p->kind == STS_SCORES_LOGITS_LSE && !p->lse) return STS_EINVAL;
-  const size_t need = pl.agg_bytes + pl.hist_bytes + pl.state_bytes + pl.chunk_bytes;
+  const size_t need = pl.agg_bytes + pl.blk_bytes + pl.hist_bytes + pl.state_bytes + pl.chunk_bytes;
   if (!p->workspace || p->workspace_bytes < need) return STS_EWORKSPACE;
   if (reinterpret_cast<uintptr_t>(p->workspace) % 256 != 0) return STS_EWORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -273,6 +293,11 @@ sts_status sts_select(const sts_select_params *p, void *stream) {
   unsigned char *w = static_cast<unsigned char *>(p->workspace);
   a.agg = p->agg_out ? p->agg_out : reinterpret_cast<float *>(w);
   w += pl.agg_bytes;
+  a.blk = pl.page > 1 ? reinterpret_cast<float *>(w) : nullptr;
+  w += pl.blk_bytes;
+  a.page = pl.page;
+  a.srcN = pl.srcN;
+  a.src = pl.page > 1 ? a.blk : a.agg;
   a.hist = reinterpret_cast<uint32_t *>(w);
   w += pl.hist_bytes;
   a.state = reinterpret_cast<uint32_t *>(w);
@@ -299,6 +324,10 @@ sts_status sts_select(const sts_select_params *p, void *stream) {
     if (rc != hipSuccess) return STS_EHIP;
     rc = run_kernel(STS_K_SELECT_AGG, s, [&] { return launch_select_agg(a, s); });
     if (rc != hipSuccess) return STS_EHIP;
+    if (pl.page > 1) {
+      rc = run_kernel(STS_K_SELECT_BLOCK, s, [&] { return launch_select_block(a, s); });
+      if (rc != hipSuccess) return STS_EHIP;
+    }
     rc = run_kernel(STS_K_SELECT_HIST, s, [&] { return launch_select_hist(a, 1, s); });
     if (rc != hipSuccess) return STS_EHIP;
     rc = run_kernel(STS_K_SELECT_HIST, s, [&] { return launch_select_hist(a, 2, s); });
@@ -321,7 +350,7 @@ const char *sts_strerror(sts_status s) {
   return "unknown status";
 }
 
-int sts_version(void) { return 100; }
+int sts_version(void) { return 101; }
 
 void sts_prof_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);

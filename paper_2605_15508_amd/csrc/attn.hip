@@ -50,7 +50,7 @@ __device__ __forceinline__ float xor_max(float x, int lanemask) {
   return fmaxf(x, __shfl_xor(x, lanemask, 64));
 }
 
-template <int D, int NQ, bool SPARSE, bool LOGITS>
+template <int D, int NQ, bool SPARSE, bool LOGITS, bool PAGED>
 __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_split_kernel(const AttnArgs A) {
   typedef typename Chunk<D>::type chunk_t;
   constexpr int NT = D / 16;         // output tiles of the PV product == elements per lane chunk
@@ -79,29 +79,34 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
   const int rows_valid = nheads * A.Tq;
   const int head0 = g * A.G + nth_member(mask, 0);
 
-  // Number of keys this unit attends to. The split boundaries come from the static upper
-  // bound (kmax or N), so the first index load below does not wait for this value; a unit
-  // with fewer keys simply leaves its last splits empty (the longest unit sets the makespan).
+  // Length of this unit's key list in token positions. Sparse index entries stand for blocks
+  // of `page` consecutive tokens (page = 1: single tokens), so entry e covers positions
+  // e*page .. e*page+page-1 of the expanded list. The split boundaries come from the static
+  // upper bound (kmax*page or N), so the first index load below does not wait for the count;
+  // a unit with fewer keys simply leaves its last splits empty (the longest unit sets the
+  // makespan).
+  const int psh = A.page_shift, pmask = A.page - 1;
   int c;
   if (SPARSE) {
     c = A.counts ? A.counts[bt * A.Hq + head0] : A.kmax;
-    c = min(max(c, 0), A.kmax);
+    c = min(max(c, 0), A.kmax) << psh;
   } else {
     c = A.seq_lens ? A.seq_lens[bt] : A.N;
     c = min(max(c, 0), A.N);
   }
-  const int len_max = SPARSE ? A.kmax : A.N;
+  const int len_max = SPARSE ? (A.kmax << psh) : A.N;
   const int tiles_max = (len_max + STS_TILE_KEYS - 1) / STS_TILE_KEYS;
   const int tps = (tiles_max + S - 1) / S;
   const int t_begin = split * tps;
   const int32_t *idx_row = SPARSE ? A.indices + ((size_t)bt * A.Hq + head0) * A.kmax : nullptr;
-  // first tile's index row, issued before anything depends on c (kmax >= 1 whenever a
-  // sparse grid is launched with tiles to do; the clamp keeps the address inside the row)
+  // first tile's index entries, issued before anything depends on the count (kmax >= 1
+  // whenever a sparse grid has tiles to do; the clamp keeps the address inside the row)
   int rows_first = 0;
   if (SPARSE && len_max > 0)
-    rows_first = idx_row[min((t_begin + wave) * STS_TILE_KEYS + (lane & 31), len_max - 1)];
+    rows_first = idx_row[min(((t_begin + wave) * STS_TILE_KEYS + (lane & 31)) >> psh, A.kmax - 1)];
   const int tiles_total = (c + STS_TILE_KEYS - 1) / STS_TILE_KEYS;
   const int t_end = min(t_begin + tps, tiles_total);
+  const int nb_max = (A.N + A.page - 1) >> psh;   // logical blocks of the cache
 
   // query rows owned by this lane: row nq*16 + b
   int q_head[NQ], q_tq[NQ];
@@ -123,34 +128,57 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
     }
   }
 
-  const unsigned char *kbase = reinterpret_cast<const unsigned char *>(A.k) +
-                               ((int64_t)bt * A.stride_b + (int64_t)g * A.stride_h) * 2 + b * CHB;
-  const unsigned char *vbase = reinterpret_cast<const unsigned char *>(A.v) +
-                               ((int64_t)bt * A.stride_b + (int64_t)g * A.stride_h) * 2 + b * CHB;
+  // a paged cache is a pool of pages shared by the batch: the page table supplies the batch part
+  const int64_t head_off = ((PAGED ? 0 : (int64_t)bt * A.stride_b) + (int64_t)g * A.stride_h) * 2 + b * CHB;
+  const unsigned char *kbase = reinterpret_cast<const unsigned char *>(A.k) + head_off;
+  const unsigned char *vbase = reinterpret_cast<const unsigned char *>(A.v) + head_off;
   const int64_t row_bytes = A.stride_n * 2;
+  const int64_t page_bytes = A.stride_page * 2;
+  const int32_t *table_row = PAGED ? A.block_table + (size_t)bt * A.table_stride : nullptr;
   unsigned char *ldsK = lds + wave * KTILE_BYTES;
 
   // row slot of load m for this lane: 16*(m/4) + 4a + m%4 (the keys the MFMA output hands
   // to lane group a)
   auto slot_of = [&](int m) { return 16 * (m >> 2) + 4 * a + (m & 3); };
 
-  // Raw token row feeding slot (lane & 31) of tile t. Branch-free on purpose: the load is
-  // unconditional (tiles past the end re-read the wave's first entry) and nothing touches the
-  // loaded value until issue_loads clamps it, so the wait for it lands right before its use
-  // instead of draining the K/V loads that are in flight.
+  // Three prefetch stages per tile, each one loop half ahead of the next, so that no stage
+  // waits on a load that was issued after the K/V loads in flight:
+  //   fetch   : raw index entry (sparse) or logical block (dense) for slot (lane & 31);
+  //   resolve : validity mask of the tile (one bit per slot) and the row to read: the token
+  //             id, or with a page table the physical page (a second, dependent load);
+  //   issue   : the 16 K/V row loads of the tile.
+  // All three are branch-free and nothing touches a loaded value before the next stage.
   const int safe_pos = (t_begin + wave) * STS_TILE_KEYS;
   auto fetch_rows = [&](int t) -> int {
     const int pos = t * STS_TILE_KEYS + (lane & 31);
     const int p = (t < t_end) ? min(pos, c - 1) : safe_pos;
-    return SPARSE ? idx_row[p] : p;
+    const int e = p >> psh;
+    return SPARSE ? idx_row[e] : e;
   };
 
-  auto issue_loads = [&](int rows, chunk_t (&Kr)[8], chunk_t (&Vr)[8]) {
+  auto resolve = [&](int raw, int t, uint32_t &tile_mask) -> int {
+    const int pos = t * STS_TILE_KEYS + (lane & 31);
+    const int blk = min(max(raw, 0), nb_max - 1);      // memory safety for arbitrary entries
+    const int tok = (blk << psh) + (pos & pmask);
+    // past the list, past the tile range, or in the unfilled part of the last page
+    const bool ok = (t < t_end) && (pos < c) && (tok < A.N);
+    tile_mask = (uint32_t)__ballot(ok);
+    if (PAGED) return table_row[min(blk, A.table_stride - 1)];
+    return min(tok, A.N - 1);
+  };
+
+  auto issue_loads = [&](int x, chunk_t (&Kr)[8], chunk_t (&Vr)[8]) {
 #pragma unroll
     for (int m = 0; m < 8; ++m) {
-      int row = __shfl(rows, slot_of(m), 64);
-      row = min(max(row, 0), A.N - 1);     // memory safety for arbitrary index values
-      const int64_t off = (int64_t)row * row_bytes;
+      const int slot = slot_of(m);
+      int X = __shfl(x, slot, 64);
+      int64_t off;
+      if (PAGED) {
+        X = min(max(X, 0), A.num_pages - 1);
+        off = (int64_t)X * page_bytes + (int64_t)(slot & pmask) * row_bytes;
+      } else {
+        off = (int64_t)X * row_bytes;
+      }
       // every K/V row is consumed once per launch: stream it past the caches
       Kr[m] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t *>(kbase + off));
       Vr[m] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t *>(vbase + off));
@@ -167,7 +195,7 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
     for (int nt = 0; nt < NT; ++nt) acc[nq][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  auto consume = [&](int t, const chunk_t (&Kr)[8], const chunk_t (&Vr)[8]) {
+  auto consume = [&](int t, const chunk_t (&Kr)[8], const chunk_t (&Vr)[8], const uint32_t tile_mask) {
     const int pos0 = t * STS_TILE_KEYS;
     // ---- K: registers -> swizzled LDS tile (row = slot, 16-byte slot index XOR row)
 #pragma unroll
@@ -224,7 +252,7 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
       for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const bool ok = pos0 + 16 * ks + 4 * a + r < c;
+          const bool ok = (tile_mask >> (16 * ks + 4 * a + r)) & 1u;
           s[4 * ks + r] = ok ? St[nq][ks][r] * A.scale_log2 : -INFINITY;
         }
       float mt = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
@@ -268,27 +296,37 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
   // ---- main loop over this wave's tiles: t_begin + wave, step 4
   if (t_begin + wave < t_end) {   // wave-uniform; a wave without tiles touches no memory
     chunk_t K0[8], V0[8], K1[8], V1[8];
+    uint32_t m0, m1, mk_next, mk_new;
     int t = t_begin + wave;
-    // entries at or past c (last tile only) are padding: any in-range row will do, they are
-    // masked out of the softmax
-    int rows_a = SPARSE ? rows_first : fetch_rows(t);
-    int rows_b = fetch_rows(t + STS_WG_WAVES);
-    issue_loads(rows_a, K0, V0);
+    constexpr int W = STS_WG_WAVES;
+    // prologue: tile t in flight, tile t+W resolved, tile t+2W fetched
+    int raw_a = SPARSE ? rows_first : fetch_rows(t);
+    int raw_b = fetch_rows(t + W);
+    int x_a = resolve(raw_a, t, m0);
+    raw_a = fetch_rows(t + 2 * W);
+    int x_b = resolve(raw_b, t + W, mk_next);
+    issue_loads(x_a, K0, V0);
     if (SPARSE) __builtin_amdgcn_sched_barrier(0);
     for (;;) {
-      rows_a = fetch_rows(t + 2 * STS_WG_WAVES);
-      if (SPARSE) __builtin_amdgcn_sched_barrier(0);   // index fetch stays ahead of the K/V loads below
-      issue_loads(rows_b, K1, V1);
-      if (SPARSE) __builtin_amdgcn_sched_barrier(0);   // ... and the loads are in flight before the tile is consumed
-      consume(t, K0, V0);
-      t += STS_WG_WAVES;
+      raw_b = fetch_rows(t + 3 * W);
+      x_a = resolve(raw_a, t + 2 * W, mk_new);
+      if (SPARSE) __builtin_amdgcn_sched_barrier(0);   // index traffic stays ahead of the K/V loads
+      issue_loads(x_b, K1, V1);
+      m1 = mk_next;
+      if (SPARSE) __builtin_amdgcn_sched_barrier(0);   // loads are in flight before the tile is consumed
+      consume(t, K0, V0, m0);
+      mk_next = mk_new;
+      t += W;
       if (t >= t_end) break;
-      rows_b = fetch_rows(t + 2 * STS_WG_WAVES);
+      raw_a = fetch_rows(t + 3 * W);
+      x_b = resolve(raw_b, t + 2 * W, mk_new);
       if (SPARSE) __builtin_amdgcn_sched_barrier(0);
-      issue_loads(rows_a, K0, V0);
+      issue_loads(x_a, K0, V0);
+      m0 = mk_next;
       if (SPARSE) __builtin_amdgcn_sched_barrier(0);
-      consume(t, K1, V1);
-      t += STS_WG_WAVES;
+      consume(t, K1, V1, m1);
+      mk_next = mk_new;
+      t += W;
       if (t >= t_end) break;
     }
   }
@@ -445,16 +483,22 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs A, con
   }
 }
 
-template <int D, int NQ>
-hipError_t launch_split_dn(const AttnArgs &a, bool sparse, hipStream_t s) {
+template <int D, int NQ, bool PAGED>
+hipError_t launch_split_dnp(const AttnArgs &a, bool sparse, hipStream_t s) {
   const dim3 grid((unsigned)((size_t)a.B * a.num_units * a.num_splits)), block(64 * STS_WG_WAVES);
   if (sparse)
-    hipLaunchKernelGGL((attn_split_kernel<D, NQ, true, false>), grid, block, 0, s, a);
+    hipLaunchKernelGGL((attn_split_kernel<D, NQ, true, false, PAGED>), grid, block, 0, s, a);
   else if (a.logits_out)
-    hipLaunchKernelGGL((attn_split_kernel<D, NQ, false, true>), grid, block, 0, s, a);
+    hipLaunchKernelGGL((attn_split_kernel<D, NQ, false, true, PAGED>), grid, block, 0, s, a);
   else
-    hipLaunchKernelGGL((attn_split_kernel<D, NQ, false, false>), grid, block, 0, s, a);
+    hipLaunchKernelGGL((attn_split_kernel<D, NQ, false, false, PAGED>), grid, block, 0, s, a);
   return hipGetLastError();
+}
+
+template <int D, int NQ>
+hipError_t launch_split_dn(const AttnArgs &a, bool sparse, hipStream_t s) {
+  return a.block_table ? launch_split_dnp<D, NQ, true>(a, sparse, s)
+                       : launch_split_dnp<D, NQ, false>(a, sparse, s);
 }
 
 template <int D>

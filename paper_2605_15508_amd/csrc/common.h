@@ -32,6 +32,10 @@ struct AttnArgs {
   int64_t stride_b, stride_h, stride_n;   // elements
   int32_t B, Tq, Hq, Hkv, G, N, kmax;
   int32_t num_units, num_splits;
+  int32_t page, page_shift;               // tokens per index entry / page (power of two <= 32)
+  const int32_t *block_table;             // [B, table_stride] logical block -> physical page, or NULL
+  int32_t table_stride, num_pages;
+  int64_t stride_page;                    // elements between pages of the pool
   float scale_log2;                       // scale * log2(e)
   float scale;
   float *part_o;                          // [B*U*S][NQ*16][D]
@@ -69,6 +73,10 @@ struct SelectArgs {
   const int32_t *seq_lens;
   int32_t *indices, *counts;
   float *agg;                 // [B,Hd,N] (agg_out or workspace)
+  float *blk;                 // [B,Hd,NB] per-block sums (page > 1), else unused
+  const float *src;           // what is ranked: agg (page == 1) or blk
+  int32_t srcN;               // row length of src: N or NB
+  int32_t page;               // tokens per block (>= 1)
   uint32_t *hist;             // [rows][3][SEL_BINS]
   uint32_t *state;            // [rows][8]: prefix key, remaining k per pass, threshold, ties
   uint32_t *chunk_cnt;        // [rows][nchunks][2]
@@ -81,6 +89,7 @@ hipError_t launch_attn_split(const AttnArgs &a, int d, int nq, bool sparse, hipS
 hipError_t launch_attn_combine(const AttnArgs &a, int d, int nq, hipStream_t s);
 hipError_t launch_select_clear(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_agg(const SelectArgs &a, hipStream_t s);
+hipError_t launch_select_block(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t s);
 hipError_t launch_select_count(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_write(const SelectArgs &a, hipStream_t s);

@@ -37,6 +37,11 @@ __device__ __forceinline__ int row_len(const SelectArgs &A, int bt) {
   return min(max(nb, 0), A.N);
 }
 
+// number of ranked units (tokens, or blocks of `page` tokens) in the row of batch bt
+__device__ __forceinline__ int src_len(const SelectArgs &A, int bt) {
+  return (row_len(A, bt) + A.page - 1) / A.page;
+}
+
 // exclusive prefix sum of one value per thread over a 256-thread block; also returns the total
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *lds_wave_tot, uint32_t &total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -147,7 +152,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_agg_kernel(const SelectArg
       *reinterpret_cast<f32x4 *>(out + n) = acc;
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        if (n + e < nb) atomicAdd(&h[key_of(acc[e]) >> (32 - SEL_BITS0)], 1u);
+        if (A.page == 1 && n + e < nb) atomicAdd(&h[key_of(acc[e]) >> (32 - SEL_BITS0)], 1u);
     }
   } else {
     for (int n = n0 + threadIdx.x; n < n1; n += SEL_THREADS) {
@@ -166,8 +171,37 @@ __global__ void __launch_bounds__(SEL_THREADS) select_agg_kernel(const SelectArg
         }
       }
       out[n] = acc;
-      if (n < nb) atomicAdd(&h[key_of(acc) >> (32 - SEL_BITS0)], 1u);
+      if (A.page == 1 && n < nb) atomicAdd(&h[key_of(acc) >> (32 - SEL_BITS0)], 1u);
     }
+  }
+  __syncthreads();
+  if (A.page != 1) return;   // block granularity: the block kernel builds the first histogram
+  uint32_t *gh = A.hist + (size_t)row * 3 * SEL_BINS;
+  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS)
+    if (h[i]) atomicAdd(&gh[i], h[i]);
+}
+
+// ----------------------------------------------------------------------- block scores
+// One thread per block: the block's aggregated scores added left to right in fp32 (tokens
+// below the valid length only), stored, and counted into the first-digit histogram.
+__global__ void __launch_bounds__(SEL_THREADS) select_block_kernel(const SelectArgs A) {
+  __shared__ uint32_t h[SEL_BINS];
+  const int row = blockIdx.y;
+  const int bt = row / A.Hd;
+  const int nb = row_len(A, bt);
+  const int nblk = (nb + A.page - 1) / A.page;
+  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) h[i] = 0u;
+  __syncthreads();
+  const float *a = A.agg + (size_t)row * A.N;
+  float *out = A.blk + (size_t)row * A.srcN;
+  const int m = blockIdx.x * SEL_THREADS + threadIdx.x;
+  if (m < A.srcN) {
+    float acc = 0.f;
+    const int n0 = m * A.page;
+    const int n1 = min(n0 + A.page, nb);
+    for (int n = n0; n < n1; ++n) acc = (n == n0) ? a[n] : acc + a[n];
+    out[m] = acc;
+    if (m < nblk) atomicAdd(&h[key_of(acc) >> (32 - SEL_BITS0)], 1u);
   }
   __syncthreads();
   uint32_t *gh = A.hist + (size_t)row * 3 * SEL_BINS;
@@ -184,7 +218,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_hist_kernel(const SelectAr
   __shared__ uint32_t tmp[16];
   const int row = blockIdx.y, chunk = blockIdx.x;
   const int bt = row / A.Hd;
-  const int nb = row_len(A, bt);
+  const int nb = src_len(A, bt);
   const uint32_t c = (uint32_t)min(A.k, nb);
   if (c == 0) return;
   uint32_t *st = A.state + (size_t)row * 8;
@@ -209,9 +243,9 @@ __global__ void __launch_bounds__(SEL_THREADS) select_hist_kernel(const SelectAr
   const uint32_t dshift = (PASS == 1) ? SEL_BITS2 : 0;
   for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) h[i] = 0u;
   __syncthreads();
-  const float *a = A.agg + (size_t)row * A.N;
+  const float *a = A.src + (size_t)row * A.srcN;
   const int n0 = chunk * SEL_CHUNK;
-  const int n1 = min(min(n0 + SEL_CHUNK, A.N), nb);
+  const int n1 = min(min(n0 + SEL_CHUNK, A.srcN), nb);
   if (VEC4) {
     for (int n = n0 + threadIdx.x * 4; n < n1; n += SEL_THREADS * 4) {
       const f32x4 x = *reinterpret_cast<const f32x4 *>(a + n);
@@ -239,7 +273,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_count_kernel(const SelectA
   __shared__ uint32_t tmp[16];
   const int row = blockIdx.y, chunk = blockIdx.x;
   const int bt = row / A.Hd;
-  const int nb = row_len(A, bt);
+  const int nb = src_len(A, bt);
   const uint32_t c = (uint32_t)min(A.k, nb);
   if (c == 0) return;
   uint32_t *st = A.state + (size_t)row * 8;
@@ -248,9 +282,9 @@ __global__ void __launch_bounds__(SEL_THREADS) select_count_kernel(const SelectA
   find_digit<(1 << SEL_BITS2)>(gh + 2 * SEL_BINS, st[3], tmp, d2, r);
   const uint32_t T = (st[0] << (SEL_BITS1 + SEL_BITS2)) | (st[2] << SEL_BITS2) | d2;
   if (chunk == 0 && threadIdx.x == 0) { st[4] = T; st[5] = r; }
-  const float *a = A.agg + (size_t)row * A.N;
+  const float *a = A.src + (size_t)row * A.srcN;
   const int n0 = chunk * SEL_CHUNK;
-  const int n1 = min(min(n0 + SEL_CHUNK, A.N), nb);
+  const int n1 = min(min(n0 + SEL_CHUNK, A.srcN), nb);
   uint32_t packed = 0;   // greater in the low half, equal in the high half (<= 8192 each)
   if (VEC4) {
     for (int n = n0 + threadIdx.x * 4; n < n1; n += SEL_THREADS * 4) {
@@ -289,7 +323,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_write_kernel(const SelectA
   __shared__ uint32_t buf[SEL_THREADS * PITCH];  // keys first, then the staged token ids
   const int row = blockIdx.y, chunk = blockIdx.x;
   const int bt = row / A.Hd, j = row % A.Hd;
-  const int nb = row_len(A, bt);
+  const int nb = src_len(A, bt);
   const uint32_t c = (uint32_t)min(A.k, nb);
   const int t0 = A.targets.off[j], t1 = A.targets.off[j + 1];
   if (chunk == 0) {
@@ -306,13 +340,13 @@ __global__ void __launch_bounds__(SEL_THREADS) select_write_kernel(const SelectA
   if (n0 >= nb) return;
   const uint32_t *st = A.state + (size_t)row * 8;
   const uint32_t T = st[4], r = st[5];
-  const float *a = A.agg + (size_t)row * A.N;
+  const float *a = A.src + (size_t)row * A.srcN;
 
   // coalesced load of the chunk; token n0 + i lands at buf[(i / PER) * PITCH + i % PER]
   if (VEC4) {
     for (int i = threadIdx.x * 4; i < SEL_CHUNK; i += SEL_THREADS * 4) {
       f32x4 x = {0.f, 0.f, 0.f, 0.f};
-      if (n0 + i < A.N) x = *reinterpret_cast<const f32x4 *>(a + n0 + i);   // N % 4 == 0
+      if (n0 + i < A.srcN) x = *reinterpret_cast<const f32x4 *>(a + n0 + i);   // srcN % 4 == 0
 #pragma unroll
       for (int e = 0; e < 4; ++e) buf[((i + e) / PER) * PITCH + (i + e) % PER] = key_of(x[e]);
     }
@@ -381,9 +415,20 @@ __global__ void __launch_bounds__(SEL_THREADS) select_write_kernel(const SelectA
 
 }  // namespace
 
-static inline bool vec_ok(const SelectArgs &a) {
+static inline bool vec_ok(const SelectArgs &a) {   // aggregation: scores and agg rows
   return (a.N % 4) == 0 && (reinterpret_cast<uintptr_t>(a.scores) % 16) == 0 &&
          (reinterpret_cast<uintptr_t>(a.agg) % 16) == 0;
+}
+
+static inline bool src_vec_ok(const SelectArgs &a) {   // ranking passes: rows of src
+  return (a.srcN % 4) == 0 && (reinterpret_cast<uintptr_t>(a.src) % 16) == 0;
+}
+
+hipError_t launch_select_block(const SelectArgs &a, hipStream_t s) {
+  if ((size_t)a.B * a.Hd == 0 || a.srcN == 0) return hipSuccess;
+  const dim3 grid((a.srcN + SEL_THREADS - 1) / SEL_THREADS, a.B * a.Hd), block(SEL_THREADS);
+  hipLaunchKernelGGL(select_block_kernel, grid, block, 0, s, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_select_clear(const SelectArgs &a, hipStream_t s) {
@@ -395,8 +440,9 @@ hipError_t launch_select_clear(const SelectArgs &a, hipStream_t s) {
 }
 
 hipError_t launch_select_agg(const SelectArgs &a, hipStream_t s) {
-  if ((size_t)a.B * a.Hd == 0 || a.nchunks == 0) return hipSuccess;
-  const dim3 grid(a.nchunks, a.B * a.Hd), block(SEL_THREADS);
+  const int chunks = (a.N + SEL_CHUNK - 1) / SEL_CHUNK;
+  if ((size_t)a.B * a.Hd == 0 || chunks == 0) return hipSuccess;
+  const dim3 grid(chunks, a.B * a.Hd), block(SEL_THREADS);
   if (vec_ok(a))
     hipLaunchKernelGGL(select_agg_kernel<true>, grid, block, 0, s, a);
   else
@@ -407,7 +453,7 @@ hipError_t launch_select_agg(const SelectArgs &a, hipStream_t s) {
 hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t s) {
   if ((size_t)a.B * a.Hd == 0 || a.nchunks == 0) return hipSuccess;
   const dim3 grid(a.nchunks, a.B * a.Hd), block(SEL_THREADS);
-  const bool v = vec_ok(a);
+  const bool v = src_vec_ok(a);
   if (pass == 1) {
     if (v) hipLaunchKernelGGL((select_hist_kernel<1, true>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((select_hist_kernel<1, false>), grid, block, 0, s, a);
@@ -421,7 +467,7 @@ hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t s) {
 hipError_t launch_select_count(const SelectArgs &a, hipStream_t s) {
   if ((size_t)a.B * a.Hd == 0 || a.nchunks == 0) return hipSuccess;
   const dim3 grid(a.nchunks, a.B * a.Hd), block(SEL_THREADS);
-  if (vec_ok(a))
+  if (src_vec_ok(a))
     hipLaunchKernelGGL(select_count_kernel<true>, grid, block, 0, s, a);
   else
     hipLaunchKernelGGL(select_count_kernel<false>, grid, block, 0, s, a);
@@ -431,7 +477,7 @@ hipError_t launch_select_count(const SelectArgs &a, hipStream_t s) {
 hipError_t launch_select_write(const SelectArgs &a, hipStream_t s) {
   if ((size_t)a.B * a.Hd == 0) return hipSuccess;
   const dim3 grid(a.nchunks > 0 ? a.nchunks : 1, a.B * a.Hd), block(SEL_THREADS);
-  if (vec_ok(a))
+  if (src_vec_ok(a))
     hipLaunchKernelGGL(select_write_kernel<true>, grid, block, 0, s, a);
   else
     hipLaunchKernelGGL(select_write_kernel<false>, grid, block, 0, s, a);

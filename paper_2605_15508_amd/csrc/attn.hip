@@ -167,17 +167,23 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
     return min(tok, A.N - 1);
   };
 
-  auto issue_loads = [&](int x, chunk_t (&Kr)[8], chunk_t (&Vr)[8]) {
+  auto issue_loads = [&](int x, int t, chunk_t (&Kr)[8], chunk_t (&Vr)[8]) {
 #pragma unroll
     for (int m = 0; m < 8; ++m) {
       const int slot = slot_of(m);
-      int X = __shfl(x, slot, 64);
       int64_t off;
-      if (PAGED) {
-        X = min(max(X, 0), A.num_pages - 1);
-        off = (int64_t)X * page_bytes + (int64_t)(slot & pmask) * row_bytes;
+      if (!SPARSE && !PAGED) {
+        // contiguous dense cache: the row is the position itself, no cross-lane traffic
+        const int row = (t < t_end) ? min(t * STS_TILE_KEYS + slot, c - 1) : 0;
+        off = (int64_t)row * row_bytes;
       } else {
-        off = (int64_t)X * row_bytes;
+        int X = __shfl(x, slot, 64);
+        if (PAGED) {
+          X = min(max(X, 0), A.num_pages - 1);
+          off = (int64_t)X * page_bytes + (int64_t)(slot & pmask) * row_bytes;
+        } else {
+          off = (int64_t)X * row_bytes;
+        }
       }
       // every K/V row is consumed once per launch: stream it past the caches
       Kr[m] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t *>(kbase + off));
@@ -305,13 +311,13 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
     int x_a = resolve(raw_a, t, m0);
     raw_a = fetch_rows(t + 2 * W);
     int x_b = resolve(raw_b, t + W, mk_next);
-    issue_loads(x_a, K0, V0);
+    issue_loads(x_a, t, K0, V0);
     if (SPARSE) __builtin_amdgcn_sched_barrier(0);
     for (;;) {
       raw_b = fetch_rows(t + 3 * W);
       x_a = resolve(raw_a, t + 2 * W, mk_new);
       if (SPARSE) __builtin_amdgcn_sched_barrier(0);   // index traffic stays ahead of the K/V loads
-      issue_loads(x_b, K1, V1);
+      issue_loads(x_b, t + W, K1, V1);
       m1 = mk_next;
       if (SPARSE) __builtin_amdgcn_sched_barrier(0);   // loads are in flight before the tile is consumed
       consume(t, K0, V0, m0);
@@ -321,7 +327,7 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
       raw_a = fetch_rows(t + 3 * W);
       x_b = resolve(raw_b, t + 2 * W, mk_new);
       if (SPARSE) __builtin_amdgcn_sched_barrier(0);
-      issue_loads(x_a, K0, V0);
+      issue_loads(x_a, t + W, K0, V0);
       m0 = mk_next;
       if (SPARSE) __builtin_amdgcn_sched_barrier(0);
       consume(t, K1, V1, m1);

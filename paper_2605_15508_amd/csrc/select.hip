@@ -209,6 +209,58 @@ __global__ void __launch_bounds__(SEL_THREADS) select_block_kernel(const SelectA
     if (h[i]) atomicAdd(&gh[i], h[i]);
 }
 
+// Coalesced variant for page % 4 == 0, page <= 256, N % 4 == 0: every lane loads 4 consecutive
+// tokens and the page/4 lanes of a block pass a running sum from left to right, so the
+// additions happen in exactly the order of the one-thread-per-block kernel above.
+__global__ void __launch_bounds__(SEL_THREADS) select_block_vec_kernel(const SelectArgs A) {
+  __shared__ uint32_t h[SEL_BINS];
+  const int row = blockIdx.y;
+  const int bt = row / A.Hd;
+  const int nb = row_len(A, bt);
+  const int nblk = (nb + A.page - 1) / A.page;
+  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) h[i] = 0u;
+  __syncthreads();
+  const float *a = A.agg + (size_t)row * A.N;
+  float *out = A.blk + (size_t)row * A.srcN;
+  const int L = A.page >> 2;                       // lanes per block (1..64, power of two)
+  const int lane = threadIdx.x & 63;
+  const int pos_in_blk = lane & (L - 1);
+  // SEL_CHUNK tokens per workgroup, 1024 per sweep
+  for (int n = blockIdx.x * SEL_CHUNK + threadIdx.x * 4; n < min((blockIdx.x + 1) * SEL_CHUNK, A.N);
+       n += SEL_THREADS * 4) {
+    const f32x4 x = *reinterpret_cast<const f32x4 *>(a + n);
+    float run = 0.f;
+    bool have = false;                             // whether `run` holds at least one term
+    for (int s = 0; s < L; ++s) {
+      if (pos_in_blk == s) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (n + e < nb) {
+            run = have ? run + x[e] : x[e];
+            have = true;
+          }
+      }
+      if (s + 1 < L) {
+        const float up = __shfl_up(run, 1, 64);
+        const int hup = __shfl_up((int)have, 1, 64);
+        if (pos_in_blk == s + 1) {
+          run = up;
+          have = hup != 0;
+        }
+      }
+    }
+    if (pos_in_blk == L - 1) {
+      const int m = n / A.page;
+      out[m] = run;                                // blocks past the valid length hold 0
+      if (m < nblk) atomicAdd(&h[key_of(run) >> (32 - SEL_BITS0)], 1u);
+    }
+  }
+  __syncthreads();
+  uint32_t *gh = A.hist + (size_t)row * 3 * SEL_BINS;
+  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS)
+    if (h[i]) atomicAdd(&gh[i], h[i]);
+}
+
 // ------------------------------------------------------------------ refinement histograms
 // PASS 1: digit 1 (bits 20..10) of keys whose digit 0 matches; PASS 2: digit 2 (bits 9..0)
 // of keys whose digits 0 and 1 match.
@@ -426,8 +478,15 @@ static inline bool src_vec_ok(const SelectArgs &a) {   // ranking passes: rows o
 
 hipError_t launch_select_block(const SelectArgs &a, hipStream_t s) {
   if ((size_t)a.B * a.Hd == 0 || a.srcN == 0) return hipSuccess;
-  const dim3 grid((a.srcN + SEL_THREADS - 1) / SEL_THREADS, a.B * a.Hd), block(SEL_THREADS);
-  hipLaunchKernelGGL(select_block_kernel, grid, block, 0, s, a);
+  const bool pow2 = (a.page & (a.page - 1)) == 0;
+  if (pow2 && a.page >= 4 && a.page <= 256 && (a.N % a.page) == 0 &&
+      (reinterpret_cast<uintptr_t>(a.agg) % 16) == 0) {
+    const dim3 grid((a.N + SEL_CHUNK - 1) / SEL_CHUNK, a.B * a.Hd), block(SEL_THREADS);
+    hipLaunchKernelGGL(select_block_vec_kernel, grid, block, 0, s, a);
+  } else {
+    const dim3 grid((a.srcN + SEL_THREADS - 1) / SEL_THREADS, a.B * a.Hd), block(SEL_THREADS);
+    hipLaunchKernelGGL(select_block_kernel, grid, block, 0, s, a);
+  }
   return hipGetLastError();
 }
 

@@ -62,7 +62,10 @@ def paged_copy(k, v, page, seed):
 
 
 @pytest.mark.parametrize("page,N,k", [(2, 1000, 77), (8, 4096, 51), (8, 20001, 300), (16, 333, 21),
-                                      (7, 500, 10), (32, 9000, 282), (8, 100, 20)])
+                                      (7, 500, 10), (32, 9000, 282), (8, 100, 20),
+                                      # shapes that take the coalesced block-sum kernel
+                                      (4, 1000, 100), (16, 4096, 30), (32, 8256, 17), (64, 2560, 5),
+                                      (8, 16392, 205)])
 def test_block_select_bit_exact(page, N, k):
     g = torch.Generator().manual_seed(page * 1000 + N)
     B, Hd, Tq, Hq = 2, 4, 5, 8

@@ -108,6 +108,13 @@ typedef struct {
  * of k and v (kv_stride_b is ignored). N stays the logical length bound; table entries are
  * clamped into [0, num_pages) for memory safety. Both options apply to sparse and dense.
  *
+ * The speculative block's own tokens (paper Section 2.1: the target checks all candidates in
+ * one parallel step, so candidate i also attends to the candidates before it). Their keys and
+ * values are not in the cache yet; pass them as k_new / v_new and they are appended after the
+ * cached keys of every query row (causally when `causal` is set) inside the combine step, so
+ * out and lse_out cover the whole verification attention. Without them the caller merges that
+ * part itself using lse_out.
+ *
  * Supported: d in {64,128}; Hq % Hkv == 0; Hq/Hkv <= 16; 1 <= Tq <= 16; Hq <= 256;
  * kv strides with kv_stride_n*2 bytes a multiple of 16 and bases 16-byte aligned.
  */
@@ -133,6 +140,8 @@ typedef struct {
   int32_t table_stride;     /* entries per batch row of block_table, >= ceil(N / page_size) */
   int32_t num_pages;        /* pages in the pool (paged only) */
   int64_t kv_stride_page;   /* elements between consecutive pages of the pool (paged only) */
+  const void *k_new, *v_new; /* [dev] optional bf16 [B,Tq,Hkv,d] contiguous: see below; both or neither */
+  int32_t causal;           /* with k_new: non-zero = query row i sees new tokens 0..i, zero = all Tq */
   void *workspace;          /* [dev] 256-byte aligned scratch */
   size_t workspace_bytes;
 } sts_attn_params;

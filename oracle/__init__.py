@@ -170,13 +170,15 @@ def remap(sel: np.ndarray, cnt: np.ndarray, head_map: np.ndarray):
 def attn(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float,
          indices: Optional[np.ndarray] = None, counts: Optional[np.ndarray] = None,
          seq_lens: Optional[np.ndarray] = None, want_logits: bool = False,
-         batches: Optional[range] = None, heads: Optional[range] = None):
+         batches: Optional[range] = None, heads: Optional[range] = None,
+         k_new: Optional[np.ndarray] = None, v_new: Optional[np.ndarray] = None, causal: bool = True):
     """Sparse (indices given) or dense (indices None) softmax attention. See oracle_attn.
 
     q [B,Tq,Hq,d] uint16 (bf16 bits); k, v [B,Hkv,N,d] uint16, any strides with unit stride on d.
     Returns dict(out [B,Tq,Hq,d] fp32, lse [B,Hq,Tq] fp32, logits [B,Hq,Tq,N] or None).
     ``batches``/``heads`` (contiguous ranges) restrict which outputs are computed; the others
-    stay zero (lse NaN).
+    stay zero (lse NaN). ``k_new``/``v_new`` [B,Tq,Hkv,d] uint16 are the speculative block's own
+    keys/values, appended after the cached keys (row i sees new tokens 0..i when ``causal``).
     """
     assert q.dtype == np.uint16 and k.dtype == np.uint16 and v.dtype == np.uint16
     q = np.ascontiguousarray(q)
@@ -195,6 +197,9 @@ def attn(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float,
             assert counts.shape == (B, Hq)
     if seq_lens is not None:
         seq_lens = _c(seq_lens, np.int32)
+    if k_new is not None:
+        k_new, v_new = np.ascontiguousarray(k_new), np.ascontiguousarray(v_new)
+        assert k_new.dtype == np.uint16 and k_new.shape == (B, Tq, Hkv, d) and v_new.shape == k_new.shape
     out = np.zeros((B, Tq, Hq, d), np.float32)
     lse = np.full((B, Hq, Tq), np.nan, np.float32)
     logits = np.zeros((B, Hq, Tq, N), np.float32) if want_logits else None
@@ -206,7 +211,8 @@ def attn(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float,
                          ctypes.c_int64(sn), _p(indices, ctypes.c_int32), _p(counts, ctypes.c_int32),
                          kmax, _p(seq_lens, ctypes.c_int32), ctypes.c_float(scale),
                          _p(out, ctypes.c_float), _p(lse, ctypes.c_float), _p(logits, ctypes.c_float),
-                         bb, be, hb, he)
+                         bb, be, hb, he, _p(k_new, ctypes.c_uint16), _p(v_new, ctypes.c_uint16),
+                         1 if causal else 0)
     _check(rc, "oracle_attn")
     return {"out": out, "lse": lse, "logits": logits}
 

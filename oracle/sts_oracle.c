@@ -175,8 +175,10 @@ int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, 
                 const int32_t *indices, const int32_t *counts, int kmax,
                 const int32_t *seq_lens, float scale, float *out, float *lse_out,
                 float *logits_out, int batch_begin, int batch_end, int head_begin,
-                int head_end) {
-  if (!q || !k || !v || !out) return -1;
+                int head_end, const uint16_t *k_new, const uint16_t *v_new, int causal) {
+  if (!q || !out) return -1;
+  if (N > 0 && (!k || !v)) return -1;
+  if ((k_new == NULL) != (v_new == NULL)) return -1;
   if (B < 0 || Tq < 1 || Hq < 1 || Hkv < 1 || d < 1 || N < 0 || Hq % Hkv != 0) return -1;
   if (indices && kmax < 0) return -1;
   if (indices && logits_out) return -1;
@@ -219,7 +221,7 @@ int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, 
     }
     const uint16_t *Kg = k + (size_t)b * stride_b + (size_t)g * stride_h;
     const uint16_t *Vg = v + (size_t)b * stride_b + (size_t)g * stride_h;
-    double *s = (double *)malloc(((size_t)c + 1) * sizeof(double));
+    double *s = (double *)malloc(((size_t)c + (size_t)Tq + 1) * sizeof(double));
     double *acc = (double *)malloc((size_t)d * sizeof(double));
     if (!s || !acc) {
       free(s);
@@ -241,17 +243,32 @@ int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, 
         if (s[j] > m) m = s[j];
         if (logits_out) logits_out[(((size_t)b * Hq + t) * Tq + i) * N + j] = (float)s[j];
       }
+      /* the block's own tokens, appended after the cached keys */
+      const int nnew = k_new ? (causal ? i + 1 : Tq) : 0;
+      for (int j = 0; j < nnew; ++j) {
+        const uint16_t *kr = k_new + (((size_t)b * Tq + j) * Hkv + g) * d;
+        double dot = 0.0;
+        for (int e = 0; e < d; ++e) dot += (double)bf16_to_float(qr[e]) * (double)bf16_to_float(kr[e]);
+        s[c + j] = (double)scale * dot;
+        if (s[c + j] > m) m = s[c + j];
+      }
       for (int e = 0; e < d; ++e) acc[e] = 0.0;
       double l = 0.0;
-      for (int j = 0; j < c; ++j) {
-        const size_t row = idx ? (size_t)idx[j] : (size_t)j;
-        const uint16_t *vr = Vg + row * stride_n;
+      for (int j = 0; j < c + nnew; ++j) {
+        const uint16_t *vr;
+        if (j < c) {
+          const size_t row = idx ? (size_t)idx[j] : (size_t)j;
+          vr = Vg + row * stride_n;
+        } else {
+          vr = v_new + (((size_t)b * Tq + (j - c)) * Hkv + g) * d;
+        }
         const double p = exp(s[j] - m);
         l += p;
         for (int e = 0; e < d; ++e) acc[e] += p * (double)bf16_to_float(vr[e]);
       }
-      for (int e = 0; e < d; ++e) o[e] = (c > 0) ? (float)(acc[e] / l) : 0.0f;
-      if (lse_out) lse_out[((size_t)b * Hq + t) * Tq + i] = (c > 0) ? (float)(m + log(l)) : -INFINITY;
+      const int total = c + nnew;
+      for (int e = 0; e < d; ++e) o[e] = (total > 0) ? (float)(acc[e] / l) : 0.0f;
+      if (lse_out) lse_out[((size_t)b * Hq + t) * Tq + i] = (total > 0) ? (float)(m + log(l)) : -INFINITY;
     }
     free(s);
     free(acc);

@@ -76,6 +76,11 @@ int oracle_remap(const int32_t *sel, const int32_t *cnt, int B, int Hd, int Hq, 
  *   out [B,Tq,Hq,d] fp32 ; lse_out [B,Hq,Tq] or NULL ; logits_out [B,Hq,Tq,N] or NULL
  *   (dense only: the scaled logits s_c, the paper's QK^T dump of Section 5).
  * A row with no valid key gives out = 0 and lse = -inf. An index outside [0,N) returns -3.
+ * k_new, v_new [B,Tq,Hkv,d] (bf16 bits) or NULL: the keys/values of the speculative block's
+ * own Tq tokens, which are not in the cache yet (Section 2.1: the target verifies all
+ * candidates in one parallel step, so candidate i also attends to candidates before it).
+ * They are appended after the cached keys of every query row: row i sees new tokens 0..i when
+ * causal != 0, all Tq otherwise.
  * head_begin/head_end restrict the computed query heads to [head_begin, head_end) and
  * batch_begin/batch_end the batches (other outputs untouched) so callers can sample. */
 int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, int Tq, int Hq,
@@ -83,7 +88,7 @@ int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, 
                 const int32_t *indices, const int32_t *counts, int kmax,
                 const int32_t *seq_lens, float scale, float *out, float *lse_out,
                 float *logits_out, int batch_begin, int batch_end, int head_begin,
-                int head_end);
+                int head_end, const uint16_t *k_new, const uint16_t *v_new, int causal);
 
 /* Algorithm 1 (head mapping construction). Traces are attention-weight rows:
  *   a_d [S,Hd,R,N], a_t [S,Ht,R,N] fp32 (S samples, R query rows each).

@@ -49,6 +49,7 @@ class AttnParams(ctypes.Structure):
                 ("logits_out", ctypes.c_void_p), ("page_size", ctypes.c_int32),
                 ("block_table", ctypes.c_void_p), ("table_stride", ctypes.c_int32),
                 ("num_pages", ctypes.c_int32), ("kv_stride_page", ctypes.c_int64),
+                ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p), ("causal", ctypes.c_int32),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
 
 
@@ -171,7 +172,7 @@ def sts_select(scores, head_map, k: int, lse=None, seq_lens=None, kind: int = ST
 
 
 def _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse_out, logits_out,
-                 page_size=1, block_table=None, N=None):
+                 page_size=1, block_table=None, N=None, k_new=None, v_new=None, causal=True):
     import torch
 
     assert q.is_cuda and q.dtype == torch.bfloat16 and q.is_contiguous()
@@ -202,6 +203,9 @@ def _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse_o
         assert seq_lens.is_cuda and seq_lens.dtype == torch.int32 and seq_lens.shape == (B,)
     hm = _host_i32(head_map) if head_map is not None else None
     out_dtype = STS_BF16 if out.dtype == torch.bfloat16 else STS_F32
+    if k_new is not None:
+        for t in (k_new, v_new):
+            assert t.is_cuda and t.dtype == torch.bfloat16 and t.is_contiguous() and tuple(t.shape) == (B, Tq, Hkv, d)
     p = AttnParams(B=B, Tq=Tq, Hq=Hq, Hkv=Hkv, d=d, N=N, q=_ptr(q), k=_ptr(k), v=_ptr(v),
                    kv_stride_b=sb, kv_stride_h=sh, kv_stride_n=sn,
                    indices=_ptr(indices), counts=_ptr(counts), kmax=kmax,
@@ -209,13 +213,15 @@ def _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse_o
                    seq_lens=_ptr(seq_lens), scale=float(scale), out=_ptr(out), out_dtype=out_dtype,
                    lse_out=_ptr(lse_out), logits_out=_ptr(logits_out), page_size=int(page_size),
                    block_table=_ptr(block_table), table_stride=tstride, num_pages=npages,
-                   kv_stride_page=sp, workspace=None, workspace_bytes=0)
+                   kv_stride_page=sp, k_new=_ptr(k_new), v_new=_ptr(v_new), causal=1 if causal else 0,
+                   workspace=None, workspace_bytes=0)
     return p, hm
 
 
 def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=None, seq_lens=None,
               out=None, out_dtype=None, want_lse=True, want_logits=False, workspace=None,
-              lse_out=None, logits_out=None, page_size=1, block_table=None, N=None):
+              lse_out=None, logits_out=None, page_size=1, block_table=None, N=None,
+              k_new=None, v_new=None, causal=True):
     import torch
 
     lib = load_library()
@@ -235,7 +241,8 @@ def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=
     for t, shape in ((lse, (B, Hq, Tq)), (logits, (B, Hq, Tq, N))):
         assert t is None or (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == shape)
     p, _keep = _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse, logits,
-                            page_size=page_size, block_table=block_table, N=N)
+                            page_size=page_size, block_table=block_table, N=N,
+                            k_new=k_new, v_new=v_new, causal=causal)
     need = lib.sts_attn_workspace_bytes(ctypes.byref(p), 1 if sparse else 0)
     ws = workspace if workspace is not None else _workspace("attn", need, dev)
     p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()
@@ -245,23 +252,25 @@ def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=
 
 
 def sts_sparse_attn(q, k, v, indices, scale, counts=None, head_map=None, out=None, out_dtype=None,
-                    want_lse=True, workspace=None, lse_out=None, page_size=1, block_table=None, N=None):
+                    want_lse=True, workspace=None, lse_out=None, page_size=1, block_table=None, N=None,
+                    k_new=None, v_new=None, causal=True):
     """Attention over the gathered rows indices[b,t,:counts[b,t]] of the full cache.
     q [B,Tq,Hq,d] bf16, k/v [B,Hkv,N,d] bf16 (strided ok) -> (out [B,Tq,Hq,d], lse [B,Hq,Tq])."""
     out, lse, _ = _run_attn(True, q, k, v, scale, indices=indices, counts=counts, head_map=head_map,
                             out=out, out_dtype=out_dtype, want_lse=want_lse, workspace=workspace,
-                            lse_out=lse_out, page_size=page_size, block_table=block_table, N=N)
+                            lse_out=lse_out, page_size=page_size, block_table=block_table, N=N,
+                            k_new=k_new, v_new=v_new, causal=causal)
     return out, lse
 
 
 def sts_dense_attn(q, k, v, scale, seq_lens=None, out=None, out_dtype=None, want_lse=True,
                    want_logits=False, workspace=None, lse_out=None, logits_out=None, page_size=1,
-                   block_table=None, N=None):
+                   block_table=None, N=None, k_new=None, v_new=None, causal=True):
     """Dense attention of the same kernel family -> (out, lse, logits [B,Hq,Tq,N] or None)."""
     return _run_attn(False, q, k, v, scale, seq_lens=seq_lens, out=out, out_dtype=out_dtype,
                      want_lse=want_lse, want_logits=want_logits, workspace=workspace,
                      lse_out=lse_out, logits_out=logits_out, page_size=page_size,
-                     block_table=block_table, N=N)
+                     block_table=block_table, N=N, k_new=k_new, v_new=v_new, causal=causal)
 
 
 def attn_plan(q, k, sparse: bool, kmax: int = 0, head_map=None, page_size: int = 1) -> Dict[str, int]:

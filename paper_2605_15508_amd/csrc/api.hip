@@ -87,6 +87,9 @@ sts_status validate_attn(const sts_attn_params *p, int sparse) {
     if ((int64_t)p->table_stride * page < p->N) return STS_EINVAL;
   }
   if (sparse && (int64_t)p->kmax * page > 0x7fffffffll - 65536) return STS_EUNSUPPORTED;
+  if ((p->k_new == nullptr) != (p->v_new == nullptr)) return STS_EINVAL;
+  if (p->k_new && (reinterpret_cast<uintptr_t>(p->k_new) % 16 != 0 || reinterpret_cast<uintptr_t>(p->v_new) % 16 != 0))
+    return STS_EUNSUPPORTED;
   return STS_OK;
 }
 
@@ -185,6 +188,9 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
   a.table_stride = p->table_stride;
   a.num_pages = p->num_pages;
   a.stride_page = p->kv_stride_page;
+  a.k_new = static_cast<const uint16_t *>(p->k_new);
+  a.v_new = static_cast<const uint16_t *>(p->v_new);
+  a.causal = p->causal;
   a.num_units = pl.num_units;
   a.num_splits = pl.num_splits;
   a.scale = p->scale;
@@ -350,7 +356,7 @@ const char *sts_strerror(sts_status s) {
   return "unknown status";
 }
 
-int sts_version(void) { return 101; }
+int sts_version(void) { return 102; }
 
 void sts_prof_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);

@@ -467,6 +467,39 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs A, con
       mstar = mnew;
     }
   }
+  // The speculative block's own tokens: candidate tq also attends to candidates 0..tq (all of
+  // them when not causal). The 16 threads of a row each hold D/16 channels: partial dot
+  // products are summed across the row's 16 lanes, then merged like one more split, in order.
+  if (A.k_new) {
+    typedef typename Chunk<D>::type seg_t;          // D/16 bf16 values = 16 or 8 bytes
+    auto widen = [](uint32_t w, int hi) -> float {
+      return __builtin_bit_cast(float, hi ? (w & 0xffff0000u) : (w << 16));
+    };
+    const seg_t qw = *reinterpret_cast<const seg_t *>(A.q + (((size_t)bt * A.Tq + tq) * A.Hq + head) * D + seg * SEGF);
+    const int nnew = A.causal ? tq + 1 : A.Tq;
+    for (int j = 0; j < A.Tq; ++j) {               // same trip count for every row of the wave
+      const size_t nrow = (((size_t)bt * A.Tq + j) * A.Hkv + g) * D + seg * SEGF;
+      const seg_t kw = *reinterpret_cast<const seg_t *>(A.k_new + nrow);
+      const seg_t vw = *reinterpret_cast<const seg_t *>(A.v_new + nrow);
+      float dot = 0.f;
+#pragma unroll
+      for (int e = 0; e < SEGF; ++e) dot += widen(qw[e >> 1], e & 1) * widen(kw[e >> 1], e & 1);
+      dot += __shfl_xor(dot, 1, 64);
+      dot += __shfl_xor(dot, 2, 64);
+      dot += __shfl_xor(dot, 4, 64);
+      dot += __shfl_xor(dot, 8, 64);
+      if (j < nnew) {
+        const float sj = dot * A.scale_log2;
+        const float mnew = fmaxf(mstar, sj);
+        const float fo = __builtin_amdgcn_exp2f(mstar - mnew);
+        const float fn = __builtin_amdgcn_exp2f(sj - mnew);
+        L = L * fo + fn;
+#pragma unroll
+        for (int e = 0; e < SEGF; ++e) o[e] = o[e] * fo + fn * widen(vw[e >> 1], e & 1);
+        mstar = mnew;
+      }
+    }
+  }
   const float inv = (L > 0.f) ? 1.f / L : 0.f;
   const size_t orow = (((size_t)bt * A.Tq + tq) * A.Hq + head) * D + seg * SEGF;
   if (A.out_dtype == STS_F32) {

@@ -36,6 +36,8 @@ struct AttnArgs {
   const int32_t *block_table;             // [B, table_stride] logical block -> physical page, or NULL
   int32_t table_stride, num_pages;
   int64_t stride_page;                    // elements between pages of the pool
+  const uint16_t *k_new, *v_new;          // [B,Tq,Hkv,d] the block's own keys/values, or NULL
+  int32_t causal;
   float scale_log2;                       // scale * log2(e)
   float scale;
   float *part_o;                          // [B*U*S][NQ*16][D]

@@ -227,3 +227,62 @@ def test_sampling_ranges_touch_only_requested_heads():
     part = oracle.attn(qb, kb, vb, 0.3, batches=range(1, 2), heads=range(1, 3))
     np.testing.assert_array_equal(part["out"][1, :, 1:3], full["out"][1, :, 1:3])
     assert (part["out"][0] == 0).all() and (part["out"][1, :, 0] == 0).all()
+
+
+# ---------------------------------------------------------- the block's own causal keys
+
+
+def _tail_case(seed, B=2, Tq=4, Hq=4, Hkv=2, d=16, N=29):
+    q, k, v = rand_case(seed, B, Tq, Hq, Hkv, d, N)
+    g = torch.Generator().manual_seed(seed + 100)
+    kn = torch.randn(B, Tq, Hkv, d, generator=g).to(torch.bfloat16)
+    vn = torch.randn(B, Tq, Hkv, d, generator=g).to(torch.bfloat16)
+    return q, k, v, kn, vn
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_block_tail_matches_sdpa_on_the_concatenated_cache(causal):
+    """Verification attends to the cached prefix (restricted to the index set) plus the
+    speculative block's own tokens, candidate i seeing candidates 0..i (Section 2.1: all
+    candidates are verified in one parallel step). Pin: torch SDPA over [K; K_new] with the
+    explicit boolean mask."""
+    q, k, v, kn, vn = _tail_case(31)
+    B, Tq, Hq, d = q.shape
+    Hkv, N = k.shape[1], k.shape[2]
+    G = Hq // Hkv
+    idx = rand_indices(31, B, Hq, N, 7)
+    r = oracle.attn(*map(oracle.bf16_bits, (q, k, v)), 0.3, idx,
+                    k_new=oracle.bf16_bits(kn), v_new=oracle.bf16_bits(vn), causal=causal)
+    kc = torch.cat([k, kn.permute(0, 2, 1, 3)], dim=2).float().repeat_interleave(G, 1)   # [B,Hq,N+Tq,d]
+    vc = torch.cat([v, vn.permute(0, 2, 1, 3)], dim=2).float().repeat_interleave(G, 1)
+    mask = torch.zeros(B, Hq, Tq, N + Tq, dtype=torch.bool)
+    for b in range(B):
+        for t in range(Hq):
+            mask[b, t, :, torch.from_numpy(idx[b, t]).long()] = True
+    for i in range(Tq):
+        mask[:, :, i, N:N + (i + 1 if causal else Tq)] = True
+    ref = torch.nn.functional.scaled_dot_product_attention(q.float().permute(0, 2, 1, 3), kc, vc,
+                                                           attn_mask=mask, scale=0.3).permute(0, 2, 1, 3)
+    np.testing.assert_allclose(r["out"], ref.numpy(), rtol=2e-5, atol=2e-6)
+
+
+def test_block_tail_non_causal_equals_dense_over_longer_cache_and_empty_prefix():
+    q, k, v, kn, vn = _tail_case(32)
+    B, Tq, Hq, d = q.shape
+    N = k.shape[2]
+    qb, kb, vb, knb, vnb = map(oracle.bf16_bits, (q, k, v, kn, vn))
+    r = oracle.attn(qb, kb, vb, 0.3, k_new=knb, v_new=vnb, causal=False)
+    kc = torch.cat([k, kn.permute(0, 2, 1, 3)], dim=2).contiguous()
+    vc = torch.cat([v, vn.permute(0, 2, 1, 3)], dim=2).contiguous()
+    d2 = oracle.attn(qb, oracle.bf16_bits(kc), oracle.bf16_bits(vc), 0.3)
+    np.testing.assert_allclose(r["out"], d2["out"], rtol=1e-6, atol=1e-7)
+    np.testing.assert_allclose(r["lse"], d2["lse"], rtol=1e-6, atol=1e-6)
+    # empty index rows: candidate 0 sees only itself -> its own value row and its own logit
+    idx = np.zeros((B, Hq, 1), np.int32)
+    cnt = np.zeros((B, Hq), np.int32)
+    e = oracle.attn(qb, kb, vb, 0.3, idx, cnt, k_new=knb, v_new=vnb, causal=True)
+    G = Hq // k.shape[1]
+    for t in range(Hq):
+        np.testing.assert_allclose(e["out"][:, 0, t], vn[:, 0, t // G].float().numpy(), rtol=1e-6, atol=1e-30)
+        s00 = 0.3 * (q[:, 0, t].double() * kn[:, 0, t // G].double()).sum(-1)
+        np.testing.assert_allclose(e["lse"][:, t, 0], s00.numpy(), rtol=1e-6, atol=1e-6)

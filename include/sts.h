@@ -146,6 +146,33 @@ typedef struct {
   size_t workspace_bytes;
 } sts_attn_params;
 
+/* ----------------------------------------------------------------------------------------
+ * sts_head_map -- offline head-mapping construction (paper Algorithm 1, Section 4.1).
+ *
+ * Traces are attention-weight rows of both models over the same inputs: a_d [S,Hd,R,N] and
+ * a_t [S,Ht,R,N] (S samples, R query rows per sample, N keys). For every target head the
+ * draft head whose top-k index sets share the most indices with the target head's, the
+ * overlap being summed over all S*R rows; a later draft head must beat the running maximum
+ * strictly, so the first draft head reaching the maximum wins, and a target head with no
+ * overlap at all maps to draft head 0. Top-k uses sts_select's order (ties to the lower
+ * index). One map per k. Not on the serving path: it runs once, offline.
+ *
+ * Supported: N < 2^31 - 2^16, 1 <= Hd, Ht; S*R*max(Hd,Ht) rows are processed in slices.
+ */
+typedef struct {
+  int32_t S, R, Hd, Ht, N;
+  int32_t k;                /* top-k size, >= 1 (k >= N keeps every index) */
+  const float *a_d;         /* [dev] [S,Hd,R,N] fp32 contiguous */
+  const float *a_t;         /* [dev] [S,Ht,R,N] fp32 contiguous */
+  int32_t *map;             /* [dev] out [Ht] target head -> draft head */
+  unsigned long long *overlap; /* [dev] out [Ht,Hd] summed intersection sizes; may be NULL */
+  void *workspace;          /* [dev] 256-byte aligned scratch */
+  size_t workspace_bytes;
+} sts_headmap_params;
+
+size_t sts_headmap_workspace_bytes(const sts_headmap_params *p);
+sts_status sts_head_map(const sts_headmap_params *p, void *stream);
+
 size_t sts_select_workspace_bytes(const sts_select_params *p);
 size_t sts_attn_workspace_bytes(const sts_attn_params *p, int sparse);
 
@@ -173,7 +200,8 @@ typedef enum {
   STS_K_ATTN_DENSE = 6,    /* split dense flash-decode */
   STS_K_ATTN_COMBINE = 7,  /* split combine */
   STS_K_SELECT_BLOCK = 8,  /* per-block score sums + first-digit histogram (page_size > 1) */
-  STS_K_COUNT_ = 9
+  STS_K_HEADMAP = 9,       /* Algorithm 1: overlap counting and argmax */
+  STS_K_COUNT_ = 10
 } sts_kernel_kind;
 #define STS_PROF_MAX 4096
 

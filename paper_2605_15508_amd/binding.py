@@ -15,12 +15,13 @@ STS_SCORES_PROBS, STS_SCORES_LOGITS_LSE = 0, 1
 STS_REDUCE_SUM, STS_REDUCE_MAX = 0, 1
 STS_BF16, STS_F32 = 0, 1
 KERNEL_KINDS = {"select_clear": 0, "select_agg": 1, "select_hist": 2, "select_count": 3,
-                "select_write": 4, "attn_sparse": 5, "attn_dense": 6, "attn_combine": 7, "select_block": 8}
+                "select_write": 4, "attn_sparse": 5, "attn_dense": 6, "attn_combine": 7, "select_block": 8,
+                "headmap": 9}
 
 # every symbol include/sts.h declares
 EXPORTS = ["sts_select_workspace_bytes", "sts_attn_workspace_bytes", "sts_select", "sts_sparse_attn",
            "sts_dense_attn", "sts_strerror", "sts_version", "sts_prof_enable", "sts_prof_reset",
-           "sts_prof_read", "sts_attn_plan"]
+           "sts_prof_read", "sts_attn_plan", "sts_head_map", "sts_headmap_workspace_bytes"]
 
 
 class StsError(RuntimeError):
@@ -51,6 +52,13 @@ class AttnParams(ctypes.Structure):
                 ("num_pages", ctypes.c_int32), ("kv_stride_page", ctypes.c_int64),
                 ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p), ("causal", ctypes.c_int32),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+
+
+class HeadmapParams(ctypes.Structure):
+    _fields_ = [("S", ctypes.c_int32), ("R", ctypes.c_int32), ("Hd", ctypes.c_int32), ("Ht", ctypes.c_int32),
+                ("N", ctypes.c_int32), ("k", ctypes.c_int32), ("a_d", ctypes.c_void_p), ("a_t", ctypes.c_void_p),
+                ("map", ctypes.c_void_p), ("overlap", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
+                ("workspace_bytes", ctypes.c_size_t)]
 
 
 _lib = None
@@ -85,6 +93,10 @@ def load_library():
     lib.sts_prof_reset.restype = None
     lib.sts_prof_read.restype = ctypes.c_int
     lib.sts_prof_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_double)]
+    lib.sts_headmap_workspace_bytes.restype = ctypes.c_size_t
+    lib.sts_headmap_workspace_bytes.argtypes = [ctypes.POINTER(HeadmapParams)]
+    lib.sts_head_map.restype = ctypes.c_int
+    lib.sts_head_map.argtypes = [ctypes.POINTER(HeadmapParams), ctypes.c_void_p]
     lib.sts_attn_plan.restype = ctypes.c_int
     lib.sts_attn_plan.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_int] + [ctypes.POINTER(ctypes.c_int32)] * 3
     _lib = lib
@@ -271,6 +283,29 @@ def sts_dense_attn(q, k, v, scale, seq_lens=None, out=None, out_dtype=None, want
                      want_lse=want_lse, want_logits=want_logits, workspace=workspace,
                      lse_out=lse_out, logits_out=logits_out, page_size=page_size,
                      block_table=block_table, N=N, k_new=k_new, v_new=v_new, causal=causal)
+
+
+def sts_head_map(a_d, a_t, k: int, workspace=None):
+    """Algorithm 1 on the GPU. a_d [S,Hd,R,N], a_t [S,Ht,R,N] fp32 attention-weight traces
+    (device) -> (map [Ht] int32, overlap [Ht,Hd] int64). See sts_head_map in include/sts.h."""
+    import torch
+
+    lib = load_library()
+    for t in (a_d, a_t):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.dim() == 4
+    S, Hd, R, N = a_d.shape
+    St, Ht, Rt, Nt = a_t.shape
+    assert (St, Rt, Nt) == (S, R, N)
+    dev = a_d.device
+    mp = torch.empty(Ht, dtype=torch.int32, device=dev)
+    ov = torch.empty(Ht, Hd, dtype=torch.int64, device=dev)
+    p = HeadmapParams(S=S, R=R, Hd=Hd, Ht=Ht, N=N, k=int(k), a_d=_ptr(a_d), a_t=_ptr(a_t), map=_ptr(mp),
+                      overlap=_ptr(ov), workspace=None, workspace_bytes=0)
+    need = lib.sts_headmap_workspace_bytes(ctypes.byref(p))
+    ws = workspace if workspace is not None else _workspace("headmap", need, dev)
+    p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()
+    _check(lib.sts_head_map(ctypes.byref(p), _stream()), "sts_head_map")
+    return mp, ov
 
 
 def attn_plan(q, k, sparse: bool, kmax: int = 0, head_map=None, page_size: int = 1) -> Dict[str, int]:

@@ -274,7 +274,7 @@ size_t sts_select_workspace_bytes(const sts_select_params *p) {
   return n ? n : 256;
 }
 
-sts_status sts_select(const sts_select_params *p, void *stream) {
+static sts_status enqueue_select(const sts_select_params *p, void *stream) {
   SelectPlan pl;
   const sts_status v = plan_select(p, pl);
   if (v != STS_OK) return v;
@@ -345,6 +345,108 @@ sts_status sts_select(const sts_select_params *p, void *stream) {
   return rc == hipSuccess ? STS_OK : STS_EHIP;
 }
 
+sts_status sts_select(const sts_select_params *p, void *stream) { return enqueue_select(p, stream); }
+
+// ---------------------------------------------------------------------------- head mapping
+namespace {
+constexpr int HM_SLICE = 32768;   // rows per selection launch (grid.y limit)
+
+struct HeadmapPlan {
+  size_t idx_d_bytes, idx_t_bytes, overlap_bytes, select_bytes;
+};
+
+sts_status plan_headmap(const sts_headmap_params *p, HeadmapPlan &pl) {
+  if (!p) return STS_EINVAL;
+  if (p->S < 0 || p->R < 0 || p->Hd < 1 || p->Ht < 1 || p->N < 0 || p->k < 1) return STS_EINVAL;
+  if ((int64_t)p->N > 0x7fffffffll - 65536) return STS_EUNSUPPORTED;
+  const size_t rows_d = (size_t)p->S * p->Hd * p->R, rows_t = (size_t)p->S * p->Ht * p->R;
+  if (rows_d > 0x7fffffffull || rows_t > 0x7fffffffull || (size_t)p->S * p->R > 0x7fffffffull) return STS_EUNSUPPORTED;
+  if (p->Ht > 65535) return STS_EUNSUPPORTED;
+  pl.idx_d_bytes = align256(rows_d * (size_t)p->k * sizeof(int32_t));
+  pl.idx_t_bytes = align256(rows_t * (size_t)p->k * sizeof(int32_t));
+  pl.overlap_bytes = align256((size_t)p->Ht * p->Hd * sizeof(unsigned long long));
+  // one selection slice at a time: B = rows of the slice, one draft head, one query row
+  sts_select_params sp;
+  memset(&sp, 0, sizeof(sp));
+  const size_t big = rows_d > rows_t ? rows_d : rows_t;
+  sp.B = (int32_t)(big < (size_t)HM_SLICE ? big : (size_t)HM_SLICE);
+  sp.Hd = 1; sp.Tq = 1; sp.N = p->N; sp.Hq = 1; sp.k = p->k;
+  SelectPlan spl;
+  const sts_status v = plan_select(&sp, spl);
+  if (v != STS_OK) return v;
+  pl.select_bytes = spl.agg_bytes + spl.blk_bytes + spl.hist_bytes + spl.state_bytes + spl.chunk_bytes;
+  return STS_OK;
+}
+
+// top-k index lists of every row of one trace, slice by slice, through the selection pipeline
+sts_status select_rows(const float *trace, size_t rows, int N, int k, int32_t *idx, void *ws, size_t ws_bytes,
+                       void *stream) {
+  static const int32_t identity[1] = {0};
+  for (size_t r0 = 0; r0 < rows; r0 += HM_SLICE) {
+    sts_select_params sp;
+    memset(&sp, 0, sizeof(sp));
+    sp.B = (int32_t)(rows - r0 < (size_t)HM_SLICE ? rows - r0 : (size_t)HM_SLICE);
+    sp.Hd = 1; sp.Tq = 1; sp.N = N; sp.Hq = 1; sp.k = k;
+    sp.scores = trace + r0 * (size_t)N;
+    sp.head_map = identity;
+    sp.indices = idx + r0 * (size_t)k;
+    sp.kind = STS_SCORES_PROBS;
+    sp.reduce = STS_REDUCE_SUM;
+    sp.workspace = ws;
+    sp.workspace_bytes = ws_bytes;
+    const sts_status v = enqueue_select(&sp, stream);
+    if (v != STS_OK) return v;
+  }
+  return STS_OK;
+}
+}  // namespace
+
+size_t sts_headmap_workspace_bytes(const sts_headmap_params *p) {
+  HeadmapPlan pl;
+  if (plan_headmap(p, pl) != STS_OK) return 0;
+  return pl.idx_d_bytes + pl.idx_t_bytes + pl.overlap_bytes + pl.select_bytes + 256;
+}
+
+sts_status sts_head_map(const sts_headmap_params *p, void *stream) {
+  HeadmapPlan pl;
+  const sts_status v = plan_headmap(p, pl);
+  if (v != STS_OK) return v;
+  if (!p->map) return STS_EINVAL;
+  const bool have_rows = (size_t)p->S * p->R > 0 && p->N > 0;
+  if (have_rows && (!p->a_d || !p->a_t)) return STS_EINVAL;
+  const size_t need = pl.idx_d_bytes + pl.idx_t_bytes + pl.overlap_bytes + pl.select_bytes;
+  if (!p->workspace || p->workspace_bytes < need) return STS_EWORKSPACE;
+  if (reinterpret_cast<uintptr_t>(p->workspace) % 256 != 0) return STS_EWORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned char *w = static_cast<unsigned char *>(p->workspace);
+  int32_t *idx_d = reinterpret_cast<int32_t *>(w);
+  w += pl.idx_d_bytes;
+  int32_t *idx_t = reinterpret_cast<int32_t *>(w);
+  w += pl.idx_t_bytes;
+  // the counts accumulate in the caller's buffer when one is given
+  unsigned long long *ov = p->overlap ? p->overlap : reinterpret_cast<unsigned long long *>(w);
+  w += pl.overlap_bytes;
+  void *sel_ws = w;
+
+  const int c = p->k < p->N ? p->k : p->N;
+  if (have_rows) {
+    sts_status rc = select_rows(p->a_d, (size_t)p->S * p->Hd * p->R, p->N, p->k, idx_d, sel_ws, pl.select_bytes, stream);
+    if (rc != STS_OK) return rc;
+    rc = select_rows(p->a_t, (size_t)p->S * p->Ht * p->R, p->N, p->k, idx_t, sel_ws, pl.select_bytes, stream);
+    if (rc != STS_OK) return rc;
+  }
+  hipError_t e = run_kernel(STS_K_HEADMAP, s, [&] { return launch_headmap_clear(ov, p->Ht * p->Hd, s); });
+  if (e != hipSuccess) return STS_EHIP;
+  if (have_rows) {
+    e = run_kernel(STS_K_HEADMAP, s, [&] {
+      return launch_headmap_overlap(idx_d, idx_t, p->S, p->R, p->Hd, p->Ht, p->k, c, ov, s);
+    });
+    if (e != hipSuccess) return STS_EHIP;
+  }
+  e = run_kernel(STS_K_HEADMAP, s, [&] { return launch_headmap_argmax(ov, p->Hd, p->Ht, p->map, s); });
+  return e == hipSuccess ? STS_OK : STS_EHIP;
+}
+
 const char *sts_strerror(sts_status s) {
   switch (s) {
     case STS_OK: return "ok";
@@ -356,7 +458,7 @@ const char *sts_strerror(sts_status s) {
   return "unknown status";
 }
 
-int sts_version(void) { return 102; }
+int sts_version(void) { return 103; }
 
 void sts_prof_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);

@@ -95,3 +95,7 @@ hipError_t launch_select_block(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t s);
 hipError_t launch_select_count(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_write(const SelectArgs &a, hipStream_t s);
+hipError_t launch_headmap_clear(unsigned long long *overlap, int n, hipStream_t s);
+hipError_t launch_headmap_overlap(const int32_t *idx_d, const int32_t *idx_t, int S, int R, int Hd, int Ht,
+                                  int k, int c, unsigned long long *overlap, hipStream_t s);
+hipError_t launch_headmap_argmax(const unsigned long long *overlap, int Hd, int Ht, int32_t *map, hipStream_t s);

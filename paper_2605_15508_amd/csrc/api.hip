@@ -140,7 +140,10 @@ sts_status plan_attn(const sts_attn_params *p, int sparse, AttnPlan &pl) {
   }
   const int64_t units_total = (int64_t)p->B * nu;
   int64_t S = units_total > 0 ? resident / units_total : 1;
-  const int64_t s_cap = (tiles + STS_WG_WAVES - 1) / STS_WG_WAVES;   // >= 1 tile per wave
+  // at least two tiles per wave, so that the partials and their combine stay small next to
+  // the gathered bytes; a list of up to 16 tiles is not split at all (its workgroup writes
+  // the result itself, one launch instead of two)
+  const int64_t s_cap = tiles <= 16 ? 1 : (tiles + 2 * STS_WG_WAVES - 1) / (2 * STS_WG_WAVES);
   if (S > s_cap) S = s_cap;
   if (S > 256) S = 256;
   if (S < 1) S = 1;
@@ -191,6 +194,7 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
   a.k_new = static_cast<const uint16_t *>(p->k_new);
   a.v_new = static_cast<const uint16_t *>(p->v_new);
   a.causal = p->causal;
+  a.direct = (pl.num_splits == 1 && !p->k_new) ? 1 : 0;
   a.num_units = pl.num_units;
   a.num_splits = pl.num_splits;
   a.scale = p->scale;
@@ -206,6 +210,7 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
   hipError_t rc = run_kernel(sparse ? STS_K_ATTN_SPARSE : STS_K_ATTN_DENSE, s,
                              [&] { return launch_attn_split(a, p->d, pl.nq, sparse != 0, s); });
   if (rc != hipSuccess) return STS_EHIP;
+  if (a.direct) return STS_OK;
   rc = run_kernel(STS_K_ATTN_COMBINE, s, [&] { return launch_attn_combine(a, p->d, pl.nq, s); });
   return rc == hipSuccess ? STS_OK : STS_EHIP;
 }

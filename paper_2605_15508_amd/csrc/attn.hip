@@ -389,6 +389,45 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
           sum[e] += x[0]; sum[e + 1] += x[1]; sum[e + 2] += x[2]; sum[e + 3] += x[3];
         }
       }
+      if (A.direct) {
+        // single split and nothing to append: this workgroup holds the whole result of its
+        // rows, so it normalises and writes them itself and no combine kernel is launched
+        const int r = nq * 16 + row;
+        if (r < rows_valid) {
+          float ms = -INFINITY;
+#pragma unroll
+          for (int w = 0; w < STS_WG_WAVES; ++w) ms = fmaxf(ms, lds_ml[w][r][0]);
+          float L = 0.f;
+#pragma unroll
+          for (int w = 0; w < STS_WG_WAVES; ++w) {
+            const float mw = lds_ml[w][r][0];
+            L += (mw == -INFINITY) ? 0.f : lds_ml[w][r][1] * __builtin_amdgcn_exp2f(mw - ms);
+          }
+          const float inv = (L > 0.f) ? 1.f / L : 0.f;
+          const int hsel = r / A.Tq, tq = r - hsel * A.Tq;
+          const int head = g * A.G + nth_member(mask, hsel);
+          const size_t orow = (((size_t)bt * A.Tq + tq) * A.Hq + head) * D + seg * SEGF;
+          if (A.out_dtype == STS_F32) {
+            float *dst = reinterpret_cast<float *>(A.out) + orow;
+#pragma unroll
+            for (int e = 0; e < SEGF; e += 4)
+              *reinterpret_cast<f32x4 *>(dst + e) =
+                  f32x4{sum[e] * inv, sum[e + 1] * inv, sum[e + 2] * inv, sum[e + 3] * inv};
+          } else {
+            uint32_t *dst = reinterpret_cast<uint32_t *>(reinterpret_cast<uint16_t *>(A.out) + orow);
+#pragma unroll
+            for (int e = 0; e < SEGF; e += 2) {
+              const f32x2 pr = {sum[e] * inv, sum[e + 1] * inv};
+              dst[e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+            }
+          }
+          if (A.lse_out && seg == 0) {
+            const float ln2 = 0.69314718055994530942f;
+            A.lse_out[((size_t)bt * A.Hq + head) * A.Tq + tq] =
+                (L > 0.f) ? (ms + __builtin_amdgcn_logf(L)) * ln2 : -INFINITY;
+          }
+        }
+      } else {
       float *dst = po + (size_t)(nq * 16 + row) * D + seg * SEGF;
 #pragma unroll
       for (int e = 0; e < SEGF; e += 4)
@@ -406,6 +445,7 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
         }
         pml[r * 2 + 0] = ms;
         pml[r * 2 + 1] = L;
+      }
       }
     }
     __syncthreads();

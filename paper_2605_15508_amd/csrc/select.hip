@@ -275,6 +275,23 @@ __global__ void __launch_bounds__(SEL_THREADS) select_hist_kernel(const SelectAr
   if (c == 0) return;
   uint32_t *st = A.state + (size_t)row * 8;
   const uint32_t *gh = A.hist + (size_t)row * 3 * SEL_BINS;
+  const float *a = A.src + (size_t)row * A.srcN;
+  const int n0 = chunk * SEL_CHUNK;
+  const int n1 = min(min(n0 + SEL_CHUNK, A.srcN), nb);
+  // The chunk's loads do not depend on the digit search: issue them first so that their
+  // latency hides behind it. They are unconditional (a branch around a load makes the compiler
+  // wait for it at the join): the address is clamped into the row, out-of-range quads are
+  // ignored when counting.
+  constexpr int IT = SEL_CHUNK / (SEL_THREADS * 4);
+  f32x4 x[IT];
+  if (VEC4) {
+#pragma unroll
+    for (int i = 0; i < IT; ++i) {
+      const int n = n0 + (i * SEL_THREADS + threadIdx.x) * 4;
+      x[i] = *reinterpret_cast<const f32x4 *>(a + min(n, A.srcN - 4));
+    }
+  }
+  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) h[i] = 0u;
   uint32_t prefix, shift, dmask;
   if (PASS == 1) {
     uint32_t d0, k1;
@@ -293,17 +310,14 @@ __global__ void __launch_bounds__(SEL_THREADS) select_hist_kernel(const SelectAr
     dmask = (1u << SEL_BITS2) - 1;
   }
   const uint32_t dshift = (PASS == 1) ? SEL_BITS2 : 0;
-  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) h[i] = 0u;
-  __syncthreads();
-  const float *a = A.src + (size_t)row * A.srcN;
-  const int n0 = chunk * SEL_CHUNK;
-  const int n1 = min(min(n0 + SEL_CHUNK, A.srcN), nb);
+  // (the barriers inside find_digit have published the zeroed histogram)
   if (VEC4) {
-    for (int n = n0 + threadIdx.x * 4; n < n1; n += SEL_THREADS * 4) {
-      const f32x4 x = *reinterpret_cast<const f32x4 *>(a + n);
+#pragma unroll
+    for (int i = 0; i < IT; ++i) {
+      const int n = n0 + (i * SEL_THREADS + threadIdx.x) * 4;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const uint32_t key = key_of(x[e]);
+        const uint32_t key = key_of(x[i][e]);
         if (n + e < n1 && (key >> shift) == prefix) atomicAdd(&h[(key >> dshift) & dmask], 1u);
       }
     }
@@ -330,20 +344,31 @@ __global__ void __launch_bounds__(SEL_THREADS) select_count_kernel(const SelectA
   if (c == 0) return;
   uint32_t *st = A.state + (size_t)row * 8;
   const uint32_t *gh = A.hist + (size_t)row * 3 * SEL_BINS;
+  const float *a = A.src + (size_t)row * A.srcN;
+  const int n0 = chunk * SEL_CHUNK;
+  const int n1 = min(min(n0 + SEL_CHUNK, A.srcN), nb);
+  // loads first (clamped, unconditional), digit search second: see select_hist_kernel
+  constexpr int IT = SEL_CHUNK / (SEL_THREADS * 4);
+  f32x4 x[IT];
+  if (VEC4) {
+#pragma unroll
+    for (int i = 0; i < IT; ++i) {
+      const int n = n0 + (i * SEL_THREADS + threadIdx.x) * 4;
+      x[i] = *reinterpret_cast<const f32x4 *>(a + min(n, A.srcN - 4));
+    }
+  }
   uint32_t d2, r;
   find_digit<(1 << SEL_BITS2)>(gh + 2 * SEL_BINS, st[3], tmp, d2, r);
   const uint32_t T = (st[0] << (SEL_BITS1 + SEL_BITS2)) | (st[2] << SEL_BITS2) | d2;
   if (chunk == 0 && threadIdx.x == 0) { st[4] = T; st[5] = r; }
-  const float *a = A.src + (size_t)row * A.srcN;
-  const int n0 = chunk * SEL_CHUNK;
-  const int n1 = min(min(n0 + SEL_CHUNK, A.srcN), nb);
   uint32_t packed = 0;   // greater in the low half, equal in the high half (<= 8192 each)
   if (VEC4) {
-    for (int n = n0 + threadIdx.x * 4; n < n1; n += SEL_THREADS * 4) {
-      const f32x4 x = *reinterpret_cast<const f32x4 *>(a + n);
+#pragma unroll
+    for (int i = 0; i < IT; ++i) {
+      const int n = n0 + (i * SEL_THREADS + threadIdx.x) * 4;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const uint32_t key = key_of(x[e]);
+        const uint32_t key = key_of(x[i][e]);
         if (n + e < n1) packed += (key > T ? 1u : 0u) + (key == T ? 0x10000u : 0u);
       }
     }

@@ -248,6 +248,14 @@ def main():
     b_set = B * units * kb * page * row_bytes               # gathered once per distinct index row
     b_req = B * Hq * kb * page * row_bytes                  # gathered per query head
     b_dense = B * Hkv * N * row_bytes
+    # union of the rows requested per (batch, KV head): what perfect reuse between the sets of a
+    # KV group would have to move (reported beside B_set so cache reuse cannot hide in it)
+    G = Hq // Hkv
+    seen = torch.zeros(B, Hkv, -(-N // page), dtype=torch.bool, device=dev)
+    ii = idx.view(B, Hkv, G * kb).long().clamp_(0, seen.shape[2] - 1)
+    seen.scatter_(2, ii, True)
+    b_uniq = int(seen.sum().item()) * page * row_bytes
+    del seen, ii
     achieved = b_set / (split_us * 1e-6) / 1e9 if split_us > 0 else 0.0
     workload = (f"{cfg.name}: B{B} N{N} Hq{Hq}/Hkv{Hkv} d{d} Tq{Tq} Hd{Hd} budget "
                 f"{kb * page} tokens ({kb * page / N:.1%})"
@@ -273,7 +281,9 @@ def main():
         "select_us": {"mean": round(select_us[0], 2), "median": round(select_us[1], 2), "min": round(select_us[2], 2)},
         "speedup_vs_dense": round(dense_us[0] / sparse_us[0], 3) if not args.no_dense and sparse_us[0] > 0 else None,
         "gathered_kv_gbs": {"b_set": round(b_set / (sparse_us[0] * 1e-6) / 1e9, 1),
-                            "b_req": round(b_req / (sparse_us[0] * 1e-6) / 1e9, 1)},
+                            "b_req": round(b_req / (sparse_us[0] * 1e-6) / 1e9, 1),
+                            "b_uniq": round(b_uniq / (sparse_us[0] * 1e-6) / 1e9, 1)},
+        "gathered_kv_bytes": {"b_set": b_set, "b_req": b_req, "b_uniq": b_uniq, "dense": b_dense},
         "dense_kv_gbs": round(b_dense / (dense_us[0] * 1e-6) / 1e9, 1) if not args.no_dense else None,
         "kernel_us": {k: round(ms * 1e3 / n, 2) for k, (n, ms) in prof.items() if n},
         "launch": plan,

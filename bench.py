@@ -295,6 +295,15 @@ def main():
         },
         "paper_context": "2.67x end-to-end speedup at ~90% sparsity on NVIDIA H20 (other hardware, whole serving stack)",
     }
+    agg_n, agg_ms = prof["select_agg"]
+    if agg_n:
+        # the one HBM-bound kernel of the selection: reads Tq rows of scores, writes one row of A
+        src_rows = B * Hd * (Tq * N + N) * 4
+        agg_us = agg_ms * 1e3 / agg_n
+        result["roofline_select_agg"] = {"bound": "hbm", "achieved": round(src_rows / (agg_us * 1e-6) / 1e9, 1),
+                                         "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                         "frac": round(src_rows / (agg_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                                         "algorithmic_bytes_per_launch": src_rows, "avg_launch_us": round(agg_us, 2)}
     if draft is not None:
         result["draft_attn_us"] = {"mean": round(draft_us[0], 2), "median": round(draft_us[1], 2)}
     if dsplit_n:

@@ -99,3 +99,50 @@ def test_product_path_has_no_oracle_import():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in text and "from oracle" not in text and "sts_oracle" not in text
+
+
+def test_split_policy_is_a_function_of_the_shape_only(lib):
+    """Deterministic results need a split count that depends on nothing but the shape."""
+    def plan(**kw):
+        p = attn_params(**kw)
+        s, u, nq = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+        assert lib.sts_attn_plan(ctypes.byref(p), kw.pop("_sparse", 1), ctypes.byref(s), ctypes.byref(u),
+                                 ctypes.byref(nq)) == 0
+        return s.value, u.value, nq.value
+    # a short list is not split at all (its workgroup writes the result itself)
+    assert plan(kmax=410)[0] == 1
+    assert plan(kmax=512)[0] == 1
+    # longer lists: at least two 32-key tiles per wave of the 4-wave workgroup
+    s, u, _ = plan(kmax=3277)
+    assert 1 < s <= (3277 // 32 + 1 + 7) // 8
+    # block granularity counts tiles in tokens
+    assert plan(kmax=52, page_size=8)[0] == plan(kmax=410)[0]
+    big = plan(B=4, N=131072, kmax=13108, kv_stride_b=8 * 131072 * 128, kv_stride_h=131072 * 128)
+    assert big[0] >= 1 and big == plan(B=4, N=131072, kmax=13108, kv_stride_b=8 * 131072 * 128,
+                                       kv_stride_h=131072 * 128)
+
+
+def test_page_and_tail_argument_validation(lib):
+    assert lib.sts_attn_workspace_bytes(ctypes.byref(attn_params(page_size=8)), 1) > 0
+    for bad in (attn_params(page_size=3), attn_params(page_size=64), attn_params(page_size=-1 * 0 + 5)):
+        assert lib.sts_attn_workspace_bytes(ctypes.byref(bad), 1) == 0
+    # a page table needs a pool size, a page stride and enough entries for N
+    assert lib.sts_attn_workspace_bytes(ctypes.byref(attn_params(page_size=8, block_table=256, table_stride=512,
+                                                                 num_pages=600, kv_stride_page=8 * 8 * 128)), 1) > 0
+    for bad in (attn_params(page_size=8, block_table=256, table_stride=100, num_pages=600, kv_stride_page=8192),
+                attn_params(page_size=8, block_table=256, table_stride=512, num_pages=0, kv_stride_page=8192),
+                attn_params(page_size=8, block_table=256, table_stride=512, num_pages=600, kv_stride_page=0)):
+        assert lib.sts_attn_workspace_bytes(ctypes.byref(bad), 1) == 0
+    # k_new without v_new is refused
+    assert lib.sts_attn_workspace_bytes(ctypes.byref(attn_params(k_new=256)), 1) == 0
+    assert lib.sts_attn_workspace_bytes(ctypes.byref(attn_params(k_new=256, v_new=512)), 1) > 0
+
+
+def test_headmap_argument_validation(lib):
+    p = binding.HeadmapParams(S=2, R=4, Hd=3, Ht=5, N=100, k=10)
+    assert lib.sts_headmap_workspace_bytes(ctypes.byref(p)) > 0
+    assert lib.sts_head_map(ctypes.byref(p), None) == -1          # map missing
+    p.k = 0
+    assert lib.sts_headmap_workspace_bytes(ctypes.byref(p)) == 0
+    sp = binding.SelectParams(B=1, Hd=2, Tq=5, N=1000, Hq=4, k=10, page_size=5000)
+    assert lib.sts_select_workspace_bytes(ctypes.byref(sp)) == 0

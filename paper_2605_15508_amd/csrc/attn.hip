@@ -452,42 +452,56 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
   }
 }
 
-// Combine the per-split partials of one (batch, unit, query tile) in split order and write
-// the final rows. One workgroup of 256 threads: row = tid / 16, D/16 floats per thread.
+// Combine the per-split partials and write the final rows. One workgroup of 256 threads per
+// (batch, unit, query tile, group of 4 rows): wave w merges the splits w, w+4, w+8, ... of its
+// 4 rows (thread = row, D/16 channels; loads in independent batches), the four waves are then
+// merged through LDS in wave order by wave 0, which also appends the block's own tokens and
+// writes the result. The order of all merges is fixed, so results are identical run to run.
 template <int D>
 __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs A, const int NQ) {
   constexpr int SEGF = D / 16;
+  constexpr int BATCH = 4;
+  __shared__ float sm_ml[4][4][2];
+  __shared__ __attribute__((aligned(16))) float sm_o[4][4][D];
   const int S = A.num_splits, U = A.num_units;
-  const int nq = blockIdx.x % NQ;
-  const int u = (blockIdx.x / NQ) % U;
-  const int bt = blockIdx.x / (NQ * U);
+  const int quarter = blockIdx.x & 3;
+  const int nq = (blockIdx.x >> 2) % NQ;
+  const int u = ((blockIdx.x >> 2) / NQ) % U;
+  const int bt = (blockIdx.x >> 2) / (NQ * U);
   const uint32_t unit = A.units.unit[u];
   const int g = unit & 0xff;
   const uint32_t mask = (unit >> 8) & 0xffff;
   const int nheads = (unit >> 24) & 0x1f;
-  const int row = threadIdx.x >> 4, seg = threadIdx.x & 15;
-  const int r = nq * 16 + row;
-  if (r >= nheads * A.Tq) return;
-  const int hsel = r / A.Tq, tq = r - hsel * A.Tq;
-  const int head = g * A.G + nth_member(mask, hsel);
+  const int wave = threadIdx.x >> 6, row4 = (threadIdx.x >> 4) & 3, seg = threadIdx.x & 15;
+  const int r = nq * 16 + quarter * 4 + row4;
+  if (nq * 16 + quarter * 4 >= nheads * A.Tq) return;          // whole workgroup has no valid row
+  const bool valid = r < nheads * A.Tq;
+  const int rr = valid ? r : nq * 16 + quarter * 4;             // padding rows mirror a valid one
   const size_t p0 = ((size_t)bt * U + u) * S;
   const size_t rows_per = (size_t)NQ * 16;
 
-  // Splits are merged in split order with a running maximum (same arithmetic every run);
-  // loads are issued in independent batches of 8 so their latencies overlap.
-  constexpr int BATCH = 8;
   float mstar = -INFINITY, L = 0.f;
   float o[SEGF];
 #pragma unroll
   for (int e = 0; e < SEGF; ++e) o[e] = 0.f;
-  for (int s0 = 0; s0 < S; s0 += BATCH) {
+  auto merge = [&](float ms, float ls, const float *x) {
+    if (ms == -INFINITY) return;
+    const float mnew = fmaxf(mstar, ms);
+    const float fo = __builtin_amdgcn_exp2f(mstar - mnew);   // 0 while nothing is accumulated
+    const float fn = __builtin_amdgcn_exp2f(ms - mnew);
+    L = L * fo + ls * fn;
+#pragma unroll
+    for (int e = 0; e < SEGF; ++e) o[e] = o[e] * fo + x[e] * fn;
+    mstar = mnew;
+  };
+  for (int s0 = wave; s0 < S; s0 += 4 * BATCH) {
     float ms[BATCH], ls[BATCH];
     f32x4 x[BATCH][SEGF / 4];
 #pragma unroll
     for (int j = 0; j < BATCH; ++j) {
-      const int sj = min(s0 + j, S - 1);
-      const size_t pr = (p0 + sj) * rows_per + r;
-      ms[j] = (s0 + j < S) ? A.part_ml[pr * 2] : -INFINITY;
+      const int sj = min(s0 + 4 * j, S - 1);
+      const size_t pr = (p0 + sj) * rows_per + rr;
+      ms[j] = (s0 + 4 * j < S) ? A.part_ml[pr * 2] : -INFINITY;
       ls[j] = A.part_ml[pr * 2 + 1];
       const float *src = A.part_o + pr * D + seg * SEGF;
 #pragma unroll
@@ -495,18 +509,26 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs A, con
     }
 #pragma unroll
     for (int j = 0; j < BATCH; ++j) {
-      if (ms[j] == -INFINITY) continue;
-      const float mnew = fmaxf(mstar, ms[j]);
-      const float fo = __builtin_amdgcn_exp2f(mstar - mnew);   // 0 while nothing is accumulated
-      const float fn = __builtin_amdgcn_exp2f(ms[j] - mnew);
-      L = L * fo + ls[j] * fn;
+      float xs[SEGF];
 #pragma unroll
-      for (int e = 0; e < SEGF / 4; ++e)
-#pragma unroll
-        for (int c4 = 0; c4 < 4; ++c4) o[4 * e + c4] = o[4 * e + c4] * fo + x[j][e][c4] * fn;
-      mstar = mnew;
+      for (int e = 0; e < SEGF; ++e) xs[e] = x[j][e >> 2][e & 3];
+      merge(ms[j], ls[j], xs);
     }
   }
+  if (seg == 0) {
+    sm_ml[wave][row4][0] = mstar;
+    sm_ml[wave][row4][1] = L;
+  }
+#pragma unroll
+  for (int e = 0; e < SEGF; ++e) sm_o[wave][row4][seg * SEGF + e] = o[e];
+  __syncthreads();
+  if (wave != 0 || !valid) return;
+  // wave 0 already holds its own share; fold in waves 1..3 in order
+#pragma unroll
+  for (int w = 1; w < 4; ++w) merge(sm_ml[w][row4][0], sm_ml[w][row4][1], &sm_o[w][row4][seg * SEGF]);
+
+  const int hsel = r / A.Tq, tq = r - hsel * A.Tq;
+  const int head = g * A.G + nth_member(mask, hsel);
   // The speculative block's own tokens: candidate tq also attends to candidates 0..tq (all of
   // them when not causal). The 16 threads of a row each hold D/16 channels: partial dot
   // products are summed across the row's 16 lanes, then merged like one more split, in order.
@@ -529,14 +551,10 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs A, con
       dot += __shfl_xor(dot, 4, 64);
       dot += __shfl_xor(dot, 8, 64);
       if (j < nnew) {
-        const float sj = dot * A.scale_log2;
-        const float mnew = fmaxf(mstar, sj);
-        const float fo = __builtin_amdgcn_exp2f(mstar - mnew);
-        const float fn = __builtin_amdgcn_exp2f(sj - mnew);
-        L = L * fo + fn;
+        float vs[SEGF];
 #pragma unroll
-        for (int e = 0; e < SEGF; ++e) o[e] = o[e] * fo + fn * widen(vw[e >> 1], e & 1);
-        mstar = mnew;
+        for (int e = 0; e < SEGF; ++e) vs[e] = widen(vw[e >> 1], e & 1);
+        merge(dot * A.scale_log2, 1.f, vs);
       }
     }
   }
@@ -600,7 +618,7 @@ hipError_t launch_attn_split(const AttnArgs &a, int d, int nq, bool sparse, hipS
 }
 
 hipError_t launch_attn_combine(const AttnArgs &a, int d, int nq, hipStream_t s) {
-  const size_t blocks = (size_t)a.B * a.num_units * nq;
+  const size_t blocks = (size_t)a.B * a.num_units * nq * 4;   // 4 groups of 4 rows per query tile
   if (blocks == 0) return hipSuccess;
   const dim3 grid((unsigned)blocks), block(256);
   if (d == 128)

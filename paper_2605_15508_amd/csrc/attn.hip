@@ -64,6 +64,11 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
   constexpr int LDS_MAIN = (STS_WG_WAVES * KTILE_BYTES > MERGE_BYTES) ? STS_WG_WAVES * KTILE_BYTES : MERGE_BYTES;
   __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_MAIN];
   __shared__ float lds_ml[STS_WG_WAVES][NQ * 16][2];
+  // With two or more query tiles the Q operands (NQ*KK registers quads per lane) no longer fit
+  // beside the accumulators and the load buffers: they live in LDS, already in MFMA B layout
+  // (one 16-byte slot per lane and (tile, step)), and are re-read for every key tile.
+  constexpr bool QLDS = NQ >= 2;
+  __shared__ __attribute__((aligned(16))) u32x4 ldsQ[QLDS ? NQ * (D / 32) * 64 : 1];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int a = lane >> 4, b = lane & 15;
@@ -111,7 +116,7 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
   // query rows owned by this lane: row nq*16 + b
   int q_head[NQ], q_tq[NQ];
   bool q_ok[NQ];
-  bf16x8 Q[NQ][KK];
+  bf16x8 Q[QLDS ? 1 : NQ][QLDS ? 1 : KK];
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) {
     const int r = nq * 16 + b;
@@ -124,9 +129,14 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
     for (int kk = 0; kk < KK; ++kk) {
       u32x4 w = {0u, 0u, 0u, 0u};
       if (q_ok[nq]) w = *reinterpret_cast<const u32x4 *>(qp + 8 * (a + 4 * kk));
-      Q[nq][kk] = __builtin_bit_cast(bf16x8, w);
+      if (QLDS) {
+        if (wave == 0) ldsQ[(nq * KK + kk) * 64 + lane] = w;   // identical for every wave
+      } else {
+        Q[nq][kk] = __builtin_bit_cast(bf16x8, w);
+      }
     }
   }
+  if (QLDS) __syncthreads();
 
   // a paged cache is a pool of pages shared by the batch: the page table supplies the batch part
   const int64_t head_off = ((PAGED ? 0 : (int64_t)bt * A.stride_b) + (int64_t)g * A.stride_h) * 2 + b * CHB;
@@ -220,15 +230,20 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) St[nq][0] = St[nq][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      const int row = 16 * ks + b;
+    for (int kk = 0; kk < KK; ++kk) {
+      bf16x8 Ka[2];
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
+      for (int ks = 0; ks < 2; ++ks) {
+        const int row = 16 * ks + b;
         const int sl = (a + 4 * kk) ^ (row & (NSLOT - 1));
-        const bf16x8 Ka = *reinterpret_cast<const bf16x8 *>(ldsK + row * ROWB + sl * 16);
+        Ka[ks] = *reinterpret_cast<const bf16x8 *>(ldsK + row * ROWB + sl * 16);
+      }
 #pragma unroll
-        for (int nq = 0; nq < NQ; ++nq)
-          St[nq][ks] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Ka, Q[nq][kk], St[nq][ks], 0, 0, 0);
+      for (int nq = 0; nq < NQ; ++nq) {
+        const bf16x8 Qb = QLDS ? __builtin_bit_cast(bf16x8, ldsQ[(nq * KK + kk) * 64 + lane]) : Q[QLDS ? 0 : nq][QLDS ? 0 : kk];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+          St[nq][ks] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Ka[ks], Qb, St[nq][ks], 0, 0, 0);
       }
     }
     if (LOGITS) {

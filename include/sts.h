@@ -201,7 +201,8 @@ typedef enum {
   STS_K_ATTN_COMBINE = 7,  /* split combine */
   STS_K_SELECT_BLOCK = 8,  /* per-block score sums + first-digit histogram (page_size > 1) */
   STS_K_HEADMAP = 9,       /* Algorithm 1: overlap counting and argmax */
-  STS_K_COUNT_ = 10
+  STS_K_SELECT_SMALL = 10, /* whole selection in one workgroup per row (rows up to 32768 tokens) */
+  STS_K_COUNT_ = 11
 } sts_kernel_kind;
 #define STS_PROF_MAX 4096
 

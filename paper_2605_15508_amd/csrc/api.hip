@@ -217,6 +217,7 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
 
 // --------------------------------------------------------------------------- select plan
 struct SelectPlan {
+  bool small;          // one workgroup per row, keys in LDS, a single launch
   int nchunks, page, srcN;
   size_t agg_bytes, blk_bytes, hist_bytes, state_bytes, chunk_bytes;
 };
@@ -234,6 +235,12 @@ sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
   pl.srcN = (p->N + pl.page - 1) / pl.page;
   pl.nchunks = (pl.srcN + SEL_CHUNK - 1) / SEL_CHUNK;
   const size_t rows = (size_t)p->B * p->Hd;
+  pl.small = pl.page == 1 && p->N <= SEL_SMALL_N;
+  if (pl.small) {
+    pl.nchunks = 0;
+    pl.agg_bytes = pl.blk_bytes = pl.hist_bytes = pl.state_bytes = pl.chunk_bytes = 0;
+    return STS_OK;
+  }
   pl.agg_bytes = p->agg_out ? 0 : align256(rows * (size_t)p->N * sizeof(float));
   pl.blk_bytes = pl.page > 1 ? align256(rows * (size_t)pl.srcN * sizeof(float)) : 0;
   pl.hist_bytes = align256(rows * 3 * SEL_BINS * sizeof(uint32_t));
@@ -290,8 +297,10 @@ static sts_status enqueue_select(const sts_select_params *p, void *stream) {
   if (p->N > 0 && !p->scores) return STS_EINVAL;
   if (p->kind == STS_SCORES_LOGITS_LSE && !p->lse) return STS_EINVAL;
   const size_t need = pl.agg_bytes + pl.blk_bytes + pl.hist_bytes + pl.state_bytes + pl.chunk_bytes;
-  if (!p->workspace || p->workspace_bytes < need) return STS_EWORKSPACE;
-  if (reinterpret_cast<uintptr_t>(p->workspace) % 256 != 0) return STS_EWORKSPACE;
+  if (need > 0) {
+    if (!p->workspace || p->workspace_bytes < need) return STS_EWORKSPACE;
+    if (reinterpret_cast<uintptr_t>(p->workspace) % 256 != 0) return STS_EWORKSPACE;
+  }
   hipStream_t s = static_cast<hipStream_t>(stream);
 
   SelectArgs a;
@@ -330,6 +339,11 @@ static sts_status enqueue_select(const sts_select_params *p, void *stream) {
   }
 
   hipError_t rc;
+  if (pl.small) {
+    a.agg = p->agg_out;   // optional output only: the keys never leave LDS
+    rc = run_kernel(STS_K_SELECT_SMALL, s, [&] { return launch_select_small(a, s); });
+    return rc == hipSuccess ? STS_OK : STS_EHIP;
+  }
   if (pl.nchunks > 0) {
     rc = run_kernel(STS_K_SELECT_CLEAR, s, [&] { return launch_select_clear(a, s); });
     if (rc != hipSuccess) return STS_EHIP;

@@ -64,6 +64,7 @@ constexpr int SEL_BITS0 = 11, SEL_BITS1 = 11, SEL_BITS2 = 10;
 constexpr int SEL_BINS = 2048;          // bins of the widest digit
 constexpr int SEL_CHUNK = 8192;         // tokens per workgroup in the scan kernels
 constexpr int SEL_THREADS = 256;
+constexpr int SEL_SMALL_N = 32768;      // rows up to this many tokens are selected by one workgroup, in LDS
 
 struct SelectTargets {
   // targets of draft head j: tgt[off[j] .. off[j+1])
@@ -93,6 +94,7 @@ hipError_t launch_attn_combine(const AttnArgs &a, int d, int nq, hipStream_t s);
 hipError_t launch_select_clear(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_agg(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_block(const SelectArgs &a, hipStream_t s);
+hipError_t launch_select_small(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t s);
 hipError_t launch_select_count(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_write(const SelectArgs &a, hipStream_t s);

@@ -42,7 +42,9 @@ __device__ __forceinline__ int src_len(const SelectArgs &A, int bt) {
   return (row_len(A, bt) + A.page - 1) / A.page;
 }
 
-// exclusive prefix sum of one value per thread over a 256-thread block; also returns the total
+// exclusive prefix sum of one value per thread over a THREADS-thread block; also returns the
+// total. lds_wave_tot needs THREADS/64 words.
+template <int THREADS = SEL_THREADS>
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *lds_wave_tot, uint32_t &total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   uint32_t incl = v;
@@ -55,7 +57,7 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *lds_wa
   __syncthreads();
   uint32_t base = 0, tot = 0;
 #pragma unroll
-  for (int w = 0; w < SEL_THREADS / 64; ++w) {
+  for (int w = 0; w < THREADS / 64; ++w) {
     const uint32_t t = lds_wave_tot[w];
     if (w < wave) base += t;
     tot += t;
@@ -67,10 +69,12 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *lds_wa
 
 // Walk a digit histogram from the top: the digit holding the krem-th largest key of the
 // candidates, and how many keys of that digit are still wanted. Requires 1 <= krem <= total.
-template <int NBINS>
+// lds_tmp needs THREADS/64 + 2 words; the result lands in its last two.
+template <int NBINS, int THREADS = SEL_THREADS>
 __device__ __forceinline__ void find_digit(const uint32_t *hist, uint32_t krem, uint32_t *lds_tmp,
                                            uint32_t &digit, uint32_t &krem_next) {
-  constexpr int PER = NBINS / SEL_THREADS;
+  constexpr int PER = NBINS / THREADS;
+  constexpr int RES = THREADS / 64;
   uint32_t loc[PER], sum = 0;
 #pragma unroll
   for (int i = 0; i < PER; ++i) {
@@ -78,19 +82,19 @@ __device__ __forceinline__ void find_digit(const uint32_t *hist, uint32_t krem, 
     sum += loc[i];
   }
   uint32_t total;
-  const uint32_t excl = block_excl_scan(sum, lds_tmp, total);
+  const uint32_t excl = block_excl_scan<THREADS>(sum, lds_tmp, total);
   uint32_t above = total - excl - sum;   // keys in bins owned by higher threads
 #pragma unroll
   for (int i = PER - 1; i >= 0; --i) {
     if (above < krem && above + loc[i] >= krem) {
-      lds_tmp[8] = threadIdx.x * PER + i;
-      lds_tmp[9] = krem - above;
+      lds_tmp[RES] = threadIdx.x * PER + i;
+      lds_tmp[RES + 1] = krem - above;
     }
     above += loc[i];
   }
   __syncthreads();
-  digit = lds_tmp[8];
-  krem_next = lds_tmp[9];
+  digit = lds_tmp[RES];
+  krem_next = lds_tmp[RES + 1];
   __syncthreads();
 }
 
@@ -490,6 +494,145 @@ __global__ void __launch_bounds__(SEL_THREADS) select_write_kernel(const SelectA
   }
 }
 
+// ------------------------------------------------- whole selection in one workgroup per row
+// For rows of up to SEL_SMALL_N tokens the keys of a row fit in LDS (128 KB of the 160 KB), so
+// one 1024-thread workgroup per (batch, draft head) does everything in a single launch:
+// aggregate (same fp32 order), three digit histograms over the LDS-resident keys, ordered
+// compaction and the copies to the target heads. No global histograms, nothing to clear.
+constexpr int SMALL_THREADS = 1024;
+__device__ __forceinline__ int small_slot(int n) { return n + (n >> 5); }   // pad 1 word per 32: conflict-free strided reads
+
+template <bool VEC4>
+__global__ void __launch_bounds__(SMALL_THREADS) select_small_kernel(const SelectArgs A) {
+  __shared__ uint32_t keys[SEL_SMALL_N + SEL_SMALL_N / 32];
+  __shared__ uint32_t h[SEL_BINS];
+  __shared__ uint32_t tmp[SMALL_THREADS / 64 + 2];
+  const int row = blockIdx.x;
+  const int bt = row / A.Hd, j = row % A.Hd;
+  const int nb = row_len(A, bt);
+  const uint32_t c = (uint32_t)min(A.k, nb);
+  const int t0 = A.targets.off[j], t1 = A.targets.off[j + 1];
+  const int tid = threadIdx.x;
+  // tail padding and counts
+  for (int ti = t0; ti < t1; ++ti) {
+    const int tgt = A.targets.tgt[ti];
+    int32_t *dst = A.indices + ((size_t)bt * A.Hq + tgt) * A.k;
+    for (uint32_t p = c + tid; p < (uint32_t)A.k; p += SMALL_THREADS) dst[p] = -1;
+    if (A.counts && tid == 0) A.counts[(size_t)bt * A.Hq + tgt] = (int32_t)c;
+  }
+  const bool want_agg = A.agg != nullptr;
+  if ((c == 0 || t0 == t1) && !want_agg) return;
+
+  for (int i = tid; i < SEL_BINS; i += SMALL_THREADS) h[i] = 0u;
+  __syncthreads();
+  const float *P = A.scores + (size_t)row * A.Tq * A.N;
+  const float *Lse = A.lse ? A.lse + (size_t)row * A.Tq : nullptr;
+  float *out = want_agg ? A.agg + (size_t)row * A.N : nullptr;
+  const bool logits = A.kind == STS_SCORES_LOGITS_LSE;
+  const bool use_max = A.reduce == STS_REDUCE_MAX;
+  auto reduce1 = [&](float acc, float p, int i) -> float {
+    if (i == 0) return p;
+    return use_max ? fmaxf(acc, p) : acc + p;
+  };
+  constexpr int AGG_BATCH = 8;
+  if (VEC4) {
+    for (int n = tid * 4; n < A.N; n += SMALL_THREADS * 4) {
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      for (int i0 = 0; i0 < A.Tq; i0 += AGG_BATCH) {
+        f32x4 p[AGG_BATCH];
+#pragma unroll
+        for (int u = 0; u < AGG_BATCH; ++u) {
+          p[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+          if (i0 + u < A.Tq)
+            p[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(P + (size_t)(i0 + u) * A.N + n));
+        }
+#pragma unroll
+        for (int u = 0; u < AGG_BATCH; ++u) {
+          const int i = i0 + u;
+          if (i < A.Tq) {
+            if (logits) {
+              const float l = Lse[i];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) p[u][e] = prob_of(p[u][e], l);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] = reduce1(acc[e], p[u][e], i);
+          }
+        }
+      }
+      if (want_agg) *reinterpret_cast<f32x4 *>(out + n) = acc;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t key = key_of(acc[e]);
+        keys[small_slot(n + e)] = key;
+        if (n + e < nb) atomicAdd(&h[key >> (32 - SEL_BITS0)], 1u);
+      }
+    }
+  } else {
+    for (int n = tid; n < A.N; n += SMALL_THREADS) {
+      float acc = 0.f;
+      for (int i = 0; i < A.Tq; ++i) {
+        float p = P[(size_t)i * A.N + n];
+        if (logits) p = prob_of(p, Lse[i]);
+        acc = reduce1(acc, p, i);
+      }
+      if (want_agg) out[n] = acc;
+      const uint32_t key = key_of(acc);
+      keys[small_slot(n)] = key;
+      if (n < nb) atomicAdd(&h[key >> (32 - SEL_BITS0)], 1u);
+    }
+  }
+  __syncthreads();
+  if (c == 0 || t0 == t1) return;
+
+  // ---- threshold: three digits, histograms rebuilt in LDS from the LDS-resident keys
+  uint32_t d0, k1, d1, k2, d2, r;
+  find_digit<(1 << SEL_BITS0), SMALL_THREADS>(h, c, tmp, d0, k1);
+  for (int i = tid; i < SEL_BINS; i += SMALL_THREADS) h[i] = 0u;
+  __syncthreads();
+  for (int n = tid; n < nb; n += SMALL_THREADS) {
+    const uint32_t key = keys[small_slot(n)];
+    if ((key >> (SEL_BITS1 + SEL_BITS2)) == d0) atomicAdd(&h[(key >> SEL_BITS2) & ((1u << SEL_BITS1) - 1)], 1u);
+  }
+  __syncthreads();
+  find_digit<(1 << SEL_BITS1), SMALL_THREADS>(h, k1, tmp, d1, k2);
+  for (int i = tid; i < SEL_BINS; i += SMALL_THREADS) h[i] = 0u;
+  __syncthreads();
+  const uint32_t pre01 = (d0 << SEL_BITS1) | d1;
+  for (int n = tid; n < nb; n += SMALL_THREADS) {
+    const uint32_t key = keys[small_slot(n)];
+    if ((key >> SEL_BITS2) == pre01) atomicAdd(&h[key & ((1u << SEL_BITS2) - 1)], 1u);
+  }
+  __syncthreads();
+  find_digit<(1 << SEL_BITS2), SMALL_THREADS>(h, k2, tmp, d2, r);
+  const uint32_t T = (pre01 << SEL_BITS2) | d2;
+
+  // ---- ordered compaction: every thread owns a run of consecutive tokens
+  const int per = (nb + SMALL_THREADS - 1) / SMALL_THREADS;      // <= 32
+  const int nlo = min(tid * per, nb), nhi = min(nlo + per, nb);
+  uint32_t cg = 0, ce = 0;
+  for (int n = nlo; n < nhi; ++n) {
+    const uint32_t key = keys[small_slot(n)];
+    cg += key > T ? 1u : 0u;
+    ce += key == T ? 1u : 0u;
+  }
+  uint32_t total;
+  const uint32_t excl = block_excl_scan<SMALL_THREADS>(cg | (ce << 16), tmp, total);
+  uint32_t g = excl & 0xffffu, q = excl >> 16;
+  for (int n = nlo; n < nhi; ++n) {
+    const uint32_t key = keys[small_slot(n)];
+    const bool is_gt = key > T, is_eq = key == T;
+    if (is_gt || (is_eq && q < r)) {
+      const uint32_t pos = g + min(q, r);
+      if (pos < c)   // always true for a consistent threshold; keeps a bad state in bounds
+        for (int ti = t0; ti < t1; ++ti)
+          A.indices[((size_t)bt * A.Hq + A.targets.tgt[ti]) * A.k + pos] = n;
+    }
+    g += is_gt ? 1u : 0u;
+    q += is_eq ? 1u : 0u;
+  }
+}
+
 }  // namespace
 
 static inline bool vec_ok(const SelectArgs &a) {   // aggregation: scores and agg rows
@@ -499,6 +642,18 @@ static inline bool vec_ok(const SelectArgs &a) {   // aggregation: scores and ag
 
 static inline bool src_vec_ok(const SelectArgs &a) {   // ranking passes: rows of src
   return (a.srcN % 4) == 0 && (reinterpret_cast<uintptr_t>(a.src) % 16) == 0;
+}
+
+hipError_t launch_select_small(const SelectArgs &a, hipStream_t s) {
+  if ((size_t)a.B * a.Hd == 0) return hipSuccess;
+  const dim3 grid(a.B * a.Hd), block(SMALL_THREADS);
+  const bool v = (a.N % 4) == 0 && (reinterpret_cast<uintptr_t>(a.scores) % 16) == 0 &&
+                 (a.agg == nullptr || (reinterpret_cast<uintptr_t>(a.agg) % 16) == 0);
+  if (v)
+    hipLaunchKernelGGL(select_small_kernel<true>, grid, block, 0, s, a);
+  else
+    hipLaunchKernelGGL(select_small_kernel<false>, grid, block, 0, s, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_select_block(const SelectArgs &a, hipStream_t s) {

@@ -39,6 +39,11 @@ def softmax_scores(seed, B, Hd, Tq, N, temp=2.0):
     (1, 2, 5, 50, 2, 50),             # k = N
     (1, 2, 5, 50, 3, 80),             # k > N: tail padded with -1
     (1, 1, 64, 300, 1, 7),            # many query rows
+    # rows longer than 32768 tokens take the multi-workgroup path (global histograms)
+    (2, 3, 5, 40000, 6, 4000),
+    (1, 2, 3, 70001, 4, 123),         # and its scalar variant (N % 4 != 0)
+    (1, 4, 5, 32768, 8, 3277),        # the largest row the single-workgroup path takes
+    (1, 2, 5, 32772, 4, 3277),        # the smallest row it does not
 ])
 def test_select_bit_exact_random(B, Hd, Tq, N, Hq, k):
     scores = softmax_scores(1, B, Hd, Tq, N)
@@ -52,13 +57,22 @@ def test_select_bit_exact_random(B, Hd, Tq, N, Hq, k):
 @pytest.mark.parametrize("levels", [1, 2, 4, 37])
 def test_select_heavy_ties(levels):
     g = torch.Generator().manual_seed(levels)
-    B, Hd, Tq, N, Hq = 2, 4, 3, 30000, 8
-    scores = torch.randint(0, levels, (B, Hd, Tq, N), generator=g).float() / 8.0
+    B, Hd, Tq, Hq = 2, 4, 3, 8
     hm = [3, 3, 0, 1, 2, 2, 0, 1]
-    for k in (1, 999, 8192, 29999):
+    for N, k in ((30000, 1), (30000, 999), (30000, 8192), (30000, 29999), (50000, 7777), (50000, 49999)):
+        scores = torch.randint(0, levels, (B, Hd, Tq, N), generator=g).float() / 8.0
         (idx, cnt, _), (o_idx, o_cnt, _) = run_both(scores, hm, k)
         np.testing.assert_array_equal(idx, o_idx)
         np.testing.assert_array_equal(cnt, o_cnt)
+
+
+def test_select_without_agg_output_matches_with():
+    # the single-workgroup path keeps the aggregate in LDS unless it is asked for
+    scores = softmax_scores(21, 2, 3, 5, 9000).to(DEV)
+    hm = [0, 1, 2, 2]
+    a_idx, a_cnt, _ = sts.sts_select(scores, hm, 700, want_agg=False)
+    b_idx, b_cnt, _ = sts.sts_select(scores, hm, 700, want_agg=True)
+    assert torch.equal(a_idx, b_idx) and torch.equal(a_cnt, b_cnt)
 
 
 def test_select_signed_zero_negative_denormal_inf():

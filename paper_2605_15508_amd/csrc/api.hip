@@ -235,7 +235,10 @@ sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
   pl.srcN = (p->N + pl.page - 1) / pl.page;
   pl.nchunks = (pl.srcN + SEL_CHUNK - 1) / SEL_CHUNK;
   const size_t rows = (size_t)p->B * p->Hd;
-  pl.small = pl.page == 1 && p->N <= SEL_SMALL_N;
+  // One workgroup ranks a whole row out of LDS at one CU's pace: a clear win for short rows
+  // (one launch instead of six), and for rows up to the LDS limit when there are enough rows
+  // to fill the chip anyway; longer or fewer rows keep the many-workgroup pipeline.
+  pl.small = pl.page == 1 && (p->N <= SEL_FUSED_N || (p->N <= SEL_SMALL_N && rows >= 256));
   if (pl.small) {
     pl.nchunks = 0;
     pl.agg_bytes = pl.blk_bytes = pl.hist_bytes = pl.state_bytes = pl.chunk_bytes = 0;

@@ -64,7 +64,8 @@ constexpr int SEL_BITS0 = 11, SEL_BITS1 = 11, SEL_BITS2 = 10;
 constexpr int SEL_BINS = 2048;          // bins of the widest digit
 constexpr int SEL_CHUNK = 8192;         // tokens per workgroup in the scan kernels
 constexpr int SEL_THREADS = 256;
-constexpr int SEL_SMALL_N = 32768;      // rows up to this many tokens are selected by one workgroup, in LDS
+constexpr int SEL_SMALL_N = 32768;      // LDS capacity of the one-workgroup-per-row selection (tokens)
+constexpr int SEL_FUSED_N = 8192;       // rows up to this many tokens always take it
 
 struct SelectTargets {
   // targets of draft head j: tgt[off[j] .. off[j+1])

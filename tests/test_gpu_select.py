@@ -42,8 +42,10 @@ def softmax_scores(seed, B, Hd, Tq, N, temp=2.0):
     # rows longer than 32768 tokens take the multi-workgroup path (global histograms)
     (2, 3, 5, 40000, 6, 4000),
     (1, 2, 3, 70001, 4, 123),         # and its scalar variant (N % 4 != 0)
-    (1, 4, 5, 32768, 8, 3277),        # the largest row the single-workgroup path takes
-    (1, 2, 5, 32772, 4, 3277),        # the smallest row it does not
+    (1, 4, 5, 8192, 8, 819),          # the longest row that always takes the single-workgroup path
+    (1, 2, 5, 8196, 4, 819),          # the shortest that does not (few rows)
+    (16, 16, 2, 20000, 16, 500),      # 256 rows: the single-workgroup path up to its LDS limit
+    (16, 16, 1, 32768, 16, 77),
 ])
 def test_select_bit_exact_random(B, Hd, Tq, N, Hq, k):
     scores = softmax_scores(1, B, Hd, Tq, N)

@@ -172,3 +172,20 @@ def test_empty_batch_and_workspace_errors():
     q0 = q[:0].contiguous()
     out, lse, _ = sts.sts_dense_attn(q0, k[:0].contiguous(), v[:0].contiguous(), 0.09)
     assert out.shape[0] == 0
+
+
+def test_maximum_head_counts_and_group_size():
+    """The largest shapes the tables carry: 256 query heads, 16 query heads per KV head,
+    16 query rows; sets wider than 64 query rows are split into several units."""
+    B, Tq, Hq, Hkv, d, N, kk = 1, 16, 256, 16, 64, 200, 24
+    q, k, v = make_qkv(21, B, Tq, Hq, Hkv, d, N)
+    hm = [t // 16 for t in range(Hq)]                 # the whole KV group shares one draft head: 256 rows per set
+    idx = make_indices(22, B, Hq, N, kk, hm)
+    ref = oracle_attn(q, k, v, 0.125, idx)
+    out, lse = sts.sts_sparse_attn(q, k, v, idx, 0.125, head_map=hm, out_dtype=torch.float32)
+    check_attn(out, lse, ref, what="Hq 256 / G 16 sparse")
+    dref = oracle_attn(q, k, v, 0.125)
+    dout, dlse, _ = sts.sts_dense_attn(q, k, v, 0.125, out_dtype=torch.float32)
+    check_attn(dout, dlse, dref, what="Hq 256 / G 16 dense")
+    plan = sts.attn_plan(q, k, True, kmax=kk, head_map=hm)
+    assert plan["query_tiles"] == 4 and plan["units_per_batch"] == 16 * 4     # 16 heads x 16 rows -> 4 units of 64 rows

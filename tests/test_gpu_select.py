@@ -190,3 +190,17 @@ def test_draft_attention_to_selection_to_sparse_attention_chain():
     dense = oracle_attn(q, k, v, w.scale)
     mass = np.exp(ref["lse"].astype(np.float64) - dense["lse"].astype(np.float64))
     assert mass.mean() > 1.1 * kb / cfg.N
+
+
+def test_select_maximum_head_counts():
+    g = torch.Generator().manual_seed(31)
+    B, Hd, Hq, Tq, N, k = 1, 256, 256, 2, 3000, 300
+    scores = torch.softmax(torch.randn(B, Hd, Tq, N, generator=g) * 2, dim=-1)
+    hm = torch.randint(0, Hd, (Hq,), generator=g).tolist()
+    (idx, cnt, agg), (o_idx, o_cnt, o_agg) = run_both(scores, hm, k)
+    np.testing.assert_array_equal(agg.view(np.uint32), o_agg.view(np.uint32))
+    np.testing.assert_array_equal(idx, o_idx)
+    np.testing.assert_array_equal(cnt, o_cnt)
+    # more heads than the tables carry is refused, not truncated
+    with pytest.raises(sts.StsError):
+        sts.sts_select(torch.zeros(1, 257, 1, 64, device=DEV), list(range(257)), 4)

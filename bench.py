@@ -65,7 +65,7 @@ def read_traffic(kernel: str, workload: str):
     return None
 
 
-def cpu_baseline(w, idx, cnt, page=1, budget_s=25.0):
+def cpu_baseline(w, idx, cnt, page=1, budget_s=25.0, scores=None, lse=None):
     """Time the CPU oracle (as it stands, untuned) on this machine's host cores on a bounded sample
     of the same workload. Returns the cpu_baseline object."""
     import numpy as np
@@ -99,9 +99,13 @@ def cpu_baseline(w, idx, cnt, page=1, budget_s=25.0):
         best = min(best, time.perf_counter() - t0)
     sparse_us_layer = best / nb * cfg.B * 1e6
     # selection on one batch element
-    sc = w.scores[:1].cpu().numpy()
+    # (the draft-layer configuration selects from the scaled logits + LSE the GPU just dumped)
+    src = w.scores if scores is None else scores
+    sc = src[:1].cpu().numpy()
+    ls = None if lse is None else lse[:1].cpu().numpy()
     t0 = time.perf_counter()
-    oracle.select_indices(sc, w.head_map.numpy(), idx.shape[2], page=page)
+    oracle.select_indices(sc, w.head_map.numpy(), idx.shape[2], page=page, lse=ls,
+                          kind=oracle.PROBS if ls is None else oracle.LOGITS_LSE)
     sel_us_layer = (time.perf_counter() - t0) * cfg.B * 1e6
     # dense on one KV group of batch 0 (extrapolated linearly)
     G = cfg.Hq // cfg.Hkv
@@ -318,7 +322,7 @@ def main():
         result["roofline_dense"] = {"achieved": round(b_dense / (dsplit_ms * 1e-3 / dsplit_n) / 1e9, 1),
                                     "frac": round(b_dense / (dsplit_ms * 1e-3 / dsplit_n) / 1e9 / HBM_PEAK_GBS, 4)}
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, idx, cnt, page=page)
+        result["cpu_baseline"] = cpu_baseline(w, idx, cnt, page=page, scores=d_logits, lse=d_lse)
     print(json.dumps(result))
 
 

@@ -168,7 +168,8 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
   if (!p->workspace || p->workspace_bytes < need) return STS_EWORKSPACE;
   if (reinterpret_cast<uintptr_t>(p->workspace) % 256 != 0) return STS_EWORKSPACE;
   if (reinterpret_cast<uintptr_t>(p->k) % 16 != 0 || reinterpret_cast<uintptr_t>(p->v) % 16 != 0 ||
-      reinterpret_cast<uintptr_t>(p->q) % 16 != 0 || reinterpret_cast<uintptr_t>(p->out) % 16 != 0)
+      reinterpret_cast<uintptr_t>(p->q) % 16 != 0 || reinterpret_cast<uintptr_t>(p->out) % 16 != 0 ||
+      reinterpret_cast<uintptr_t>(p->logits_out) % 16 != 0)
     return STS_EUNSUPPORTED;
 
   AttnArgs a;

@@ -13,6 +13,8 @@
  *    with the *_workspace_bytes functions (the size depends only on the integer shape
  *    fields, `sparse`/flags and pointer NULL-ness, never on device data).
  *  - Inputs are never written. Outputs and workspace must not alias inputs or each other.
+ *    Calls that share a workspace or an output buffer must be ordered by the caller (same
+ *    stream, or events between streams): the library holds no state and takes no locks.
  *  - Return value: STS_OK (0) or a negative sts_status. On error nothing has been enqueued
  *    (except STS_EHIP, a failed launch, after which earlier kernels of the call may have
  *    been enqueued). No exceptions, no errno, no logging.

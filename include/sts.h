@@ -65,6 +65,13 @@ typedef enum { STS_BF16 = 0, STS_F32 = 1 } sts_dtype;
  * ceil(N_b / p) blocks; k then counts blocks and `indices` holds ascending block ids.
  * agg_out stays per token.
  *
+ * Per-head budgets (paper Section 6.4: how much can be pruned differs strongly between
+ * layers, so budgets are set per layer; the same holds per head). The budget of a layer is
+ * simply the k of that layer's call. With k_head != NULL draft head j keeps
+ * c = min(k_head[j], N_b) entries instead; k stays the row pitch of `indices` and the upper
+ * bound of every k_head[j]. Rows are padded with -1 from c on, counts hold c, so the lists
+ * feed sts_sparse_attn unchanged (kmax = k, counts given).
+ *
  * Supported: 1 <= Tq <= 64, 1 <= Hq <= 256, 1 <= Hd <= 256, N < 2^31 - 2^16,
  * page_size <= 4096. Rows of size zero are handled (nothing is read; counts are 0).
  */
@@ -81,6 +88,8 @@ typedef struct {
   int32_t kind;             /* sts_score_kind */
   int32_t reduce;           /* sts_reduce */
   int32_t page_size;        /* 0 or 1: token granularity. p > 1: block granularity (see below) */
+  const int32_t *k_head;    /* [host] optional [Hd]: budget of draft head j, 1 <= k_head[j] <= k
+                               (see below); NULL = k for every head */
   void *workspace;          /* [dev] 256-byte aligned scratch */
   size_t workspace_bytes;
 } sts_select_params;

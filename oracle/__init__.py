@@ -137,16 +137,34 @@ def expand_blocks(indices: np.ndarray, counts: Optional[np.ndarray], page: int, 
     return tok, cnt
 
 
-def select_indices(scores, head_map, k, lse=None, kind=PROBS, reduce=SUM, seq_lens=None, page=1):
+def select_per_head(A: np.ndarray, k: int, k_head, seq_lens: Optional[np.ndarray] = None):
+    """Per-head budgets (Section 6.4: layers, and heads, differ in how much they can drop):
+    head j keeps min(k_head[j], N_b) entries, rows stay k wide and are padded with -1."""
+    A = _c(A, np.float32)
+    B, Hd, N = A.shape
+    assert len(k_head) == Hd and all(1 <= int(x) <= k for x in k_head)
+    sel = np.full((B, Hd, k), -1, np.int32)
+    cnt = np.zeros((B, Hd), np.int32)
+    for j in range(Hd):
+        kj = int(k_head[j])
+        s, c = select(A[:, j:j + 1], kj, seq_lens)
+        sel[:, j, :kj] = s[:, 0]
+        cnt[:, j] = c[:, 0]
+    return sel, cnt
+
+
+def select_indices(scores, head_map, k, lse=None, kind=PROBS, reduce=SUM, seq_lens=None, page=1,
+                   k_head=None):
     """The whole selection half: aggregate -> [block scores] -> select -> remap. With page > 1
     the result holds block ids (k counts blocks). Returns (indices, counts, A)."""
     A = aggregate(scores, lse, kind, reduce)
+    pick = select if k_head is None else (lambda a, kk, ln: select_per_head(a, kk, k_head, ln))
     if page > 1:
         src = block_scores(A, page, seq_lens)
         lens = None if seq_lens is None else (np.asarray(seq_lens, np.int64) + page - 1) // page
-        sel, cnt = select(src, k, None if lens is None else lens.astype(np.int32))
+        sel, cnt = pick(src, k, None if lens is None else lens.astype(np.int32))
     else:
-        sel, cnt = select(A, k, seq_lens)
+        sel, cnt = pick(A, k, seq_lens)
     indices, counts = remap(sel, cnt, head_map)
     return indices, counts, A
 

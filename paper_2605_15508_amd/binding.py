@@ -34,7 +34,7 @@ class SelectParams(ctypes.Structure):
                 ("scores", ctypes.c_void_p), ("lse", ctypes.c_void_p), ("head_map", ctypes.c_void_p),
                 ("seq_lens", ctypes.c_void_p), ("indices", ctypes.c_void_p), ("counts", ctypes.c_void_p),
                 ("agg_out", ctypes.c_void_p), ("kind", ctypes.c_int32), ("reduce", ctypes.c_int32),
-                ("page_size", ctypes.c_int32),
+                ("page_size", ctypes.c_int32), ("k_head", ctypes.c_void_p),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
 
 
@@ -150,10 +150,11 @@ def _host_i32(seq) -> ctypes.Array:
 
 def sts_select(scores, head_map, k: int, lse=None, seq_lens=None, kind: int = STS_SCORES_PROBS,
                reduce: int = STS_REDUCE_SUM, want_agg: bool = False, out=None, workspace=None,
-               page_size: int = 1):
+               page_size: int = 1, k_head=None):
     """scores [B,Hd,Tq,N] fp32 (device), head_map [Hq] (host ints) -> (indices [B,Hq,k] int32,
     counts [B,Hq] int32, agg [B,Hd,N] fp32 or None). With page_size > 1, k counts blocks and the
-    indices are block ids. See sts_select in include/sts.h."""
+    indices are block ids. k_head [Hd] (host ints, each <= k) gives every draft head its own
+    budget. See sts_select in include/sts.h."""
     import torch
 
     lib = load_library()
@@ -161,6 +162,10 @@ def sts_select(scores, head_map, k: int, lse=None, seq_lens=None, kind: int = ST
     B, Hd, Tq, N = scores.shape
     hm = _host_i32(head_map)
     Hq = len(hm)
+    kh = None
+    if k_head is not None:
+        kh = _host_i32(k_head)
+        assert len(kh) == Hd
     dev = scores.device
     if out is None:
         indices = torch.empty(B, Hq, k, dtype=torch.int32, device=dev)
@@ -175,7 +180,9 @@ def sts_select(scores, head_map, k: int, lse=None, seq_lens=None, kind: int = ST
     p = SelectParams(B=B, Hd=Hd, Tq=Tq, N=N, Hq=Hq, k=int(k), scores=_ptr(scores), lse=_ptr(lse),
                      head_map=ctypes.cast(hm, ctypes.c_void_p), seq_lens=_ptr(seq_lens),
                      indices=_ptr(indices), counts=_ptr(counts), agg_out=_ptr(agg), kind=kind,
-                     reduce=reduce, page_size=int(page_size), workspace=None, workspace_bytes=0)
+                     reduce=reduce, page_size=int(page_size),
+                     k_head=ctypes.cast(kh, ctypes.c_void_p) if kh is not None else None,
+                     workspace=None, workspace_bytes=0)
     need = lib.sts_select_workspace_bytes(ctypes.byref(p))
     ws = workspace if workspace is not None else _workspace("select", need, dev)
     p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()

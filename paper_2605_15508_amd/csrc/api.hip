@@ -297,6 +297,9 @@ static sts_status enqueue_select(const sts_select_params *p, void *stream) {
   if (!p->head_map || !p->indices) return STS_EINVAL;
   for (int t = 0; t < p->Hq; ++t)
     if (p->head_map[t] < 0 || p->head_map[t] >= p->Hd) return STS_EINVAL;
+  if (p->k_head)
+    for (int j = 0; j < p->Hd; ++j)
+      if (p->k_head[j] < 1 || p->k_head[j] > p->k) return STS_EINVAL;
   if (p->B == 0) return STS_OK;
   if (p->N > 0 && !p->scores) return STS_EINVAL;
   if (p->kind == STS_SCORES_LOGITS_LSE && !p->lse) return STS_EINVAL;
@@ -329,6 +332,7 @@ static sts_status enqueue_select(const sts_select_params *p, void *stream) {
   a.chunk_cnt = reinterpret_cast<uint32_t *>(w);
   a.B = p->B; a.Hd = p->Hd; a.Tq = p->Tq; a.N = p->N; a.Hq = p->Hq; a.k = p->k;
   a.kind = p->kind; a.reduce = p->reduce; a.nchunks = pl.nchunks;
+  for (int j = 0; j < p->Hd; ++j) a.kh[j] = p->k_head ? p->k_head[j] : p->k;
   // inverse of the head map: the target heads fed by each draft head, in head order
   {
     int cnt[STS_MAX_HEADS + 1] = {0};
@@ -481,7 +485,7 @@ const char *sts_strerror(sts_status s) {
   return "unknown status";
 }
 
-int sts_version(void) { return 103; }
+int sts_version(void) { return 104; }
 
 void sts_prof_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);

@@ -85,8 +85,9 @@ struct SelectArgs {
   uint32_t *hist;             // [rows][3][SEL_BINS]
   uint32_t *state;            // [rows][8]: prefix key, remaining k per pass, threshold, ties
   uint32_t *chunk_cnt;        // [rows][nchunks][2]
-  int32_t B, Hd, Tq, N, Hq, k, kind, reduce, nchunks;
+  int32_t B, Hd, Tq, N, Hq, k, kind, reduce, nchunks;   // k: row pitch of indices = largest budget
   SelectTargets targets;
+  int32_t kh[STS_MAX_HEADS];  // budget of draft head j (<= k)
 };
 
 // launches (defined in the .hip files); each returns hipGetLastError() of its launch

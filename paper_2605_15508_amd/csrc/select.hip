@@ -275,7 +275,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_hist_kernel(const SelectAr
   const int row = blockIdx.y, chunk = blockIdx.x;
   const int bt = row / A.Hd;
   const int nb = src_len(A, bt);
-  const uint32_t c = (uint32_t)min(A.k, nb);
+  const uint32_t c = (uint32_t)min(A.kh[row % A.Hd], nb);
   if (c == 0) return;
   uint32_t *st = A.state + (size_t)row * 8;
   const uint32_t *gh = A.hist + (size_t)row * 3 * SEL_BINS;
@@ -344,7 +344,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_count_kernel(const SelectA
   const int row = blockIdx.y, chunk = blockIdx.x;
   const int bt = row / A.Hd;
   const int nb = src_len(A, bt);
-  const uint32_t c = (uint32_t)min(A.k, nb);
+  const uint32_t c = (uint32_t)min(A.kh[row % A.Hd], nb);
   if (c == 0) return;
   uint32_t *st = A.state + (size_t)row * 8;
   const uint32_t *gh = A.hist + (size_t)row * 3 * SEL_BINS;
@@ -405,7 +405,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_write_kernel(const SelectA
   const int row = blockIdx.y, chunk = blockIdx.x;
   const int bt = row / A.Hd, j = row % A.Hd;
   const int nb = src_len(A, bt);
-  const uint32_t c = (uint32_t)min(A.k, nb);
+  const uint32_t c = (uint32_t)min(A.kh[j], nb);
   const int t0 = A.targets.off[j], t1 = A.targets.off[j + 1];
   if (chunk == 0) {
     // tail padding and counts for every target head of this draft head
@@ -510,7 +510,7 @@ __global__ void __launch_bounds__(SMALL_THREADS) select_small_kernel(const Selec
   const int row = blockIdx.x;
   const int bt = row / A.Hd, j = row % A.Hd;
   const int nb = row_len(A, bt);
-  const uint32_t c = (uint32_t)min(A.k, nb);
+  const uint32_t c = (uint32_t)min(A.kh[j], nb);
   const int t0 = A.targets.off[j], t1 = A.targets.off[j + 1];
   const int tid = threadIdx.x;
   // tail padding and counts

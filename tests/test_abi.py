@@ -92,6 +92,52 @@ def test_select_argument_validation(lib):
     assert lib.sts_select(ctypes.byref(p), None) == -1
 
 
+def test_per_head_budgets_are_validated(lib):
+    hm = (ctypes.c_int32 * 4)(0, 1, 1, 0)
+    p = binding.SelectParams(B=1, Hd=2, Tq=5, N=1000, Hq=4, k=10, head_map=ctypes.cast(hm, ctypes.c_void_p),
+                             indices=256)
+    for bad in ((0, 5), (5, 11), (-3, 2)):                      # below 1 or above the row pitch k
+        kh = (ctypes.c_int32 * 2)(*bad)
+        p.k_head = ctypes.cast(kh, ctypes.c_void_p)
+        assert lib.sts_select(ctypes.byref(p), None) == -1
+    kh = (ctypes.c_int32 * 2)(10, 1)                            # valid budgets: the next check (scores) fails
+    p.k_head = ctypes.cast(kh, ctypes.c_void_p)
+    assert lib.sts_select(ctypes.byref(p), None) == -1
+    p.B = 0                                                     # empty batch: accepted, nothing enqueued
+    assert lib.sts_select(ctypes.byref(p), None) == 0
+
+
+def test_ctypes_structs_match_the_header(tmp_path):
+    """The Python binding restates the parameter structs: compile the header as C11 and compare
+    size and every field offset."""
+    import subprocess
+
+    structs = {"sts_select_params": binding.SelectParams, "sts_attn_params": binding.AttnParams,
+               "sts_headmap_params": binding.HeadmapParams}
+    lines = ["#include <stdio.h>", "#include <stddef.h>", '#include "sts.h"', "int main(void) {"]
+    for cname, cls in structs.items():
+        lines.append(f'  printf("{cname} %zu\\n", sizeof({cname}));')
+        for fname, _ in cls._fields_:
+            lines.append(f'  printf("{cname}.{fname} %zu\\n", offsetof({cname}, {fname}));')
+    lines += ["  return 0;", "}"]
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
+                   check=True)
+    got = dict(line.split() for line in subprocess.run([str(exe)], check=True, capture_output=True,
+                                                       text=True).stdout.splitlines())
+    for cname, cls in structs.items():
+        assert int(got[cname]) == ctypes.sizeof(cls), cname
+        for fname, _ in cls._fields_:
+            assert int(got[f"{cname}.{fname}"]) == getattr(cls, fname).offset, f"{cname}.{fname}"
+        # and no field of the header is missing from the binding
+        text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "sts.h")).read(), flags=re.S)
+        body = re.search(r"typedef struct \{([^}]*)\} " + cname + ";", text).group(1)
+        declared = re.findall(r"\b\*?([A-Za-z_][A-Za-z0-9_]*)\s*(?:,|;)", body)
+        assert sorted(declared) == sorted(f for f, _ in cls._fields_), cname
+
+
 def test_product_path_has_no_oracle_import():
     pkg = os.path.join(ROOT, "paper_2605_15508_amd")
     for dirpath, _, files in os.walk(pkg):

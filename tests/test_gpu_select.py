@@ -26,6 +26,15 @@ def run_both(scores, head_map, k, lse=None, seq_lens=None, kind=0, reduce=0):
     return (idx.cpu().numpy(), cnt.cpu().numpy(), agg.cpu().numpy()), (o_idx, o_cnt, o_agg)
 
 
+def run_both_budgets(scores, head_map, k, k_head, seq_lens=None, page=1):
+    idx, cnt, _ = sts.sts_select(scores.to(DEV), head_map, k, k_head=k_head, page_size=page,
+                                 seq_lens=None if seq_lens is None else seq_lens.to(DEV))
+    torch.cuda.synchronize()
+    o_idx, o_cnt, _ = oracle.select_indices(scores.numpy(), np.asarray(head_map, np.int32), k, k_head=k_head,
+                                            page=page, seq_lens=None if seq_lens is None else seq_lens.numpy())
+    return (idx.cpu().numpy(), cnt.cpu().numpy()), (o_idx, o_cnt)
+
+
 def softmax_scores(seed, B, Hd, Tq, N, temp=2.0):
     g = torch.Generator().manual_seed(seed)
     return torch.softmax(torch.randn(B, Hd, Tq, N, generator=g) * temp, dim=-1)
@@ -204,3 +213,45 @@ def test_select_maximum_head_counts():
     # more heads than the tables carry is refused, not truncated
     with pytest.raises(sts.StsError):
         sts.sts_select(torch.zeros(1, 257, 1, 64, device=DEV), list(range(257)), 4)
+
+
+@pytest.mark.parametrize("B,Hd,Tq,N,Hq,k,page", [
+    (2, 4, 5, 4096, 8, 410, 1),        # single-workgroup path
+    (2, 4, 5, 50000, 8, 5000, 1),      # multi-workgroup path, ragged last chunk
+    (1, 3, 2, 70001, 6, 900, 1),       # scalar variant
+    (2, 4, 5, 65536, 8, 512, 8),       # block granularity: budgets count blocks
+])
+def test_select_per_head_budgets(B, Hd, Tq, N, Hq, k, page):
+    """Section 6.4: budgets differ per layer (the k of the call) and, here, per draft head."""
+    scores = softmax_scores(21, B, Hd, Tq, N)
+    hm = [(t * Hd) // Hq for t in range(Hq)]
+    rng = np.random.default_rng(5)
+    kh = [int(x) for x in rng.integers(1, k + 1, Hd)]
+    kh[0], kh[-1] = k, 1                                  # both ends of the allowed range
+    lens = torch.tensor([N] + [max(1, N // 3)] * (B - 1), dtype=torch.int32)
+    (idx, cnt), (o_idx, o_cnt) = run_both_budgets(scores, hm, k, kh, seq_lens=lens, page=page)
+    np.testing.assert_array_equal(cnt, o_cnt)
+    np.testing.assert_array_equal(idx, o_idx)
+    # equal budgets are the same as none
+    (idx2, cnt2), _ = run_both_budgets(scores, hm, k, [k] * Hd, seq_lens=lens, page=page)
+    ref, rcnt, _ = sts.sts_select(scores.to(DEV), hm, k, seq_lens=lens.to(DEV), page_size=page)
+    np.testing.assert_array_equal(idx2, ref.cpu().numpy())
+    np.testing.assert_array_equal(cnt2, rcnt.cpu().numpy())
+
+
+def test_per_head_budgets_feed_sparse_attention():
+    """Lists of different lengths in one call: counts carry each head's own length."""
+    cfg = replace(CONFIGS["c1"], N=6000)
+    w = make_workload(cfg, seed=9)
+    k = w.k_budget
+    kh = [max(1, (k * (j + 1)) // w.scores.shape[1]) for j in range(w.scores.shape[1])]
+    idx, cnt, _ = sts.sts_select(w.scores.to(DEV), w.head_map, k, k_head=kh)
+    out, lse = sts.sts_sparse_attn(w.q.to(DEV), w.k.to(DEV), w.v.to(DEV), idx, w.scale, counts=cnt,
+                                   head_map=w.head_map, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    o_idx, o_cnt, _ = oracle.select_indices(w.scores.numpy(), np.asarray(w.head_map, np.int32), k, k_head=kh)
+    np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
+    ref = oracle.attn(oracle.bf16_bits(w.q), oracle.bf16_bits(w.k), oracle.bf16_bits(w.v), w.scale,
+                      indices=o_idx, counts=o_cnt)
+    assert np.abs(out.cpu().numpy() - ref["out"]).max() < 1e-2
+    assert np.abs(lse.cpu().numpy() - ref["lse"]).max() < 1e-3

@@ -155,6 +155,32 @@ def test_select_seq_lens():
     np.testing.assert_array_equal(sel[0, 1], brute_select(A[0, 1], 10))
 
 
+def test_per_head_budgets_are_nested_prefixes_of_the_ranking():
+    """With the deterministic tie rule the c best tokens contain the c' < c best ones, so the
+    list of a head with a smaller budget is the larger list filtered; budgets equal to k change
+    nothing; each head is checked against the counting definition by brute force."""
+    rng = np.random.default_rng(12)
+    A = np.round(rng.standard_normal((2, 3, 200)) * 2).astype(np.float32) / 2    # many ties
+    lens = np.array([200, 37], np.int32)
+    k, kh = 40, [40, 1, 13]
+    full, cfull = oracle.select(A, k, lens)
+    sel, cnt = oracle.select_per_head(A, k, kh, lens)
+    np.testing.assert_array_equal(cnt, np.minimum(np.array(kh)[None, :], lens[:, None]))
+    np.testing.assert_array_equal(sel[:, 0], full[:, 0])
+    for b in range(2):
+        for j in range(3):
+            c = cnt[b, j]
+            want = brute_select(A[b, j, :lens[b]], kh[j])
+            np.testing.assert_array_equal(sel[b, j, :c], want)
+            assert (sel[b, j, c:] == -1).all()
+            assert set(sel[b, j, :c]) <= set(full[b, j, :cfull[b, j]])
+    idx, counts, _ = oracle.select_indices(np.repeat(A[:, :, None, :], 1, axis=2), np.array([2, 0, 1, 2], np.int32),
+                                           k, seq_lens=lens, k_head=kh)
+    np.testing.assert_array_equal(idx[:, 0], sel[:, 2])
+    np.testing.assert_array_equal(idx[:, 3], sel[:, 2])
+    np.testing.assert_array_equal(counts[:, 1], cnt[:, 0])
+
+
 def test_select_rejects_nan():
     a = np.array([[[0.0, np.nan, 1.0]]], np.float32)
     with pytest.raises(ValueError):

@@ -221,6 +221,7 @@ struct SelectPlan {
   bool small;          // one workgroup per row, keys in LDS, a single launch
   int nchunks, page, srcN;
   size_t agg_bytes, blk_bytes, hist_bytes, state_bytes, chunk_bytes;
+  size_t total() const { return agg_bytes + blk_bytes + hist_bytes + state_bytes + chunk_bytes; }
 };
 
 sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
@@ -249,7 +250,7 @@ sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
   pl.blk_bytes = pl.page > 1 ? align256(rows * (size_t)pl.srcN * sizeof(float)) : 0;
   pl.hist_bytes = align256(rows * 3 * SEL_BINS * sizeof(uint32_t));
   pl.state_bytes = align256(rows * 8 * sizeof(uint32_t));
-  pl.chunk_bytes = align256(rows * (size_t)pl.nchunks * 2 * sizeof(uint32_t));
+  pl.chunk_bytes = align256(rows * (size_t)pl.nchunks * SEL_FLAG_PITCH * sizeof(uint32_t));
   return STS_OK;
 }
 
@@ -286,7 +287,7 @@ sts_status sts_dense_attn(const sts_attn_params *p, void *stream) {
 size_t sts_select_workspace_bytes(const sts_select_params *p) {
   SelectPlan pl;
   if (plan_select(p, pl) != STS_OK) return 0;
-  const size_t n = pl.agg_bytes + pl.blk_bytes + pl.hist_bytes + pl.state_bytes + pl.chunk_bytes;
+  const size_t n = pl.total();
   return n ? n : 256;
 }
 
@@ -303,7 +304,7 @@ static sts_status enqueue_select(const sts_select_params *p, void *stream) {
   if (p->B == 0) return STS_OK;
   if (p->N > 0 && !p->scores) return STS_EINVAL;
   if (p->kind == STS_SCORES_LOGITS_LSE && !p->lse) return STS_EINVAL;
-  const size_t need = pl.agg_bytes + pl.blk_bytes + pl.hist_bytes + pl.state_bytes + pl.chunk_bytes;
+  const size_t need = pl.total();
   if (need > 0) {
     if (!p->workspace || p->workspace_bytes < need) return STS_EWORKSPACE;
     if (reinterpret_cast<uintptr_t>(p->workspace) % 256 != 0) return STS_EWORKSPACE;
@@ -333,6 +334,14 @@ static sts_status enqueue_select(const sts_select_params *p, void *stream) {
   a.B = p->B; a.Hd = p->Hd; a.Tq = p->Tq; a.N = p->N; a.Hq = p->Hq; a.k = p->k;
   a.kind = p->kind; a.reduce = p->reduce; a.nchunks = pl.nchunks;
   for (int j = 0; j < p->Hd; ++j) a.kh[j] = p->k_head ? p->k_head[j] : p->k;
+  a.clear_words = (pl.hist_bytes + pl.state_bytes + pl.chunk_bytes) / sizeof(uint32_t);
+  // Test knob: STS_SELECT_SPIN_LIMIT bounds the polls of an earlier chunk's published counts
+  // before the waiting workgroup recounts that chunk itself (0: one look, then recount).
+  {
+    const char *e = getenv("STS_SELECT_SPIN_LIMIT");
+    const int v = e ? atoi(e) : 256;
+    a.spin_limit = v < 0 ? 0 : (v > 65536 ? 65536 : v);
+  }
   // inverse of the head map: the target heads fed by each draft head, in head order
   {
     int cnt[STS_MAX_HEADS + 1] = {0};
@@ -364,8 +373,6 @@ static sts_status enqueue_select(const sts_select_params *p, void *stream) {
     rc = run_kernel(STS_K_SELECT_HIST, s, [&] { return launch_select_hist(a, 1, s); });
     if (rc != hipSuccess) return STS_EHIP;
     rc = run_kernel(STS_K_SELECT_HIST, s, [&] { return launch_select_hist(a, 2, s); });
-    if (rc != hipSuccess) return STS_EHIP;
-    rc = run_kernel(STS_K_SELECT_COUNT, s, [&] { return launch_select_count(a, s); });
     if (rc != hipSuccess) return STS_EHIP;
   }
   rc = run_kernel(STS_K_SELECT_WRITE, s, [&] { return launch_select_write(a, s); });
@@ -401,7 +408,7 @@ sts_status plan_headmap(const sts_headmap_params *p, HeadmapPlan &pl) {
   SelectPlan spl;
   const sts_status v = plan_select(&sp, spl);
   if (v != STS_OK) return v;
-  pl.select_bytes = spl.agg_bytes + spl.blk_bytes + spl.hist_bytes + spl.state_bytes + spl.chunk_bytes;
+  pl.select_bytes = spl.total();
   return STS_OK;
 }
 

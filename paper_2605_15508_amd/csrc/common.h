@@ -65,6 +65,7 @@ constexpr int SEL_BINS = 2048;          // bins of the widest digit
 constexpr int SEL_CHUNK = 8192;         // tokens per workgroup in the scan kernels
 constexpr int SEL_THREADS = 256;
 constexpr int SEL_SMALL_N = 32768;      // LDS capacity of the one-workgroup-per-row selection (tokens)
+constexpr int SEL_FLAG_PITCH = 32;      // words between the published counts of two chunks: one 128-byte line each
 constexpr int SEL_FUSED_N = 8192;       // rows up to this many tokens always take it
 
 struct SelectTargets {
@@ -83,8 +84,10 @@ struct SelectArgs {
   int32_t srcN;               // row length of src: N or NB
   int32_t page;               // tokens per block (>= 1)
   uint32_t *hist;             // [rows][3][SEL_BINS]
-  uint32_t *state;            // [rows][8]: prefix key, remaining k per pass, threshold, ties
-  uint32_t *chunk_cnt;        // [rows][nchunks][2]
+  uint32_t *state;            // [rows][8]: digits 0/1 and remaining k after each, [6] budget
+  uint32_t *chunk_cnt;        // [rows][nchunks][SEL_FLAG_PITCH], word 0: published flag | equal count << 14 | greater count
+  uint64_t clear_words;       // words to zero from `hist` on: histograms, state and chunk flags
+  int32_t spin_limit;         // polls of an unpublished earlier chunk before it is recounted locally
   int32_t B, Hd, Tq, N, Hq, k, kind, reduce, nchunks;   // k: row pitch of indices = largest budget
   SelectTargets targets;
   int32_t kh[STS_MAX_HEADS];  // budget of draft head j (<= k)
@@ -98,7 +101,6 @@ hipError_t launch_select_agg(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_block(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_small(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t s);
-hipError_t launch_select_count(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_write(const SelectArgs &a, hipStream_t s);
 hipError_t launch_headmap_clear(unsigned long long *overlap, int n, hipStream_t s);
 hipError_t launch_headmap_overlap(const int32_t *idx_d, const int32_t *idx_t, int S, int R, int Hd, int Ht,

@@ -98,6 +98,18 @@ __device__ __forceinline__ void find_digit(const uint32_t *hist, uint32_t krem, 
   __syncthreads();
 }
 
+// Add a workgroup's LDS histogram to the row's global one. Two neighbouring 32-bit bins travel
+// in one 64-bit atomic (a row holds fewer than 2^32 keys, so the low bin never carries into
+// the high one), which halves the number of atomics.
+template <int NBINS, int THREADS = SEL_THREADS>
+__device__ __forceinline__ void flush_hist(uint32_t *global_bins, const uint32_t *lds_bins) {
+  unsigned long long *g2 = reinterpret_cast<unsigned long long *>(global_bins);
+  for (int i = threadIdx.x; i < NBINS / 2; i += THREADS) {
+    const unsigned long long v = (unsigned long long)lds_bins[2 * i] | ((unsigned long long)lds_bins[2 * i + 1] << 32);
+    if (v) atomicAdd(&g2[i], v);
+  }
+}
+
 __global__ void __launch_bounds__(SEL_THREADS) select_clear_kernel(uint32_t *p, size_t n) {
   const size_t i = (size_t)blockIdx.x * SEL_THREADS + threadIdx.x;
   if (i < n) p[i] = 0u;
@@ -181,8 +193,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_agg_kernel(const SelectArg
   __syncthreads();
   if (A.page != 1) return;   // block granularity: the block kernel builds the first histogram
   uint32_t *gh = A.hist + (size_t)row * 3 * SEL_BINS;
-  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS)
-    if (h[i]) atomicAdd(&gh[i], h[i]);
+  flush_hist<SEL_BINS>(gh, h);
 }
 
 // ----------------------------------------------------------------------- block scores
@@ -209,8 +220,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_block_kernel(const SelectA
   }
   __syncthreads();
   uint32_t *gh = A.hist + (size_t)row * 3 * SEL_BINS;
-  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS)
-    if (h[i]) atomicAdd(&gh[i], h[i]);
+  flush_hist<SEL_BINS>(gh, h);
 }
 
 // Coalesced variant for page % 4 == 0, page <= 256, N % 4 == 0: every lane loads 4 consecutive
@@ -261,8 +271,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_block_vec_kernel(const Sel
   }
   __syncthreads();
   uint32_t *gh = A.hist + (size_t)row * 3 * SEL_BINS;
-  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS)
-    if (h[i]) atomicAdd(&gh[i], h[i]);
+  flush_hist<SEL_BINS>(gh, h);
 }
 
 // ------------------------------------------------------------------ refinement histograms
@@ -333,62 +342,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_hist_kernel(const SelectAr
   }
   __syncthreads();
   uint32_t *go = A.hist + ((size_t)row * 3 + PASS) * SEL_BINS;
-  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS)
-    if (h[i]) atomicAdd(&go[i], h[i]);
-}
-
-// --------------------------------------------------------------------- per-chunk counts
-template <bool VEC4>
-__global__ void __launch_bounds__(SEL_THREADS) select_count_kernel(const SelectArgs A) {
-  __shared__ uint32_t tmp[16];
-  const int row = blockIdx.y, chunk = blockIdx.x;
-  const int bt = row / A.Hd;
-  const int nb = src_len(A, bt);
-  const uint32_t c = (uint32_t)min(A.kh[row % A.Hd], nb);
-  if (c == 0) return;
-  uint32_t *st = A.state + (size_t)row * 8;
-  const uint32_t *gh = A.hist + (size_t)row * 3 * SEL_BINS;
-  const float *a = A.src + (size_t)row * A.srcN;
-  const int n0 = chunk * SEL_CHUNK;
-  const int n1 = min(min(n0 + SEL_CHUNK, A.srcN), nb);
-  // loads first (clamped, unconditional), digit search second: see select_hist_kernel
-  constexpr int IT = SEL_CHUNK / (SEL_THREADS * 4);
-  f32x4 x[IT];
-  if (VEC4) {
-#pragma unroll
-    for (int i = 0; i < IT; ++i) {
-      const int n = n0 + (i * SEL_THREADS + threadIdx.x) * 4;
-      x[i] = *reinterpret_cast<const f32x4 *>(a + min(n, A.srcN - 4));
-    }
-  }
-  uint32_t d2, r;
-  find_digit<(1 << SEL_BITS2)>(gh + 2 * SEL_BINS, st[3], tmp, d2, r);
-  const uint32_t T = (st[0] << (SEL_BITS1 + SEL_BITS2)) | (st[2] << SEL_BITS2) | d2;
-  if (chunk == 0 && threadIdx.x == 0) { st[4] = T; st[5] = r; }
-  uint32_t packed = 0;   // greater in the low half, equal in the high half (<= 8192 each)
-  if (VEC4) {
-#pragma unroll
-    for (int i = 0; i < IT; ++i) {
-      const int n = n0 + (i * SEL_THREADS + threadIdx.x) * 4;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const uint32_t key = key_of(x[i][e]);
-        if (n + e < n1) packed += (key > T ? 1u : 0u) + (key == T ? 0x10000u : 0u);
-      }
-    }
-  } else {
-    for (int n = n0 + threadIdx.x; n < n1; n += SEL_THREADS) {
-      const uint32_t key = key_of(a[n]);
-      packed += (key > T ? 1u : 0u) + (key == T ? 0x10000u : 0u);
-    }
-  }
-  uint32_t total;
-  (void)block_excl_scan(packed, tmp, total);
-  if (threadIdx.x == 0) {
-    uint32_t *cc = A.chunk_cnt + ((size_t)row * A.nchunks + chunk) * 2;
-    cc[0] = total & 0xffffu;
-    cc[1] = total >> 16;
-  }
+  flush_hist<SEL_BINS>(go, h);
 }
 
 // ------------------------------------------------------ ordered compaction + head remap
@@ -397,7 +351,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_count_kernel(const SelectA
 // order. The kept tokens of a chunk occupy one contiguous range of the output list: they are
 // staged in LDS at their local rank and copied out with coalesced stores, once per target.
 template <bool VEC4>
-__global__ void __launch_bounds__(SEL_THREADS) select_write_kernel(const SelectArgs A) {
+__global__ void __launch_bounds__(SEL_THREADS, 4) select_write_kernel(const SelectArgs A) {   // <= 128 VGPRs: 4 workgroups per CU
   constexpr int PER = SEL_CHUNK / SEL_THREADS;   // 32 tokens per thread
   constexpr int PITCH = PER + 1;                 // odd pitch: conflict-free per-thread rows
   __shared__ uint32_t tmp[16];
@@ -420,7 +374,6 @@ __global__ void __launch_bounds__(SEL_THREADS) select_write_kernel(const SelectA
   const int n0 = chunk * SEL_CHUNK;
   if (n0 >= nb) return;
   const uint32_t *st = A.state + (size_t)row * 8;
-  const uint32_t T = st[4], r = st[5];
   const float *a = A.src + (size_t)row * A.srcN;
 
   // coalesced load of the chunk; token n0 + i lands at buf[(i / PER) * PITCH + i % PER]
@@ -436,21 +389,10 @@ __global__ void __launch_bounds__(SEL_THREADS) select_write_kernel(const SelectA
       buf[(i / PER) * PITCH + i % PER] = (n0 + i < nb) ? key_of(a[n0 + i]) : 0u;
   }
 
-  // keys greater / equal in the chunks before this one
-  uint32_t pre = 0, pre_eq = 0;
-  {
-    const uint32_t *cc = A.chunk_cnt + (size_t)row * A.nchunks * 2;
-    uint32_t g = 0, e = 0;
-    for (int ch = threadIdx.x; ch < chunk; ch += SEL_THREADS) {
-      g += cc[ch * 2];
-      e += cc[ch * 2 + 1];
-    }
-    uint32_t tg, te;
-    (void)block_excl_scan(g, tmp, tg);    // contains the barrier that publishes buf
-    (void)block_excl_scan(e, tmp, te);
-    pre = tg;
-    pre_eq = te;
-  }
+  // threshold key and tie quota of the row
+  uint32_t d2, r;
+  find_digit<(1 << SEL_BITS2)>(A.hist + ((size_t)row * 3 + 2) * SEL_BINS, st[3], tmp, d2, r);   // barriers: buf visible
+  const uint32_t T = (st[0] << (SEL_BITS1 + SEL_BITS2)) | (st[2] << SEL_BITS2) | d2;
 
   const int base_n = n0 + threadIdx.x * PER;
   uint32_t keys[PER];
@@ -464,8 +406,72 @@ __global__ void __launch_bounds__(SEL_THREADS) select_write_kernel(const SelectA
   }
   uint32_t total;
   const uint32_t excl = block_excl_scan(cg | (ce << 16), tmp, total);   // barriers: buf is free
-  uint32_t g = pre + (excl & 0xffffu), q = pre_eq + (excl >> 16);
   const uint32_t chunk_gt = total & 0xffffu, chunk_eq = total >> 16;
+
+  // keys greater / equal in the chunks before this one
+  uint32_t pre = 0, pre_eq = 0;
+  uint32_t *cc = A.chunk_cnt + (size_t)row * A.nchunks * SEL_FLAG_PITCH;
+  {
+    // Every chunk publishes its own counts in one word (flag | equal << 14 | greater) with a
+    // device-scope atomic store and reads the words of the chunks before it, one per thread.
+    // The payload travels inside the flag, so no fence is involved. A chunk whose word does
+    // not show up within the poll limit is simply recounted from the scores by this workgroup,
+    // so the wait is bounded and no workgroup depends on another one being scheduled.
+    uint32_t *miss = reinterpret_cast<uint32_t *>(buf);   // list of chunks to recount
+    if (threadIdx.x == 0) {
+      __hip_atomic_store(&cc[chunk * SEL_FLAG_PITCH], 0x80000000u | (chunk_eq << 14) | chunk_gt, __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+      tmp[8] = 0;                                          // number of entries in miss
+    }
+    __syncthreads();
+    uint32_t g = 0, e = 0;
+    for (int ch = threadIdx.x; ch < chunk; ch += SEL_THREADS) {
+      uint32_t f = __hip_atomic_load(&cc[ch * SEL_FLAG_PITCH], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      for (int spin = 0; !(f >> 31) && spin < A.spin_limit; ++spin) {
+        __builtin_amdgcn_s_sleep(8);
+        f = __hip_atomic_load(&cc[ch * SEL_FLAG_PITCH], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      if (f >> 31) {
+        g += f & 0x3fffu;
+        e += (f >> 14) & 0x3fffu;
+      } else {
+        const uint32_t slot = atomicAdd(&tmp[8], 1u);
+        if (slot < (uint32_t)(SEL_THREADS * PITCH)) {
+          miss[slot] = (uint32_t)ch;
+        } else {   // list full (only with thousands of chunks per row): this thread recounts alone
+          for (int i = 0; i < SEL_CHUNK; ++i) {
+            const uint32_t key = key_of(a[ch * SEL_CHUNK + i]);
+            g += key > T ? 1u : 0u;
+            e += key == T ? 1u : 0u;
+          }
+        }
+      }
+    }
+    __syncthreads();
+    const uint32_t nmiss = min(tmp[8], (uint32_t)(SEL_THREADS * PITCH));
+    for (uint32_t mi = 0; mi < nmiss; ++mi) {
+      // recount chunk miss[mi] (it lies wholly below nb: it precedes this chunk)
+      const int m0 = (int)miss[mi] * SEL_CHUNK;
+      uint32_t packed = 0;
+      for (int i = threadIdx.x; i < SEL_CHUNK; i += SEL_THREADS) {
+        const uint32_t key = key_of(a[m0 + i]);
+        packed += (key > T ? 1u : 0u) + (key == T ? 0x10000u : 0u);
+      }
+      // one thread per wave carries the wave's sum into the running totals
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) packed += __shfl_xor(packed, off, 64);
+      if ((threadIdx.x & 63) == 0) {
+        g += packed & 0xffffu;
+        e += packed >> 16;
+      }
+    }
+    uint32_t tg, te;
+    (void)block_excl_scan(g, tmp, tg);
+    (void)block_excl_scan(e, tmp, te);
+    pre = tg;
+    pre_eq = te;
+  }
+  uint32_t g = pre + (excl & 0xffffu), q = pre_eq + (excl >> 16);
   // output range of this chunk: [first, last)
   const uint32_t first = pre + min(pre_eq, r);
   const uint32_t last = min((pre + chunk_gt) + min(pre_eq + chunk_eq, r), c);
@@ -671,7 +677,7 @@ hipError_t launch_select_block(const SelectArgs &a, hipStream_t s) {
 }
 
 hipError_t launch_select_clear(const SelectArgs &a, hipStream_t s) {
-  const size_t n = (size_t)a.B * a.Hd * 3 * SEL_BINS;
+  const size_t n = (size_t)a.clear_words;
   if (n == 0) return hipSuccess;
   hipLaunchKernelGGL(select_clear_kernel, dim3((unsigned)((n + SEL_THREADS - 1) / SEL_THREADS)),
                      dim3(SEL_THREADS), 0, s, a.hist, n);
@@ -700,16 +706,6 @@ hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t s) {
     if (v) hipLaunchKernelGGL((select_hist_kernel<2, true>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((select_hist_kernel<2, false>), grid, block, 0, s, a);
   }
-  return hipGetLastError();
-}
-
-hipError_t launch_select_count(const SelectArgs &a, hipStream_t s) {
-  if ((size_t)a.B * a.Hd == 0 || a.nchunks == 0) return hipSuccess;
-  const dim3 grid(a.nchunks, a.B * a.Hd), block(SEL_THREADS);
-  if (src_vec_ok(a))
-    hipLaunchKernelGGL(select_count_kernel<true>, grid, block, 0, s, a);
-  else
-    hipLaunchKernelGGL(select_count_kernel<false>, grid, block, 0, s, a);
   return hipGetLastError();
 }
 

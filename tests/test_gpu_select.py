@@ -255,3 +255,22 @@ def test_per_head_budgets_feed_sparse_attention():
                       indices=o_idx, counts=o_cnt)
     assert np.abs(out.cpu().numpy() - ref["out"]).max() < 1e-2
     assert np.abs(lse.cpu().numpy() - ref["lse"]).max() < 1e-3
+
+
+@pytest.mark.parametrize("spin_limit", ["0", "3"])
+def test_lookback_recount_path(spin_limit, monkeypatch):
+    """The compaction kernel reads the counts that earlier chunks of the row publish; a chunk
+    whose counts do not show up within the poll limit is recounted by the waiting workgroup.
+    A tiny limit (set from the host) forces that path; the result must not change."""
+    monkeypatch.setenv("STS_SELECT_SPIN_LIMIT", spin_limit)
+    hm = [0, 1, 1, 2]
+    for N, k, levels in ((200000, 20000, 0), (70001, 7000, 0), (100000, 50000, 3)):
+        if levels:
+            g = torch.Generator().manual_seed(N)
+            scores = torch.randint(0, levels, (2, 3, 2, N), generator=g).float() / 4.0
+        else:
+            scores = softmax_scores(N, 2, 3, 2, N)
+        lens = torch.tensor([N, N - 12345], dtype=torch.int32)
+        (idx, cnt, _), (o_idx, o_cnt, _) = run_both(scores, hm, k, seq_lens=lens)
+        np.testing.assert_array_equal(cnt, o_cnt)
+        np.testing.assert_array_equal(idx, o_idx)

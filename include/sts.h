@@ -205,8 +205,8 @@ typedef enum {
   STS_K_SELECT_CLEAR = 0,  /* zero histograms */
   STS_K_SELECT_AGG = 1,    /* aggregation + first-digit histogram */
   STS_K_SELECT_HIST = 2,   /* refinement histograms */
-  STS_K_SELECT_COUNT = 3,  /* per-chunk counts against the threshold */
-  STS_K_SELECT_WRITE = 4,  /* ordered compaction + head remap */
+  STS_K_SELECT_COUNT = 3,  /* not launched any more: the compaction kernel counts its own chunk */
+  STS_K_SELECT_WRITE = 4,  /* per-chunk counts, ordered compaction + head remap */
   STS_K_ATTN_SPARSE = 5,   /* split sparse gather flash-decode */
   STS_K_ATTN_DENSE = 6,    /* split dense flash-decode */
   STS_K_ATTN_COMBINE = 7,  /* split combine */

@@ -289,7 +289,7 @@ def main():
                    "layers": L, "cache": "cold: every pass reads KV that has left the caches" if (L > 1 or kv_bytes > (256 << 20)) else "warm", "head_map": "t*Hd//Hq", "step": ("%d layers x (" % L if L > 1 else "(") + "select + sparse_attn" + ("" if args.no_dense else " + dense_attn")
                    + (" + draft dense attn with logits dump" if draft is not None else "") + ")"},
         "sparse_attn_us": {"mean": round(sparse_us[0], 2), "median": round(sparse_us[1], 2), "min": round(sparse_us[2], 2), "p10": round(sparse_us[3], 2), "p90": round(sparse_us[4], 2)},
-        "dense_attn_us": {"mean": round(dense_us[0], 2), "median": round(dense_us[1], 2), "min": round(dense_us[2], 2), "p10": round(dense_us[3], 2), "p90": round(dense_us[4], 2)},
+        "dense_attn_us": None if args.no_dense else {"mean": round(dense_us[0], 2), "median": round(dense_us[1], 2), "min": round(dense_us[2], 2), "p10": round(dense_us[3], 2), "p90": round(dense_us[4], 2)},
         "select_us": {"mean": round(select_us[0], 2), "median": round(select_us[1], 2), "min": round(select_us[2], 2), "p10": round(select_us[3], 2), "p90": round(select_us[4], 2)},
         "speedup_vs_dense": round(dense_us[0] / sparse_us[0], 3) if not args.no_dense and sparse_us[0] > 0 else None,
         "gathered_kv_gbs": {"b_set": round(b_set / (sparse_us[0] * 1e-6) / 1e9, 1),

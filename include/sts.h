@@ -21,6 +21,12 @@
  *  - Results are deterministic run to run: the split count depends only on the shape and the
  *    partial results are combined in a fixed order; selection uses integer arithmetic only.
  *  - bf16 tensors are raw 16-bit patterns. All accumulation is fp32.
+ *  - Two environment variables are read per call, for tuning and tests only:
+ *    STS_ATTN_WGS_PER_CU (target workgroups per compute unit when the context is split; it
+ *    changes the split count, hence the attention workspace size and the rounding of the
+ *    output, so keep it constant within a process) and STS_SELECT_SPIN_LIMIT (polls of
+ *    another workgroup's published chunk counts before they are recomputed locally; default
+ *    256; no effect on results).
  */
 #ifndef STS_H
 #define STS_H

@@ -219,7 +219,9 @@ typedef enum {
   STS_K_SELECT_BLOCK = 8,  /* per-block score sums + first-digit histogram (page_size > 1) */
   STS_K_HEADMAP = 9,       /* Algorithm 1: overlap counting and argmax */
   STS_K_SELECT_SMALL = 10, /* whole selection in one workgroup per row (rows up to 32768 tokens) */
-  STS_K_COUNT_ = 11
+  STS_K_SELECT_LOCAL = 11, /* small budgets: aggregation + top-k inside each 8192-token chunk */
+  STS_K_SELECT_POOL = 12,  /* small budgets: ranking of the chunks' winners, one workgroup per row */
+  STS_K_COUNT_ = 13
 } sts_kernel_kind;
 #define STS_PROF_MAX 4096
 

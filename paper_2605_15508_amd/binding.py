@@ -16,7 +16,7 @@ STS_REDUCE_SUM, STS_REDUCE_MAX = 0, 1
 STS_BF16, STS_F32 = 0, 1
 KERNEL_KINDS = {"select_clear": 0, "select_agg": 1, "select_hist": 2, "select_count": 3,
                 "select_write": 4, "attn_sparse": 5, "attn_dense": 6, "attn_combine": 7, "select_block": 8,
-                "headmap": 9, "select_small": 10}
+                "headmap": 9, "select_small": 10, "select_local": 11, "select_pool": 12}
 
 # every symbol include/sts.h declares
 EXPORTS = ["sts_select_workspace_bytes", "sts_attn_workspace_bytes", "sts_select", "sts_sparse_attn",

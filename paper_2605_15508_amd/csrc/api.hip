@@ -219,9 +219,15 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
 // --------------------------------------------------------------------------- select plan
 struct SelectPlan {
   bool small;          // one workgroup per row, keys in LDS, a single launch
-  int nchunks, page, srcN;
+  bool pool;           // shape allows chunk-local top-k + one ranking workgroup per row
+  int nchunks, page, srcN, pool_pitch;
   size_t agg_bytes, blk_bytes, hist_bytes, state_bytes, chunk_bytes;
-  size_t total() const { return agg_bytes + blk_bytes + hist_bytes + state_bytes + chunk_bytes; }
+  size_t pool_key_bytes, pool_cnt_bytes;
+  size_t pipeline_total() const { return agg_bytes + blk_bytes + hist_bytes + state_bytes + chunk_bytes; }
+  size_t pool_total() const { return pool ? 2 * pool_key_bytes + pool_cnt_bytes : 0; }
+  // a pool-shaped call falls back to the pipeline when its pointers are not 16-byte aligned,
+  // so the workspace covers both
+  size_t total() const { return pipeline_total() > pool_total() ? pipeline_total() : pool_total(); }
 };
 
 sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
@@ -241,10 +247,31 @@ sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
   // (one launch instead of six), and for rows up to the LDS limit when there are enough rows
   // to fill the chip anyway; longer or fewer rows keep the many-workgroup pipeline.
   pl.small = pl.page == 1 && (p->N <= SEL_FUSED_N || (p->N <= SEL_SMALL_N && rows >= 256));
+  pl.pool = false;
+  pl.pool_pitch = 0;
+  pl.pool_key_bytes = pl.pool_cnt_bytes = 0;
   if (pl.small) {
     pl.nchunks = 0;
     pl.agg_bytes = pl.blk_bytes = pl.hist_bytes = pl.state_bytes = pl.chunk_bytes = 0;
     return STS_OK;
+  }
+  // Small budgets on long rows: each 8192-token chunk keeps its own best k tokens and one
+  // workgroup per row ranks that pool out of LDS (two launches, the scores are read once and
+  // the aggregate is never stored). The ranking workgroup works at one CU's pace, about 1.2 us
+  // per 1000 pooled pairs on top of 10 us, so the pool must be small: up to 8192 pairs it beats
+  // the five-launch pipeline for every shape measured, up to 16384 only when the pipeline's
+  // passes over the aggregate are long (8M scores or more in the call).
+  {
+    const int64_t pitch = p->k < SEL_CHUNK ? p->k : SEL_CHUNK;
+    const int64_t pooled = (int64_t)pl.nchunks * pitch;
+    const bool fits = pooled <= SEL_POOL_MAX / 2 ||
+                      (pooled <= SEL_POOL_MAX && (int64_t)rows * p->N >= (int64_t)1 << 23);
+    if (pl.page == 1 && (p->N % 4) == 0 && pl.nchunks <= 1024 && fits) {
+      pl.pool = true;
+      pl.pool_pitch = (int)pitch;
+      pl.pool_key_bytes = align256(rows * (size_t)pl.nchunks * (size_t)pitch * sizeof(uint32_t));
+      pl.pool_cnt_bytes = align256(rows * (size_t)pl.nchunks * sizeof(uint32_t));
+    }
   }
   pl.agg_bytes = p->agg_out ? 0 : align256(rows * (size_t)p->N * sizeof(float));
   pl.blk_bytes = pl.page > 1 ? align256(rows * (size_t)pl.srcN * sizeof(float)) : 0;
@@ -356,6 +383,19 @@ static sts_status enqueue_select(const sts_select_params *p, void *stream) {
   }
 
   hipError_t rc;
+  if (pl.pool && reinterpret_cast<uintptr_t>(p->scores) % 16 == 0 &&
+      (!p->agg_out || reinterpret_cast<uintptr_t>(p->agg_out) % 16 == 0)) {
+    unsigned char *pw = static_cast<unsigned char *>(p->workspace);
+    a.pool_key = reinterpret_cast<uint32_t *>(pw);
+    a.pool_idx = reinterpret_cast<int32_t *>(pw + pl.pool_key_bytes);
+    a.pool_cnt = reinterpret_cast<uint32_t *>(pw + 2 * pl.pool_key_bytes);
+    a.pool_pitch = pl.pool_pitch;
+    a.agg = p->agg_out;   // optional output only
+    rc = run_kernel(STS_K_SELECT_LOCAL, s, [&] { return launch_select_local(a, s); });
+    if (rc != hipSuccess) return STS_EHIP;
+    rc = run_kernel(STS_K_SELECT_POOL, s, [&] { return launch_select_pool(a, s); });
+    return rc == hipSuccess ? STS_OK : STS_EHIP;
+  }
   if (pl.small) {
     a.agg = p->agg_out;   // optional output only: the keys never leave LDS
     rc = run_kernel(STS_K_SELECT_SMALL, s, [&] { return launch_select_small(a, s); });
@@ -492,7 +532,7 @@ const char *sts_strerror(sts_status s) {
   return "unknown status";
 }
 
-int sts_version(void) { return 104; }
+int sts_version(void) { return 105; }
 
 void sts_prof_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);

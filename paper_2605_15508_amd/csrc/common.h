@@ -66,7 +66,8 @@ constexpr int SEL_CHUNK = 8192;         // tokens per workgroup in the scan kern
 constexpr int SEL_THREADS = 256;
 constexpr int SEL_SMALL_N = 32768;      // LDS capacity of the one-workgroup-per-row selection (tokens)
 constexpr int SEL_FLAG_PITCH = 32;      // words between the published counts of two chunks: one 128-byte line each
-constexpr int SEL_FUSED_N = 8192;       // rows up to this many tokens always take it
+constexpr int SEL_FUSED_N = 8192;
+constexpr int SEL_POOL_MAX = 16384;     // chunk-local winners per row that the pool kernel ranks out of LDS       // rows up to this many tokens always take it
 
 struct SelectTargets {
   // targets of draft head j: tgt[off[j] .. off[j+1])
@@ -86,6 +87,10 @@ struct SelectArgs {
   uint32_t *hist;             // [rows][3][SEL_BINS]
   uint32_t *state;            // [rows][8]: digits 0/1 and remaining k after each, [6] budget
   uint32_t *chunk_cnt;        // [rows][nchunks][SEL_FLAG_PITCH], word 0: published flag | equal count << 14 | greater count
+  uint32_t *pool_key;         // [rows][nchunks][pool_pitch] chunk-local winners (small budgets), in token order
+  int32_t *pool_idx;          // their token ids
+  uint32_t *pool_cnt;         // [rows][nchunks] pairs kept per chunk
+  int32_t pool_pitch;         // min(k, SEL_CHUNK)
   uint64_t clear_words;       // words to zero from `hist` on: histograms, state and chunk flags
   int32_t spin_limit;         // polls of an unpublished earlier chunk before it is recounted locally
   int32_t B, Hd, Tq, N, Hq, k, kind, reduce, nchunks;   // k: row pitch of indices = largest budget
@@ -100,6 +105,8 @@ hipError_t launch_select_clear(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_agg(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_block(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_small(const SelectArgs &a, hipStream_t s);
+hipError_t launch_select_local(const SelectArgs &a, hipStream_t s);
+hipError_t launch_select_pool(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t s);
 hipError_t launch_select_write(const SelectArgs &a, hipStream_t s);
 hipError_t launch_headmap_clear(unsigned long long *overlap, int n, hipStream_t s);

@@ -2,17 +2,24 @@
 // index sets, remapped to the target heads (paper Section 4.2; Section 4.3: one mask per
 // speculative batch).
 //
-// Pipeline, one row = one (batch, draft head), every kernel on a (chunk, row) grid:
-//   clear  zero the three digit histograms of every row
-//   agg    A[n] = ((P[0,n] + P[1,n]) + ...) in fp32, stored; histogram of the top 11 key bits
-//   hist1  find the first digit of the k-th largest key, histogram the next 11 bits of the
-//          keys that share it
-//   hist2  same for the last 10 bits
-//   count  the k-th largest key T is now known, with r = how many keys equal to T are kept;
-//          per-chunk counts of keys > T and == T
-//   write  ordered compaction: token n is kept iff key > T, or key == T and fewer than r equal
-//          keys precede it; its output position is (#greater before n) + min(#equal before n, r).
-//          The list is written to every target head mapped to this draft head.
+// Three ways through, chosen on the host from the shape; one row = one (batch, draft head):
+//  * long rows, any budget -- every kernel on a (chunk, row) grid of 8192-token chunks:
+//      clear  zero the three digit histograms and the chunk flags of every row
+//      agg    A[n] = ((P[0,n] + P[1,n]) + ...) in fp32, stored; histogram of the top 11 key bits
+//      hist1  find the first digit of the k-th largest key, histogram the next 11 bits of the
+//             keys that share it
+//      hist2  same for the last 10 bits
+//      write  the k-th largest key T is now known, with r = how many keys equal to T are kept.
+//             Ordered compaction: token n is kept iff key > T, or key == T and fewer than r
+//             equal keys precede it; its output position is (#greater before n) + min(#equal
+//             before n, r). The counts of the chunks before this one come from the words those
+//             chunks publish. The list is written to every target head mapped to the draft head.
+//  * long rows, small budgets (chunks * budget <= 16384) -- two launches, nothing to clear:
+//      local  aggregate a chunk, keep its keys in registers, and rank them inside the chunk: the
+//             chunk's own top-k (same tie rule) goes to a pool, in token order. Every token of
+//             the row's top-k is in the top-k of its chunk.
+//      pool   one workgroup per row ranks the pooled candidates out of LDS and writes the list.
+//  * short rows -- one workgroup per row does everything out of LDS (select_small_kernel).
 // Keys are the usual order-preserving map of fp32 to uint32 (with -0 folded onto +0), so the
 // whole selection is integer arithmetic: the index sets are exact, ties go to the lower token.
 // Histograms use LDS atomics per workgroup and integer global atomics to merge (order-free).
@@ -42,17 +49,27 @@ __device__ __forceinline__ int src_len(const SelectArgs &A, int bt) {
   return (row_len(A, bt) + A.page - 1) / A.page;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves (no LDS
+// round trips): shifts by 1, 2, 4, 8 inside each row of 16 lanes (a lane whose source lies
+// outside its row adds 0), then lane 15 of row 0 / 2 is added to row 1 / 3, then lane 31 to
+// rows 2 and 3.
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
+  int x = (int)v;
+  x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, false);   // row_shr:1
+  x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, false);   // row_shr:2
+  x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, false);   // row_shr:4
+  x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, false);   // row_shr:8
+  x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+  x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+  return (uint32_t)x;
+}
+
 // exclusive prefix sum of one value per thread over a THREADS-thread block; also returns the
 // total. lds_wave_tot needs THREADS/64 words.
 template <int THREADS = SEL_THREADS>
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *lds_wave_tot, uint32_t &total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  uint32_t incl = v;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t o = __shfl_up(incl, off, 64);
-    if (lane >= off) incl += o;
-  }
+  const uint32_t incl = wave_incl_scan(v);
   if (lane == 63) lds_wave_tot[wave] = incl;
   __syncthreads();
   uint32_t base = 0, tot = 0;
@@ -98,6 +115,88 @@ __device__ __forceinline__ void find_digit(const uint32_t *hist, uint32_t krem, 
   __syncthreads();
 }
 
+// ------------------------------------------------------------------- aggregation of a row
+// The Tq score rows of one (batch, draft head), reduced per token strictly in row order.
+struct AggRow {
+  const float *P;   // [Tq][N]
+  const float *L;   // [Tq] natural-log normalisers (scaled-logit input) or nullptr
+  int Tq, N;
+  bool logits, use_max;
+};
+
+__device__ __forceinline__ AggRow agg_row(const SelectArgs &A, int row) {
+  AggRow R;
+  R.P = A.scores + (size_t)row * A.Tq * A.N;
+  R.L = A.lse ? A.lse + (size_t)row * A.Tq : nullptr;
+  R.Tq = A.Tq;
+  R.N = A.N;
+  R.logits = A.kind == STS_SCORES_LOGITS_LSE;
+  R.use_max = A.reduce == STS_REDUCE_MAX;
+  return R;
+}
+
+// NROWS consecutive score rows, from row i on, of the token(s) at n: all loads first (their
+// latencies overlap; nontemporal: every score is read exactly once), then the reduction
+// strictly in row order. FIRST: row i is row 0 and initialises the accumulator. V is float (one
+// token) or f32x4 (tokens n..n+3, n % 4 == 0, rows 16-byte aligned).
+template <int NROWS, bool FIRST, class V>
+__device__ __forceinline__ void agg_rows(const AggRow &R, int i, int n, V &acc) {
+  V p[NROWS];
+#pragma unroll
+  for (int u = 0; u < NROWS; ++u)
+    p[u] = __builtin_nontemporal_load(reinterpret_cast<const V *>(R.P + (size_t)(i + u) * R.N + n));
+#pragma unroll
+  for (int u = 0; u < NROWS; ++u) {
+    if (R.logits) {
+      const float l = R.L[i + u];
+      if constexpr (sizeof(V) == sizeof(float)) {
+        p[u] = prob_of(p[u], l);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) p[u][e] = prob_of(p[u][e], l);
+      }
+    }
+    if (FIRST && u == 0) {
+      acc = p[u];
+    } else if (R.use_max) {
+      if constexpr (sizeof(V) == sizeof(float)) {
+        acc = fmaxf(acc, p[u]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] = fmaxf(acc[e], p[u][e]);
+      }
+    } else {
+      acc = acc + p[u];
+    }
+  }
+}
+
+template <bool FIRST, class V>
+__device__ __forceinline__ void agg_group(const AggRow &R, int i, int rows, int n, V &acc) {
+  switch (rows) {   // uniform: a scalar branch; every case is straight-line code
+    case 1: agg_rows<1, FIRST>(R, i, n, acc); break;
+    case 2: agg_rows<2, FIRST>(R, i, n, acc); break;
+    case 3: agg_rows<3, FIRST>(R, i, n, acc); break;
+    case 4: agg_rows<4, FIRST>(R, i, n, acc); break;
+    case 5: agg_rows<5, FIRST>(R, i, n, acc); break;
+    case 6: agg_rows<6, FIRST>(R, i, n, acc); break;
+    case 7: agg_rows<7, FIRST>(R, i, n, acc); break;
+    default: agg_rows<8, FIRST>(R, i, n, acc); break;
+  }
+}
+
+// aggregated score(s) at n: rows in groups of up to 8 loads in flight
+template <class V>
+__device__ __forceinline__ V agg_at(const AggRow &R, int n) {
+  V acc;
+  agg_group<true>(R, 0, min(R.Tq, 8), n, acc);
+  for (int i = 8; i < R.Tq; i += 8) agg_group<false>(R, i, min(R.Tq - i, 8), n, acc);
+  return acc;
+}
+
+__device__ __forceinline__ f32x4 agg_quad(const AggRow &R, int n) { return agg_at<f32x4>(R, n); }
+__device__ __forceinline__ float agg_one(const AggRow &R, int n) { return agg_at<float>(R, n); }
+
 // Add a workgroup's LDS histogram to the row's global one. Two neighbouring 32-bit bins travel
 // in one 64-bit atomic (a row holds fewer than 2^32 keys, so the low bin never carries into
 // the high one), which halves the number of atomics.
@@ -124,47 +223,13 @@ __global__ void __launch_bounds__(SEL_THREADS) select_agg_kernel(const SelectArg
   const int nb = row_len(A, bt);
   for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) h[i] = 0u;
   __syncthreads();
-  const float *P = A.scores + (size_t)row * A.Tq * A.N;
-  const float *L = A.lse ? A.lse + (size_t)row * A.Tq : nullptr;
+  const AggRow R = agg_row(A, row);
   float *out = A.agg + (size_t)row * A.N;
   const int n0 = chunk * SEL_CHUNK;
   const int n1 = min(n0 + SEL_CHUNK, A.N);
-  const bool logits = A.kind == STS_SCORES_LOGITS_LSE;
-  const bool use_max = A.reduce == STS_REDUCE_MAX;
-
-  auto reduce1 = [&](float acc, float p, int i) -> float {
-    if (i == 0) return p;
-    return use_max ? fmaxf(acc, p) : acc + p;
-  };
-
-  // The Tq rows are loaded in independent batches of AGG_BATCH so their latencies overlap;
-  // the reduction itself stays strictly in row order.
-  constexpr int AGG_BATCH = 8;
   if (VEC4) {
     for (int n = n0 + threadIdx.x * 4; n < n1; n += SEL_THREADS * 4) {
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-      for (int i0 = 0; i0 < A.Tq; i0 += AGG_BATCH) {
-        f32x4 p[AGG_BATCH];
-#pragma unroll
-        for (int u = 0; u < AGG_BATCH; ++u) {
-          p[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-          if (i0 + u < A.Tq)   // uniform: no load is issued for rows that do not exist
-            p[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(P + (size_t)(i0 + u) * A.N + n));
-        }
-#pragma unroll
-        for (int u = 0; u < AGG_BATCH; ++u) {
-          const int i = i0 + u;
-          if (i < A.Tq) {
-            if (logits) {
-              const float l = L[i];
-#pragma unroll
-              for (int e = 0; e < 4; ++e) p[u][e] = prob_of(p[u][e], l);
-            }
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[e] = reduce1(acc[e], p[u][e], i);
-          }
-        }
-      }
+      const f32x4 acc = agg_quad(R, n);
       *reinterpret_cast<f32x4 *>(out + n) = acc;
 #pragma unroll
       for (int e = 0; e < 4; ++e)
@@ -172,20 +237,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_agg_kernel(const SelectArg
     }
   } else {
     for (int n = n0 + threadIdx.x; n < n1; n += SEL_THREADS) {
-      float acc = 0.f;
-      for (int i0 = 0; i0 < A.Tq; i0 += AGG_BATCH) {
-        float p[AGG_BATCH];
-#pragma unroll
-        for (int u = 0; u < AGG_BATCH; ++u) p[u] = (i0 + u < A.Tq) ? P[(size_t)(i0 + u) * A.N + n] : 0.f;
-#pragma unroll
-        for (int u = 0; u < AGG_BATCH; ++u) {
-          const int i = i0 + u;
-          if (i < A.Tq) {
-            const float x = logits ? prob_of(p[u], L[i]) : p[u];
-            acc = reduce1(acc, x, i);
-          }
-        }
-      }
+      const float acc = agg_one(R, n);
       out[n] = acc;
       if (A.page == 1 && n < nb) atomicAdd(&h[key_of(acc) >> (32 - SEL_BITS0)], 1u);
     }
@@ -500,14 +552,85 @@ __global__ void __launch_bounds__(SEL_THREADS, 4) select_write_kernel(const Sele
   }
 }
 
+// ------------------------------------------------------- ranking keys that sit in LDS
+constexpr int SMALL_THREADS = 1024;
+__device__ __forceinline__ int small_slot(int n) { return n + (n >> 5); }   // pad 1 word per 32: conflict-free strided reads
+
+// The c-th largest of keys[small_slot(0 .. m)) and the number r of keys equal to it that are
+// kept. On entry h holds the histogram of the first digit of those m keys; h and tmp
+// (THREADS/64 + 2 words) are scratch. Requires 1 <= c <= m.
+template <int THREADS>
+__device__ __forceinline__ void lds_threshold(const uint32_t *keys, int m, uint32_t *h, uint32_t *tmp, uint32_t c,
+                                              uint32_t &T, uint32_t &r) {
+  const int tid = threadIdx.x;
+  uint32_t d0, k1, d1, k2, d2;
+  find_digit<(1 << SEL_BITS0), THREADS>(h, c, tmp, d0, k1);
+  for (int i = tid; i < SEL_BINS; i += THREADS) h[i] = 0u;
+  __syncthreads();
+  for (int n = tid; n < m; n += THREADS) {
+    const uint32_t key = keys[small_slot(n)];
+    if ((key >> (SEL_BITS1 + SEL_BITS2)) == d0) atomicAdd(&h[(key >> SEL_BITS2) & ((1u << SEL_BITS1) - 1)], 1u);
+  }
+  __syncthreads();
+  find_digit<(1 << SEL_BITS1), THREADS>(h, k1, tmp, d1, k2);
+  for (int i = tid; i < SEL_BINS; i += THREADS) h[i] = 0u;
+  __syncthreads();
+  const uint32_t pre01 = (d0 << SEL_BITS1) | d1;
+  for (int n = tid; n < m; n += THREADS) {
+    const uint32_t key = keys[small_slot(n)];
+    if ((key >> SEL_BITS2) == pre01) atomicAdd(&h[key & ((1u << SEL_BITS2) - 1)], 1u);
+  }
+  __syncthreads();
+  find_digit<(1 << SEL_BITS2), THREADS>(h, k2, tmp, d2, r);
+  T = (pre01 << SEL_BITS2) | d2;
+}
+
+// Ordered compaction of the same keys: every thread owns a run of consecutive entries; entry n
+// is kept iff key > T, or key == T and fewer than r equal keys precede it, and emit(pos, n) is
+// called with its position in the output list, pos = (#greater before n) + min(#equal before n, r).
+template <int THREADS, class Emit>
+__device__ __forceinline__ void lds_compact(const uint32_t *keys, int m, uint32_t T, uint32_t r, uint32_t c,
+                                            uint32_t *tmp, Emit emit) {
+  const int tid = threadIdx.x;
+  const int per = (m + THREADS - 1) / THREADS;
+  const int nlo = min(tid * per, m), nhi = min(nlo + per, m);
+  uint32_t cg = 0, ce = 0;
+  for (int n = nlo; n < nhi; ++n) {
+    const uint32_t key = keys[small_slot(n)];
+    cg += key > T ? 1u : 0u;
+    ce += key == T ? 1u : 0u;
+  }
+  uint32_t total;
+  const uint32_t excl = block_excl_scan<THREADS>(cg | (ce << 16), tmp, total);   // m <= 32768: both sums fit 16 bits
+  uint32_t g = excl & 0xffffu, q = excl >> 16;
+  for (int n = nlo; n < nhi; ++n) {
+    const uint32_t key = keys[small_slot(n)];
+    const bool is_gt = key > T, is_eq = key == T;
+    if (is_gt || (is_eq && q < r)) {
+      const uint32_t pos = g + min(q, r);
+      if (pos < c) emit(pos, n);   // always true for a consistent threshold; keeps a bad state in bounds
+    }
+    g += is_gt ? 1u : 0u;
+    q += is_eq ? 1u : 0u;
+  }
+}
+
+// tail padding (-1 from position c on) and counts for every target head of draft head j
+template <int THREADS>
+__device__ __forceinline__ void write_tail(const SelectArgs &A, int bt, int j, uint32_t c) {
+  for (int ti = A.targets.off[j]; ti < A.targets.off[j + 1]; ++ti) {
+    const int tgt = A.targets.tgt[ti];
+    int32_t *dst = A.indices + ((size_t)bt * A.Hq + tgt) * A.k;
+    for (uint32_t p = c + threadIdx.x; p < (uint32_t)A.k; p += THREADS) dst[p] = -1;
+    if (A.counts && threadIdx.x == 0) A.counts[(size_t)bt * A.Hq + tgt] = (int32_t)c;
+  }
+}
+
 // ------------------------------------------------- whole selection in one workgroup per row
 // For rows of up to SEL_SMALL_N tokens the keys of a row fit in LDS (128 KB of the 160 KB), so
 // one 1024-thread workgroup per (batch, draft head) does everything in a single launch:
 // aggregate (same fp32 order), three digit histograms over the LDS-resident keys, ordered
 // compaction and the copies to the target heads. No global histograms, nothing to clear.
-constexpr int SMALL_THREADS = 1024;
-__device__ __forceinline__ int small_slot(int n) { return n + (n >> 5); }   // pad 1 word per 32: conflict-free strided reads
-
 template <bool VEC4>
 __global__ void __launch_bounds__(SMALL_THREADS) select_small_kernel(const SelectArgs A) {
   __shared__ uint32_t keys[SEL_SMALL_N + SEL_SMALL_N / 32];
@@ -519,53 +642,17 @@ __global__ void __launch_bounds__(SMALL_THREADS) select_small_kernel(const Selec
   const uint32_t c = (uint32_t)min(A.kh[j], nb);
   const int t0 = A.targets.off[j], t1 = A.targets.off[j + 1];
   const int tid = threadIdx.x;
-  // tail padding and counts
-  for (int ti = t0; ti < t1; ++ti) {
-    const int tgt = A.targets.tgt[ti];
-    int32_t *dst = A.indices + ((size_t)bt * A.Hq + tgt) * A.k;
-    for (uint32_t p = c + tid; p < (uint32_t)A.k; p += SMALL_THREADS) dst[p] = -1;
-    if (A.counts && tid == 0) A.counts[(size_t)bt * A.Hq + tgt] = (int32_t)c;
-  }
+  write_tail<SMALL_THREADS>(A, bt, j, c);
   const bool want_agg = A.agg != nullptr;
   if ((c == 0 || t0 == t1) && !want_agg) return;
 
   for (int i = tid; i < SEL_BINS; i += SMALL_THREADS) h[i] = 0u;
   __syncthreads();
-  const float *P = A.scores + (size_t)row * A.Tq * A.N;
-  const float *Lse = A.lse ? A.lse + (size_t)row * A.Tq : nullptr;
+  const AggRow R = agg_row(A, row);
   float *out = want_agg ? A.agg + (size_t)row * A.N : nullptr;
-  const bool logits = A.kind == STS_SCORES_LOGITS_LSE;
-  const bool use_max = A.reduce == STS_REDUCE_MAX;
-  auto reduce1 = [&](float acc, float p, int i) -> float {
-    if (i == 0) return p;
-    return use_max ? fmaxf(acc, p) : acc + p;
-  };
-  constexpr int AGG_BATCH = 8;
   if (VEC4) {
     for (int n = tid * 4; n < A.N; n += SMALL_THREADS * 4) {
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-      for (int i0 = 0; i0 < A.Tq; i0 += AGG_BATCH) {
-        f32x4 p[AGG_BATCH];
-#pragma unroll
-        for (int u = 0; u < AGG_BATCH; ++u) {
-          p[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-          if (i0 + u < A.Tq)
-            p[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(P + (size_t)(i0 + u) * A.N + n));
-        }
-#pragma unroll
-        for (int u = 0; u < AGG_BATCH; ++u) {
-          const int i = i0 + u;
-          if (i < A.Tq) {
-            if (logits) {
-              const float l = Lse[i];
-#pragma unroll
-              for (int e = 0; e < 4; ++e) p[u][e] = prob_of(p[u][e], l);
-            }
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[e] = reduce1(acc[e], p[u][e], i);
-          }
-        }
-      }
+      const f32x4 acc = agg_quad(R, n);
       if (want_agg) *reinterpret_cast<f32x4 *>(out + n) = acc;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
@@ -576,12 +663,7 @@ __global__ void __launch_bounds__(SMALL_THREADS) select_small_kernel(const Selec
     }
   } else {
     for (int n = tid; n < A.N; n += SMALL_THREADS) {
-      float acc = 0.f;
-      for (int i = 0; i < A.Tq; ++i) {
-        float p = P[(size_t)i * A.N + n];
-        if (logits) p = prob_of(p, Lse[i]);
-        acc = reduce1(acc, p, i);
-      }
+      const float acc = agg_one(R, n);
       if (want_agg) out[n] = acc;
       const uint32_t key = key_of(acc);
       keys[small_slot(n)] = key;
@@ -591,52 +673,237 @@ __global__ void __launch_bounds__(SMALL_THREADS) select_small_kernel(const Selec
   __syncthreads();
   if (c == 0 || t0 == t1) return;
 
-  // ---- threshold: three digits, histograms rebuilt in LDS from the LDS-resident keys
-  uint32_t d0, k1, d1, k2, d2, r;
-  find_digit<(1 << SEL_BITS0), SMALL_THREADS>(h, c, tmp, d0, k1);
-  for (int i = tid; i < SEL_BINS; i += SMALL_THREADS) h[i] = 0u;
+  uint32_t T, r;
+  lds_threshold<SMALL_THREADS>(keys, nb, h, tmp, c, T, r);
+  lds_compact<SMALL_THREADS>(keys, nb, T, r, c, tmp, [&](uint32_t pos, int n) {
+    for (int ti = t0; ti < t1; ++ti) A.indices[((size_t)bt * A.Hq + A.targets.tgt[ti]) * A.k + pos] = n;
+  });
+}
+
+// ---------------------------------------------- small budgets on long rows: chunk-local top-k
+// Every token of a row's top-c (ordered by key descending, then token ascending) has fewer
+// than c tokens of the whole row before it in that order, hence fewer than c tokens of its own
+// chunk: it belongs to the top-c of its chunk under the same rule. So each chunk keeps only
+// its own best min(c, chunk length) tokens (the pool), and the row is ranked from the pool.
+//
+// Local kernel, (chunk, row) grid, 256 threads: aggregates the chunk (same fp32 order), keeps
+// the 32 keys of each thread in registers, finds the chunk's threshold with three LDS digit
+// histograms, and writes the kept (key, token) pairs to the chunk's pool segment in token
+// order. Thread t owns tokens n0 + i*1024 + 4t .. +3 for i = 0..7, so token order is (i, t).
+template <int IT>
+struct LocalKeys {
+  uint32_t k[IT][4];
+};
+
+__global__ void __launch_bounds__(SEL_THREADS) select_local_kernel(const SelectArgs A) {
+  constexpr int IT = SEL_CHUNK / (SEL_THREADS * 4);
+  __shared__ uint32_t h[SEL_BINS];
+  __shared__ uint32_t tmp[16];
+  const int row = blockIdx.y, chunk = blockIdx.x;
+  const int bt = row / A.Hd, j = row % A.Hd;
+  const int nb = row_len(A, bt);
+  const int n0 = chunk * SEL_CHUNK;
+  const int nvalid = max(0, min(n0 + SEL_CHUNK, nb) - n0);     // ranked tokens of this chunk
+  uint32_t c = (uint32_t)min(A.kh[j], nvalid);
+  const bool want_agg = A.agg != nullptr;
+  uint32_t *cnt_out = A.pool_cnt + (size_t)row * A.nchunks + chunk;
+  if (A.targets.off[j] == A.targets.off[j + 1]) c = 0;        // no target head reads this draft head
+  if (c == 0 && !want_agg) {
+    if (threadIdx.x == 0) *cnt_out = 0u;
+    return;
+  }
+  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) h[i] = 0u;
   __syncthreads();
-  for (int n = tid; n < nb; n += SMALL_THREADS) {
-    const uint32_t key = keys[small_slot(n)];
-    if ((key >> (SEL_BITS1 + SEL_BITS2)) == d0) atomicAdd(&h[(key >> SEL_BITS2) & ((1u << SEL_BITS1) - 1)], 1u);
+  const AggRow R = agg_row(A, row);
+  float *out = want_agg ? A.agg + (size_t)row * A.N : nullptr;
+  LocalKeys<IT> K;
+#pragma clang loop unroll(full)
+  for (int i = 0; i < IT; ++i) {
+    const int n = n0 + (i * SEL_THREADS + threadIdx.x) * 4;
+    if (n < A.N) {                                             // N % 4 == 0 on this path
+      const f32x4 acc = agg_quad(R, n);
+      if (want_agg) *reinterpret_cast<f32x4 *>(out + n) = acc;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        K.k[i][e] = key_of(acc[e]);
+        if (n + e < nb) atomicAdd(&h[K.k[i][e] >> (32 - SEL_BITS0)], 1u);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) K.k[i][e] = 0u;
+    }
   }
   __syncthreads();
-  find_digit<(1 << SEL_BITS1), SMALL_THREADS>(h, k1, tmp, d1, k2);
-  for (int i = tid; i < SEL_BINS; i += SMALL_THREADS) h[i] = 0u;
+  if (c == 0) {
+    if (threadIdx.x == 0) *cnt_out = 0u;
+    return;
+  }
+  // threshold of the chunk: three digits over the register-resident keys
+  uint32_t d0, k1, d1, k2, d2, r;
+  find_digit<(1 << SEL_BITS0)>(h, c, tmp, d0, k1);
+  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) h[i] = 0u;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < IT; ++i)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int n = n0 + (i * SEL_THREADS + threadIdx.x) * 4 + e;
+      const uint32_t key = K.k[i][e];
+      if (n < nb && (key >> (SEL_BITS1 + SEL_BITS2)) == d0) atomicAdd(&h[(key >> SEL_BITS2) & ((1u << SEL_BITS1) - 1)], 1u);
+    }
+  __syncthreads();
+  find_digit<(1 << SEL_BITS1)>(h, k1, tmp, d1, k2);
+  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) h[i] = 0u;
   __syncthreads();
   const uint32_t pre01 = (d0 << SEL_BITS1) | d1;
-  for (int n = tid; n < nb; n += SMALL_THREADS) {
-    const uint32_t key = keys[small_slot(n)];
-    if ((key >> SEL_BITS2) == pre01) atomicAdd(&h[key & ((1u << SEL_BITS2) - 1)], 1u);
-  }
+#pragma unroll
+  for (int i = 0; i < IT; ++i)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int n = n0 + (i * SEL_THREADS + threadIdx.x) * 4 + e;
+      const uint32_t key = K.k[i][e];
+      if (n < nb && (key >> SEL_BITS2) == pre01) atomicAdd(&h[key & ((1u << SEL_BITS2) - 1)], 1u);
+    }
   __syncthreads();
-  find_digit<(1 << SEL_BITS2), SMALL_THREADS>(h, k2, tmp, d2, r);
+  find_digit<(1 << SEL_BITS2)>(h, k2, tmp, d2, r);
   const uint32_t T = (pre01 << SEL_BITS2) | d2;
 
-  // ---- ordered compaction: every thread owns a run of consecutive tokens
-  const int per = (nb + SMALL_THREADS - 1) / SMALL_THREADS;      // <= 32
-  const int nlo = min(tid * per, nb), nhi = min(nlo + per, nb);
-  uint32_t cg = 0, ce = 0;
-  for (int n = nlo; n < nhi; ++n) {
-    const uint32_t key = keys[small_slot(n)];
-    cg += key > T ? 1u : 0u;
-    ce += key == T ? 1u : 0u;
-  }
-  uint32_t total;
-  const uint32_t excl = block_excl_scan<SMALL_THREADS>(cg | (ce << 16), tmp, total);
-  uint32_t g = excl & 0xffffu, q = excl >> 16;
-  for (int n = nlo; n < nhi; ++n) {
-    const uint32_t key = keys[small_slot(n)];
-    const bool is_gt = key > T, is_eq = key == T;
-    if (is_gt || (is_eq && q < r)) {
-      const uint32_t pos = g + min(q, r);
-      if (pos < c)   // always true for a consistent threshold; keeps a bad state in bounds
-        for (int ti = t0; ti < t1; ++ti)
-          A.indices[((size_t)bt * A.Hq + A.targets.tgt[ti]) * A.k + pos] = n;
+  // ordered compaction into the chunk's pool segment: one block scan per sweep of 1024 tokens
+  uint32_t *pk = A.pool_key + ((size_t)row * A.nchunks + chunk) * A.pool_pitch;
+  int32_t *pi = A.pool_idx + ((size_t)row * A.nchunks + chunk) * A.pool_pitch;
+  uint32_t g0 = 0, q0 = 0;                                     // greater / equal in the sweeps before
+#pragma unroll
+  for (int i = 0; i < IT; ++i) {
+    const int n = n0 + (i * SEL_THREADS + threadIdx.x) * 4;
+    uint32_t cg = 0, ce = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const bool in = n + e < nb;
+      cg += (in && K.k[i][e] > T) ? 1u : 0u;
+      ce += (in && K.k[i][e] == T) ? 1u : 0u;
     }
-    g += is_gt ? 1u : 0u;
-    q += is_eq ? 1u : 0u;
+    uint32_t total;
+    const uint32_t excl = block_excl_scan(cg | (ce << 16), tmp, total);
+    uint32_t g = g0 + (excl & 0xffffu), q = q0 + (excl >> 16);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const bool in = n + e < nb;
+      const bool is_gt = in && K.k[i][e] > T, is_eq = in && K.k[i][e] == T;
+      if (is_gt || (is_eq && q < r)) {
+        const uint32_t pos = g + min(q, r);
+        if (pos < c) {                 // always true for a consistent threshold
+          pk[pos] = K.k[i][e];
+          pi[pos] = n + e;
+        }
+      }
+      g += is_gt ? 1u : 0u;
+      q += is_eq ? 1u : 0u;
+    }
+    g0 += total & 0xffffu;
+    q0 += total >> 16;
   }
+  if (threadIdx.x == 0) *cnt_out = c;
+}
+
+// Pool kernel, one 1024-thread workgroup per row: the chunks' kept pairs, concatenated in
+// chunk order (= token order), are loaded into LDS and ranked like a short row; the kept
+// tokens go to every target head of the draft head.
+constexpr int POOL_MAX = SEL_POOL_MAX;   // pooled pairs per row: keys and tokens fit in LDS
+__global__ void __launch_bounds__(SMALL_THREADS) select_pool_kernel(const SelectArgs A) {
+  __shared__ uint32_t keys[POOL_MAX + POOL_MAX / 32];
+  __shared__ int32_t toks[POOL_MAX + POOL_MAX / 32];
+  __shared__ uint32_t h[SEL_BINS];
+  __shared__ uint32_t offs[SMALL_THREADS];                     // first pooled position of each chunk
+  __shared__ uint32_t tmp[SMALL_THREADS / 64 + 2];
+  const int row = blockIdx.x;
+  const int bt = row / A.Hd, j = row % A.Hd;
+  const int nb = row_len(A, bt);
+  const uint32_t c = (uint32_t)min(A.kh[j], nb);
+  const int t0 = A.targets.off[j], t1 = A.targets.off[j + 1];
+  const int tid = threadIdx.x;
+  write_tail<SMALL_THREADS>(A, bt, j, c);
+  if (c == 0 || t0 == t1) return;
+  for (int i = tid; i < SEL_BINS; i += SMALL_THREADS) h[i] = 0u;
+  // nchunks <= 1024 on this path: one thread per chunk
+  const uint32_t mine = tid < A.nchunks ? A.pool_cnt[(size_t)row * A.nchunks + tid] : 0u;
+  uint32_t m;
+  offs[tid] = block_excl_scan<SMALL_THREADS>(mine, tmp, m);
+  __syncthreads();
+  m = min(m, (uint32_t)POOL_MAX);
+  // The pooled pairs were written by other workgroups: their loads miss the caches, so eight
+  // independent ones are issued per thread before any is used (uniform trip count, clamped
+  // addresses, the surplus ignored).
+  uint32_t kmin = 0xffffffffu, kmax = 0u;
+  for (uint32_t e0 = 0; e0 < m; e0 += SMALL_THREADS * 8) {
+    size_t src[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const uint32_t e = min(e0 + u * SMALL_THREADS + tid, m - 1);
+      // chunk of pooled position e: the last chunk whose first position is <= e (empty chunks
+      // share their first position with the next one and are skipped by taking the last)
+      int lo = 0, hi = A.nchunks - 1;
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (offs[mid] <= e) lo = mid; else hi = mid - 1;
+      }
+      src[u] = ((size_t)row * A.nchunks + lo) * A.pool_pitch + (e - offs[lo]);
+    }
+    uint32_t key[8];
+    int32_t tok[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      key[u] = A.pool_key[src[u]];
+      tok[u] = A.pool_idx[src[u]];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const uint32_t e = e0 + u * SMALL_THREADS + tid;
+      if (e < m) {
+        keys[small_slot((int)e)] = key[u];
+        toks[small_slot((int)e)] = tok[u];
+        kmin = min(kmin, key[u]);
+        kmax = max(kmax, key[u]);
+      }
+    }
+  }
+  // The pooled keys are all large, so their leading bits agree and the first digit would put
+  // them into a handful of bins (LDS atomics on one address serialise). Ranking the keys
+  // shifted left by the length of their common prefix is the same ranking and spreads them.
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off, 64));
+    kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off, 64));
+  }
+  uint32_t *red = reinterpret_cast<uint32_t *>(offs);          // offs is no longer needed
+  __syncthreads();
+  if ((tid & 63) == 0) {
+    red[(tid >> 6) * 2] = kmin;
+    red[(tid >> 6) * 2 + 1] = kmax;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < SMALL_THREADS / 64; ++w) {
+    kmin = min(kmin, red[w * 2]);
+    kmax = max(kmax, red[w * 2 + 1]);
+  }
+  uint32_t T, r;
+  if (kmin == kmax) {
+    T = kmin;            // all pooled keys are equal: the first c in token order are kept
+    r = c;
+  } else {
+    const int shift = __clz((int)(kmin ^ kmax));               // 0..31
+    for (uint32_t e = tid; e < m; e += SMALL_THREADS) {
+      const uint32_t key = keys[small_slot((int)e)] << shift;
+      keys[small_slot((int)e)] = key;
+      atomicAdd(&h[key >> (32 - SEL_BITS0)], 1u);
+    }
+    __syncthreads();
+    lds_threshold<SMALL_THREADS>(keys, (int)m, h, tmp, c, T, r);
+  }
+  lds_compact<SMALL_THREADS>(keys, (int)m, T, r, c, tmp, [&](uint32_t pos, int n) {
+    const int32_t tok = toks[small_slot(n)];
+    for (int ti = t0; ti < t1; ++ti) A.indices[((size_t)bt * A.Hq + A.targets.tgt[ti]) * A.k + pos] = tok;
+  });
 }
 
 }  // namespace
@@ -659,6 +926,18 @@ hipError_t launch_select_small(const SelectArgs &a, hipStream_t s) {
     hipLaunchKernelGGL(select_small_kernel<true>, grid, block, 0, s, a);
   else
     hipLaunchKernelGGL(select_small_kernel<false>, grid, block, 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_select_local(const SelectArgs &a, hipStream_t s) {
+  if ((size_t)a.B * a.Hd == 0 || a.nchunks == 0) return hipSuccess;
+  hipLaunchKernelGGL(select_local_kernel, dim3(a.nchunks, a.B * a.Hd), dim3(SEL_THREADS), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_select_pool(const SelectArgs &a, hipStream_t s) {
+  if ((size_t)a.B * a.Hd == 0) return hipSuccess;
+  hipLaunchKernelGGL(select_pool_kernel, dim3(a.B * a.Hd), dim3(SMALL_THREADS), 0, s, a);
   return hipGetLastError();
 }
 

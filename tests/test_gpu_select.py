@@ -42,7 +42,7 @@ def softmax_scores(seed, B, Hd, Tq, N, temp=2.0):
 
 @pytest.mark.parametrize("B,Hd,Tq,N,Hq,k", [
     (1, 16, 5, 4096, 32, 410),        # the 4K configuration's shape
-    (2, 3, 5, 20000, 6, 2000),        # several chunks per row, ragged last chunk
+    (2, 3, 5, 20000, 6, 2000),        # several chunks per row, ragged last chunk (pool path)
     (1, 2, 1, 8192, 4, 1),            # single query row, k = 1
     (2, 4, 8, 1001, 8, 100),          # N % 4 != 0: scalar path
     (1, 2, 5, 50, 2, 50),             # k = N
@@ -52,7 +52,7 @@ def softmax_scores(seed, B, Hd, Tq, N, temp=2.0):
     (2, 3, 5, 40000, 6, 4000),
     (1, 2, 3, 70001, 4, 123),         # and its scalar variant (N % 4 != 0)
     (1, 4, 5, 8192, 8, 819),          # the longest row that always takes the single-workgroup path
-    (1, 2, 5, 8196, 4, 819),          # the shortest that does not (few rows)
+    (1, 2, 5, 8196, 4, 819),          # the shortest that does not (few rows): chunk-local top-k + pool
     (16, 16, 2, 20000, 16, 500),      # 256 rows: the single-workgroup path up to its LDS limit
     (16, 16, 1, 32768, 16, 77),
 ])
@@ -272,5 +272,82 @@ def test_lookback_recount_path(spin_limit, monkeypatch):
             scores = softmax_scores(N, 2, 3, 2, N)
         lens = torch.tensor([N, N - 12345], dtype=torch.int32)
         (idx, cnt, _), (o_idx, o_cnt, _) = run_both(scores, hm, k, seq_lens=lens)
+        np.testing.assert_array_equal(cnt, o_cnt)
+        np.testing.assert_array_equal(idx, o_idx)
+
+
+def launched(fn):
+    """Kernel kinds launched by fn(), from the library's own launch records."""
+    sts.prof_enable(True)
+    sts.prof_reset()
+    try:
+        fn()
+        torch.cuda.synchronize()
+        return {k for k, (n, _) in sts.prof_read().items() if n}
+    finally:
+        sts.prof_enable(False)
+
+
+def test_each_selection_path_is_taken_where_expected():
+    """Three ways through sts_select, chosen from the shape: one workgroup per row (short rows),
+    chunk-local top-k + pool (small budgets on long rows), the histogram pipeline (the rest)."""
+    def run(B, Hd, N, k):
+        s = softmax_scores(3, B, Hd, 2, N).to(DEV)
+        return launched(lambda: sts.sts_select(s, list(range(Hd)), k))
+    assert run(1, 4, 8192, 100) == {"select_small"}
+    assert run(16, 16, 20000, 100) == {"select_small"}                      # 256 rows
+    assert run(1, 4, 65536, 512) == {"select_local", "select_pool"}         # 8 chunks x 512
+    assert run(1, 4, 65536, 1024) == {"select_local", "select_pool"}        # 8192 pooled pairs: the limit
+    assert run(1, 4, 65536, 1025) == {"select_clear", "select_agg", "select_hist", "select_write"}
+    assert run(1, 4, 65532 + 2, 512) == {"select_clear", "select_agg", "select_hist", "select_write"}   # N % 4 != 0
+    assert run(8, 16, 65536, 2048) == {"select_local", "select_pool"}       # 16384 pooled, 8M scores
+    assert run(4, 16, 65536, 2048) == {"select_clear", "select_agg", "select_hist", "select_write"}
+
+
+@pytest.mark.parametrize("kind,reduce", [(0, 0), (0, 1), (1, 0)])
+def test_pool_path_options(kind, reduce):
+    """Chunk-local top-k + pool with every option of the call: scaled-logit input, maximum
+    reduction, ragged lengths (one ending inside the first chunk, one between chunks, one
+    empty), per-head budgets, a draft head nobody reads, and the aggregate on request."""
+    B, Hd, Tq, N, k = 4, 4, 3, 40000, 700
+    g = torch.Generator().manual_seed(17 + kind + 2 * reduce)
+    logits = torch.randn(B, Hd, Tq, N, generator=g) * 2.0
+    lse = torch.logsumexp(logits, dim=-1)
+    scores = logits if kind == 1 else torch.softmax(logits, dim=-1)
+    hm = [0, 0, 2, 3, 3, 2]                                # draft head 1 is not read
+    kh = [700, 5, 1, 333]
+    lens = torch.tensor([N, 5000, 16384, 0], dtype=torch.int32)
+    sd = scores.to(DEV)
+    got = {}
+    def call():
+        got["r"] = sts.sts_select(sd, hm, k, lse=lse.to(DEV) if kind == 1 else None, seq_lens=lens.to(DEV),
+                                  kind=kind, reduce=reduce, want_agg=True, k_head=kh)
+    assert launched(call) == {"select_local", "select_pool"}
+    idx, cnt, agg = got["r"]
+    agg = agg.cpu().numpy()
+    o_agg = oracle.aggregate(scores.numpy(), lse.numpy() if kind == 1 else None, kind, reduce)
+    if kind == 0:
+        np.testing.assert_array_equal(agg.view(np.uint32), o_agg.view(np.uint32))
+    else:
+        np.testing.assert_allclose(agg, o_agg, rtol=1e-5, atol=1e-12)
+    # stage-wise: rank the GPU's own aggregate with the oracle
+    sel, c = oracle.select_per_head(agg, k, kh, lens.numpy())
+    o_idx, o_cnt = oracle.remap(sel, c, np.asarray(hm, np.int32))
+    np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
+    np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
+    # without the aggregate output the lists are the same
+    idx2, cnt2, _ = sts.sts_select(sd, hm, k, lse=lse.to(DEV) if kind == 1 else None, seq_lens=lens.to(DEV),
+                                   kind=kind, reduce=reduce, k_head=kh)
+    assert torch.equal(idx2, idx) and torch.equal(cnt2, cnt)
+
+
+@pytest.mark.parametrize("levels", [1, 2, 5])
+def test_pool_path_ties_across_chunks(levels):
+    """Equal scores in different chunks: the lower token must win, whichever chunk holds it."""
+    B, Hd, Tq, N = 2, 3, 2, 81920                           # 10 chunks
+    g = torch.Generator().manual_seed(levels)
+    scores = torch.randint(0, levels, (B, Hd, Tq, N), generator=g).float() / 4.0
+    for k in (1, 7, 300, 819):
+        (idx, cnt, _), (o_idx, o_cnt, _) = run_both(scores, [0, 1, 2, 1], k)
         np.testing.assert_array_equal(cnt, o_cnt)
         np.testing.assert_array_equal(idx, o_idx)

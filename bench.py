@@ -46,6 +46,8 @@ def parse_args():
     ap.add_argument("--warm", action="store_true",
                     help="reuse one KV buffer even when it fits the 256 MB Infinity Cache (default: rotate over "
                          "enough distinct layers to exceed 2 GiB so that every pass starts cache-cold)")
+    ap.add_argument("--scores", default="fp32", choices=["fp32", "bf16"],
+                    help="type of the draft scores read by sts_select (and of the logits dump of the draft layer)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (scales rocprofv3 --pmc byte counters)")
     return ap.parse_args()
@@ -101,7 +103,7 @@ def cpu_baseline(w, idx, cnt, page=1, budget_s=25.0, scores=None, lse=None):
     # selection on one batch element
     # (the draft-layer configuration selects from the scaled logits + LSE the GPU just dumped)
     src = w.scores if scores is None else scores
-    sc = src[:1].cpu().numpy()
+    sc = src[:1].float().cpu().numpy()       # bf16 scores are widened exactly, as the library does
     ls = None if lse is None else lse[:1].cpu().numpy()
     t0 = time.perf_counter()
     oracle.select_indices(sc, w.head_map.numpy(), idx.shape[2], page=page, lse=ls,
@@ -185,7 +187,9 @@ def main():
     if draft is not None:
         d_out = torch.empty(B, Tq, Hd, cfg.draft_d, dtype=torch.bfloat16, device=dev)
         d_lse = torch.empty(B, Hd, Tq, dtype=torch.float32, device=dev)
-        d_logits = torch.empty(B, Hd, Tq, N, dtype=torch.float32, device=dev)
+        d_logits = torch.empty(B, Hd, Tq, N, dtype=torch.bfloat16 if args.scores == "bf16" else torch.float32, device=dev)
+    elif args.scores == "bf16":
+        w.scores = w.scores.to(torch.bfloat16)
 
     def step(ev=None, layer=0):
         lk, lv = layers[layer]
@@ -286,7 +290,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": workload, "context": N, "batch": B, "budget_tokens": kb * page, "page_size": page, "paged_kv": bool(args.paged),
-                   "layers": L, "cache": "cold: every pass reads KV that has left the caches" if (L > 1 or kv_bytes > (256 << 20)) else "warm", "head_map": "t*Hd//Hq", "step": ("%d layers x (" % L if L > 1 else "(") + "select + sparse_attn" + ("" if args.no_dense else " + dense_attn")
+                   "layers": L, "cache": "cold: every pass reads KV that has left the caches" if (L > 1 or kv_bytes > (256 << 20)) else "warm", "head_map": "t*Hd//Hq", "scores": args.scores, "step": ("%d layers x (" % L if L > 1 else "(") + "select + sparse_attn" + ("" if args.no_dense else " + dense_attn")
                    + (" + draft dense attn with logits dump" if draft is not None else "") + ")"},
         "sparse_attn_us": {"mean": round(sparse_us[0], 2), "median": round(sparse_us[1], 2), "min": round(sparse_us[2], 2), "p10": round(sparse_us[3], 2), "p90": round(sparse_us[4], 2)},
         "dense_attn_us": None if args.no_dense else {"mean": round(dense_us[0], 2), "median": round(dense_us[1], 2), "min": round(dense_us[2], 2), "p10": round(dense_us[3], 2), "p90": round(dense_us[4], 2)},
@@ -310,7 +314,7 @@ def main():
     agg_n, agg_ms = prof["select_agg"]
     if agg_n:
         # the one HBM-bound kernel of the selection: reads Tq rows of scores, writes one row of A
-        src_rows = B * Hd * (Tq * N + N) * 4
+        src_rows = B * Hd * (Tq * N * (2 if args.scores == "bf16" else 4) + N * 4)
         agg_us = agg_ms * 1e3 / agg_n
         result["roofline_select_agg"] = {"bound": "hbm", "achieved": round(src_rows / (agg_us * 1e-6) / 1e9, 1),
                                          "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -71,6 +71,11 @@ typedef enum { STS_BF16 = 0, STS_F32 = 1 } sts_dtype;
  * ceil(N_b / p) blocks; k then counts blocks and `indices` holds ascending block ids.
  * agg_out stays per token.
  *
+ * Score precision (paper Section 5: the draft's attention kernel dumps the query-key products
+ * to global memory; the paper does not say in which type). The scores are fp32, or, with
+ * scores_bf16, bf16: every value is widened exactly and everything after that is the same
+ * fp32 arithmetic, so the result equals that of the call on the widened tensor. lse stays fp32.
+ *
  * Per-head budgets (paper Section 6.4: how much can be pruned differs strongly between
  * layers, so budgets are set per layer; the same holds per head). The budget of a layer is
  * simply the k of that layer's call. With k_head != NULL draft head j keeps
@@ -84,7 +89,8 @@ typedef enum { STS_BF16 = 0, STS_F32 = 1 } sts_dtype;
 typedef struct {
   int32_t B, Hd, Tq, N, Hq;
   int32_t k;                /* token budget per head, >= 1; k >= N_b selects everything */
-  const float *scores;      /* [dev] [B,Hd,Tq,N] fp32 contiguous: probabilities or scaled logits */
+  const void *scores;       /* [dev] [B,Hd,Tq,N] contiguous, fp32 (or bf16, see scores_bf16):
+                               probabilities or scaled logits */
   const float *lse;         /* [dev] [B,Hd,Tq] natural-log normalisers; LOGITS_LSE only, else NULL */
   const int32_t *head_map;  /* [host] [Hq] target head -> draft head, values in [0,Hd) */
   const int32_t *seq_lens;  /* [dev] [B] valid lengths N_b <= N, or NULL (N_b = N) */
@@ -96,6 +102,8 @@ typedef struct {
   int32_t page_size;        /* 0 or 1: token granularity. p > 1: block granularity (see below) */
   const int32_t *k_head;    /* [host] optional [Hd]: budget of draft head j, 1 <= k_head[j] <= k
                                (see below); NULL = k for every head */
+  int32_t scores_bf16;      /* 0: scores are fp32. Non-zero: scores are bf16 bit patterns, widened
+                               exactly to fp32 before any arithmetic (half the bytes to read) */
   void *workspace;          /* [dev] 256-byte aligned scratch */
   size_t workspace_bytes;
 } sts_select_params;
@@ -151,7 +159,8 @@ typedef struct {
   void *out;                /* [dev] [B,Tq,Hq,d] of out_dtype */
   int32_t out_dtype;        /* sts_dtype */
   float *lse_out;           /* [dev] optional [B,Hq,Tq], natural log */
-  float *logits_out;        /* [dev] dense only, optional [B,Hq,Tq,N] scaled logits s_c */
+  void *logits_out;         /* [dev] dense only, optional [B,Hq,Tq,N] scaled logits s_c, fp32 or
+                               (logits_bf16) rounded to nearest-even bf16 */
   int32_t page_size;        /* 0 or 1: entries are tokens; else tokens per entry / per page */
   const int32_t *block_table; /* [dev] [B, table_stride] logical block -> physical page, or NULL */
   int32_t table_stride;     /* entries per batch row of block_table, >= ceil(N / page_size) */
@@ -159,6 +168,7 @@ typedef struct {
   int64_t kv_stride_page;   /* elements between consecutive pages of the pool (paged only) */
   const void *k_new, *v_new; /* [dev] optional bf16 [B,Tq,Hkv,d] contiguous: see below; both or neither */
   int32_t causal;           /* with k_new: non-zero = query row i sees new tokens 0..i, zero = all Tq */
+  int32_t logits_bf16;      /* type of logits_out: 0 fp32, non-zero bf16 (feeds sts_select's scores_bf16) */
   void *workspace;          /* [dev] 256-byte aligned scratch */
   size_t workspace_bytes;
 } sts_attn_params;

@@ -34,7 +34,7 @@ class SelectParams(ctypes.Structure):
                 ("scores", ctypes.c_void_p), ("lse", ctypes.c_void_p), ("head_map", ctypes.c_void_p),
                 ("seq_lens", ctypes.c_void_p), ("indices", ctypes.c_void_p), ("counts", ctypes.c_void_p),
                 ("agg_out", ctypes.c_void_p), ("kind", ctypes.c_int32), ("reduce", ctypes.c_int32),
-                ("page_size", ctypes.c_int32), ("k_head", ctypes.c_void_p),
+                ("page_size", ctypes.c_int32), ("k_head", ctypes.c_void_p), ("scores_bf16", ctypes.c_int32),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
 
 
@@ -51,6 +51,7 @@ class AttnParams(ctypes.Structure):
                 ("block_table", ctypes.c_void_p), ("table_stride", ctypes.c_int32),
                 ("num_pages", ctypes.c_int32), ("kv_stride_page", ctypes.c_int64),
                 ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p), ("causal", ctypes.c_int32),
+                ("logits_bf16", ctypes.c_int32),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
 
 
@@ -151,14 +152,14 @@ def _host_i32(seq) -> ctypes.Array:
 def sts_select(scores, head_map, k: int, lse=None, seq_lens=None, kind: int = STS_SCORES_PROBS,
                reduce: int = STS_REDUCE_SUM, want_agg: bool = False, out=None, workspace=None,
                page_size: int = 1, k_head=None):
-    """scores [B,Hd,Tq,N] fp32 (device), head_map [Hq] (host ints) -> (indices [B,Hq,k] int32,
+    """scores [B,Hd,Tq,N] fp32 or bf16 (device), head_map [Hq] (host ints) -> (indices [B,Hq,k] int32,
     counts [B,Hq] int32, agg [B,Hd,N] fp32 or None). With page_size > 1, k counts blocks and the
     indices are block ids. k_head [Hd] (host ints, each <= k) gives every draft head its own
     budget. See sts_select in include/sts.h."""
     import torch
 
     lib = load_library()
-    assert scores.is_cuda and scores.dtype == torch.float32 and scores.is_contiguous()
+    assert scores.is_cuda and scores.dtype in (torch.float32, torch.bfloat16) and scores.is_contiguous()
     B, Hd, Tq, N = scores.shape
     hm = _host_i32(head_map)
     Hq = len(hm)
@@ -182,6 +183,7 @@ def sts_select(scores, head_map, k: int, lse=None, seq_lens=None, kind: int = ST
                      indices=_ptr(indices), counts=_ptr(counts), agg_out=_ptr(agg), kind=kind,
                      reduce=reduce, page_size=int(page_size),
                      k_head=ctypes.cast(kh, ctypes.c_void_p) if kh is not None else None,
+                     scores_bf16=1 if scores.dtype == torch.bfloat16 else 0,
                      workspace=None, workspace_bytes=0)
     need = lib.sts_select_workspace_bytes(ctypes.byref(p))
     ws = workspace if workspace is not None else _workspace("select", need, dev)
@@ -256,15 +258,20 @@ def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=
         lse = torch.empty(B, Hq, Tq, dtype=torch.float32, device=dev)
     logits = logits_out
     if logits is None and want_logits:
-        logits = torch.empty(B, Hq, Tq, N, dtype=torch.float32, device=dev)
-    for t, shape in ((lse, (B, Hq, Tq)), (logits, (B, Hq, Tq, N))):
-        assert t is None or (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == shape)
+        # want_logits=True: fp32; a torch dtype (float32 or bfloat16) chooses the type of the dump
+        ldt = want_logits if isinstance(want_logits, torch.dtype) else torch.float32
+        logits = torch.empty(B, Hq, Tq, N, dtype=ldt, device=dev)
+    assert lse is None or (lse.is_cuda and lse.dtype == torch.float32 and lse.is_contiguous()
+                           and tuple(lse.shape) == (B, Hq, Tq))
+    assert logits is None or (logits.is_cuda and logits.dtype in (torch.float32, torch.bfloat16)
+                              and logits.is_contiguous() and tuple(logits.shape) == (B, Hq, Tq, N))
     p, _keep = _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse, logits,
                             page_size=page_size, block_table=block_table, N=N,
                             k_new=k_new, v_new=v_new, causal=causal)
     need = lib.sts_attn_workspace_bytes(ctypes.byref(p), 1 if sparse else 0)
     ws = workspace if workspace is not None else _workspace("attn", need, dev)
     p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()
+    p.logits_bf16 = 1 if (logits is not None and logits.dtype == torch.bfloat16) else 0
     fn = lib.sts_sparse_attn if sparse else lib.sts_dense_attn
     _check(fn(ctypes.byref(p), _stream()), "sts_sparse_attn" if sparse else "sts_dense_attn")
     return out, lse, logits
@@ -285,7 +292,9 @@ def sts_sparse_attn(q, k, v, indices, scale, counts=None, head_map=None, out=Non
 def sts_dense_attn(q, k, v, scale, seq_lens=None, out=None, out_dtype=None, want_lse=True,
                    want_logits=False, workspace=None, lse_out=None, logits_out=None, page_size=1,
                    block_table=None, N=None, k_new=None, v_new=None, causal=True):
-    """Dense attention of the same kernel family -> (out, lse, logits [B,Hq,Tq,N] or None)."""
+    """Dense attention of the same kernel family -> (out, lse, logits [B,Hq,Tq,N] or None).
+    want_logits: True (fp32 dump) or a torch dtype (float32 / bfloat16); logits_out: a buffer of
+    either type."""
     return _run_attn(False, q, k, v, scale, seq_lens=seq_lens, out=out, out_dtype=out_dtype,
                      want_lse=want_lse, want_logits=want_logits, workspace=workspace,
                      lse_out=lse_out, logits_out=logits_out, page_size=page_size,

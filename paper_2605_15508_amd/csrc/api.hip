@@ -203,6 +203,7 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
   a.part_o = static_cast<float *>(p->workspace);
   a.part_ml = reinterpret_cast<float *>(static_cast<unsigned char *>(p->workspace) + pl.part_o_bytes);
   a.logits_out = sparse ? nullptr : p->logits_out;
+  a.logits_bf16 = p->logits_bf16 ? 1 : 0;
   a.out = p->out;
   a.lse_out = p->lse_out;
   a.out_dtype = p->out_dtype;
@@ -341,6 +342,7 @@ static sts_status enqueue_select(const sts_select_params *p, void *stream) {
   SelectArgs a;
   memset(&a, 0, sizeof(a));
   a.scores = p->scores;
+  a.scores_bf16 = p->scores_bf16 ? 1 : 0;
   a.lse = p->kind == STS_SCORES_LOGITS_LSE ? p->lse : nullptr;
   a.seq_lens = p->seq_lens;
   a.indices = p->indices;
@@ -532,7 +534,7 @@ const char *sts_strerror(sts_status s) {
   return "unknown status";
 }
 
-int sts_version(void) { return 105; }
+int sts_version(void) { return 106; }
 
 void sts_prof_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);

@@ -250,16 +250,34 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq) {
         if (!q_ok[nq]) continue;
-        float *lp = A.logits_out + (((size_t)bt * A.Hq + q_head[nq]) * A.Tq + q_tq[nq]) * (size_t)A.N;
+        const size_t lrow = (((size_t)bt * A.Hq + q_head[nq]) * A.Tq + q_tq[nq]) * (size_t)A.N;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
           const int p = pos0 + 16 * ks + 4 * a;
-          if (p + 3 < c && (A.N & 3) == 0) {
-            *reinterpret_cast<f32x4 *>(lp + p) = St[nq][ks] * A.scale;
-          } else {
+          const f32x4 sc = St[nq][ks] * A.scale;
+          if (A.logits_bf16) {
+            uint16_t *lp = static_cast<uint16_t *>(A.logits_out) + lrow;
+            const bf16x2 lo = __builtin_convertvector(f32x2{sc[0], sc[1]}, bf16x2);   // round to nearest even
+            const bf16x2 hi = __builtin_convertvector(f32x2{sc[2], sc[3]}, bf16x2);
+            const uint32_t w01 = __builtin_bit_cast(uint32_t, lo), w23 = __builtin_bit_cast(uint32_t, hi);
+            if (p + 3 < c && (A.N & 3) == 0) {
+              *reinterpret_cast<u32x2 *>(lp + p) = u32x2{w01, w23};
+            } else {
+              const uint16_t h4[4] = {(uint16_t)(w01 & 0xffffu), (uint16_t)(w01 >> 16), (uint16_t)(w23 & 0xffffu),
+                                      (uint16_t)(w23 >> 16)};
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-              if (p + r < c) lp[p + r] = St[nq][ks][r] * A.scale;
+              for (int r = 0; r < 4; ++r)
+                if (p + r < c) lp[p + r] = h4[r];
+            }
+          } else {
+            float *lp = static_cast<float *>(A.logits_out) + lrow;
+            if (p + 3 < c && (A.N & 3) == 0) {
+              *reinterpret_cast<f32x4 *>(lp + p) = sc;
+            } else {
+#pragma unroll
+              for (int r = 0; r < 4; ++r)
+                if (p + r < c) lp[p + r] = sc[r];
+            }
           }
         }
       }

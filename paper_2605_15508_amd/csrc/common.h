@@ -43,7 +43,8 @@ struct AttnArgs {
   float scale;
   float *part_o;                          // [B*U*S][NQ*16][D]
   float *part_ml;                         // [B*U*S][NQ*16][2]  (max in log2 domain, sum)
-  float *logits_out;
+  void *logits_out;
+  int32_t logits_bf16;
   void *out;
   float *lse_out;
   int32_t out_dtype;
@@ -76,7 +77,9 @@ struct SelectTargets {
 };
 
 struct SelectArgs {
-  const float *scores, *lse;
+  const void *scores;         // fp32 or bf16 (scores_bf16)
+  const float *lse;
+  int32_t scores_bf16;
   const int32_t *seq_lens;
   int32_t *indices, *counts;
   float *agg;                 // [B,Hd,N] (agg_out or workspace)

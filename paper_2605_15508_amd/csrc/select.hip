@@ -118,15 +118,18 @@ __device__ __forceinline__ void find_digit(const uint32_t *hist, uint32_t krem, 
 // ------------------------------------------------------------------- aggregation of a row
 // The Tq score rows of one (batch, draft head), reduced per token strictly in row order.
 struct AggRow {
-  const float *P;   // [Tq][N]
+  const void *P;    // [Tq][N] fp32, or bf16 bit patterns
   const float *L;   // [Tq] natural-log normalisers (scaled-logit input) or nullptr
   int Tq, N;
-  bool logits, use_max;
+  bool bf16, logits, use_max;
 };
 
 __device__ __forceinline__ AggRow agg_row(const SelectArgs &A, int row) {
   AggRow R;
-  R.P = A.scores + (size_t)row * A.Tq * A.N;
+  const size_t off = (size_t)row * A.Tq * A.N;
+  R.bf16 = A.scores_bf16 != 0;
+  R.P = R.bf16 ? static_cast<const void *>(static_cast<const uint16_t *>(A.scores) + off)
+               : static_cast<const void *>(static_cast<const float *>(A.scores) + off);
   R.L = A.lse ? A.lse + (size_t)row * A.Tq : nullptr;
   R.Tq = A.Tq;
   R.N = A.N;
@@ -135,53 +138,93 @@ __device__ __forceinline__ AggRow agg_row(const SelectArgs &A, int row) {
   return R;
 }
 
+// One score (V = float) or four consecutive ones (V = f32x4, n % 4 == 0) of row i, as stored:
+// the raw load, and its exact widening to fp32. Nontemporal: every score is read exactly once.
+template <class V, bool BF16>
+struct ScoreLoad;
+template <>
+struct ScoreLoad<float, false> {
+  typedef float raw;
+  static __device__ __forceinline__ raw load(const AggRow &R, int i, int n) {
+    return __builtin_nontemporal_load(static_cast<const float *>(R.P) + (size_t)i * R.N + n);
+  }
+  static __device__ __forceinline__ float widen(raw x) { return x; }
+};
+template <>
+struct ScoreLoad<f32x4, false> {
+  typedef f32x4 raw;
+  static __device__ __forceinline__ raw load(const AggRow &R, int i, int n) {
+    return __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(static_cast<const float *>(R.P) + (size_t)i * R.N + n));
+  }
+  static __device__ __forceinline__ f32x4 widen(raw x) { return x; }
+};
+template <>
+struct ScoreLoad<float, true> {
+  typedef uint16_t raw;
+  static __device__ __forceinline__ raw load(const AggRow &R, int i, int n) {
+    return __builtin_nontemporal_load(static_cast<const uint16_t *>(R.P) + (size_t)i * R.N + n);
+  }
+  static __device__ __forceinline__ float widen(raw x) { return __builtin_bit_cast(float, (uint32_t)x << 16); }
+};
+template <>
+struct ScoreLoad<f32x4, true> {
+  typedef u32x2 raw;   // four bf16 values, 8-byte aligned
+  static __device__ __forceinline__ raw load(const AggRow &R, int i, int n) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(R.P) + (size_t)i * R.N + n));
+  }
+  static __device__ __forceinline__ f32x4 widen(raw x) {
+    return f32x4{__builtin_bit_cast(float, x[0] << 16), __builtin_bit_cast(float, x[0] & 0xffff0000u),
+                 __builtin_bit_cast(float, x[1] << 16), __builtin_bit_cast(float, x[1] & 0xffff0000u)};
+  }
+};
+
 // NROWS consecutive score rows, from row i on, of the token(s) at n: all loads first (their
-// latencies overlap; nontemporal: every score is read exactly once), then the reduction
-// strictly in row order. FIRST: row i is row 0 and initialises the accumulator. V is float (one
-// token) or f32x4 (tokens n..n+3, n % 4 == 0, rows 16-byte aligned).
-template <int NROWS, bool FIRST, class V>
+// latencies overlap), then the reduction strictly in row order. FIRST: row i is row 0 and
+// initialises the accumulator.
+template <int NROWS, bool FIRST, bool BF16, class V>
 __device__ __forceinline__ void agg_rows(const AggRow &R, int i, int n, V &acc) {
-  V p[NROWS];
+  typedef ScoreLoad<V, BF16> SL;
+  typename SL::raw raw[NROWS];
 #pragma unroll
-  for (int u = 0; u < NROWS; ++u)
-    p[u] = __builtin_nontemporal_load(reinterpret_cast<const V *>(R.P + (size_t)(i + u) * R.N + n));
+  for (int u = 0; u < NROWS; ++u) raw[u] = SL::load(R, i + u, n);
 #pragma unroll
   for (int u = 0; u < NROWS; ++u) {
+    V p = SL::widen(raw[u]);
     if (R.logits) {
       const float l = R.L[i + u];
       if constexpr (sizeof(V) == sizeof(float)) {
-        p[u] = prob_of(p[u], l);
+        p = prob_of(p, l);
       } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) p[u][e] = prob_of(p[u][e], l);
+        for (int e = 0; e < 4; ++e) p[e] = prob_of(p[e], l);
       }
     }
     if (FIRST && u == 0) {
-      acc = p[u];
+      acc = p;
     } else if (R.use_max) {
       if constexpr (sizeof(V) == sizeof(float)) {
-        acc = fmaxf(acc, p[u]);
+        acc = fmaxf(acc, p);
       } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[e] = fmaxf(acc[e], p[u][e]);
+        for (int e = 0; e < 4; ++e) acc[e] = fmaxf(acc[e], p[e]);
       }
     } else {
-      acc = acc + p[u];
+      acc = acc + p;
     }
   }
 }
 
-template <bool FIRST, class V>
+template <bool FIRST, bool BF16, class V>
 __device__ __forceinline__ void agg_group(const AggRow &R, int i, int rows, int n, V &acc) {
   switch (rows) {   // uniform: a scalar branch; every case is straight-line code
-    case 1: agg_rows<1, FIRST>(R, i, n, acc); break;
-    case 2: agg_rows<2, FIRST>(R, i, n, acc); break;
-    case 3: agg_rows<3, FIRST>(R, i, n, acc); break;
-    case 4: agg_rows<4, FIRST>(R, i, n, acc); break;
-    case 5: agg_rows<5, FIRST>(R, i, n, acc); break;
-    case 6: agg_rows<6, FIRST>(R, i, n, acc); break;
-    case 7: agg_rows<7, FIRST>(R, i, n, acc); break;
-    default: agg_rows<8, FIRST>(R, i, n, acc); break;
+    case 1: agg_rows<1, FIRST, BF16>(R, i, n, acc); break;
+    case 2: agg_rows<2, FIRST, BF16>(R, i, n, acc); break;
+    case 3: agg_rows<3, FIRST, BF16>(R, i, n, acc); break;
+    case 4: agg_rows<4, FIRST, BF16>(R, i, n, acc); break;
+    case 5: agg_rows<5, FIRST, BF16>(R, i, n, acc); break;
+    case 6: agg_rows<6, FIRST, BF16>(R, i, n, acc); break;
+    case 7: agg_rows<7, FIRST, BF16>(R, i, n, acc); break;
+    default: agg_rows<8, FIRST, BF16>(R, i, n, acc); break;
   }
 }
 
@@ -189,8 +232,13 @@ __device__ __forceinline__ void agg_group(const AggRow &R, int i, int rows, int 
 template <class V>
 __device__ __forceinline__ V agg_at(const AggRow &R, int n) {
   V acc;
-  agg_group<true>(R, 0, min(R.Tq, 8), n, acc);
-  for (int i = 8; i < R.Tq; i += 8) agg_group<false>(R, i, min(R.Tq - i, 8), n, acc);
+  if (R.bf16) {
+    agg_group<true, true>(R, 0, min(R.Tq, 8), n, acc);
+    for (int i = 8; i < R.Tq; i += 8) agg_group<false, true>(R, i, min(R.Tq - i, 8), n, acc);
+  } else {
+    agg_group<true, false>(R, 0, min(R.Tq, 8), n, acc);
+    for (int i = 8; i < R.Tq; i += 8) agg_group<false, false>(R, i, min(R.Tq - i, 8), n, acc);
+  }
   return acc;
 }
 

@@ -137,6 +137,26 @@ def test_logits_dump_head_dim_64_unaligned_n():
     assert np.abs(logits.cpu().numpy() - ref["logits"]).max() < 2e-3
 
 
+@pytest.mark.parametrize("d,N", [(128, 640), (64, 301), (128, 4099)])
+def test_logits_dump_in_bf16(d, N):
+    """The dump rounded to bf16 (Section 5 names no type for it): equal, bit for bit, to the fp32
+    dump rounded to nearest even, and within one bf16 unit of the oracle's logits; sentinels
+    planted beyond the valid length stay untouched."""
+    B, Tq, Hq, Hkv = 2, 5, 8, 2
+    q, k, v = make_qkv(31, B, Tq, Hq, Hkv, d, N)
+    lens = torch.tensor([N, N // 3], dtype=torch.int32, device=DEV)
+    out32, lse32, lg32 = sts.sts_dense_attn(q, k, v, 0.09, seq_lens=lens, out_dtype=torch.float32, want_logits=True)
+    dump = torch.full((B, Hq, Tq, N), 7.0, dtype=torch.bfloat16, device=DEV)
+    out16, lse16, lg16 = sts.sts_dense_attn(q, k, v, 0.09, seq_lens=lens, out_dtype=torch.float32, logits_out=dump)
+    assert lg16 is dump and torch.equal(out16, out32) and torch.equal(lse16, lse32)
+    ref = oracle_attn(q, k, v, 0.09, seq_lens=lens, want_logits=True)["logits"]
+    for b, n in enumerate(lens.tolist()):
+        assert torch.equal(lg16[b, :, :, :n], lg32[b, :, :, :n].to(torch.bfloat16))
+        assert (lg16[b, :, :, n:] == 7.0).all()
+        got = lg16[b, :, :, :n].float().cpu().numpy()
+        assert (np.abs(got - ref[b, :, :, :n]) <= np.abs(ref[b, :, :, :n]) * 2.0 ** -7 + 1e-6).all()
+
+
 def test_results_are_deterministic_run_to_run():
     B, Tq, Hq, Hkv, d, N, kk = 2, 5, 8, 2, 128, 4000, 400
     q, k, v = make_qkv(9, B, Tq, Hq, Hkv, d, N)

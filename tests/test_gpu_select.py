@@ -351,3 +351,58 @@ def test_pool_path_ties_across_chunks(levels):
         (idx, cnt, _), (o_idx, o_cnt, _) = run_both(scores, [0, 1, 2, 1], k)
         np.testing.assert_array_equal(cnt, o_cnt)
         np.testing.assert_array_equal(idx, o_idx)
+
+
+@pytest.mark.parametrize("B,Hd,Tq,N,Hq,k", [
+    (1, 16, 5, 4096, 32, 410),        # one workgroup per row
+    (2, 3, 5, 20000, 6, 2000),        # chunk-local top-k + pool
+    (2, 3, 5, 40000, 6, 4000),        # histogram pipeline
+    (1, 2, 3, 70001, 4, 123),         # its scalar variant (N % 4 != 0)
+    (1, 2, 9, 1001, 2, 100),          # scalar, more than one group of eight rows
+])
+@pytest.mark.parametrize("kind", [0, 1])
+def test_select_bf16_scores(B, Hd, Tq, N, Hq, k, kind):
+    """Scores stored as bf16 (half the bytes): the result equals that of the same call on the
+    widened tensor, which is what the oracle gets."""
+    g = torch.Generator().manual_seed(N + kind)
+    logits = (torch.randn(B, Hd, Tq, N, generator=g) * 2.0).to(torch.bfloat16)
+    lse = torch.logsumexp(logits.float(), dim=-1)
+    scores = logits if kind == 1 else torch.softmax(logits.float(), dim=-1).to(torch.bfloat16)
+    hm = [(t * Hd) // Hq for t in range(Hq)]
+    idx, cnt, agg = sts.sts_select(scores.to(DEV), hm, k, lse=lse.to(DEV) if kind == 1 else None, kind=kind,
+                                   want_agg=True)
+    torch.cuda.synchronize()
+    wide = scores.float().numpy()
+    o_agg = oracle.aggregate(wide, lse.numpy() if kind == 1 else None, kind, 0)
+    agg = agg.cpu().numpy()
+    if kind == 0:
+        np.testing.assert_array_equal(agg.view(np.uint32), o_agg.view(np.uint32))
+    else:
+        np.testing.assert_allclose(agg, o_agg, rtol=1e-5, atol=1e-12)
+    sel, c = oracle.select(agg, k)
+    o_idx, o_cnt = oracle.remap(sel, c, np.asarray(hm, np.int32))
+    np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
+    np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
+    # the same call on the widened tensor gives the same lists
+    idx32, cnt32, _ = sts.sts_select(scores.float().to(DEV), hm, k, lse=lse.to(DEV) if kind == 1 else None, kind=kind)
+    assert torch.equal(idx32, idx) and torch.equal(cnt32, cnt)
+
+
+def test_bf16_dump_feeds_selection():
+    """Draft attention dumps bf16 logits + fp32 LSE; the selection reads them as they are."""
+    cfg = replace(CONFIGS["c5"], B=1, N=20000, Hq=16, Hkv=2, Tq=4, Hd=8, draft_Hkv=2)
+    from workload import make_draft_layer
+    w = make_workload(cfg, seed=4)
+    dl = make_draft_layer(w)
+    dq, dk, dv = dl["q"].to(DEV), dl["k"].to(DEV), dl["v"].to(DEV)
+    _, d_lse, d_logits = sts.sts_dense_attn(dq, dk, dv, dl["scale"], want_logits=torch.bfloat16)
+    assert d_logits.dtype == torch.bfloat16
+    k = 1500
+    idx, cnt, agg = sts.sts_select(d_logits, w.head_map, k, lse=d_lse, kind=sts.STS_SCORES_LOGITS_LSE, want_agg=True)
+    torch.cuda.synchronize()
+    o_agg = oracle.aggregate(d_logits.float().cpu().numpy(), d_lse.cpu().numpy(), 1, 0)
+    np.testing.assert_allclose(agg.cpu().numpy(), o_agg, rtol=1e-5, atol=1e-12)
+    sel, c = oracle.select(agg.cpu().numpy(), k)
+    o_idx, o_cnt = oracle.remap(sel, c, np.asarray(w.head_map, np.int32))
+    np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
+    np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)

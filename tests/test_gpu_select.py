@@ -406,3 +406,21 @@ def test_bf16_dump_feeds_selection():
     o_idx, o_cnt = oracle.remap(sel, c, np.asarray(w.head_map, np.int32))
     np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
     np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
+
+
+def test_misaligned_scores_fall_back_to_the_pipeline():
+    """A pool-shaped call whose score pointer is not 16-byte aligned runs the histogram pipeline
+    (scalar loads) inside the same workspace, with the same result."""
+    B, Hd, Tq, N, k = 1, 3, 2, 40000, 500
+    base = torch.zeros(B * Hd * Tq * N + 1, dtype=torch.float32)
+    scores = base[1:].view(B, Hd, Tq, N)
+    scores.copy_(softmax_scores(8, B, Hd, Tq, N))
+    dbase = base.to(DEV)
+    sd = dbase[1:].view(B, Hd, Tq, N)
+    assert sd.data_ptr() % 16 == 4
+    got = {}
+    kinds = launched(lambda: got.update(r=sts.sts_select(sd, [0, 1, 2], k)))
+    assert kinds == {"select_clear", "select_agg", "select_hist", "select_write"}
+    o_idx, o_cnt, _ = oracle.select_indices(scores.numpy(), np.asarray([0, 1, 2], np.int32), k)
+    np.testing.assert_array_equal(got["r"][0].cpu().numpy(), o_idx)
+    np.testing.assert_array_equal(got["r"][1].cpu().numpy(), o_cnt)

@@ -223,9 +223,9 @@ struct SelectPlan {
   bool pool;           // shape allows chunk-local top-k + one ranking workgroup per row
   int nchunks, page, srcN, pool_pitch;
   size_t agg_bytes, blk_bytes, hist_bytes, state_bytes, chunk_bytes;
-  size_t pool_key_bytes, pool_cnt_bytes;
+  size_t pool_key_bytes;
   size_t pipeline_total() const { return agg_bytes + blk_bytes + hist_bytes + state_bytes + chunk_bytes; }
-  size_t pool_total() const { return pool ? 2 * pool_key_bytes + pool_cnt_bytes : 0; }
+  size_t pool_total() const { return pool ? 2 * pool_key_bytes : 0; }
   // a pool-shaped call falls back to the pipeline when its pointers are not 16-byte aligned,
   // so the workspace covers both
   size_t total() const { return pipeline_total() > pool_total() ? pipeline_total() : pool_total(); }
@@ -250,7 +250,7 @@ sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
   pl.small = pl.page == 1 && (p->N <= SEL_FUSED_N || (p->N <= SEL_SMALL_N && rows >= 256));
   pl.pool = false;
   pl.pool_pitch = 0;
-  pl.pool_key_bytes = pl.pool_cnt_bytes = 0;
+  pl.pool_key_bytes = 0;
   if (pl.small) {
     pl.nchunks = 0;
     pl.agg_bytes = pl.blk_bytes = pl.hist_bytes = pl.state_bytes = pl.chunk_bytes = 0;
@@ -271,7 +271,6 @@ sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
       pl.pool = true;
       pl.pool_pitch = (int)pitch;
       pl.pool_key_bytes = align256(rows * (size_t)pl.nchunks * (size_t)pitch * sizeof(uint32_t));
-      pl.pool_cnt_bytes = align256(rows * (size_t)pl.nchunks * sizeof(uint32_t));
     }
   }
   pl.agg_bytes = p->agg_out ? 0 : align256(rows * (size_t)p->N * sizeof(float));
@@ -390,7 +389,6 @@ static sts_status enqueue_select(const sts_select_params *p, void *stream) {
     unsigned char *pw = static_cast<unsigned char *>(p->workspace);
     a.pool_key = reinterpret_cast<uint32_t *>(pw);
     a.pool_idx = reinterpret_cast<int32_t *>(pw + pl.pool_key_bytes);
-    a.pool_cnt = reinterpret_cast<uint32_t *>(pw + 2 * pl.pool_key_bytes);
     a.pool_pitch = pl.pool_pitch;
     a.agg = p->agg_out;   // optional output only
     rc = run_kernel(STS_K_SELECT_LOCAL, s, [&] { return launch_select_local(a, s); });

@@ -90,9 +90,9 @@ struct SelectArgs {
   uint32_t *hist;             // [rows][3][SEL_BINS]
   uint32_t *state;            // [rows][8]: digits 0/1 and remaining k after each, [6] budget
   uint32_t *chunk_cnt;        // [rows][nchunks][SEL_FLAG_PITCH], word 0: published flag | equal count << 14 | greater count
-  uint32_t *pool_key;         // [rows][nchunks][pool_pitch] chunk-local winners (small budgets), in token order
+  uint32_t *pool_key;         // [rows][nchunks * pool_pitch] chunk-local winners (small budgets), token order,
+                              // contiguous per row: chunk c starts at c * min(budget of the row, SEL_CHUNK)
   int32_t *pool_idx;          // their token ids
-  uint32_t *pool_cnt;         // [rows][nchunks] pairs kept per chunk
   int32_t pool_pitch;         // min(k, SEL_CHUNK)
   uint64_t clear_words;       // words to zero from `hist` on: histograms, state and chunk flags
   int32_t spin_limit;         // polls of an unpublished earlier chunk before it is recounted locally

@@ -633,27 +633,32 @@ __device__ __forceinline__ void lds_threshold(const uint32_t *keys, int m, uint3
   T = (pre01 << SEL_BITS2) | d2;
 }
 
-// Ordered compaction of the same keys: every thread owns a run of consecutive entries; entry n
-// is kept iff key > T, or key == T and fewer than r equal keys precede it, and emit(pos, n) is
-// called with its position in the output list, pos = (#greater before n) + min(#equal before n, r).
-template <int THREADS, class Emit>
-__device__ __forceinline__ void lds_compact(const uint32_t *keys, int m, uint32_t T, uint32_t r, uint32_t c,
-                                            uint32_t *tmp, Emit emit) {
+// Ordered compaction of the same keys: every thread owns a run of at most MAXPER consecutive
+// entries (m <= MAXPER * THREADS), read once into registers; entry n is kept iff key > T, or
+// key == T and fewer than r equal keys precede it, and emit(pos, n) is called with its position
+// in the output list, pos = (#greater before n) + min(#equal before n, r).
+template <int THREADS, int MAXPER, class Emit>
+__device__ __forceinline__ void lds_compact_run(const uint32_t *keys, int m, uint32_t T, uint32_t r, uint32_t c,
+                                                uint32_t *tmp, Emit emit) {
   const int tid = threadIdx.x;
   const int per = (m + THREADS - 1) / THREADS;
   const int nlo = min(tid * per, m), nhi = min(nlo + per, m);
+  uint32_t kk[MAXPER];
   uint32_t cg = 0, ce = 0;
-  for (int n = nlo; n < nhi; ++n) {
-    const uint32_t key = keys[small_slot(n)];
-    cg += key > T ? 1u : 0u;
-    ce += key == T ? 1u : 0u;
+#pragma unroll
+  for (int i = 0; i < MAXPER; ++i) {
+    const int n = nlo + i;
+    kk[i] = keys[small_slot(min(n, m - 1))];
+    cg += (n < nhi && kk[i] > T) ? 1u : 0u;
+    ce += (n < nhi && kk[i] == T) ? 1u : 0u;
   }
   uint32_t total;
   const uint32_t excl = block_excl_scan<THREADS>(cg | (ce << 16), tmp, total);   // m <= 32768: both sums fit 16 bits
   uint32_t g = excl & 0xffffu, q = excl >> 16;
-  for (int n = nlo; n < nhi; ++n) {
-    const uint32_t key = keys[small_slot(n)];
-    const bool is_gt = key > T, is_eq = key == T;
+#pragma unroll
+  for (int i = 0; i < MAXPER; ++i) {
+    const int n = nlo + i;
+    const bool is_gt = n < nhi && kk[i] > T, is_eq = n < nhi && kk[i] == T;
     if (is_gt || (is_eq && q < r)) {
       const uint32_t pos = g + min(q, r);
       if (pos < c) emit(pos, n);   // always true for a consistent threshold; keeps a bad state in bounds
@@ -661,6 +666,17 @@ __device__ __forceinline__ void lds_compact(const uint32_t *keys, int m, uint32_
     g += is_gt ? 1u : 0u;
     q += is_eq ? 1u : 0u;
   }
+}
+
+// the same with the run length (a uniform value) rounded up to 4, 8, 16 or MAXPER
+template <int THREADS, int MAXPER, class Emit>
+__device__ __forceinline__ void lds_compact(const uint32_t *keys, int m, uint32_t T, uint32_t r, uint32_t c,
+                                            uint32_t *tmp, Emit emit) {
+  const int per = (m + THREADS - 1) / THREADS;
+  if (MAXPER > 4 && per <= 4) lds_compact_run<THREADS, 4>(keys, m, T, r, c, tmp, emit);
+  else if (MAXPER > 8 && per <= 8) lds_compact_run<THREADS, 8>(keys, m, T, r, c, tmp, emit);
+  else if (MAXPER > 16 && per <= 16) lds_compact_run<THREADS, 16>(keys, m, T, r, c, tmp, emit);
+  else lds_compact_run<THREADS, MAXPER>(keys, m, T, r, c, tmp, emit);
 }
 
 // tail padding (-1 from position c on) and counts for every target head of draft head j
@@ -723,7 +739,7 @@ __global__ void __launch_bounds__(SMALL_THREADS) select_small_kernel(const Selec
 
   uint32_t T, r;
   lds_threshold<SMALL_THREADS>(keys, nb, h, tmp, c, T, r);
-  lds_compact<SMALL_THREADS>(keys, nb, T, r, c, tmp, [&](uint32_t pos, int n) {
+  lds_compact<SMALL_THREADS, SEL_SMALL_N / SMALL_THREADS>(keys, nb, T, r, c, tmp, [&](uint32_t pos, int n) {
     for (int ti = t0; ti < t1; ++ti) A.indices[((size_t)bt * A.Hq + A.targets.tgt[ti]) * A.k + pos] = n;
   });
 }
@@ -754,12 +770,8 @@ __global__ void __launch_bounds__(SEL_THREADS) select_local_kernel(const SelectA
   const int nvalid = max(0, min(n0 + SEL_CHUNK, nb) - n0);     // ranked tokens of this chunk
   uint32_t c = (uint32_t)min(A.kh[j], nvalid);
   const bool want_agg = A.agg != nullptr;
-  uint32_t *cnt_out = A.pool_cnt + (size_t)row * A.nchunks + chunk;
   if (A.targets.off[j] == A.targets.off[j + 1]) c = 0;        // no target head reads this draft head
-  if (c == 0 && !want_agg) {
-    if (threadIdx.x == 0) *cnt_out = 0u;
-    return;
-  }
+  if (c == 0 && !want_agg) return;
   for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) h[i] = 0u;
   __syncthreads();
   const AggRow R = agg_row(A, row);
@@ -782,10 +794,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_local_kernel(const SelectA
     }
   }
   __syncthreads();
-  if (c == 0) {
-    if (threadIdx.x == 0) *cnt_out = 0u;
-    return;
-  }
+  if (c == 0) return;
   // threshold of the chunk: three digits over the register-resident keys
   uint32_t d0, k1, d1, k2, d2, r;
   find_digit<(1 << SEL_BITS0)>(h, c, tmp, d0, k1);
@@ -816,9 +825,12 @@ __global__ void __launch_bounds__(SEL_THREADS) select_local_kernel(const SelectA
   find_digit<(1 << SEL_BITS2)>(h, k2, tmp, d2, r);
   const uint32_t T = (pre01 << SEL_BITS2) | d2;
 
-  // ordered compaction into the chunk's pool segment: one block scan per sweep of 1024 tokens
-  uint32_t *pk = A.pool_key + ((size_t)row * A.nchunks + chunk) * A.pool_pitch;
-  int32_t *pi = A.pool_idx + ((size_t)row * A.nchunks + chunk) * A.pool_pitch;
+  // Ordered compaction into the chunk's pool segment, one block scan per sweep of 1024 tokens.
+  // Every chunk before this one is full and keeps min(budget, SEL_CHUNK) pairs, so the row's
+  // pool is contiguous and this chunk's place in it is known without communication.
+  const size_t seg = (size_t)row * A.nchunks * A.pool_pitch + (size_t)chunk * min(A.kh[j], SEL_CHUNK);
+  uint32_t *pk = A.pool_key + seg;
+  int32_t *pi = A.pool_idx + seg;
   uint32_t g0 = 0, q0 = 0;                                     // greater / equal in the sweeps before
 #pragma unroll
   for (int i = 0; i < IT; ++i) {
@@ -850,7 +862,6 @@ __global__ void __launch_bounds__(SEL_THREADS) select_local_kernel(const SelectA
     g0 += total & 0xffffu;
     q0 += total >> 16;
   }
-  if (threadIdx.x == 0) *cnt_out = c;
 }
 
 // Pool kernel, one 1024-thread workgroup per row: the chunks' kept pairs, concatenated in
@@ -861,7 +872,7 @@ __global__ void __launch_bounds__(SMALL_THREADS) select_pool_kernel(const Select
   __shared__ uint32_t keys[POOL_MAX + POOL_MAX / 32];
   __shared__ int32_t toks[POOL_MAX + POOL_MAX / 32];
   __shared__ uint32_t h[SEL_BINS];
-  __shared__ uint32_t offs[SMALL_THREADS];                     // first pooled position of each chunk
+  __shared__ uint32_t red[2 * SMALL_THREADS / 64];
   __shared__ uint32_t tmp[SMALL_THREADS / 64 + 2];
   const int row = blockIdx.x;
   const int bt = row / A.Hd, j = row % A.Hd;
@@ -872,36 +883,25 @@ __global__ void __launch_bounds__(SMALL_THREADS) select_pool_kernel(const Select
   write_tail<SMALL_THREADS>(A, bt, j, c);
   if (c == 0 || t0 == t1) return;
   for (int i = tid; i < SEL_BINS; i += SMALL_THREADS) h[i] = 0u;
-  // nchunks <= 1024 on this path: one thread per chunk
-  const uint32_t mine = tid < A.nchunks ? A.pool_cnt[(size_t)row * A.nchunks + tid] : 0u;
-  uint32_t m;
-  offs[tid] = block_excl_scan<SMALL_THREADS>(mine, tmp, m);
-  __syncthreads();
-  m = min(m, (uint32_t)POOL_MAX);
-  // The pooled pairs were written by other workgroups: their loads miss the caches, so eight
+  // pooled pairs of the row: the full chunks keep min(budget, SEL_CHUNK) each, the last one
+  // min(budget, its length)
+  const uint32_t kfull = (uint32_t)min(A.kh[j], SEL_CHUNK);
+  const uint32_t m = min((uint32_t)(nb / SEL_CHUNK) * kfull + min((uint32_t)A.kh[j], (uint32_t)(nb % SEL_CHUNK)),
+                         (uint32_t)POOL_MAX);
+  const uint32_t *pk = A.pool_key + (size_t)row * A.nchunks * A.pool_pitch;
+  const int32_t *pi = A.pool_idx + (size_t)row * A.nchunks * A.pool_pitch;
+  // The pairs were written by other workgroups: their loads miss the caches, so eight
   // independent ones are issued per thread before any is used (uniform trip count, clamped
   // addresses, the surplus ignored).
   uint32_t kmin = 0xffffffffu, kmax = 0u;
   for (uint32_t e0 = 0; e0 < m; e0 += SMALL_THREADS * 8) {
-    size_t src[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const uint32_t e = min(e0 + u * SMALL_THREADS + tid, m - 1);
-      // chunk of pooled position e: the last chunk whose first position is <= e (empty chunks
-      // share their first position with the next one and are skipped by taking the last)
-      int lo = 0, hi = A.nchunks - 1;
-      while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (offs[mid] <= e) lo = mid; else hi = mid - 1;
-      }
-      src[u] = ((size_t)row * A.nchunks + lo) * A.pool_pitch + (e - offs[lo]);
-    }
     uint32_t key[8];
     int32_t tok[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      key[u] = A.pool_key[src[u]];
-      tok[u] = A.pool_idx[src[u]];
+      const uint32_t e = min(e0 + u * SMALL_THREADS + tid, m - 1);
+      key[u] = pk[e];
+      tok[u] = pi[e];
     }
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
@@ -922,8 +922,6 @@ __global__ void __launch_bounds__(SMALL_THREADS) select_pool_kernel(const Select
     kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off, 64));
     kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off, 64));
   }
-  uint32_t *red = reinterpret_cast<uint32_t *>(offs);          // offs is no longer needed
-  __syncthreads();
   if ((tid & 63) == 0) {
     red[(tid >> 6) * 2] = kmin;
     red[(tid >> 6) * 2 + 1] = kmax;
@@ -948,7 +946,7 @@ __global__ void __launch_bounds__(SMALL_THREADS) select_pool_kernel(const Select
     __syncthreads();
     lds_threshold<SMALL_THREADS>(keys, (int)m, h, tmp, c, T, r);
   }
-  lds_compact<SMALL_THREADS>(keys, (int)m, T, r, c, tmp, [&](uint32_t pos, int n) {
+  lds_compact<SMALL_THREADS, POOL_MAX / SMALL_THREADS>(keys, (int)m, T, r, c, tmp, [&](uint32_t pos, int n) {
     const int32_t tok = toks[small_slot(n)];
     for (int ti = t0; ti < t1; ++ti) A.indices[((size_t)bt * A.Hq + A.targets.tgt[ti]) * A.k + pos] = tok;
   });

@@ -14,7 +14,8 @@
 //             equal keys precede it; its output position is (#greater before n) + min(#equal
 //             before n, r). The counts of the chunks before this one come from the words those
 //             chunks publish. The list is written to every target head mapped to the draft head.
-//  * long rows, small budgets (chunks * budget <= 16384) -- two launches, nothing to clear:
+//  * long rows, small budgets (chunks * budget small enough for one workgroup's LDS, see the
+//    host's rule) -- two launches, nothing to clear:
 //      local  aggregate a chunk, keep its keys in registers, and rank them inside the chunk: the
 //             chunk's own top-k (same tie rule) goes to a pool, in token order. Every token of
 //             the row's top-k is in the top-k of its chunk.

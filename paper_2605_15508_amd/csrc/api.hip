@@ -47,15 +47,13 @@ hipError_t run_kernel(int kind, hipStream_t s, F &&launch) {
 }
 
 int cu_count() {
-  static int cus = 0;
-  if (cus == 0) {
+  static const int cus = [] {   // once per process (thread-safe initialisation)
     int dev = 0, n = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-      cus = n;
-    else
-      cus = 256;
-  }
+      return n;
+    return 256;
+  }();
   return cus;
 }
 

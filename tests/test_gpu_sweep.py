@@ -112,3 +112,65 @@ def test_random_select_case(seed):
     np.testing.assert_array_equal(agg.cpu().numpy().view(np.uint32), o_agg.view(np.uint32), err_msg=what)
     np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt, err_msg=what)
     np.testing.assert_array_equal(idx.cpu().numpy(), o_idx, err_msg=what)
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_random_selection_case(seed):
+    """Random shapes and options of sts_select: row lengths on both sides of every path switch
+    (one workgroup per row, chunk-local top-k + pool, histogram pipeline, vector and scalar
+    loads), budgets from 1 to beyond N, ragged lengths, per-head budgets, block granularity,
+    both score kinds and reductions, fp32 and bf16 scores, quantised scores (ties)."""
+    rng = np.random.default_rng(5000 + seed)
+    B = int(rng.integers(1, 4))
+    Hd = int(rng.integers(1, 6))
+    Hq = int(rng.integers(1, 9))
+    Tq = int(rng.choice([1, 2, 5, 8, 11]))
+    N = int(rng.choice([rng.integers(1, 9000), rng.integers(9000, 40000), rng.integers(40000, 120000)]))
+    if rng.integers(0, 3):
+        N = max(4, N - N % 4)                                  # mostly the vector paths
+    page = int(rng.choice([1, 1, 1, 4, 8, 16]))
+    nunits = (N + page - 1) // page
+    k = int(rng.choice([1, rng.integers(1, 64), rng.integers(1, max(2, nunits // 8)), rng.integers(1, nunits + 50)]))
+    kind = int(rng.integers(0, 2))
+    reduce = int(rng.integers(0, 2)) if kind == 0 else 0
+    bf16 = bool(rng.integers(0, 3) == 0)
+    ties = bool(rng.integers(0, 4) == 0)
+    g = torch.Generator().manual_seed(seed)
+    logits = torch.randn(B, Hd, Tq, N, generator=g) * 2.0
+    if ties:
+        logits = torch.round(logits)
+    if bf16:
+        logits = logits.to(torch.bfloat16).float()
+    lse = torch.logsumexp(logits, dim=-1)
+    scores = logits if kind == 1 else torch.softmax(logits, dim=-1)
+    if bf16:
+        scores = scores.to(torch.bfloat16)
+    hm = rng.integers(0, Hd, size=Hq).tolist()
+    lens = None
+    if rng.integers(0, 2):
+        lens = torch.tensor([int(rng.integers(0, N + 1)) for _ in range(B)], dtype=torch.int32)
+    kh = None
+    if rng.integers(0, 2):
+        kh = [int(x) for x in rng.integers(1, k + 1, Hd)]
+    what = f"seed {seed}: B{B} Hd{Hd} Hq{Hq} Tq{Tq} N{N} k{k} page{page} kind{kind} reduce{reduce} bf16{bf16} ties{ties}"
+    idx, cnt, agg = sts.sts_select(scores.to(DEV), hm, k, lse=lse.to(DEV) if kind == 1 else None,
+                                   seq_lens=None if lens is None else lens.to(DEV), kind=kind, reduce=reduce,
+                                   want_agg=True, page_size=page, k_head=kh)
+    torch.cuda.synchronize()
+    agg = agg.cpu().numpy()
+    o_agg = oracle.aggregate(scores.float().numpy(), lse.numpy() if kind == 1 else None, kind, reduce)
+    if kind == 0:
+        np.testing.assert_array_equal(agg.view(np.uint32), o_agg.view(np.uint32), err_msg=what)
+    else:
+        np.testing.assert_allclose(agg, o_agg, rtol=1e-5, atol=1e-12, err_msg=what)
+    # stage-wise: the ranking is checked on the GPU's own aggregate
+    lens_np = None if lens is None else lens.numpy()
+    if page > 1:
+        src = oracle.block_scores(agg, page, lens_np)
+        l2 = None if lens_np is None else ((lens_np.astype(np.int64) + page - 1) // page).astype(np.int32)
+    else:
+        src, l2 = agg, lens_np
+    sel, c = oracle.select(src, k, l2) if kh is None else oracle.select_per_head(src, k, kh, l2)
+    o_idx, o_cnt = oracle.remap(sel, c, np.asarray(hm, np.int32))
+    np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt, err_msg=what)
+    np.testing.assert_array_equal(idx.cpu().numpy(), o_idx, err_msg=what)

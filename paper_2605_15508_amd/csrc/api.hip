@@ -219,7 +219,7 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
 struct SelectPlan {
   bool small;          // one workgroup per row, keys in LDS, a single launch
   bool pool;           // shape allows chunk-local top-k + one ranking workgroup per row
-  int nchunks, page, srcN, pool_pitch;
+  int nchunks, page, srcN, pool_pitch, pool_chunk, pool_nchunks;
   size_t agg_bytes, blk_bytes, hist_bytes, state_bytes, chunk_bytes;
   size_t pool_key_bytes;
   size_t pipeline_total() const { return agg_bytes + blk_bytes + hist_bytes + state_bytes + chunk_bytes; }
@@ -254,21 +254,29 @@ sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
     pl.agg_bytes = pl.blk_bytes = pl.hist_bytes = pl.state_bytes = pl.chunk_bytes = 0;
     return STS_OK;
   }
-  // Small budgets on long rows: each 8192-token chunk keeps its own best k tokens and one
+  // Small budgets on long rows: each chunk of the row keeps its own best k tokens and one
   // workgroup per row ranks that pool out of LDS (two launches, the scores are read once and
   // the aggregate is never stored). The ranking workgroup works at one CU's pace, about 1.2 us
   // per 1000 pooled pairs on top of 10 us, so the pool must be small: up to 8192 pairs it beats
   // the five-launch pipeline for every shape measured, up to 16384 only when the pipeline's
-  // passes over the aggregate are long (8M scores or more in the call).
-  {
-    const int64_t pitch = p->k < SEL_CHUNK ? p->k : SEL_CHUNK;
-    const int64_t pooled = (int64_t)pl.nchunks * pitch;
-    const bool fits = pooled <= SEL_POOL_MAX / 2 ||
-                      (pooled <= SEL_POOL_MAX && (int64_t)rows * p->N >= (int64_t)1 << 23);
-    if (pl.page == 1 && (p->N % 4) == 0 && pl.nchunks <= 1024 && fits) {
-      pl.pool = true;
-      pl.pool_pitch = (int)pitch;
-      pl.pool_key_bytes = align256(rows * (size_t)pl.nchunks * (size_t)pitch * sizeof(uint32_t));
+  // passes over the aggregate are long (8M scores or more in the call). Chunks are 8192 tokens,
+  // or 32768 when only that keeps the pool small enough (long rows, middle budgets).
+  pl.pool_chunk = pl.pool_nchunks = 0;
+  if (pl.page == 1 && (p->N % 4) == 0) {
+    for (const int chunk : {SEL_CHUNK, 4 * SEL_CHUNK}) {
+      const int64_t nch = ((int64_t)p->N + chunk - 1) / chunk;
+      const int64_t pitch = p->k < chunk ? p->k : chunk;
+      const int64_t pooled = nch * pitch;
+      // a grid of few large workgroups leaves most of the chip idle: then the pipeline is as fast
+      if (chunk > SEL_CHUNK && (int64_t)rows * nch < 128) break;
+      if (pooled <= SEL_POOL_MAX / 2 || (pooled <= SEL_POOL_MAX && (int64_t)rows * p->N >= (int64_t)1 << 23)) {
+        pl.pool = true;
+        pl.pool_chunk = chunk;
+        pl.pool_nchunks = (int)nch;
+        pl.pool_pitch = (int)pitch;
+        pl.pool_key_bytes = align256(rows * (size_t)nch * (size_t)pitch * sizeof(uint32_t));
+        break;
+      }
     }
   }
   pl.agg_bytes = p->agg_out ? 0 : align256(rows * (size_t)p->N * sizeof(float));
@@ -388,6 +396,8 @@ static sts_status enqueue_select(const sts_select_params *p, void *stream) {
     a.pool_key = reinterpret_cast<uint32_t *>(pw);
     a.pool_idx = reinterpret_cast<int32_t *>(pw + pl.pool_key_bytes);
     a.pool_pitch = pl.pool_pitch;
+    a.pool_chunk = pl.pool_chunk;
+    a.pool_nchunks = pl.pool_nchunks;
     a.agg = p->agg_out;   // optional output only
     rc = run_kernel(STS_K_SELECT_LOCAL, s, [&] { return launch_select_local(a, s); });
     if (rc != hipSuccess) return STS_EHIP;

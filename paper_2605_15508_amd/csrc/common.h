@@ -90,10 +90,12 @@ struct SelectArgs {
   uint32_t *hist;             // [rows][3][SEL_BINS]
   uint32_t *state;            // [rows][8]: digits 0/1 and remaining k after each, [6] budget
   uint32_t *chunk_cnt;        // [rows][nchunks][SEL_FLAG_PITCH], word 0: published flag | equal count << 14 | greater count
-  uint32_t *pool_key;         // [rows][nchunks * pool_pitch] chunk-local winners (small budgets), token order,
-                              // contiguous per row: chunk c starts at c * min(budget of the row, SEL_CHUNK)
+  uint32_t *pool_key;         // [rows][pool_nchunks * pool_pitch] chunk-local winners (small budgets), token
+                              // order, contiguous per row: chunk c starts at c * min(budget of the row, pool_chunk)
   int32_t *pool_idx;          // their token ids
-  int32_t pool_pitch;         // min(k, SEL_CHUNK)
+  int32_t pool_chunk;         // tokens per chunk of the local kernel: 8192 or 32768
+  int32_t pool_nchunks;       // ceil(N / pool_chunk)
+  int32_t pool_pitch;         // min(k, pool_chunk)
   uint64_t clear_words;       // words to zero from `hist` on: histograms, state and chunk flags
   int32_t spin_limit;         // polls of an unpublished earlier chunk before it is recounted locally
   int32_t B, Hd, Tq, N, Hq, k, kind, reduce, nchunks;   // k: row pitch of indices = largest budget

@@ -751,36 +751,39 @@ __global__ void __launch_bounds__(SMALL_THREADS) select_small_kernel(const Selec
 // chunk: it belongs to the top-c of its chunk under the same rule. So each chunk keeps only
 // its own best min(c, chunk length) tokens (the pool), and the row is ranked from the pool.
 //
-// Local kernel, (chunk, row) grid, 256 threads: aggregates the chunk (same fp32 order), keeps
-// the 32 keys of each thread in registers, finds the chunk's threshold with three LDS digit
+// Local kernel, (chunk, row) grid, 256 threads per 8192-token chunk or 1024 per 32768-token
+// chunk (fewer, larger chunks keep the pool small on very long rows): aggregates the chunk (same
+// fp32 order), keeps the 32 keys of each thread in registers, finds the chunk's threshold with three LDS digit
 // histograms, and writes the kept (key, token) pairs to the chunk's pool segment in token
-// order. Thread t owns tokens n0 + i*1024 + 4t .. +3 for i = 0..7, so token order is (i, t).
+// order. Thread t owns tokens n0 + (i*THREADS + t)*4 .. +3 for i = 0..7, so token order is (i, t).
 template <int IT>
 struct LocalKeys {
   uint32_t k[IT][4];
 };
 
-__global__ void __launch_bounds__(SEL_THREADS) select_local_kernel(const SelectArgs A) {
-  constexpr int IT = SEL_CHUNK / (SEL_THREADS * 4);
+template <int THREADS>
+__global__ void __launch_bounds__(THREADS) select_local_kernel(const SelectArgs A) {
+  constexpr int CHUNK = THREADS * 32;          // 32 keys per thread
+  constexpr int IT = 8;
   __shared__ uint32_t h[SEL_BINS];
-  __shared__ uint32_t tmp[16];
+  __shared__ uint32_t tmp[THREADS / 64 + 2];
   const int row = blockIdx.y, chunk = blockIdx.x;
   const int bt = row / A.Hd, j = row % A.Hd;
   const int nb = row_len(A, bt);
-  const int n0 = chunk * SEL_CHUNK;
-  const int nvalid = max(0, min(n0 + SEL_CHUNK, nb) - n0);     // ranked tokens of this chunk
+  const int n0 = chunk * CHUNK;
+  const int nvalid = max(0, min(n0 + CHUNK, nb) - n0);     // ranked tokens of this chunk
   uint32_t c = (uint32_t)min(A.kh[j], nvalid);
   const bool want_agg = A.agg != nullptr;
   if (A.targets.off[j] == A.targets.off[j + 1]) c = 0;        // no target head reads this draft head
   if (c == 0 && !want_agg) return;
-  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) h[i] = 0u;
+  for (int i = threadIdx.x; i < SEL_BINS; i += THREADS) h[i] = 0u;
   __syncthreads();
   const AggRow R = agg_row(A, row);
   float *out = want_agg ? A.agg + (size_t)row * A.N : nullptr;
   LocalKeys<IT> K;
 #pragma clang loop unroll(full)
   for (int i = 0; i < IT; ++i) {
-    const int n = n0 + (i * SEL_THREADS + threadIdx.x) * 4;
+    const int n = n0 + (i * THREADS + threadIdx.x) * 4;
     if (n < A.N) {                                             // N % 4 == 0 on this path
       const f32x4 acc = agg_quad(R, n);
       if (want_agg) *reinterpret_cast<f32x4 *>(out + n) = acc;
@@ -798,44 +801,44 @@ __global__ void __launch_bounds__(SEL_THREADS) select_local_kernel(const SelectA
   if (c == 0) return;
   // threshold of the chunk: three digits over the register-resident keys
   uint32_t d0, k1, d1, k2, d2, r;
-  find_digit<(1 << SEL_BITS0)>(h, c, tmp, d0, k1);
-  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) h[i] = 0u;
+  find_digit<(1 << SEL_BITS0), THREADS>(h, c, tmp, d0, k1);
+  for (int i = threadIdx.x; i < SEL_BINS; i += THREADS) h[i] = 0u;
   __syncthreads();
 #pragma unroll
   for (int i = 0; i < IT; ++i)
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const int n = n0 + (i * SEL_THREADS + threadIdx.x) * 4 + e;
+      const int n = n0 + (i * THREADS + threadIdx.x) * 4 + e;
       const uint32_t key = K.k[i][e];
       if (n < nb && (key >> (SEL_BITS1 + SEL_BITS2)) == d0) atomicAdd(&h[(key >> SEL_BITS2) & ((1u << SEL_BITS1) - 1)], 1u);
     }
   __syncthreads();
-  find_digit<(1 << SEL_BITS1)>(h, k1, tmp, d1, k2);
-  for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) h[i] = 0u;
+  find_digit<(1 << SEL_BITS1), THREADS>(h, k1, tmp, d1, k2);
+  for (int i = threadIdx.x; i < SEL_BINS; i += THREADS) h[i] = 0u;
   __syncthreads();
   const uint32_t pre01 = (d0 << SEL_BITS1) | d1;
 #pragma unroll
   for (int i = 0; i < IT; ++i)
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const int n = n0 + (i * SEL_THREADS + threadIdx.x) * 4 + e;
+      const int n = n0 + (i * THREADS + threadIdx.x) * 4 + e;
       const uint32_t key = K.k[i][e];
       if (n < nb && (key >> SEL_BITS2) == pre01) atomicAdd(&h[key & ((1u << SEL_BITS2) - 1)], 1u);
     }
   __syncthreads();
-  find_digit<(1 << SEL_BITS2)>(h, k2, tmp, d2, r);
+  find_digit<(1 << SEL_BITS2), THREADS>(h, k2, tmp, d2, r);
   const uint32_t T = (pre01 << SEL_BITS2) | d2;
 
   // Ordered compaction into the chunk's pool segment, one block scan per sweep of 1024 tokens.
-  // Every chunk before this one is full and keeps min(budget, SEL_CHUNK) pairs, so the row's
+  // Every chunk before this one is full and keeps min(budget, CHUNK) pairs, so the row's
   // pool is contiguous and this chunk's place in it is known without communication.
-  const size_t seg = (size_t)row * A.nchunks * A.pool_pitch + (size_t)chunk * min(A.kh[j], SEL_CHUNK);
+  const size_t seg = (size_t)row * A.pool_nchunks * A.pool_pitch + (size_t)chunk * min(A.kh[j], CHUNK);
   uint32_t *pk = A.pool_key + seg;
   int32_t *pi = A.pool_idx + seg;
   uint32_t g0 = 0, q0 = 0;                                     // greater / equal in the sweeps before
 #pragma unroll
   for (int i = 0; i < IT; ++i) {
-    const int n = n0 + (i * SEL_THREADS + threadIdx.x) * 4;
+    const int n = n0 + (i * THREADS + threadIdx.x) * 4;
     uint32_t cg = 0, ce = 0;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -844,7 +847,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_local_kernel(const SelectA
       ce += (in && K.k[i][e] == T) ? 1u : 0u;
     }
     uint32_t total;
-    const uint32_t excl = block_excl_scan(cg | (ce << 16), tmp, total);
+    const uint32_t excl = block_excl_scan<THREADS>(cg | (ce << 16), tmp, total);
     uint32_t g = g0 + (excl & 0xffffu), q = q0 + (excl >> 16);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -884,13 +887,13 @@ __global__ void __launch_bounds__(SMALL_THREADS) select_pool_kernel(const Select
   write_tail<SMALL_THREADS>(A, bt, j, c);
   if (c == 0 || t0 == t1) return;
   for (int i = tid; i < SEL_BINS; i += SMALL_THREADS) h[i] = 0u;
-  // pooled pairs of the row: the full chunks keep min(budget, SEL_CHUNK) each, the last one
+  // pooled pairs of the row: the full chunks keep min(budget, chunk length) each, the last one
   // min(budget, its length)
-  const uint32_t kfull = (uint32_t)min(A.kh[j], SEL_CHUNK);
-  const uint32_t m = min((uint32_t)(nb / SEL_CHUNK) * kfull + min((uint32_t)A.kh[j], (uint32_t)(nb % SEL_CHUNK)),
+  const uint32_t kfull = (uint32_t)min(A.kh[j], A.pool_chunk);
+  const uint32_t m = min((uint32_t)(nb / A.pool_chunk) * kfull + min((uint32_t)A.kh[j], (uint32_t)(nb % A.pool_chunk)),
                          (uint32_t)POOL_MAX);
-  const uint32_t *pk = A.pool_key + (size_t)row * A.nchunks * A.pool_pitch;
-  const int32_t *pi = A.pool_idx + (size_t)row * A.nchunks * A.pool_pitch;
+  const uint32_t *pk = A.pool_key + (size_t)row * A.pool_nchunks * A.pool_pitch;
+  const int32_t *pi = A.pool_idx + (size_t)row * A.pool_nchunks * A.pool_pitch;
   // The pairs were written by other workgroups: their loads miss the caches, so eight
   // independent ones are issued per thread before any is used (uniform trip count, clamped
   // addresses, the surplus ignored).
@@ -977,8 +980,12 @@ hipError_t launch_select_small(const SelectArgs &a, hipStream_t s) {
 }
 
 hipError_t launch_select_local(const SelectArgs &a, hipStream_t s) {
-  if ((size_t)a.B * a.Hd == 0 || a.nchunks == 0) return hipSuccess;
-  hipLaunchKernelGGL(select_local_kernel, dim3(a.nchunks, a.B * a.Hd), dim3(SEL_THREADS), 0, s, a);
+  if ((size_t)a.B * a.Hd == 0 || a.pool_nchunks == 0) return hipSuccess;
+  const dim3 grid(a.pool_nchunks, a.B * a.Hd);
+  if (a.pool_chunk == 256 * 32)
+    hipLaunchKernelGGL(select_local_kernel<256>, grid, dim3(256), 0, s, a);
+  else   // 1024 * 32
+    hipLaunchKernelGGL(select_local_kernel<1024>, grid, dim3(1024), 0, s, a);
   return hipGetLastError();
 }
 

@@ -294,14 +294,19 @@ def test_each_selection_path_is_taken_where_expected():
     def run(B, Hd, N, k):
         s = softmax_scores(3, B, Hd, 2, N).to(DEV)
         return launched(lambda: sts.sts_select(s, list(range(Hd)), k))
+    pipeline = {"select_clear", "select_agg", "select_hist", "select_write"}
+    pool = {"select_local", "select_pool"}
     assert run(1, 4, 8192, 100) == {"select_small"}
     assert run(16, 16, 20000, 100) == {"select_small"}                      # 256 rows
-    assert run(1, 4, 65536, 512) == {"select_local", "select_pool"}         # 8 chunks x 512
-    assert run(1, 4, 65536, 1024) == {"select_local", "select_pool"}        # 8192 pooled pairs: the limit
-    assert run(1, 4, 65536, 1025) == {"select_clear", "select_agg", "select_hist", "select_write"}
-    assert run(1, 4, 65532 + 2, 512) == {"select_clear", "select_agg", "select_hist", "select_write"}   # N % 4 != 0
-    assert run(8, 16, 65536, 2048) == {"select_local", "select_pool"}       # 16384 pooled, 8M scores
-    assert run(4, 16, 65536, 2048) == {"select_clear", "select_agg", "select_hist", "select_write"}
+    assert run(1, 4, 65536, 512) == pool                                    # 8 chunks of 8192 x 512
+    assert run(1, 4, 65536, 1024) == pool                                   # 8192 pooled pairs: the limit
+    assert run(1, 4, 65536, 4096) == pipeline                               # 2 chunks of 32768: 8 workgroups only
+    assert run(16, 4, 65536, 4096) == pool                                  # 64 rows x 2 chunks of 32768 x 4096
+    assert run(16, 4, 65536, 4097) == pipeline
+    assert run(1, 4, 65532 + 2, 512) == pipeline                            # N % 4 != 0
+    assert run(8, 16, 65536, 2048) == pool                                  # 16384 pooled, 8M scores
+    assert run(8, 16, 65536, 8192) == pool                                  # 2 x 8192 pooled, 8M scores
+    assert run(8, 16, 65536, 8193) == pipeline
 
 
 @pytest.mark.parametrize("kind,reduce", [(0, 0), (0, 1), (1, 0)])
@@ -424,3 +429,27 @@ def test_misaligned_scores_fall_back_to_the_pipeline():
     o_idx, o_cnt, _ = oracle.select_indices(scores.numpy(), np.asarray([0, 1, 2], np.int32), k)
     np.testing.assert_array_equal(got["r"][0].cpu().numpy(), o_idx)
     np.testing.assert_array_equal(got["r"][1].cpu().numpy(), o_cnt)
+
+
+@pytest.mark.parametrize("levels", [0, 3])
+def test_pool_path_with_32768_token_chunks(levels):
+    """Long rows with middle budgets: the pool stays small only with 32768-token chunks (1024
+    threads per workgroup). Ragged lengths ending inside a chunk, on a chunk boundary and at 0."""
+    B, Hd, Tq, N, k = 3, 11, 3, 100000, 2000         # 13 x 2000 is too much, 4 x 2000 fits; 33 rows x 4 chunks
+    g = torch.Generator().manual_seed(40 + levels)
+    if levels:
+        scores = torch.randint(0, levels, (B, Hd, Tq, N), generator=g).float() / 4.0
+    else:
+        scores = softmax_scores(40, B, Hd, Tq, N)
+    lens = torch.tensor([N, 65536, 0], dtype=torch.int32)
+    hm, kh = [1, 0, 10, 5], [2000, 77] + [1500] * 9
+    sd = scores.to(DEV)
+    got = {}
+    kinds = launched(lambda: got.update(r=sts.sts_select(sd, hm, k, seq_lens=lens.to(DEV), k_head=kh, want_agg=True)))
+    assert kinds == {"select_local", "select_pool"}
+    idx, cnt, agg = got["r"]
+    o_idx, o_cnt, o_agg = oracle.select_indices(scores.numpy(), np.asarray(hm, np.int32), k, seq_lens=lens.numpy(),
+                                                k_head=kh)
+    np.testing.assert_array_equal(agg.cpu().numpy().view(np.uint32), o_agg.view(np.uint32))
+    np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
+    np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)

@@ -46,6 +46,12 @@ def parse_args():
     ap.add_argument("--warm", action="store_true",
                     help="reuse one KV buffer even when it fits the 256 MB Infinity Cache (default: rotate over "
                          "enough distinct layers to exceed 2 GiB so that every pass starts cache-cold)")
+    ap.add_argument("--gain", type=float, default=None,
+                    help="strength of the planted keys (default: the configuration's, 3.0)")
+    ap.add_argument("--head-map", default="default", choices=["default", "random"],
+                    help="target head -> draft head: t*Hd//Hq, or a seeded random map (robustness point)")
+    ap.add_argument("--positions", default="scattered", choices=["scattered", "recent"],
+                    help="heavy tokens scattered over the context (worst case for the gather) or clustered at its end")
     ap.add_argument("--scores", default="fp32", choices=["fp32", "bf16"],
                     help="type of the draft scores read by sts_select (and of the logits dump of the draft layer)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -133,6 +139,8 @@ def main():
     import torch
 
     import paper_2605_15508_amd as sts
+    from dataclasses import replace
+
     from workload import CONFIGS, budget_tokens, make_draft_layer, make_workload
 
     if not torch.cuda.is_available():
@@ -142,7 +150,16 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     cfg = CONFIGS[args.config]
-    w = make_workload(cfg, seed=args.seed, device=dev, budget=args.budget, with_scores=not cfg.draft_d)
+    if args.gain is not None:
+        cfg = replace(cfg, gain=args.gain)
+    if args.positions == "recent":
+        cfg = replace(cfg, clustered=True)
+    head_map = None
+    if args.head_map == "random":
+        hg = torch.Generator().manual_seed(args.seed + 4242)
+        head_map = torch.randint(0, cfg.Hd, (cfg.Hq,), generator=hg, dtype=torch.int32)
+    w = make_workload(cfg, seed=args.seed, device=dev, budget=args.budget, with_scores=not cfg.draft_d,
+                      head_map=head_map)
     page = max(1, args.page_size)
     kb = -(-w.k_budget // page)          # same token budget, counted in blocks of `page` tokens
     B, N, Hq, Hkv, d, Tq, Hd = cfg.B, cfg.N, cfg.Hq, cfg.Hkv, cfg.d, cfg.Tq, cfg.Hd
@@ -290,7 +307,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": workload, "context": N, "batch": B, "budget_tokens": kb * page, "page_size": page, "paged_kv": bool(args.paged),
-                   "layers": L, "cache": "cold: every pass reads KV that has left the caches" if (L > 1 or kv_bytes > (256 << 20)) else "warm", "head_map": "t*Hd//Hq", "scores": args.scores, "step": ("%d layers x (" % L if L > 1 else "(") + "select + sparse_attn" + ("" if args.no_dense else " + dense_attn")
+                   "layers": L, "cache": "cold: every pass reads KV that has left the caches" if (L > 1 or kv_bytes > (256 << 20)) else "warm", "head_map": "t*Hd//Hq" if args.head_map == "default" else "seeded random", "gain": cfg.gain, "heavy_positions": args.positions, "scores": args.scores, "step": ("%d layers x (" % L if L > 1 else "(") + "select + sparse_attn" + ("" if args.no_dense else " + dense_attn")
                    + (" + draft dense attn with logits dump" if draft is not None else "") + ")"},
         "sparse_attn_us": {"mean": round(sparse_us[0], 2), "median": round(sparse_us[1], 2), "min": round(sparse_us[2], 2), "p10": round(sparse_us[3], 2), "p90": round(sparse_us[4], 2)},
         "dense_attn_us": None if args.no_dense else {"mean": round(dense_us[0], 2), "median": round(dense_us[1], 2), "min": round(dense_us[2], 2), "p10": round(dense_us[3], 2), "p90": round(dense_us[4], 2)},

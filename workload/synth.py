@@ -35,6 +35,7 @@ class WorkloadConfig:
     recent: int = 64           # trailing positions planted
     noise: float = 0.5         # std of the logit noise between target and draft
     gain: float = 3.0          # planted keys get gain * q_hat added
+    clustered: bool = False    # heavy positions: rank r sits at N - r (recency-clustered) instead of scattered
     kv_std: float = 0.5
     layers: int = 1            # distinct resident layers (bench only)
     # draft attention layer of its own (70B-shaped config): query heads Hd, these extras
@@ -82,16 +83,18 @@ class Workload:
     extras: dict = field(default_factory=dict)
 
 
-def _heavy_positions(N: int, count: int, s: float, gen: torch.Generator, device) -> torch.Tensor:
+def _heavy_positions(N: int, count: int, s: float, gen: torch.Generator, device,
+                     clustered: bool = False) -> torch.Tensor:
     """`count` distinct positions whose ranks follow a truncated Zipf(s), scattered by a
-    seeded permutation. Sequential weighted draws without replacement are realised with
-    Gumbel perturbations of the log-weights (same distribution, one pass)."""
+    seeded permutation (the worst case for gather locality), or, `clustered`, rank r at
+    position N - r. Sequential weighted draws without replacement are realised with Gumbel
+    perturbations of the log-weights (same distribution, one pass)."""
     ranks = torch.arange(1, N + 1, device=device, dtype=torch.float32)
     u = torch.rand(N, generator=gen, device=device, dtype=torch.float32).clamp_(1e-12, 1 - 1e-7)
     keyed = -s * torch.log(ranks) - torch.log(-torch.log(u))
     chosen = torch.topk(keyed, count).indices
-    perm = torch.randperm(N, generator=gen, device=device)
-    return perm[chosen]
+    perm = torch.randperm(N, generator=gen, device=device)     # drawn in both modes: same stream of numbers after it
+    return (N - 1 - chosen) if clustered else perm[chosen]
 
 
 def make_workload(cfg: WorkloadConfig, seed: int = 20251127, device="cpu", with_scores: bool = True,
@@ -117,7 +120,7 @@ def make_workload(cfg: WorkloadConfig, seed: int = 20251127, device="cpu", with_
         qsum = q[b].float().reshape(Tq, Hkv, G, d).sum(dim=(0, 2))
         qhat = qsum / qsum.norm(dim=-1, keepdim=True).clamp_min(1e-20)
         for g in range(Hkv):
-            pos = torch.unique(torch.cat([fixed, _heavy_positions(N, n_heavy, cfg.zipf_s, gen, dev)]))
+            pos = torch.unique(torch.cat([fixed, _heavy_positions(N, n_heavy, cfg.zipf_s, gen, dev, cfg.clustered)]))
             kb[g, pos] += cfg.gain * qhat[g]
         k[b] = kb.to(torch.bfloat16)
         del kb

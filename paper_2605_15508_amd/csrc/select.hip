@@ -477,23 +477,40 @@ __global__ void __launch_bounds__(SEL_THREADS, 4) select_write_kernel(const Sele
   const uint32_t *st = A.state + (size_t)row * 8;
   const float *a = A.src + (size_t)row * A.srcN;
 
-  // coalesced load of the chunk; token n0 + i lands at buf[(i / PER) * PITCH + i % PER]
+  uint32_t *cc = A.chunk_cnt + (size_t)row * A.nchunks * SEL_FLAG_PITCH;
+  // Everything this workgroup needs from memory is asked for at once, before anything is used:
+  // the chunk (coalesced, clamped addresses, unconditional), a first look at the counts the
+  // earlier chunks publish (they are often there already), and, inside find_digit, the last
+  // digit's histogram.
+  constexpr int IT = SEL_CHUNK / (SEL_THREADS * 4);
+  f32x4 x[IT];
   if (VEC4) {
-    for (int i = threadIdx.x * 4; i < SEL_CHUNK; i += SEL_THREADS * 4) {
-      f32x4 x = {0.f, 0.f, 0.f, 0.f};
-      if (n0 + i < A.srcN) x = *reinterpret_cast<const f32x4 *>(a + n0 + i);   // srcN % 4 == 0
 #pragma unroll
-      for (int e = 0; e < 4; ++e) buf[((i + e) / PER) * PITCH + (i + e) % PER] = key_of(x[e]);
+    for (int i = 0; i < IT; ++i)
+      x[i] = *reinterpret_cast<const f32x4 *>(a + min(n0 + (i * SEL_THREADS + (int)threadIdx.x) * 4, A.srcN - 4));
+  }
+  uint32_t early = 0;
+  if ((int)threadIdx.x < chunk)
+    early = __hip_atomic_load(&cc[threadIdx.x * SEL_FLAG_PITCH], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+  // threshold key and tie quota of the row
+  uint32_t d2, r;
+  find_digit<(1 << SEL_BITS2)>(A.hist + ((size_t)row * 3 + 2) * SEL_BINS, st[3], tmp, d2, r);
+  const uint32_t T = (st[0] << (SEL_BITS1 + SEL_BITS2)) | (st[2] << SEL_BITS2) | d2;
+
+  // token n0 + i lands at buf[(i / PER) * PITCH + i % PER]
+  if (VEC4) {
+#pragma unroll
+    for (int i = 0; i < IT; ++i) {
+      const int t = (i * SEL_THREADS + (int)threadIdx.x) * 4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) buf[((t + e) / PER) * PITCH + (t + e) % PER] = key_of(x[i][e]);   // srcN % 4 == 0
     }
   } else {
     for (int i = threadIdx.x; i < SEL_CHUNK; i += SEL_THREADS)
       buf[(i / PER) * PITCH + i % PER] = (n0 + i < nb) ? key_of(a[n0 + i]) : 0u;
   }
-
-  // threshold key and tie quota of the row
-  uint32_t d2, r;
-  find_digit<(1 << SEL_BITS2)>(A.hist + ((size_t)row * 3 + 2) * SEL_BINS, st[3], tmp, d2, r);   // barriers: buf visible
-  const uint32_t T = (st[0] << (SEL_BITS1 + SEL_BITS2)) | (st[2] << SEL_BITS2) | d2;
+  __syncthreads();
 
   const int base_n = n0 + threadIdx.x * PER;
   uint32_t keys[PER];
@@ -511,7 +528,6 @@ __global__ void __launch_bounds__(SEL_THREADS, 4) select_write_kernel(const Sele
 
   // keys greater / equal in the chunks before this one
   uint32_t pre = 0, pre_eq = 0;
-  uint32_t *cc = A.chunk_cnt + (size_t)row * A.nchunks * SEL_FLAG_PITCH;
   {
     // Every chunk publishes its own counts in one word (flag | equal << 14 | greater) with a
     // device-scope atomic store and reads the words of the chunks before it, one per thread.
@@ -527,7 +543,9 @@ __global__ void __launch_bounds__(SEL_THREADS, 4) select_write_kernel(const Sele
     __syncthreads();
     uint32_t g = 0, e = 0;
     for (int ch = threadIdx.x; ch < chunk; ch += SEL_THREADS) {
-      uint32_t f = __hip_atomic_load(&cc[ch * SEL_FLAG_PITCH], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      uint32_t f = early;                                  // the first look, taken at the start
+      if (ch != (int)threadIdx.x || !(f >> 31))
+        f = __hip_atomic_load(&cc[ch * SEL_FLAG_PITCH], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       for (int spin = 0; !(f >> 31) && spin < A.spin_limit; ++spin) {
         __builtin_amdgcn_s_sleep(8);
         f = __hip_atomic_load(&cc[ch * SEL_FLAG_PITCH], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -566,11 +584,19 @@ __global__ void __launch_bounds__(SEL_THREADS, 4) select_write_kernel(const Sele
         e += packed >> 16;
       }
     }
-    uint32_t tg, te;
-    (void)block_excl_scan(g, tmp, tg);
-    (void)block_excl_scan(e, tmp, te);
-    pre = tg;
-    pre_eq = te;
+    // block totals of both counts (a row holds fewer than 2^31 tokens: two 32-bit sums)
+    const uint32_t wg = wave_incl_scan(g), we = wave_incl_scan(e);
+    if ((threadIdx.x & 63) == 63) {
+      tmp[2 * (threadIdx.x >> 6)] = wg;
+      tmp[2 * (threadIdx.x >> 6) + 1] = we;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < SEL_THREADS / 64; ++w) {
+      pre += tmp[2 * w];
+      pre_eq += tmp[2 * w + 1];
+    }
+    __syncthreads();
   }
   uint32_t g = pre + (excl & 0xffffu), q = pre_eq + (excl >> 16);
   // output range of this chunk: [first, last)

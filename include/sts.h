@@ -169,6 +169,11 @@ typedef struct {
   const void *k_new, *v_new; /* [dev] optional bf16 [B,Tq,Hkv,d] contiguous: see below; both or neither */
   int32_t causal;           /* with k_new: non-zero = query row i sees new tokens 0..i, zero = all Tq */
   int32_t logits_bf16;      /* type of logits_out: 0 fp32, non-zero bf16 (feeds sts_select's scores_bf16) */
+  int64_t idx_stride_b;     /* elements between the batches of `indices`; 0 = Hq*kmax (contiguous). Lets a
+                               call read its heads out of a wider list, e.g. the layer slice
+                               [:, l*Hq:(l+1)*Hq, :] of one sts_select over the target heads of several
+                               layers that share draft heads (the aggregation is then paid once) */
+  int64_t cnt_stride_b;     /* same for `counts`; 0 = Hq */
   void *workspace;          /* [dev] 256-byte aligned scratch */
   size_t workspace_bytes;
 } sts_attn_params;

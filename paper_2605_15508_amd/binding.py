@@ -51,7 +51,7 @@ class AttnParams(ctypes.Structure):
                 ("block_table", ctypes.c_void_p), ("table_stride", ctypes.c_int32),
                 ("num_pages", ctypes.c_int32), ("kv_stride_page", ctypes.c_int64),
                 ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p), ("causal", ctypes.c_int32),
-                ("logits_bf16", ctypes.c_int32),
+                ("logits_bf16", ctypes.c_int32), ("idx_stride_b", ctypes.c_int64), ("cnt_stride_b", ctypes.c_int64),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
 
 
@@ -214,12 +214,17 @@ def _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse_o
         assert block_table.shape[0] == B
         sb, sh, sn, sp, tstride = 0, k.stride(1), k.stride(2), k.stride(0), block_table.shape[1]
     kmax = 0
+    isb = csb = 0
     if indices is not None:
-        assert indices.is_cuda and indices.dtype == torch.int32 and indices.is_contiguous()
-        assert indices.shape[:2] == (B, Hq)
+        # [B,Hq,kmax], rows contiguous; the batch stride may be wider (a slice of heads of a wider list)
+        assert indices.is_cuda and indices.dtype == torch.int32 and indices.shape[:2] == (B, Hq)
         kmax = indices.shape[2]
+        assert kmax == 0 or (indices.stride(2) == 1 and (Hq == 1 or indices.stride(1) == kmax))
+        isb = indices.stride(0) if B > 1 else 0
     if counts is not None:
-        assert counts.is_cuda and counts.dtype == torch.int32 and counts.is_contiguous() and counts.shape == (B, Hq)
+        assert counts.is_cuda and counts.dtype == torch.int32 and counts.shape == (B, Hq)
+        assert Hq == 1 or counts.stride(1) == 1
+        csb = counts.stride(0) if B > 1 else 0
     if seq_lens is not None:
         assert seq_lens.is_cuda and seq_lens.dtype == torch.int32 and seq_lens.shape == (B,)
     hm = _host_i32(head_map) if head_map is not None else None
@@ -235,7 +240,7 @@ def _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse_o
                    lse_out=_ptr(lse_out), logits_out=_ptr(logits_out), page_size=int(page_size),
                    block_table=_ptr(block_table), table_stride=tstride, num_pages=npages,
                    kv_stride_page=sp, k_new=_ptr(k_new), v_new=_ptr(v_new), causal=1 if causal else 0,
-                   workspace=None, workspace_bytes=0)
+                   idx_stride_b=isb, cnt_stride_b=csb, workspace=None, workspace_bytes=0)
     return p, hm
 
 

@@ -85,6 +85,9 @@ sts_status validate_attn(const sts_attn_params *p, int sparse) {
     if ((int64_t)p->table_stride * page < p->N) return STS_EINVAL;
   }
   if (sparse && (int64_t)p->kmax * page > 0x7fffffffll - 65536) return STS_EUNSUPPORTED;
+  if (p->idx_stride_b < 0 || p->cnt_stride_b < 0) return STS_EINVAL;
+  if (sparse && p->idx_stride_b && p->idx_stride_b < (int64_t)p->Hq * p->kmax) return STS_EINVAL;
+  if (sparse && p->cnt_stride_b && p->cnt_stride_b < p->Hq) return STS_EINVAL;
   if ((p->k_new == nullptr) != (p->v_new == nullptr)) return STS_EINVAL;
   if (p->k_new && (reinterpret_cast<uintptr_t>(p->k_new) % 16 != 0 || reinterpret_cast<uintptr_t>(p->v_new) % 16 != 0))
     return STS_EUNSUPPORTED;
@@ -177,6 +180,8 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
   a.v = static_cast<const uint16_t *>(p->v);
   a.indices = sparse ? p->indices : nullptr;
   a.counts = sparse ? p->counts : nullptr;
+  a.idx_stride_b = p->idx_stride_b ? p->idx_stride_b : (int64_t)p->Hq * p->kmax;
+  a.cnt_stride_b = p->cnt_stride_b ? p->cnt_stride_b : p->Hq;
   a.seq_lens = sparse ? nullptr : p->seq_lens;
   a.stride_b = p->kv_stride_b;
   a.stride_h = p->kv_stride_h;
@@ -540,7 +545,7 @@ const char *sts_strerror(sts_status s) {
   return "unknown status";
 }
 
-int sts_version(void) { return 106; }
+int sts_version(void) { return 107; }
 
 void sts_prof_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);

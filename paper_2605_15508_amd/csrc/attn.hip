@@ -93,7 +93,7 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
   const int psh = A.page_shift, pmask = A.page - 1;
   int c;
   if (SPARSE) {
-    c = A.counts ? A.counts[bt * A.Hq + head0] : A.kmax;
+    c = A.counts ? A.counts[(size_t)bt * A.cnt_stride_b + head0] : A.kmax;
     c = min(max(c, 0), A.kmax) << psh;
   } else {
     c = A.seq_lens ? A.seq_lens[bt] : A.N;
@@ -103,7 +103,7 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
   const int tiles_max = (len_max + STS_TILE_KEYS - 1) / STS_TILE_KEYS;
   const int tps = (tiles_max + S - 1) / S;
   const int t_begin = split * tps;
-  const int32_t *idx_row = SPARSE ? A.indices + ((size_t)bt * A.Hq + head0) * A.kmax : nullptr;
+  const int32_t *idx_row = SPARSE ? A.indices + (size_t)bt * A.idx_stride_b + (size_t)head0 * A.kmax : nullptr;
   // first tile's index entries, issued before anything depends on the count (kmax >= 1
   // whenever a sparse grid has tiles to do; the clamp keeps the address inside the row)
   int rows_first = 0;

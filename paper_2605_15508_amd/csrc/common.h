@@ -30,6 +30,7 @@ struct AttnArgs {
   const uint16_t *q, *k, *v;
   const int32_t *indices, *counts, *seq_lens;
   int64_t stride_b, stride_h, stride_n;   // elements
+  int64_t idx_stride_b, cnt_stride_b;     // elements between batches of indices / counts
   int32_t B, Tq, Hq, Hkv, G, N, kmax;
   int32_t num_units, num_splits;
   int32_t page, page_shift;               // tokens per index entry / page (power of two <= 32)

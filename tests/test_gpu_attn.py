@@ -209,3 +209,28 @@ def test_maximum_head_counts_and_group_size():
     check_attn(dout, dlse, dref, what="Hq 256 / G 16 dense")
     plan = sts.attn_plan(q, k, True, kmax=kk, head_map=hm)
     assert plan["query_tiles"] == 4 and plan["units_per_batch"] == 16 * 4     # 16 heads x 16 rows -> 4 units of 64 rows
+
+
+def test_layers_read_their_slice_of_one_selection():
+    """Several target layers whose heads map to the same draft heads: one sts_select over all
+    their heads (the scores are aggregated and ranked once), then every layer's attention reads
+    its own slice [:, l*Hq:(l+1)*Hq, :] of the index lists in place (batch stride wider than
+    Hq*kmax), against the oracle on contiguous copies."""
+    import oracle
+    L, B, Tq, Hq, Hkv, Hd, d, N, k = 3, 2, 5, 8, 2, 4, 128, 3000, 300
+    g = torch.Generator().manual_seed(77)
+    scores = torch.softmax(torch.randn(B, Hd, Tq, N, generator=g) * 2, dim=-1)
+    hm_all = [int(x) for x in torch.randint(0, Hd, (L * Hq,), generator=g)]
+    kh = [300, 120, 300, 7]
+    idx_all, cnt_all, _ = sts.sts_select(scores.to(DEV), hm_all, k, k_head=kh)
+    o_idx, o_cnt, _ = oracle.select_indices(scores.numpy(), np.asarray(hm_all, np.int32), k, k_head=kh)
+    np.testing.assert_array_equal(idx_all.cpu().numpy(), o_idx)
+    for l in range(L):
+        q, kc, vc = make_qkv(100 + l, B, Tq, Hq, Hkv, d, N)
+        sl = slice(l * Hq, (l + 1) * Hq)
+        idx_l, cnt_l = idx_all[:, sl], cnt_all[:, sl]
+        assert not idx_l.is_contiguous()
+        out, lse = sts.sts_sparse_attn(q, kc, vc, idx_l, 0.09, counts=cnt_l, head_map=hm_all[sl],
+                                       out_dtype=torch.float32)
+        ref = oracle_attn(q, kc, vc, 0.09, idx_l.contiguous(), cnt_l.contiguous())
+        check_attn(out, lse, ref, what=f"layer {l} slice")

@@ -453,3 +453,19 @@ def test_pool_path_with_32768_token_chunks(levels):
     np.testing.assert_array_equal(agg.cpu().numpy().view(np.uint32), o_agg.view(np.uint32))
     np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
     np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
+
+
+def test_hand_worked_cases_on_the_gpu():
+    """The hand-worked fixture (tests/golden/select_handworked.json) straight through the library."""
+    import json
+    import os
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "select_handworked.json")) as f:
+        cases = json.load(f)["cases"]
+    for case in cases:
+        P = torch.tensor(case["probs"], dtype=torch.float32)[None].contiguous()      # [1,Hd,Tq,N]
+        idx, cnt, agg = sts.sts_select(P.to(DEV), case["head_map"], case["k"], page_size=case.get("page", 1),
+                                       k_head=case.get("k_head"), want_agg=True)
+        np.testing.assert_array_equal(idx[0].cpu().numpy(), np.array(case["indices"], np.int32))
+        np.testing.assert_array_equal(agg[0].cpu().numpy(), np.array(case["agg"], np.float32))
+        if "counts" in case:
+            np.testing.assert_array_equal(cnt[0].cpu().numpy(), np.array(case["counts"], np.int32))

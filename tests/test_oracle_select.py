@@ -193,9 +193,14 @@ def test_select_golden_fixture():
     for case in cases:
         P = np.array(case["probs"], np.float32)[None]          # [1,Hd,Tq,N]
         hm = np.array(case["head_map"], np.int32)
-        idx, cnt, A = oracle.select_indices(P, hm, case["k"])
+        idx, cnt, A = oracle.select_indices(P, hm, case["k"], page=case.get("page", 1), k_head=case.get("k_head"))
         np.testing.assert_array_equal(idx[0], np.array(case["indices"], np.int32))
         np.testing.assert_allclose(A[0], np.array(case["agg"], np.float32), rtol=0, atol=1e-7)
+        if "counts" in case:
+            np.testing.assert_array_equal(cnt[0], np.array(case["counts"], np.int32))
+        if "block_scores" in case:
+            np.testing.assert_array_equal(oracle.block_scores(A, case["page"])[0],
+                                          np.array(case["block_scores"], np.float32))
 
 
 # ---------------------------------------------------------------------- remap

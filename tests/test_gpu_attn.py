@@ -234,3 +234,32 @@ def test_layers_read_their_slice_of_one_selection():
                                        out_dtype=torch.float32)
         ref = oracle_attn(q, kc, vc, 0.09, idx_l.contiguous(), cnt_l.contiguous())
         check_attn(out, lse, ref, what=f"layer {l} slice")
+
+
+def test_closed_forms_on_the_gpu():
+    """Values fixed by the mathematics alone, without the oracle: zero queries give the plain
+    mean of the gathered value rows and LSE = ln(count); constant values come back unchanged."""
+    B, Tq, Hq, Hkv, d, N, kk = 2, 5, 8, 2, 128, 5000, 777
+    q, k, v = make_qkv(5, B, Tq, Hq, Hkv, d, N)
+    hm = [t // 2 for t in range(Hq)]
+    idx = make_indices(6, B, Hq, N, kk, head_map=hm)
+    cnt = torch.full((B, Hq), kk, dtype=torch.int32, device=DEV)
+    cnt[0, 2:4] = 100                                        # heads 2 and 3 share a row: same count
+    out, lse = sts.sts_sparse_attn(torch.zeros_like(q), k, v, idx, 0.09, counts=cnt, head_map=hm,
+                                   out_dtype=torch.float32)
+    G = Hq // Hkv
+    for b in range(B):
+        for t in range(Hq):
+            c = int(cnt[b, t])
+            rows = v[b, t // G][idx[b, t, :c].long()].float()            # [c, d]
+            want = rows.mean(dim=0)
+            assert (out[b, :, t] - want[None]).abs().max().item() < 2e-3  # P is rounded to bf16 before P.V
+            assert (lse[b, t] - math.log(c)).abs().max().item() < 1e-5
+    vc = torch.full_like(v, 0.75)
+    out, _ = sts.sts_sparse_attn(q, k, vc, idx, 0.09, counts=cnt, head_map=hm, out_dtype=torch.float32)
+    assert (out - 0.75).abs().max().item() < 4e-3
+    out, lse, _ = sts.sts_dense_attn(torch.zeros_like(q), k, v, 0.09, out_dtype=torch.float32)
+    want = v.float().mean(dim=2)                                          # [B,Hkv,d]
+    for t in range(Hq):
+        assert (out[:, :, t] - want[:, t // G][:, None]).abs().max().item() < 2e-3
+    assert (lse - math.log(N)).abs().max().item() < 1e-5

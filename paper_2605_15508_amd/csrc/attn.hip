@@ -158,7 +158,7 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
   //             id, or with a page table the physical page (a second, dependent load);
   //   issue   : the 16 K/V row loads of the tile.
   // All three are branch-free and nothing touches a loaded value before the next stage.
-  const int safe_pos = (t_begin + wave) * STS_TILE_KEYS;
+  const int safe_pos = (LOGITS ? t_begin + 2 * wave : t_begin + wave) * STS_TILE_KEYS;
   auto fetch_rows = [&](int t) -> int {
     const int pos = t * STS_TILE_KEYS + (lane & 31);
     const int p = (t < t_end) ? min(pos, c - 1) : safe_pos;
@@ -211,7 +211,34 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
     for (int nt = 0; nt < NT; ++nt) acc[nq][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  auto consume = [&](int t, const chunk_t (&Kr)[8], const chunk_t (&Vr)[8], const uint32_t tile_mask) {
+  // bf16 dump: the words of the first tile of a pair wait here for the second one, so that both
+  // halves of every 128-byte line of a logits row are stored back to back (a half-line write
+  // costs the memory system as much as a whole line)
+  u32x2 stash[NQ][2];
+  int stash_pos = -1;            // first token of the stashed tile, or -1
+  auto store_bf16_tile = [&](const u32x2 (&w)[NQ][2], int pos0) {
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+      if (!q_ok[nq]) continue;
+      uint16_t *lp = static_cast<uint16_t *>(A.logits_out) +
+                     (((size_t)bt * A.Hq + q_head[nq]) * A.Tq + q_tq[nq]) * (size_t)A.N;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const int p = pos0 + 16 * ks + 4 * a;
+        if (p + 3 < c && (A.N & 3) == 0) {
+          *reinterpret_cast<u32x2 *>(lp + p) = w[nq][ks];
+        } else {
+          const uint16_t h4[4] = {(uint16_t)(w[nq][ks][0] & 0xffffu), (uint16_t)(w[nq][ks][0] >> 16),
+                                  (uint16_t)(w[nq][ks][1] & 0xffffu), (uint16_t)(w[nq][ks][1] >> 16)};
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (p + r < c) lp[p + r] = h4[r];
+        }
+      }
+    }
+  };
+
+  auto consume = [&](int t, const chunk_t (&Kr)[8], const chunk_t (&Vr)[8], const uint32_t tile_mask, const bool second) {
     const int pos0 = t * STS_TILE_KEYS;
     // ---- K: registers -> swizzled LDS tile (row = slot, 16-byte slot index XOR row)
 #pragma unroll
@@ -246,31 +273,40 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
           St[nq][ks] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Ka[ks], Qb, St[nq][ks], 0, 0, 0);
       }
     }
-    if (LOGITS) {
+    if constexpr (LOGITS) {
+      if (A.logits_bf16) {
+        u32x2 w[NQ][2];
 #pragma unroll
-      for (int nq = 0; nq < NQ; ++nq) {
-        if (!q_ok[nq]) continue;
-        const size_t lrow = (((size_t)bt * A.Hq + q_head[nq]) * A.Tq + q_tq[nq]) * (size_t)A.N;
+        for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-          const int p = pos0 + 16 * ks + 4 * a;
-          const f32x4 sc = St[nq][ks] * A.scale;
-          if (A.logits_bf16) {
-            uint16_t *lp = static_cast<uint16_t *>(A.logits_out) + lrow;
+          for (int ks = 0; ks < 2; ++ks) {
+            const f32x4 sc = St[nq][ks] * A.scale;
             const bf16x2 lo = __builtin_convertvector(f32x2{sc[0], sc[1]}, bf16x2);   // round to nearest even
             const bf16x2 hi = __builtin_convertvector(f32x2{sc[2], sc[3]}, bf16x2);
-            const uint32_t w01 = __builtin_bit_cast(uint32_t, lo), w23 = __builtin_bit_cast(uint32_t, hi);
-            if (p + 3 < c && (A.N & 3) == 0) {
-              *reinterpret_cast<u32x2 *>(lp + p) = u32x2{w01, w23};
-            } else {
-              const uint16_t h4[4] = {(uint16_t)(w01 & 0xffffu), (uint16_t)(w01 >> 16), (uint16_t)(w23 & 0xffffu),
-                                      (uint16_t)(w23 >> 16)};
+            w[nq][ks] = u32x2{__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+          }
+        if (!second) {
 #pragma unroll
-              for (int r = 0; r < 4; ++r)
-                if (p + r < c) lp[p + r] = h4[r];
-            }
-          } else {
-            float *lp = static_cast<float *>(A.logits_out) + lrow;
+          for (int nq = 0; nq < NQ; ++nq) {
+            stash[nq][0] = w[nq][0];
+            stash[nq][1] = w[nq][1];
+          }
+          stash_pos = pos0;
+        } else {
+          if (stash_pos >= 0) store_bf16_tile(stash, stash_pos);
+          stash_pos = -1;
+          store_bf16_tile(w, pos0);
+        }
+      } else {
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) {
+          if (!q_ok[nq]) continue;
+          float *lp = static_cast<float *>(A.logits_out) +
+                      (((size_t)bt * A.Hq + q_head[nq]) * A.Tq + q_tq[nq]) * (size_t)A.N;
+#pragma unroll
+          for (int ks = 0; ks < 2; ++ks) {
+            const int p = pos0 + 16 * ks + 4 * a;
+            const f32x4 sc = St[nq][ks] * A.scale;
             if (p + 3 < c && (A.N & 3) == 0) {
               *reinterpret_cast<f32x4 *>(lp + p) = sc;
             } else {
@@ -332,42 +368,48 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
     }
   };
 
-  // ---- main loop over this wave's tiles: t_begin + wave, step 4
-  if (t_begin + wave < t_end) {   // wave-uniform; a wave without tiles touches no memory
+  // ---- main loop over this wave's tiles. Wave w takes tiles t_begin + w, + 4, + 8, ...; the
+  // kernels that dump the logits take pairs of neighbouring tiles instead (2w, 2w + 1, then + 8),
+  // so that one wave writes whole 128-byte lines of the dump.
+  constexpr int W = STS_WG_WAVES;
+  auto tile_of = [&](int v) -> int {
+    return LOGITS ? t_begin + (v >> 1) * (2 * W) + 2 * wave + (v & 1) : t_begin + wave + v * W;
+  };
+  if (tile_of(0) < t_end) {   // wave-uniform; a wave without tiles touches no memory
     chunk_t K0[8], V0[8], K1[8], V1[8];
     uint32_t m0, m1, mk_next, mk_new;
-    int t = t_begin + wave;
-    constexpr int W = STS_WG_WAVES;
-    // prologue: tile t in flight, tile t+W resolved, tile t+2W fetched
-    int raw_a = SPARSE ? rows_first : fetch_rows(t);
-    int raw_b = fetch_rows(t + W);
-    int x_a = resolve(raw_a, t, m0);
-    raw_a = fetch_rows(t + 2 * W);
-    int x_b = resolve(raw_b, t + W, mk_next);
-    issue_loads(x_a, t, K0, V0);
+    int v = 0;
+    // prologue: tile v in flight, tile v+1 resolved, tile v+2 fetched
+    int raw_a = SPARSE ? rows_first : fetch_rows(tile_of(0));
+    int raw_b = fetch_rows(tile_of(1));
+    int x_a = resolve(raw_a, tile_of(0), m0);
+    raw_a = fetch_rows(tile_of(2));
+    int x_b = resolve(raw_b, tile_of(1), mk_next);
+    issue_loads(x_a, tile_of(0), K0, V0);
     if (SPARSE) __builtin_amdgcn_sched_barrier(0);
     for (;;) {
-      raw_b = fetch_rows(t + 3 * W);
-      x_a = resolve(raw_a, t + 2 * W, mk_new);
+      raw_b = fetch_rows(tile_of(v + 3));
+      x_a = resolve(raw_a, tile_of(v + 2), mk_new);
       if (SPARSE) __builtin_amdgcn_sched_barrier(0);   // index traffic stays ahead of the K/V loads
-      issue_loads(x_b, t + W, K1, V1);
+      issue_loads(x_b, tile_of(v + 1), K1, V1);
       m1 = mk_next;
       if (SPARSE) __builtin_amdgcn_sched_barrier(0);   // loads are in flight before the tile is consumed
-      consume(t, K0, V0, m0);
+      consume(tile_of(v), K0, V0, m0, false);          // even step: first tile of a pair
       mk_next = mk_new;
-      t += W;
-      if (t >= t_end) break;
-      raw_a = fetch_rows(t + 3 * W);
-      x_b = resolve(raw_b, t + 2 * W, mk_new);
+      ++v;
+      if (tile_of(v) >= t_end) break;
+      raw_a = fetch_rows(tile_of(v + 3));
+      x_b = resolve(raw_b, tile_of(v + 2), mk_new);
       if (SPARSE) __builtin_amdgcn_sched_barrier(0);
-      issue_loads(x_a, t + W, K0, V0);
+      issue_loads(x_a, tile_of(v + 1), K0, V0);
       m0 = mk_next;
       if (SPARSE) __builtin_amdgcn_sched_barrier(0);
-      consume(t, K1, V1, m1);
+      consume(tile_of(v), K1, V1, m1, true);           // odd step: second tile of the pair
       mk_next = mk_new;
-      t += W;
-      if (t >= t_end) break;
+      ++v;
+      if (tile_of(v) >= t_end) break;
     }
+    if (LOGITS && stash_pos >= 0) store_bf16_tile(stash, stash_pos);   // a range that ends on a first tile
   }
 
   // ---- merge the 4 waves, write one partial per workgroup

@@ -14,9 +14,14 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def test_graph_replays_match_eager():
-    cfg = replace(CONFIGS["c1"], N=6000)          # not a multiple of the chunk or tile sizes
-    ws = [make_workload(cfg, seed=s) for s in (1, 2, 3)]
+@pytest.mark.parametrize("N,budget", [
+    (6000, 0.10),      # one workgroup per row; N is not a multiple of the chunk or tile sizes
+    (40000, 0.02),     # chunk-local top-k + pool
+    (40000, 0.25),     # histogram pipeline: clear kernel, published chunk counts
+])
+def test_graph_replays_match_eager(N, budget):
+    cfg = replace(CONFIGS["c1"], N=N)
+    ws = [make_workload(cfg, seed=s, budget=budget) for s in (1, 2, 3)]
     k = ws[0].k_budget
     hm = ws[0].head_map
     B, Hq, Tq, d = cfg.B, cfg.Hq, cfg.Tq, cfg.d

@@ -374,6 +374,13 @@ static sts_status enqueue_select(const sts_select_params *p, void *stream) {
   a.kind = p->kind; a.reduce = p->reduce; a.nchunks = pl.nchunks;
   for (int j = 0; j < p->Hd; ++j) a.kh[j] = p->k_head ? p->k_head[j] : p->k;
   a.clear_words = (pl.hist_bytes + pl.state_bytes + pl.chunk_bytes) / sizeof(uint32_t);
+  // The refinement histograms pay a digit search, a zeroed LDS histogram and a flush of up to
+  // 2048 global atomics per workgroup: with more than about a thousand workgroups it is cheaper
+  // to give each of them 2 or 4 consecutive chunks (1M-token rows: 22 -> 17.7 us per pass).
+  {
+    const size_t wgs = (size_t)p->B * p->Hd * (size_t)(pl.nchunks > 0 ? pl.nchunks : 1);
+    a.hist_cpw = wgs >= 4096 ? 4 : (wgs >= 2048 ? 2 : 1);
+  }
   // Test knob: STS_SELECT_SPIN_LIMIT bounds the polls of an earlier chunk's published counts
   // before the waiting workgroup recounts that chunk itself (0: one look, then recount).
   {

@@ -98,6 +98,7 @@ struct SelectArgs {
   int32_t pool_nchunks;       // ceil(N / pool_chunk)
   int32_t pool_pitch;         // min(k, pool_chunk)
   uint64_t clear_words;       // words to zero from `hist` on: histograms, state and chunk flags
+  int32_t hist_cpw;           // consecutive chunks per workgroup of the refinement histograms (1, 2 or 4)
   int32_t spin_limit;         // polls of an unpublished earlier chunk before it is recounted locally
   int32_t B, Hd, Tq, N, Hq, k, kind, reduce, nchunks;   // k: row pitch of indices = largest budget
   SelectTargets targets;

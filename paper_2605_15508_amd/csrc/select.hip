@@ -382,7 +382,8 @@ template <int PASS, bool VEC4>
 __global__ void __launch_bounds__(SEL_THREADS) select_hist_kernel(const SelectArgs A) {
   __shared__ uint32_t h[SEL_BINS];
   __shared__ uint32_t tmp[16];
-  const int row = blockIdx.y, chunk = blockIdx.x;
+  const int row = blockIdx.y;
+  const int chunk0 = blockIdx.x * A.hist_cpw;      // this workgroup takes hist_cpw consecutive chunks
   const int bt = row / A.Hd;
   const int nb = src_len(A, bt);
   const uint32_t c = (uint32_t)min(A.kh[row % A.Hd], nb);
@@ -390,9 +391,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_hist_kernel(const SelectAr
   uint32_t *st = A.state + (size_t)row * 8;
   const uint32_t *gh = A.hist + (size_t)row * 3 * SEL_BINS;
   const float *a = A.src + (size_t)row * A.srcN;
-  const int n0 = chunk * SEL_CHUNK;
-  const int n1 = min(min(n0 + SEL_CHUNK, A.srcN), nb);
-  // The chunk's loads do not depend on the digit search: issue them first so that their
+  // The first chunk's loads do not depend on the digit search: issue them first so that their
   // latency hides behind it. They are unconditional (a branch around a load makes the compiler
   // wait for it at the join): the address is clamped into the row, out-of-range quads are
   // ignored when counting.
@@ -401,7 +400,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_hist_kernel(const SelectAr
   if (VEC4) {
 #pragma unroll
     for (int i = 0; i < IT; ++i) {
-      const int n = n0 + (i * SEL_THREADS + threadIdx.x) * 4;
+      const int n = chunk0 * SEL_CHUNK + (i * SEL_THREADS + (int)threadIdx.x) * 4;
       x[i] = *reinterpret_cast<const f32x4 *>(a + min(n, A.srcN - 4));
     }
   }
@@ -410,7 +409,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_hist_kernel(const SelectAr
   if (PASS == 1) {
     uint32_t d0, k1;
     find_digit<(1 << SEL_BITS0)>(gh, c, tmp, d0, k1);
-    if (chunk == 0 && threadIdx.x == 0) { st[0] = d0; st[1] = k1; st[6] = c; }
+    if (chunk0 == 0 && threadIdx.x == 0) { st[0] = d0; st[1] = k1; st[6] = c; }
     prefix = d0;
     shift = SEL_BITS1 + SEL_BITS2;
     dmask = (1u << SEL_BITS1) - 1;
@@ -418,27 +417,39 @@ __global__ void __launch_bounds__(SEL_THREADS) select_hist_kernel(const SelectAr
     const uint32_t d0 = st[0], k1 = st[1];
     uint32_t d1, k2;
     find_digit<(1 << SEL_BITS1)>(gh + SEL_BINS, k1, tmp, d1, k2);
-    if (chunk == 0 && threadIdx.x == 0) { st[2] = d1; st[3] = k2; }
+    if (chunk0 == 0 && threadIdx.x == 0) { st[2] = d1; st[3] = k2; }
     prefix = (d0 << SEL_BITS1) | d1;
     shift = SEL_BITS2;
     dmask = (1u << SEL_BITS2) - 1;
   }
   const uint32_t dshift = (PASS == 1) ? SEL_BITS2 : 0;
   // (the barriers inside find_digit have published the zeroed histogram)
-  if (VEC4) {
+  for (int cc = 0; cc < A.hist_cpw; ++cc) {
+    const int n0 = (chunk0 + cc) * SEL_CHUNK;
+    const int n1 = min(min(n0 + SEL_CHUNK, A.srcN), nb);
+    if (n0 >= n1) break;
+    if (VEC4) {
+      if (cc > 0) {
 #pragma unroll
-    for (int i = 0; i < IT; ++i) {
-      const int n = n0 + (i * SEL_THREADS + threadIdx.x) * 4;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const uint32_t key = key_of(x[i][e]);
-        if (n + e < n1 && (key >> shift) == prefix) atomicAdd(&h[(key >> dshift) & dmask], 1u);
+        for (int i = 0; i < IT; ++i) {
+          const int n = n0 + (i * SEL_THREADS + (int)threadIdx.x) * 4;
+          x[i] = *reinterpret_cast<const f32x4 *>(a + min(n, A.srcN - 4));
+        }
       }
-    }
-  } else {
-    for (int n = n0 + threadIdx.x; n < n1; n += SEL_THREADS) {
-      const uint32_t key = key_of(a[n]);
-      if ((key >> shift) == prefix) atomicAdd(&h[(key >> dshift) & dmask], 1u);
+#pragma unroll
+      for (int i = 0; i < IT; ++i) {
+        const int n = n0 + (i * SEL_THREADS + (int)threadIdx.x) * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t key = key_of(x[i][e]);
+          if (n + e < n1 && (key >> shift) == prefix) atomicAdd(&h[(key >> dshift) & dmask], 1u);
+        }
+      }
+    } else {
+      for (int n = n0 + threadIdx.x; n < n1; n += SEL_THREADS) {
+        const uint32_t key = key_of(a[n]);
+        if ((key >> shift) == prefix) atomicAdd(&h[(key >> dshift) & dmask], 1u);
+      }
     }
   }
   __syncthreads();
@@ -1056,7 +1067,7 @@ hipError_t launch_select_agg(const SelectArgs &a, hipStream_t s) {
 
 hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t s) {
   if ((size_t)a.B * a.Hd == 0 || a.nchunks == 0) return hipSuccess;
-  const dim3 grid(a.nchunks, a.B * a.Hd), block(SEL_THREADS);
+  const dim3 grid((a.nchunks + a.hist_cpw - 1) / a.hist_cpw, a.B * a.Hd), block(SEL_THREADS);
   const bool v = src_vec_ok(a);
   if (pass == 1) {
     if (v) hipLaunchKernelGGL((select_hist_kernel<1, true>), grid, block, 0, s, a);

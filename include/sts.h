@@ -83,6 +83,11 @@ typedef enum { STS_BF16 = 0, STS_F32 = 1 } sts_dtype;
  * bound of every k_head[j]. Rows are padded with -1 from c on, counts hold c, so the lists
  * feed sts_sparse_attn unchanged (kmax = k, counts given).
  *
+ * The Hq target heads need not belong to one layer: every target head of any layer that maps
+ * to these draft heads can be listed (up to 256), the scores are then aggregated and ranked
+ * once per draft head, and each layer's sts_sparse_attn reads its heads' slice of `indices`
+ * in place (idx_stride_b / cnt_stride_b there).
+ *
  * Supported: 1 <= Tq <= 64, 1 <= Hq <= 256, 1 <= Hd <= 256, N < 2^31 - 2^16,
  * page_size <= 4096. Rows of size zero are handled (nothing is read; counts are 0).
  */
@@ -99,9 +104,9 @@ typedef struct {
   float *agg_out;           /* [dev] out [B,Hd,N] the aggregated scores A; may be NULL */
   int32_t kind;             /* sts_score_kind */
   int32_t reduce;           /* sts_reduce */
-  int32_t page_size;        /* 0 or 1: token granularity. p > 1: block granularity (see below) */
+  int32_t page_size;        /* 0 or 1: token granularity. p > 1: block granularity (see above) */
   const int32_t *k_head;    /* [host] optional [Hd]: budget of draft head j, 1 <= k_head[j] <= k
-                               (see below); NULL = k for every head */
+                               (see above); NULL = k for every head */
   int32_t scores_bf16;      /* 0: scores are fp32. Non-zero: scores are bf16 bit patterns, widened
                                exactly to fp32 before any arithmetic (half the bytes to read) */
   void *workspace;          /* [dev] 256-byte aligned scratch */

@@ -112,6 +112,9 @@ hipError_t launch_select_clear(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_agg(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_block(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_small(const SelectArgs &a, hipStream_t s);
+hipError_t launch_select_rank(const SelectArgs &a, hipStream_t s);
+bool select_aggblock_ok(const SelectArgs &a);
+hipError_t launch_select_aggblock(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_local(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_pool(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t s);

@@ -375,6 +375,63 @@ __global__ void __launch_bounds__(SEL_THREADS) select_block_vec_kernel(const Sel
   flush_hist<SEL_BINS>(gh, h);
 }
 
+// Aggregation and block sums in one pass (page % 4 == 0, page <= 256, N % page == 0, 16-byte
+// aligned scores): every lane aggregates 4 consecutive tokens in registers and the page/4
+// lanes of a block pass the running sum from left to right, exactly as above; the per-token
+// aggregate is stored only when the caller asks for it. With A.hist == nullptr no histogram is
+// built (the blocks are ranked out of LDS afterwards).
+__global__ void __launch_bounds__(SEL_THREADS) select_aggblock_kernel(const SelectArgs A) {
+  __shared__ uint32_t h[SEL_BINS];
+  const int row = blockIdx.y;
+  const int bt = row / A.Hd;
+  const int nb = row_len(A, bt);
+  const int nblk = (nb + A.page - 1) / A.page;
+  const bool want_hist = A.hist != nullptr;
+  if (want_hist) {
+    for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) h[i] = 0u;
+    __syncthreads();
+  }
+  const AggRow R = agg_row(A, row);
+  float *tok_out = A.agg ? A.agg + (size_t)row * A.N : nullptr;
+  float *out = A.blk + (size_t)row * A.srcN;
+  const int L = A.page >> 2;                       // lanes per block (1..64, power of two)
+  const int lane = threadIdx.x & 63;
+  const int pos_in_blk = lane & (L - 1);
+  for (int n = blockIdx.x * SEL_CHUNK + threadIdx.x * 4; n < min((blockIdx.x + 1) * SEL_CHUNK, A.N);
+       n += SEL_THREADS * 4) {
+    const f32x4 x = agg_quad(R, n);
+    if (tok_out) *reinterpret_cast<f32x4 *>(tok_out + n) = x;
+    float run = 0.f;
+    bool have = false;                             // whether `run` holds at least one term
+    for (int s = 0; s < L; ++s) {
+      if (pos_in_blk == s) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (n + e < nb) {
+            run = have ? run + x[e] : x[e];
+            have = true;
+          }
+      }
+      if (s + 1 < L) {
+        const float up = __shfl_up(run, 1, 64);
+        const int hup = __shfl_up((int)have, 1, 64);
+        if (pos_in_blk == s + 1) {
+          run = up;
+          have = hup != 0;
+        }
+      }
+    }
+    if (pos_in_blk == L - 1) {
+      const int m = n / A.page;
+      out[m] = run;                                // blocks past the valid length hold 0
+      if (want_hist && m < nblk) atomicAdd(&h[key_of(run) >> (32 - SEL_BITS0)], 1u);
+    }
+  }
+  if (!want_hist) return;
+  __syncthreads();
+  flush_hist<SEL_BINS>(A.hist + (size_t)row * 3 * SEL_BINS, h);
+}
+
 // ------------------------------------------------------------------ refinement histograms
 // PASS 1: digit 1 (bits 20..10) of keys whose digit 0 matches; PASS 2: digit 2 (bits 9..0)
 // of keys whose digits 0 and 1 match.
@@ -733,26 +790,35 @@ __device__ __forceinline__ void write_tail(const SelectArgs &A, int bt, int j, u
 // one 1024-thread workgroup per (batch, draft head) does everything in a single launch:
 // aggregate (same fp32 order), three digit histograms over the LDS-resident keys, ordered
 // compaction and the copies to the target heads. No global histograms, nothing to clear.
-template <bool VEC4>
+// FROM_SRC: the scores to rank are already there (A.src, row pitch A.srcN: the block sums of
+// block-granular selection) and only have to be loaded.
+template <bool VEC4, bool FROM_SRC>
 __global__ void __launch_bounds__(SMALL_THREADS) select_small_kernel(const SelectArgs A) {
   __shared__ uint32_t keys[SEL_SMALL_N + SEL_SMALL_N / 32];
   __shared__ uint32_t h[SEL_BINS];
   __shared__ uint32_t tmp[SMALL_THREADS / 64 + 2];
   const int row = blockIdx.x;
   const int bt = row / A.Hd, j = row % A.Hd;
-  const int nb = row_len(A, bt);
+  const int nb = FROM_SRC ? src_len(A, bt) : row_len(A, bt);
   const uint32_t c = (uint32_t)min(A.kh[j], nb);
   const int t0 = A.targets.off[j], t1 = A.targets.off[j + 1];
   const int tid = threadIdx.x;
   write_tail<SMALL_THREADS>(A, bt, j, c);
-  const bool want_agg = A.agg != nullptr;
+  const bool want_agg = !FROM_SRC && A.agg != nullptr;
   if ((c == 0 || t0 == t1) && !want_agg) return;
 
   for (int i = tid; i < SEL_BINS; i += SMALL_THREADS) h[i] = 0u;
   __syncthreads();
   const AggRow R = agg_row(A, row);
   float *out = want_agg ? A.agg + (size_t)row * A.N : nullptr;
-  if (VEC4) {
+  if (FROM_SRC) {
+    const float *src = A.src + (size_t)row * A.srcN;
+    for (int n = tid; n < nb; n += SMALL_THREADS) {
+      const uint32_t key = key_of(src[n]);
+      keys[small_slot(n)] = key;
+      atomicAdd(&h[key >> (32 - SEL_BITS0)], 1u);
+    }
+  } else if (VEC4) {
     for (int n = tid * 4; n < A.N; n += SMALL_THREADS * 4) {
       const f32x4 acc = agg_quad(R, n);
       if (want_agg) *reinterpret_cast<f32x4 *>(out + n) = acc;
@@ -1010,9 +1076,30 @@ hipError_t launch_select_small(const SelectArgs &a, hipStream_t s) {
   const bool v = (a.N % 4) == 0 && (reinterpret_cast<uintptr_t>(a.scores) % 16) == 0 &&
                  (a.agg == nullptr || (reinterpret_cast<uintptr_t>(a.agg) % 16) == 0);
   if (v)
-    hipLaunchKernelGGL(select_small_kernel<true>, grid, block, 0, s, a);
+    hipLaunchKernelGGL((select_small_kernel<true, false>), grid, block, 0, s, a);
   else
-    hipLaunchKernelGGL(select_small_kernel<false>, grid, block, 0, s, a);
+    hipLaunchKernelGGL((select_small_kernel<false, false>), grid, block, 0, s, a);
+  return hipGetLastError();
+}
+
+// ranks the rows of a.src (up to SEL_SMALL_N entries each) out of LDS
+hipError_t launch_select_rank(const SelectArgs &a, hipStream_t s) {
+  if ((size_t)a.B * a.Hd == 0) return hipSuccess;
+  hipLaunchKernelGGL((select_small_kernel<false, true>), dim3(a.B * a.Hd), dim3(SMALL_THREADS), 0, s, a);
+  return hipGetLastError();
+}
+
+bool select_aggblock_ok(const SelectArgs &a) {
+  const bool pow2 = (a.page & (a.page - 1)) == 0;
+  return pow2 && a.page >= 4 && a.page <= 256 && (a.N % a.page) == 0 &&
+         (reinterpret_cast<uintptr_t>(a.scores) % 16) == 0 &&
+         (a.agg == nullptr || (reinterpret_cast<uintptr_t>(a.agg) % 16) == 0);
+}
+
+hipError_t launch_select_aggblock(const SelectArgs &a, hipStream_t s) {
+  if ((size_t)a.B * a.Hd == 0 || a.N == 0) return hipSuccess;
+  const dim3 grid((a.N + SEL_CHUNK - 1) / SEL_CHUNK, a.B * a.Hd), block(SEL_THREADS);
+  hipLaunchKernelGGL(select_aggblock_kernel, grid, block, 0, s, a);
   return hipGetLastError();
 }
 

@@ -155,3 +155,55 @@ def test_page_arguments_are_validated():
         sts.sts_sparse_attn(q.to(DEV), k.to(DEV), v.to(DEV), idx, 0.09, page_size=3)
     with pytest.raises(sts.StsError):
         sts.sts_sparse_attn(q.to(DEV), k.to(DEV), v.to(DEV), idx, 0.09, page_size=64)
+
+
+@pytest.mark.parametrize("page,N,k,kind,bf16", [
+    (8, 65536, 700, 0, False),       # 8192 blocks per row: fused aggregation + ranking out of LDS
+    (16, 262144, 1600, 0, False),    # 16384 blocks per row: the limit of that path
+    (8, 262144, 3000, 0, False),     # 32768 blocks per row: fused aggregation + histogram pipeline
+    (8, 65536, 700, 1, True),        # scaled logits stored as bf16
+    (8, 65528, 700, 0, False),       # N % page == 0 but a ragged last chunk
+    (8, 65532, 700, 0, False),       # N % page != 0: separate aggregation and block kernels
+])
+def test_block_select_fused_paths(page, N, k, kind, bf16):
+    """Block-granular selection through its launch sequences, with and without the per-token
+    aggregate on request, per-head budgets and ragged lengths; stage-wise against the oracle."""
+    from test_gpu_select import launched
+    g = torch.Generator().manual_seed(N + page + kind)
+    B, Hd, Tq, Hq = 2, 3, 2, 6
+    logits = torch.randn(B, Hd, Tq, N, generator=g) * 2
+    if bf16:
+        logits = logits.to(torch.bfloat16).float()
+    lse = torch.logsumexp(logits, dim=-1)
+    scores = logits if kind == 1 else torch.softmax(logits, dim=-1)
+    sd = (scores.to(torch.bfloat16) if bf16 else scores).to(DEV)
+    hm = [2, 0, 0, 1, 2, 1]
+    kh = [k, 3, max(1, k // 2)]
+    lens = torch.tensor([N, N // 2 + 3], dtype=torch.int32)
+    got = {}
+    def call(want_agg):
+        got["r"] = sts.sts_select(sd, hm, k, lse=lse.to(DEV) if kind == 1 else None, seq_lens=lens.to(DEV), kind=kind,
+                                  want_agg=want_agg, page_size=page, k_head=kh)
+    kinds = launched(lambda: call(True))
+    nblk = (N + page - 1) // page
+    if N % page:
+        assert "select_block" in kinds
+    elif nblk <= 16384:
+        assert kinds == {"select_agg", "select_small"}
+    else:
+        assert kinds == {"select_clear", "select_agg", "select_hist", "select_write"}
+    idx, cnt, agg = got["r"]
+    agg = agg.cpu().numpy()
+    o_agg = oracle.aggregate(scores.numpy(), lse.numpy() if kind == 1 else None, kind, 0)
+    if kind == 0:
+        np.testing.assert_array_equal(agg.view(np.uint32), o_agg.view(np.uint32))
+    else:
+        np.testing.assert_allclose(agg, o_agg, rtol=1e-5, atol=1e-12)
+    blk = oracle.block_scores(agg, page, lens.numpy())
+    l2 = ((lens.numpy().astype(np.int64) + page - 1) // page).astype(np.int32)
+    sel, c = oracle.select_per_head(blk, k, kh, l2)
+    o_idx, o_cnt = oracle.remap(sel, c, np.asarray(hm, np.int32))
+    np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
+    np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
+    call(False)                                            # the lists do not depend on the optional output
+    assert torch.equal(got["r"][0], idx) and torch.equal(got["r"][1], cnt)

@@ -54,6 +54,10 @@ def parse_args():
                     help="heavy tokens scattered over the context (worst case for the gather) or clustered at its end")
     ap.add_argument("--scores", default="fp32", choices=["fp32", "bf16"],
                     help="type of the draft scores read by sts_select (and of the logits dump of the draft layer)")
+    ap.add_argument("--draft-scores", default="dump", choices=["dump", "sum"],
+                    help="draft-layer configuration: the draft attention dumps its logits and sts_select aggregates "
+                         "them (dump), or it sums the attention weights over the query block itself in a second "
+                         "pass over K and sts_select ranks that aggregate (sum)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (scales rocprofv3 --pmc byte counters)")
     return ap.parse_args()
@@ -200,18 +204,26 @@ def main():
     cnt = torch.empty(B, Hq, dtype=torch.int32, device=dev)
     out_s = torch.empty(B, Tq, Hq, d, dtype=torch.bfloat16, device=dev)
     out_d = torch.empty_like(out_s)
-    d_out = d_lse = d_logits = None
+    d_out = d_lse = d_logits = d_sum = None
     if draft is not None:
         d_out = torch.empty(B, Tq, Hd, cfg.draft_d, dtype=torch.bfloat16, device=dev)
         d_lse = torch.empty(B, Hd, Tq, dtype=torch.float32, device=dev)
-        d_logits = torch.empty(B, Hd, Tq, N, dtype=torch.bfloat16 if args.scores == "bf16" else torch.float32, device=dev)
+        if args.draft_scores == "sum":
+            d_sum = torch.empty(B, Hd, N, dtype=torch.float32, device=dev)
+        else:
+            d_logits = torch.empty(B, Hd, Tq, N, dtype=torch.bfloat16 if args.scores == "bf16" else torch.float32, device=dev)
     elif args.scores == "bf16":
         w.scores = w.scores.to(torch.bfloat16)
 
     def step(ev=None, layer=0):
         lk, lv = layers[layer]
         if ev: ev[0].record()
-        if draft is not None:
+        if draft is not None and d_sum is not None:
+            sts.sts_dense_attn(draft["q"], draft["k"], draft["v"], draft["scale"], out=d_out,
+                               lse_out=d_lse, weights_sum_out=d_sum)
+            if ev: ev[1].record()
+            sts.sts_select(d_sum.view(B, Hd, 1, N), w.head_map, kb, out=(idx, cnt), page_size=page)
+        elif draft is not None:
             sts.sts_dense_attn(draft["q"], draft["k"], draft["v"], draft["scale"], out=d_out,
                                lse_out=d_lse, logits_out=d_logits)
             if ev: ev[1].record()
@@ -308,7 +320,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": workload, "context": N, "batch": B, "budget_tokens": kb * page, "page_size": page, "paged_kv": bool(args.paged),
                    "layers": L, "cache": "cold: every pass reads KV that has left the caches" if (L > 1 or kv_bytes > (256 << 20)) else "warm", "head_map": "t*Hd//Hq" if args.head_map == "default" else "seeded random", "gain": cfg.gain, "heavy_positions": args.positions, "scores": args.scores, "step": ("%d layers x (" % L if L > 1 else "(") + "select + sparse_attn" + ("" if args.no_dense else " + dense_attn")
-                   + (" + draft dense attn with logits dump" if draft is not None else "") + ")"},
+                   + ((" + draft dense attn with logits dump" if d_sum is None else " + draft dense attn with summed weights") if draft is not None else "") + ")"},
         "sparse_attn_us": {"mean": round(sparse_us[0], 2), "median": round(sparse_us[1], 2), "min": round(sparse_us[2], 2), "p10": round(sparse_us[3], 2), "p90": round(sparse_us[4], 2)},
         "dense_attn_us": None if args.no_dense else {"mean": round(dense_us[0], 2), "median": round(dense_us[1], 2), "min": round(dense_us[2], 2), "p10": round(dense_us[3], 2), "p90": round(dense_us[4], 2)},
         "select_us": {"mean": round(select_us[0], 2), "median": round(select_us[1], 2), "min": round(select_us[2], 2), "p10": round(select_us[3], 2), "p90": round(select_us[4], 2)},
@@ -332,7 +344,8 @@ def main():
     agg_n, agg_ms = prof["select_agg"]
     if agg_n:
         # the one HBM-bound kernel of the selection: reads Tq rows of scores, writes one row of A
-        src_rows = B * Hd * (Tq * N * (2 if args.scores == "bf16" else 4) + N * 4)
+        tq_in = 1 if d_sum is not None else Tq
+        src_rows = B * Hd * (tq_in * N * (2 if args.scores == "bf16" else 4) + N * 4)
         agg_us = agg_ms * 1e3 / agg_n
         result["roofline_select_agg"] = {"bound": "hbm", "achieved": round(src_rows / (agg_us * 1e-6) / 1e9, 1),
                                          "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -344,7 +357,10 @@ def main():
         result["roofline_dense"] = {"achieved": round(b_dense / (dsplit_ms * 1e-3 / dsplit_n) / 1e9, 1),
                                     "frac": round(b_dense / (dsplit_ms * 1e-3 / dsplit_n) / 1e9 / HBM_PEAK_GBS, 4)}
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, idx, cnt, page=page, scores=d_logits, lse=d_lse)
+        if d_sum is not None:
+            result["cpu_baseline"] = cpu_baseline(w, idx, cnt, page=page, scores=d_sum.view(B, Hd, 1, N), lse=None)
+        else:
+            result["cpu_baseline"] = cpu_baseline(w, idx, cnt, page=page, scores=d_logits, lse=d_lse)
     print(json.dumps(result))
 
 

@@ -21,12 +21,13 @@
  *  - Results are deterministic run to run: the split count depends only on the shape and the
  *    partial results are combined in a fixed order; selection uses integer arithmetic only.
  *  - bf16 tensors are raw 16-bit patterns. All accumulation is fp32.
- *  - Two environment variables are read per call, for tuning and tests only:
+ *  - Three environment variables are read per call, for tuning and tests only:
  *    STS_ATTN_WGS_PER_CU (target workgroups per compute unit when the context is split; it
  *    changes the split count, hence the attention workspace size and the rounding of the
  *    output, so keep it constant within a process) and STS_SELECT_SPIN_LIMIT (polls of
  *    another workgroup's published chunk counts before they are recomputed locally; default
- *    256; no effect on results).
+ *    256; no effect on results) and STS_PROBSUM_WGS_PER_CU (workgroups per compute unit of the
+ *    pass that writes weights_sum_out; no effect on results).
  */
 #ifndef STS_H
 #define STS_H
@@ -145,6 +146,14 @@ typedef struct {
  * out and lse_out cover the whole verification attention. Without them the caller merges that
  * part itself using lse_out.
  *
+ * Summed attention weights (paper Section 4.3: one mask per speculative batch, from the draft's
+ * attention over the whole query block; Section 5: the draft layer hands its scores to the
+ * selection). With weights_sum_out the dense call makes a second pass over K once the row
+ * normalisers are known and writes A[b,t,n] = sum_i exp(s[i,n] - lse[i]) -- bit for bit what
+ * logits_out + lse_out fed to sts_select (kind LOGITS_LSE, reduce SUM) aggregate to -- so the
+ * Tq times larger logits never reach memory. Feed it to sts_select as kind PROBS with Tq = 1.
+ * Contiguous caches only (no block_table, kv_stride_n <= 2^26), without k_new.
+ *
  * Supported: d in {64,128}; Hq % Hkv == 0; Hq/Hkv <= 16; 1 <= Tq <= 16; Hq <= 256;
  * kv strides with kv_stride_n*2 bytes a multiple of 16 and bases 16-byte aligned.
  */
@@ -179,6 +188,9 @@ typedef struct {
                                [:, l*Hq:(l+1)*Hq, :] of one sts_select over the target heads of several
                                layers that share draft heads (the aggregation is then paid once) */
   int64_t cnt_stride_b;     /* same for `counts`; 0 = Hq */
+  float *weights_sum_out;   /* [dev] dense only, optional [B,Hq,N] fp32: the attention weights summed over
+                               the Tq query rows, sum_i exp(s[i,n] - lse[i]), rows added in order; 0 at
+                               n >= N_b (see below) */
   void *workspace;          /* [dev] 256-byte aligned scratch */
   size_t workspace_bytes;
 } sts_attn_params;
@@ -241,7 +253,8 @@ typedef enum {
   STS_K_SELECT_SMALL = 10, /* whole selection in one workgroup per row (rows up to 32768 tokens) */
   STS_K_SELECT_LOCAL = 11, /* small budgets: aggregation + top-k inside each 8192-token chunk */
   STS_K_SELECT_POOL = 12,  /* small budgets: ranking of the chunks' winners, one workgroup per row */
-  STS_K_COUNT_ = 13
+  STS_K_ATTN_PROBSUM = 13, /* dense second pass over K: attention weights summed over the query block */
+  STS_K_COUNT_ = 14
 } sts_kernel_kind;
 #define STS_PROF_MAX 4096
 

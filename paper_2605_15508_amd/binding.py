@@ -16,7 +16,8 @@ STS_REDUCE_SUM, STS_REDUCE_MAX = 0, 1
 STS_BF16, STS_F32 = 0, 1
 KERNEL_KINDS = {"select_clear": 0, "select_agg": 1, "select_hist": 2, "select_count": 3,
                 "select_write": 4, "attn_sparse": 5, "attn_dense": 6, "attn_combine": 7, "select_block": 8,
-                "headmap": 9, "select_small": 10, "select_local": 11, "select_pool": 12}
+                "headmap": 9, "select_small": 10, "select_local": 11, "select_pool": 12,
+                "attn_probsum": 13}
 
 # every symbol include/sts.h declares
 EXPORTS = ["sts_select_workspace_bytes", "sts_attn_workspace_bytes", "sts_select", "sts_sparse_attn",
@@ -52,6 +53,7 @@ class AttnParams(ctypes.Structure):
                 ("num_pages", ctypes.c_int32), ("kv_stride_page", ctypes.c_int64),
                 ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p), ("causal", ctypes.c_int32),
                 ("logits_bf16", ctypes.c_int32), ("idx_stride_b", ctypes.c_int64), ("cnt_stride_b", ctypes.c_int64),
+                ("weights_sum_out", ctypes.c_void_p),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
 
 
@@ -247,7 +249,7 @@ def _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse_o
 def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=None, seq_lens=None,
               out=None, out_dtype=None, want_lse=True, want_logits=False, workspace=None,
               lse_out=None, logits_out=None, page_size=1, block_table=None, N=None,
-              k_new=None, v_new=None, causal=True):
+              k_new=None, v_new=None, causal=True, weights_sum_out=None):
     import torch
 
     lib = load_library()
@@ -277,6 +279,15 @@ def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=
     ws = workspace if workspace is not None else _workspace("attn", need, dev)
     p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()
     p.logits_bf16 = 1 if (logits is not None and logits.dtype == torch.bfloat16) else 0
+    if weights_sum_out is not None:
+        w = weights_sum_out
+        assert not sparse and w.is_cuda and w.dtype == torch.float32 and w.is_contiguous()
+        assert tuple(w.shape) == (B, Hq, N)
+        p.weights_sum_out = w.data_ptr()
+        need = lib.sts_attn_workspace_bytes(ctypes.byref(p), 0)
+        if workspace is None:
+            ws = _workspace("attn", need, dev)
+            p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()
     fn = lib.sts_sparse_attn if sparse else lib.sts_dense_attn
     _check(fn(ctypes.byref(p), _stream()), "sts_sparse_attn" if sparse else "sts_dense_attn")
     return out, lse, logits
@@ -296,14 +307,17 @@ def sts_sparse_attn(q, k, v, indices, scale, counts=None, head_map=None, out=Non
 
 def sts_dense_attn(q, k, v, scale, seq_lens=None, out=None, out_dtype=None, want_lse=True,
                    want_logits=False, workspace=None, lse_out=None, logits_out=None, page_size=1,
-                   block_table=None, N=None, k_new=None, v_new=None, causal=True):
+                   block_table=None, N=None, k_new=None, v_new=None, causal=True, weights_sum_out=None):
     """Dense attention of the same kernel family -> (out, lse, logits [B,Hq,Tq,N] or None).
     want_logits: True (fp32 dump) or a torch dtype (float32 / bfloat16); logits_out: a buffer of
-    either type."""
+    either type. weights_sum_out: an fp32 [B,Hq,N] buffer that receives the attention weights
+    summed over the Tq query rows (what sts_select aggregates the dump to; feed it to sts_select
+    as probabilities with Tq = 1)."""
     return _run_attn(False, q, k, v, scale, seq_lens=seq_lens, out=out, out_dtype=out_dtype,
                      want_lse=want_lse, want_logits=want_logits, workspace=workspace,
                      lse_out=lse_out, logits_out=logits_out, page_size=page_size,
-                     block_table=block_table, N=N, k_new=k_new, v_new=v_new, causal=causal)
+                     block_table=block_table, N=N, k_new=k_new, v_new=v_new, causal=causal,
+                     weights_sum_out=weights_sum_out)
 
 
 def sts_head_map(a_d, a_t, k: int, workspace=None):

@@ -153,6 +153,8 @@ sts_status plan_attn(const sts_attn_params *p, int sparse, AttnPlan &pl) {
   if ((size_t)units_total * (size_t)S > 0x7fffffffull) return STS_EUNSUPPORTED;
   pl.part_o_bytes = align256(parts * (size_t)pl.nq * 16 * p->d * sizeof(float));
   pl.part_ml_bytes = align256(parts * (size_t)pl.nq * 16 * 2 * sizeof(float));
+  pl.lse_bytes = (!sparse && p->weights_sum_out && !p->lse_out)
+                     ? align256((size_t)p->B * p->Hq * p->Tq * sizeof(float)) : 0;
   return STS_OK;
 }
 
@@ -165,9 +167,15 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
   if (p->N > 0 && (!p->k || !p->v)) return STS_EINVAL;
   if (sparse && p->kmax > 0 && !p->indices) return STS_EINVAL;
   if (sparse && p->kmax > 0 && p->N == 0) return STS_EINVAL;
-  const size_t need = pl.part_o_bytes + pl.part_ml_bytes;
+  const size_t need = pl.part_o_bytes + pl.part_ml_bytes + pl.lse_bytes;
   if (!p->workspace || p->workspace_bytes < need) return STS_EWORKSPACE;
   if (reinterpret_cast<uintptr_t>(p->workspace) % 256 != 0) return STS_EWORKSPACE;
+  const bool want_sum = !sparse && p->weights_sum_out != nullptr;
+  // (the second pass adds a 32-bit lane offset of up to 12 rows to a 64-bit tile address)
+  if (want_sum && (p->block_table || p->k_new || page_of(p) != 1 ||
+                   reinterpret_cast<uintptr_t>(p->weights_sum_out) % 4 != 0 ||
+                   p->kv_stride_n < 0 || p->kv_stride_n > (int64_t)1 << 26))
+    return STS_EUNSUPPORTED;
   if (reinterpret_cast<uintptr_t>(p->k) % 16 != 0 || reinterpret_cast<uintptr_t>(p->v) % 16 != 0 ||
       reinterpret_cast<uintptr_t>(p->q) % 16 != 0 || reinterpret_cast<uintptr_t>(p->out) % 16 != 0 ||
       reinterpret_cast<uintptr_t>(p->logits_out) % 16 != 0)
@@ -209,15 +217,49 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
   a.logits_bf16 = p->logits_bf16 ? 1 : 0;
   a.out = p->out;
   a.lse_out = p->lse_out;
+  if (want_sum && !a.lse_out)   // the second pass needs the row normalisers
+    a.lse_out = reinterpret_cast<float *>(static_cast<unsigned char *>(p->workspace) + pl.part_o_bytes + pl.part_ml_bytes);
   a.out_dtype = p->out_dtype;
   a.units = pl.units;
 
   hipError_t rc = run_kernel(sparse ? STS_K_ATTN_SPARSE : STS_K_ATTN_DENSE, s,
                              [&] { return launch_attn_split(a, p->d, pl.nq, sparse != 0, s); });
   if (rc != hipSuccess) return STS_EHIP;
-  if (a.direct) return STS_OK;
-  rc = run_kernel(STS_K_ATTN_COMBINE, s, [&] { return launch_attn_combine(a, p->d, pl.nq, s); });
-  return rc == hipSuccess ? STS_OK : STS_EHIP;
+  if (!a.direct) {
+    rc = run_kernel(STS_K_ATTN_COMBINE, s, [&] { return launch_attn_combine(a, p->d, pl.nq, s); });
+    if (rc != hipSuccess) return STS_EHIP;
+  }
+  if (want_sum && p->N > 0) {
+    // Second pass over K. Heads of a KV group share a workgroup in sets of up to 64 rows; the key
+    // range is cut so that the grid is one full residency of the chip (a second, partly filled
+    // round would cost more than finer balancing gains), each wave keeping at least 4 tiles.
+    a.agg_out = p->weights_sum_out;
+    int tp = 1;
+    while (tp < p->Tq) tp *= 2;      // a head's rows fill an aligned power-of-two run of MFMA columns
+    int hs = 64 / tp;
+    if (hs > a.G) hs = a.G;
+    a.ps_tp = tp;
+    a.ps_heads = hs;
+    a.ps_sets = (a.G + hs - 1) / hs;
+    const int rows = hs * tp;
+    const int nq = rows <= 16 ? 1 : (rows <= 32 ? 2 : 4);
+    const int64_t tiles = ((int64_t)p->N + STS_TILE_KEYS - 1) / STS_TILE_KEYS;
+    const int64_t groups = (int64_t)p->B * p->Hkv * a.ps_sets;
+    double per_cu = attn_probsum_wgs_per_cu(p->d, nq);
+    if (const char *e = getenv("STS_PROBSUM_WGS_PER_CU")) {   // tuning knob
+      const double f = atof(e);
+      if (f > 0.0) per_cu = f;
+    }
+    int64_t S = (int64_t)(cu_count() * per_cu) / groups;
+    const int64_t s_cap = (tiles + 4 * STS_WG_WAVES - 1) / (4 * STS_WG_WAVES);
+    if (S > s_cap) S = s_cap;
+    if (S < 1) S = 1;
+    if (groups * S > 0x7fffffffll) return STS_EUNSUPPORTED;
+    a.ps_splits = (int)S;
+    rc = run_kernel(STS_K_ATTN_PROBSUM, s, [&] { return launch_attn_probsum(a, p->d, nq, s); });
+    if (rc != hipSuccess) return STS_EHIP;
+  }
+  return STS_OK;
 }
 
 // --------------------------------------------------------------------------- select plan
@@ -299,7 +341,7 @@ extern "C" {
 size_t sts_attn_workspace_bytes(const sts_attn_params *p, int sparse) {
   AttnPlan pl;
   if (plan_attn(p, sparse, pl) != STS_OK) return 0;
-  const size_t n = pl.part_o_bytes + pl.part_ml_bytes;
+  const size_t n = pl.part_o_bytes + pl.part_ml_bytes + pl.lse_bytes;
   return n ? n : 256;
 }
 
@@ -434,6 +476,14 @@ static sts_status enqueue_select(const sts_select_params *p, void *stream) {
     if (rc != hipSuccess) return STS_EHIP;
     rc = run_kernel(STS_K_SELECT_SMALL, s, [&] { return launch_select_rank(f, s); });
     return rc == hipSuccess ? STS_OK : STS_EHIP;
+  }
+  // One fp32 probability row per head (an aggregate computed elsewhere, e.g. the draft layer's
+  // summed attention weights): the aggregate is the input itself, so the first pass only builds
+  // the first-digit histogram and the later passes read the caller's tensor.
+  if (pl.page == 1 && p->Tq == 1 && p->kind == STS_SCORES_PROBS && !p->scores_bf16 && !p->agg_out) {
+    a.agg = const_cast<float *>(static_cast<const float *>(p->scores));
+    a.src = a.agg;
+    a.agg_is_input = 1;
   }
   if (pl.nchunks > 0) {
     rc = run_kernel(STS_K_SELECT_CLEAR, s, [&] { return launch_select_clear(a, s); });
@@ -571,7 +621,7 @@ const char *sts_strerror(sts_status s) {
   return "unknown status";
 }
 
-int sts_version(void) { return 107; }
+int sts_version(void) { return 108; }
 
 void sts_prof_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);

@@ -28,6 +28,9 @@
 // buffer), indices one tile further ahead.
 #include "common.h"
 
+#include <mutex>
+#include <type_traits>
+
 namespace {
 
 template <int D> struct Chunk;
@@ -683,6 +686,243 @@ hipError_t launch_split_d(const AttnArgs &a, int nq, bool sparse, hipStream_t s)
   return hipErrorInvalidValue;
 }
 
+// -------------------------------------------------- summed attention weights of a query block
+// A second pass over K for the draft layer: agg[b, head, n] = sum over the Tq query rows, in row
+// order, of exp(s[row, n] - lse[row]) -- the aggregate sts_select ranks (paper Section 4.3: one
+// mask per speculative batch) -- without writing the Tq times larger logits to memory and
+// reading them back. s comes from the same MFMA instruction on the same operands as in the
+// logits dump (operands swapped, which transposes the result tile) and goes through the same
+// fp32 arithmetic, so the result is bit for bit what the dump followed by the selection's own
+// aggregation gives. One workgroup of 4 waves per (batch, KV head, set of heads, piece of the key
+// range); dense, contiguous cache.
+//
+// Layout: S = Q K^T leaves lane (a, b) with rows 4a..4a+3 of a 16-row query tile for key b, so
+// with Tq padded to a power of two Tp (padding rows weigh +0) a head's rows are registers of one
+// lane (Tp <= 4) or of Tp/4 lanes 16 apart (Tp = 8, 16). The sum over rows is a left-to-right
+// fold: inside the lane, then handed on from lane to lane. The kernel is bound by vector ALU
+// work per tile, not by memory, which is why the fold is arranged to take few instructions.
+template <int TP>
+__device__ __forceinline__ void fold_rows(const float (&p)[4], float (&s)[4], int a) {
+  constexpr int RPL = TP < 4 ? TP : 4;       // rows of one head held by a lane
+  constexpr int HPL = 4 / RPL;               // heads per lane
+  constexpr int CH = TP > 4 ? TP / 4 : 1;    // lanes a head's rows are spread over
+#pragma unroll
+  for (int j = 0; j < HPL; ++j) {
+    s[j] = p[j * RPL];
+#pragma unroll
+    for (int i = 1; i < RPL; ++i) s[j] = s[j] + p[j * RPL + i];
+  }
+  if constexpr (CH > 1) {
+    const int from = (((int)threadIdx.x - 16) & 63) << 2;   // the lane holding the four rows before mine
+#pragma unroll
+    for (int step = 1; step < CH; ++step) {
+      float t = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(from, __builtin_bit_cast(int, s[0])));
+#pragma unroll
+      for (int i = 0; i < 4; ++i) t = t + p[i];
+      s[0] = ((a & (CH - 1)) == step) ? t : s[0];
+    }
+  }
+}
+
+template <int D, int NQ>
+__global__ void __launch_bounds__(64 * STS_WG_WAVES) attn_probsum_kernel(const AttnArgs A) {
+  typedef typename Chunk<D>::type chunk_t;
+  constexpr int KK = D / 32;
+  constexpr int CHB = D / 8;
+  constexpr int ROWB = D * 2;
+  constexpr int NSLOT = D / 8;
+  constexpr int KTILE_BYTES = STS_TILE_KEYS * ROWB;
+  constexpr int W = STS_WG_WAVES;
+  constexpr int PS_STAGES = 3;
+  __shared__ __attribute__((aligned(16))) unsigned char ldsK_all[W * KTILE_BYTES];
+  __shared__ __attribute__((aligned(16))) u32x4 ldsQ[NQ * KK * 64];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tile addresses stay wave-uniform
+  const int a = lane >> 4, b = lane & 15;
+  const int S = A.ps_splits;
+  const int split = blockIdx.x % S;
+  const int set = (blockIdx.x / S) % A.ps_sets;
+  const int g = (blockIdx.x / (S * A.ps_sets)) % A.Hkv;
+  const int bt = blockIdx.x / (S * A.ps_sets * A.Hkv);
+  const int Tp = A.ps_tp;                                // Tq rounded up to a power of two, <= 16
+  const int tp_shift = 31 - __builtin_clz(Tp);
+  const int h0 = set * A.ps_heads;                       // first head of the set handled here
+  const int nh = min(A.ps_heads, A.G - h0);
+  int c = A.seq_lens ? A.seq_lens[bt] : A.N;
+  c = min(max(c, 0), A.N);
+  const int tiles_all = (A.N + STS_TILE_KEYS - 1) / STS_TILE_KEYS;   // every key position gets a value
+  const int tps = (tiles_all + S - 1) / S;
+  const int t_begin = split * tps;
+  const int t_end = min(t_begin + tps, tiles_all);
+
+  // Q tiles into LDS in the MFMA operand layout (lane (a, b): row b, channels 8(a + 4kk)..)
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq) {
+    const int r = nq * 16 + b;
+    const int hsel = r >> tp_shift, tq = r & (Tp - 1);
+    const bool ok = hsel < nh && tq < A.Tq;
+    const uint16_t *qp = A.q + (((size_t)bt * A.Tq + (ok ? tq : 0)) * A.Hq + g * A.G + h0 + (ok ? hsel : 0)) * D;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      u32x4 w = {0u, 0u, 0u, 0u};
+      if (ok) w = *reinterpret_cast<const u32x4 *>(qp + 8 * (a + 4 * kk));
+      if (wave == 0) ldsQ[(nq * KK + kk) * 64 + lane] = w;
+    }
+  }
+  // normalisers of the rows this lane holds after the MFMA: 4a..4a+3 of every query tile.
+  // +inf for padding rows: their logits are 0 (zero Q rows), so their weights come out as +0.
+  float lse_r[NQ][4];
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row = nq * 16 + 4 * a + r;
+      const int hsel = row >> tp_shift, tq = row & (Tp - 1);
+      const bool ok = hsel < nh && tq < A.Tq;
+      lse_r[nq][r] = ok ? A.lse_out[((size_t)bt * A.Hq + g * A.G + h0 + hsel) * A.Tq + tq] : INFINITY;
+    }
+  __syncthreads();
+
+  // addresses: a wave-uniform base per tile plus a 32-bit lane offset (the host checks that it fits)
+  const unsigned char *kuni = reinterpret_cast<const unsigned char *>(A.k) +
+                              ((int64_t)bt * A.stride_b + (int64_t)g * A.stride_h) * 2;
+  const int64_t row_bytes = A.stride_n * 2;
+  const unsigned lane_off = (unsigned)(4 * a) * (unsigned)row_bytes + (unsigned)(b * CHB);
+  unsigned char *ldsK = ldsK_all + wave * KTILE_BYTES;
+  auto slot_of = [&](int m) { return 16 * (m >> 2) + 4 * a + (m & 3); };
+  float *agg_set = A.agg_out + ((size_t)bt * A.Hq + g * A.G + h0) * (size_t)A.N;
+
+  auto issue_loads = [&](int t, chunk_t (&Kr)[8]) {
+    if (t >= t_end) return;        // wave-uniform: the slot is never consumed
+    if ((t + 1) * STS_TILE_KEYS <= c) {
+      const unsigned char *tb = kuni + (int64_t)t * STS_TILE_KEYS * row_bytes;
+#pragma unroll
+      for (int m = 0; m < 8; ++m)
+        Kr[m] = __builtin_nontemporal_load(
+            reinterpret_cast<const chunk_t *>(tb + (int64_t)(16 * (m >> 2) + (m & 3)) * row_bytes + lane_off));
+    } else {                       // the tile holding the end of the sequence, and tiles past it
+#pragma unroll
+      for (int m = 0; m < 8; ++m) {
+        const int row = c > 0 ? min(t * STS_TILE_KEYS + slot_of(m), c - 1) : 0;
+        Kr[m] = __builtin_nontemporal_load(
+            reinterpret_cast<const chunk_t *>(kuni + (int64_t)row * row_bytes + b * CHB));
+      }
+    }
+  };
+
+  // weights of the tile, folded over each head's rows; the lane at the end of a head's rows
+  // holds the sums for keys b and 16 + b of the tile
+  auto finish = [&](auto tp_c, const f32x4 (&Sq)[NQ][2], int pos0) {
+    constexpr int TP = decltype(tp_c)::value;
+    constexpr int HPL = TP >= 4 ? 1 : 4 / TP;
+    constexpr int CH = TP > 4 ? TP / 4 : 1;
+    constexpr int TPS = TP == 1 ? 0 : (TP == 2 ? 1 : (TP == 4 ? 2 : (TP == 8 ? 3 : 4)));
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+      float sum[2][4];
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+#pragma clang fp contract(off)   // the scaled logit is rounded before the subtraction, as in the dump
+        float pr[4];
+        const f32x4 sc = Sq[nq][ks] * A.scale;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          pr[r] = __builtin_amdgcn_exp2f((sc[r] - lse_r[nq][r]) * 1.44269504088896340736f);
+        fold_rows<TP>(pr, sum[ks], a);
+      }
+      // Stores. Lanes a and a^1 (16 apart) swap one half each, so that one store instruction
+      // covers a head's whole 128-byte line with 32 lanes (a line written as two 64-byte halves
+      // costs the memory system about three times as much). First the line of the even lane's
+      // head, then the line of the odd lane's head; a lane pair whose lane is not the end of a
+      // head's rows has nothing to store.
+      const int odd = a & 1;
+      const int pos = pos0 + 16 * odd + b;
+      const bool in_row = pos < A.N;
+      const bool live = pos < c;
+#pragma unroll
+      for (int j = 0; j < HPL; ++j) {
+        const float mine = odd ? sum[0][j] : sum[1][j];
+        const float theirs = __builtin_bit_cast(
+            float, __builtin_amdgcn_ds_bpermute(((int)threadIdx.x ^ 16) << 2, __builtin_bit_cast(int, mine)));
+        const int a_e = a & ~1, a_o = a | 1;
+        const int head_e = ((nq * 16 + 4 * a_e) >> TPS) + j, head_o = ((nq * 16 + 4 * a_o) >> TPS) + j;
+        if (CH == 1 && head_e < nh && in_row) {
+          const float v = odd ? theirs : sum[0][j];
+          agg_set[(size_t)head_e * (size_t)A.N + pos] = live ? v : 0.f;
+        }
+        if ((a_o & (CH - 1)) == CH - 1 && head_o < nh && in_row) {
+          const float v = odd ? sum[1][j] : theirs;
+          agg_set[(size_t)head_o * (size_t)A.N + pos] = live ? v : 0.f;
+        }
+      }
+    }
+  };
+
+  auto consume = [&](int t, const chunk_t (&Kr)[8]) {
+    const int pos0 = t * STS_TILE_KEYS;
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      const int row = slot_of(m);
+      if (D == 128) {
+        const int sl = b ^ (row & (NSLOT - 1));
+        *reinterpret_cast<chunk_t *>(ldsK + row * ROWB + sl * 16) = Kr[m];
+      } else {
+        const int sl = (b >> 1) ^ (row & (NSLOT - 1));
+        *reinterpret_cast<chunk_t *>(ldsK + row * ROWB + sl * 16 + (b & 1) * 8) = Kr[m];
+      }
+    }
+    // S = Q K^T: lane (a, b) gets rows 4a..4a+3 of each query tile for keys b and 16 + b
+    f32x4 Sq[NQ][2];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) Sq[nq][0] = Sq[nq][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      bf16x8 Ka[2];
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const int row = 16 * ks + b;
+        const int sl = (a + 4 * kk) ^ (row & (NSLOT - 1));
+        Ka[ks] = *reinterpret_cast<const bf16x8 *>(ldsK + row * ROWB + sl * 16);
+      }
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq) {
+        const bf16x8 Qb = __builtin_bit_cast(bf16x8, ldsQ[(nq * KK + kk) * 64 + lane]);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+          Sq[nq][ks] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Qb, Ka[ks], Sq[nq][ks], 0, 0, 0);
+      }
+    }
+    switch (Tp) {
+      case 1: finish(std::integral_constant<int, 1>(), Sq, pos0); break;
+      case 2: finish(std::integral_constant<int, 2>(), Sq, pos0); break;
+      case 4: finish(std::integral_constant<int, 4>(), Sq, pos0); break;
+      case 8: finish(std::integral_constant<int, 8>(), Sq, pos0); break;
+      default: finish(std::integral_constant<int, 16>(), Sq, pos0); break;
+    }
+  };
+
+  // ring of PS_STAGES tiles in flight per wave
+  if (t_begin + wave < t_end) {
+    chunk_t Kst[PS_STAGES][8];
+    int t = t_begin + wave;
+#pragma unroll
+    for (int u = 0; u < PS_STAGES - 1; ++u) issue_loads(t + u * W, Kst[u]);
+    bool more = true;
+    while (more) {
+#pragma unroll
+      for (int u = 0; u < PS_STAGES; ++u) {
+        if (more) {
+          issue_loads(t + (PS_STAGES - 1) * W, Kst[(u + PS_STAGES - 1) % PS_STAGES]);
+          consume(t, Kst[u]);
+          t += W;
+          more = t < t_end;
+        }
+      }
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t launch_attn_split(const AttnArgs &a, int d, int nq, bool sparse, hipStream_t s) {
@@ -702,5 +942,45 @@ hipError_t launch_attn_combine(const AttnArgs &a, int d, int nq, hipStream_t s) 
     hipLaunchKernelGGL((attn_combine_kernel<64>), grid, block, 0, s, a, nq);
   else
     return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+// resident workgroups per CU of the second-pass kernel for this head size and query-tile count
+// (register use differs a lot between the variants), asked from the runtime once per variant
+int attn_probsum_wgs_per_cu(int d, int nq) {
+  static std::mutex mu;
+  static int cached[2][5] = {{0}};
+  if ((d != 64 && d != 128) || (nq != 1 && nq != 2 && nq != 4)) return 1;
+  std::lock_guard<std::mutex> lk(mu);
+  int &slot = cached[d == 128][nq];
+  if (slot == 0) {
+    int n = 0;
+    hipError_t rc = hipErrorInvalidValue;
+#define STS_OCC(DD, QQ) rc = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, attn_probsum_kernel<DD, QQ>, 64 * STS_WG_WAVES, 0)
+    if (d == 128 && nq == 1) STS_OCC(128, 1);
+    else if (d == 128 && nq == 2) STS_OCC(128, 2);
+    else if (d == 128 && nq == 4) STS_OCC(128, 4);
+    else if (d == 64 && nq == 1) STS_OCC(64, 1);
+    else if (d == 64 && nq == 2) STS_OCC(64, 2);
+    else STS_OCC(64, 4);
+#undef STS_OCC
+    slot = (rc == hipSuccess && n > 0) ? n : 1;
+  }
+  return slot;
+}
+
+hipError_t launch_attn_probsum(const AttnArgs &a, int d, int nq, hipStream_t s) {
+  const size_t blocks = (size_t)a.B * a.Hkv * a.ps_sets * a.ps_splits;
+  if (blocks == 0) return hipSuccess;
+  const dim3 grid((unsigned)blocks), block(64 * STS_WG_WAVES);
+#define STS_PROBSUM(DD, QQ) hipLaunchKernelGGL((attn_probsum_kernel<DD, QQ>), grid, block, 0, s, a)
+  if (d == 128 && nq == 1) STS_PROBSUM(128, 1);
+  else if (d == 128 && nq == 2) STS_PROBSUM(128, 2);
+  else if (d == 128 && nq == 4) STS_PROBSUM(128, 4);
+  else if (d == 64 && nq == 1) STS_PROBSUM(64, 1);
+  else if (d == 64 && nq == 2) STS_PROBSUM(64, 2);
+  else if (d == 64 && nq == 4) STS_PROBSUM(64, 4);
+  else return hipErrorInvalidValue;
+#undef STS_PROBSUM
   return hipGetLastError();
 }

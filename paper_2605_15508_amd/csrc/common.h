@@ -46,6 +46,9 @@ struct AttnArgs {
   float *part_ml;                         // [B*U*S][NQ*16][2]  (max in log2 domain, sum)
   void *logits_out;
   int32_t logits_bf16;
+  float *agg_out;                         // [B,Hq,N] summed attention weights of the query block (dense only), or NULL
+  int32_t ps_heads, ps_sets, ps_splits;   // second pass: heads per workgroup, such sets per KV head, key-range splits
+  int32_t ps_tp;                          // second pass: rows per head, Tq rounded up to a power of two
   void *out;
   float *lse_out;
   int32_t out_dtype;
@@ -56,7 +59,7 @@ struct AttnPlan {
   int32_t nq;          // query tiles of 16 rows per unit (1, 2 or 4)
   int32_t num_units;   // per batch element
   int32_t num_splits;
-  size_t part_o_bytes, part_ml_bytes;
+  size_t part_o_bytes, part_ml_bytes, lse_bytes;
   AttnUnitTable units;
 };
 
@@ -100,6 +103,7 @@ struct SelectArgs {
   uint64_t clear_words;       // words to zero from `hist` on: histograms, state and chunk flags
   int32_t hist_cpw;           // consecutive chunks per workgroup of the refinement histograms (1, 2 or 4)
   int32_t spin_limit;         // polls of an unpublished earlier chunk before it is recounted locally
+  int32_t agg_is_input;       // `agg` is the caller's score tensor itself (one fp32 probability row per head): never stored to
   int32_t B, Hd, Tq, N, Hq, k, kind, reduce, nchunks;   // k: row pitch of indices = largest budget
   SelectTargets targets;
   int32_t kh[STS_MAX_HEADS];  // budget of draft head j (<= k)
@@ -108,6 +112,8 @@ struct SelectArgs {
 // launches (defined in the .hip files); each returns hipGetLastError() of its launch
 hipError_t launch_attn_split(const AttnArgs &a, int d, int nq, bool sparse, hipStream_t s);
 hipError_t launch_attn_combine(const AttnArgs &a, int d, int nq, hipStream_t s);
+hipError_t launch_attn_probsum(const AttnArgs &a, int d, int nq, hipStream_t s);
+int attn_probsum_wgs_per_cu(int d, int nq);
 hipError_t launch_select_clear(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_agg(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_block(const SelectArgs &a, hipStream_t s);

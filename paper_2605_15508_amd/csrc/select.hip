@@ -279,7 +279,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_agg_kernel(const SelectArg
   if (VEC4) {
     for (int n = n0 + threadIdx.x * 4; n < n1; n += SEL_THREADS * 4) {
       const f32x4 acc = agg_quad(R, n);
-      *reinterpret_cast<f32x4 *>(out + n) = acc;
+      if (!A.agg_is_input) *reinterpret_cast<f32x4 *>(out + n) = acc;
 #pragma unroll
       for (int e = 0; e < 4; ++e)
         if (A.page == 1 && n + e < nb) atomicAdd(&h[key_of(acc[e]) >> (32 - SEL_BITS0)], 1u);
@@ -287,7 +287,7 @@ __global__ void __launch_bounds__(SEL_THREADS) select_agg_kernel(const SelectArg
   } else {
     for (int n = n0 + threadIdx.x; n < n1; n += SEL_THREADS) {
       const float acc = agg_one(R, n);
-      out[n] = acc;
+      if (!A.agg_is_input) out[n] = acc;
       if (A.page == 1 && n < nb) atomicAdd(&h[key_of(acc) >> (32 - SEL_BITS0)], 1u);
     }
   }

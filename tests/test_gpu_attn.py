@@ -263,3 +263,60 @@ def test_closed_forms_on_the_gpu():
     for t in range(Hq):
         assert (out[:, :, t] - want[:, t // G][:, None]).abs().max().item() < 2e-3
     assert (lse - math.log(N)).abs().max().item() < 1e-5
+
+
+@pytest.mark.parametrize("B,Tq,Hq,Hkv,d,N", [
+    (2, 5, 8, 2, 128, 1000),     # 20 rows per KV head: two query tiles, ragged last key tile
+    (1, 8, 16, 2, 128, 2500),    # GQA 8 x 8 rows: four query tiles
+    (2, 8, 8, 2, 64, 4100),      # head dim 64; several key-range pieces
+    (1, 16, 16, 1, 64, 644),     # 16 heads x 16 rows: the heads of a KV group in four sets
+    (1, 1, 4, 4, 128, 36),       # one query row: the sum is the row itself
+    (1, 3, 6, 2, 64, 21),        # less than one key tile
+])
+def test_weights_summed_over_the_query_block(B, Tq, Hq, Hkv, d, N):
+    """The second pass over K (Section 4.3: one mask per speculative batch; Section 5: the draft
+    layer hands over its scores): equal, bit for bit, to what the selection aggregates the logits
+    dump to, equal to the oracle's aggregate within the dump's tolerance, zero past the valid
+    length, and the selection it feeds picks the same indices."""
+    import oracle
+    q, k, v = make_qkv(41, B, Tq, Hq, Hkv, d, N)
+    lens = torch.tensor([N - 7, N // 3][:B], dtype=torch.int32, device=DEV)
+    scale = 1.0 / math.sqrt(d)
+    A = torch.full((B, Hq, N), 9.0, dtype=torch.float32, device=DEV)
+    out, lse, logits = sts.sts_dense_attn(q, k, v, scale, seq_lens=lens, out_dtype=torch.float32,
+                                          want_logits=True, weights_sum_out=A)
+    out0, lse0, lg0 = sts.sts_dense_attn(q, k, v, scale, seq_lens=lens, out_dtype=torch.float32, want_logits=True)
+    assert torch.equal(out, out0) and torch.equal(lse, lse0)      # the second pass leaves the first alone
+    kk = max(1, N // 10)
+    hm = list(range(Hq))
+    idx_d, cnt_d, agg_d = sts.sts_select(logits, hm, kk, lse=lse, seq_lens=lens,
+                                         kind=sts.STS_SCORES_LOGITS_LSE, want_agg=True)
+    idx_a, cnt_a, _ = sts.sts_select(A.view(B, Hq, 1, N), hm, kk, seq_lens=lens)
+    assert torch.equal(idx_a, idx_d) and torch.equal(cnt_a, cnt_d)
+    ref = oracle_attn(q, k, v, scale, seq_lens=lens, want_logits=True)
+    ref_A = oracle.aggregate(ref["logits"], ref["lse"], kind=oracle.LOGITS_LSE)
+    got = A.cpu().numpy()
+    for b, n in enumerate(lens.tolist()):
+        assert torch.equal(A[b, :, :n], agg_d[b, :, :n])
+        assert (A[b, :, n:] == 0).all()
+        assert (np.abs(got[b, :, :n] - ref_A[b, :, :n]) <= 5e-3 * ref_A[b, :, :n] + 1e-7).all()
+        # each row's weights sum to one, so the aggregate sums to Tq
+        assert np.allclose(got[b, :, :n].sum(-1, dtype=np.float64), Tq, atol=2e-3)
+    # without a caller's lse buffer the normalisers live in the workspace (no dump: the first
+    # pass visits the tiles in another order, so its normalisers differ in the last bits)
+    A2 = torch.empty_like(A)
+    sts.sts_dense_attn(q, k, v, scale, seq_lens=lens, want_lse=False, weights_sum_out=A2)
+    assert torch.allclose(A2, A, rtol=1e-4, atol=1e-9)
+
+
+def test_weights_sum_unaligned_length_and_rejections():
+    """A length that is no multiple of 4 (scalar tail of the dump, partial last line of the sum),
+    and the cases the second pass does not cover: the speculative block's own keys, paged caches."""
+    q, k, v = make_qkv(42, 1, 4, 4, 2, 128, 131)
+    A = torch.empty(1, 4, 131, dtype=torch.float32, device=DEV)
+    _, lse, logits = sts.sts_dense_attn(q, k, v, 0.1, want_logits=True, weights_sum_out=A)
+    _, _, agg = sts.sts_select(logits, [0, 1, 2, 3], 13, lse=lse, kind=sts.STS_SCORES_LOGITS_LSE, want_agg=True)
+    assert torch.equal(A, agg)
+    kn = torch.zeros(1, 4, 2, 128, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(RuntimeError):
+        sts.sts_dense_attn(q, k, v, 0.1, k_new=kn, v_new=kn, weights_sum_out=A)

@@ -469,3 +469,37 @@ def test_hand_worked_cases_on_the_gpu():
         np.testing.assert_array_equal(agg[0].cpu().numpy(), np.array(case["agg"], np.float32))
         if "counts" in case:
             np.testing.assert_array_equal(cnt[0].cpu().numpy(), np.array(case["counts"], np.int32))
+
+
+@pytest.mark.parametrize("N,k,levels,off", [
+    (40000, 9000, 0, 0),       # vector path
+    (40000, 9000, 50, 0),      # heavy ties across chunks
+    (70001, 20000, 0, 0),      # N % 4 != 0: scalar path
+    (40004, 9000, 0, 1),       # misaligned base: scalar path on the caller's own tensor
+])
+def test_single_row_input_is_ranked_in_place(N, k, levels, off):
+    """One fp32 probability row per head (Tq = 1; e.g. a ready-made aggregate) on the
+    multi-workgroup pipeline: the rows are ranked where they lie (no copy into the workspace),
+    the input stays untouched, and asking for the aggregate returns the input itself."""
+    B, Hd, Hq = 2, 3, 6
+    g = torch.Generator().manual_seed(5)
+    if levels:
+        s = torch.randint(0, levels, (B, Hd, 1, N), generator=g).float() / levels
+    else:
+        s = torch.softmax(torch.randn(B, Hd, 1, N, generator=g) * 2.0, dim=-1)
+    head_map = [0, 0, 1, 1, 2, 2]
+    lens = torch.tensor([N, N - 4097], dtype=torch.int32)
+    flat = torch.zeros(s.numel() + 4, dtype=torch.float32, device=DEV)
+    sd = flat[off:off + s.numel()].view(B, Hd, 1, N)
+    sd.copy_(s)
+    got = {}
+    kinds = launched(lambda: got.update(r=sts.sts_select(sd, head_map, k, seq_lens=lens.to(DEV))))
+    assert kinds == {"select_clear", "select_agg", "select_hist", "select_write"}
+    idx, cnt, _ = got["r"]
+    assert torch.equal(sd.cpu(), s)
+    o_idx, o_cnt, o_agg = oracle.select_indices(s.numpy(), np.asarray(head_map, np.int32), k, seq_lens=lens.numpy())
+    assert np.array_equal(idx.cpu().numpy(), o_idx) and np.array_equal(cnt.cpu().numpy(), o_cnt)
+    idx2, cnt2, agg2 = sts.sts_select(sd, head_map, k, seq_lens=lens.to(DEV), want_agg=True)
+    assert torch.equal(idx2, idx) and torch.equal(cnt2, cnt)
+    for b, n in enumerate(lens.tolist()):
+        assert np.array_equal(agg2[b, :, :n].cpu().numpy(), o_agg[b, :, :n])

@@ -147,6 +147,10 @@ sts_status plan_attn(const sts_attn_params *p, int sparse, AttnPlan &pl) {
   const int64_t s_cap = tiles <= 16 ? 1 : (tiles + 2 * STS_WG_WAVES - 1) / (2 * STS_WG_WAVES);
   if (S > s_cap) S = s_cap;
   if (S > 256) S = 256;
+  // With at least one unit per CU, halving every unit only adds the combine launch: one
+  // workgroup per CU keeps enough loads in flight (70B-shaped layer, 256 units of 410 tiles:
+  // 268 us unsplit against 278 us in two halves).
+  if (S == 2 && units_total >= cu_count() && !getenv("STS_ATTN_WGS_PER_CU")) S = 1;
   if (S < 1) S = 1;
   pl.num_splits = (int)S;
   const size_t parts = (size_t)units_total * (size_t)S;

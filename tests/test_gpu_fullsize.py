@@ -145,3 +145,16 @@ def test_c5_two_batch_elements_of_the_70b_shaped_chain():
     o_agg = oracle.aggregate(d_logits[:1, :4].cpu().numpy(), d_lse[:1, :4].cpu().numpy(), kind=oracle.LOGITS_LSE)
     np.testing.assert_allclose(a[:1, :4], o_agg, rtol=1e-5, atol=1e-12)
     _sample_heads(w, idx, cnt, out, lse, [(0, 3), (1, 40), (1, 63)], "c5")
+    # the other route: the draft layer sums its attention weights itself (second pass over K)
+    # and the selection ranks that tensor in place: same aggregate bit for bit, same index sets;
+    # one sampled head against the oracle's aggregate of its own logits
+    A = torch.empty(cfg.B, cfg.Hd, cfg.N, dtype=torch.float32, device=DEV)
+    sts.sts_dense_attn(dl["q"], dl["k"], dl["v"], dl["scale"], logits_out=d_logits, lse_out=d_lse,
+                       weights_sum_out=A)
+    assert torch.equal(A, agg)
+    idx2, cnt2, _ = sts.sts_select(A.view(cfg.B, cfg.Hd, 1, cfg.N), w.head_map, kb)
+    assert torch.equal(idx2, idx) and torch.equal(cnt2, cnt)
+    ref_A = oracle.aggregate(ref_d["logits"][:, j - gd * Gd:j - gd * Gd + 1],
+                             ref_d["lse"][:, j - gd * Gd:j - gd * Gd + 1], kind=oracle.LOGITS_LSE)[0, 0]
+    got_A = A[b, j].cpu().numpy()
+    assert (np.abs(got_A - ref_A) <= 5e-3 * ref_A + 1e-9).all()

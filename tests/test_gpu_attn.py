@@ -272,6 +272,10 @@ def test_closed_forms_on_the_gpu():
     (1, 16, 16, 1, 64, 644),     # 16 heads x 16 rows: the heads of a KV group in four sets
     (1, 1, 4, 4, 128, 36),       # one query row: the sum is the row itself
     (1, 3, 6, 2, 64, 21),        # less than one key tile
+    (2, 2, 12, 2, 64, 333),      # two rows per head: two heads per lane
+    (1, 16, 6, 1, 128, 200),     # 6 heads x 16 rows: a full set of four heads and a set of two
+    (1, 4, 20, 2, 128, 515),     # 10 heads x 4 rows per KV head: one head per lane
+    (1, 7, 12, 1, 64, 1030),     # 12 heads x 7 rows (padded to 8): sets of 8 and 4 heads
 ])
 def test_weights_summed_over_the_query_block(B, Tq, Hq, Hkv, d, N):
     """The second pass over K (Section 4.3: one mask per speculative batch; Section 5: the draft

@@ -174,3 +174,50 @@ def test_random_selection_case(seed):
     o_idx, o_cnt = oracle.remap(sel, c, np.asarray(hm, np.int32))
     np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt, err_msg=what)
     np.testing.assert_array_equal(idx.cpu().numpy(), o_idx, err_msg=what)
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_random_summed_weights_case(seed):
+    """The draft layer's summed attention weights over random shapes (query rows 1..16, groups
+    1..16, both head dims, strided caches, ragged lengths): bit for bit what the logits dump and
+    the selection's aggregation give, the same index sets, and within the dump's tolerance of the
+    oracle's aggregate of its own logits."""
+    rng = np.random.default_rng(3000 + seed)
+    d = int(rng.choice([64, 128]))
+    Hkv = int(rng.choice([1, 2, 3]))
+    G = int(rng.choice([1, 2, 3, 4, 6, 8, 16]))
+    Hq = Hkv * G
+    Tq = int(rng.integers(1, 17))
+    B = int(rng.integers(1, 4))
+    N = int(rng.integers(1, 3000))
+    g = torch.Generator().manual_seed(seed)
+    q = torch.randn(B, Tq, Hq, d, generator=g).to(torch.bfloat16)
+    k = (torch.randn(B, Hkv, N, d, generator=g) * 0.5).to(torch.bfloat16)
+    v = (torch.randn(B, Hkv, N, d, generator=g) * 0.5).to(torch.bfloat16)
+    scale = float(rng.uniform(0.05, 0.3))
+    if rng.integers(0, 2):     # interleaved K/V cache: row stride 2d
+        kv = torch.stack([k, v], dim=3).contiguous().to(DEV)
+        kd, vd = kv[:, :, :, 0], kv[:, :, :, 1]
+    else:
+        kd, vd = k.to(DEV), v.to(DEV)
+    lens = torch.from_numpy(rng.integers(0, N + 1, size=B).astype(np.int32)) if rng.integers(0, 2) else None
+    ld = None if lens is None else lens.to(DEV)
+    A = torch.full((B, Hq, N), -3.0, dtype=torch.float32, device=DEV)
+    _, lse, logits = sts.sts_dense_attn(q.to(DEV), kd, vd, scale, seq_lens=ld, want_logits=True, weights_sum_out=A)
+    kk = int(rng.integers(1, N + 1))
+    hm = list(range(Hq))
+    idx_d, cnt_d, agg_d = sts.sts_select(logits, hm, kk, lse=lse, seq_lens=ld, kind=sts.STS_SCORES_LOGITS_LSE,
+                                         want_agg=True)
+    idx_a, cnt_a, _ = sts.sts_select(A.view(B, Hq, 1, N), hm, kk, seq_lens=ld)
+    what = f"seed {seed}: d{d} Hkv{Hkv} G{G} Tq{Tq} B{B} N{N} k{kk}"
+    assert torch.equal(idx_a, idx_d) and torch.equal(cnt_a, cnt_d), what
+    ref = oracle.attn(oracle.bf16_bits(q), oracle.bf16_bits(k), oracle.bf16_bits(v), scale,
+                      seq_lens=None if lens is None else lens.numpy(), want_logits=True)
+    got = A.cpu().numpy()
+    for b in range(B):
+        n = N if lens is None else int(lens[b])
+        assert torch.equal(A[b, :, :n], agg_d[b, :, :n]), what
+        assert (A[b, :, n:] == 0).all(), what
+        if n > 0:
+            ref_A = oracle.aggregate(ref["logits"][b:b + 1, :, :, :n].copy(), ref["lse"][b:b + 1], kind=oracle.LOGITS_LSE)[0]
+            assert (np.abs(got[b, :, :n] - ref_A) <= 5e-3 * ref_A + 1e-7).all(), what

@@ -234,7 +234,8 @@ int sts_version(void);
 
 /* ----------------------------------------------------------------------------------------
  * Measurement aid (not on the hot path): when enabled, every kernel launch of the calls
- * above is bracketed by HIP events on the call's stream. sts_prof_read synchronises those
+ * above carries a pair of HIP events that its dispatch on the call's stream stamps with the
+ * kernel's own begin and end times. sts_prof_read synchronises those
  * events and returns, per kernel kind, the number of launches and their summed duration
  * since the last sts_prof_reset. Enabling allocates events lazily; at most STS_PROF_MAX
  * launches are kept per reset, later ones are not recorded.

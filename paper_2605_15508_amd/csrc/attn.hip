@@ -662,11 +662,11 @@ template <int D, int NQ, bool PAGED>
 hipError_t launch_split_dnp(const AttnArgs &a, bool sparse, hipStream_t s) {
   const dim3 grid((unsigned)((size_t)a.B * a.num_units * a.num_splits)), block(64 * STS_WG_WAVES);
   if (sparse)
-    hipLaunchKernelGGL((attn_split_kernel<D, NQ, true, false, PAGED>), grid, block, 0, s, a);
+    STS_LAUNCH((attn_split_kernel<D, NQ, true, false, PAGED>), grid, block, 0, s, a);
   else if (a.logits_out)
-    hipLaunchKernelGGL((attn_split_kernel<D, NQ, false, true, PAGED>), grid, block, 0, s, a);
+    STS_LAUNCH((attn_split_kernel<D, NQ, false, true, PAGED>), grid, block, 0, s, a);
   else
-    hipLaunchKernelGGL((attn_split_kernel<D, NQ, false, false, PAGED>), grid, block, 0, s, a);
+    STS_LAUNCH((attn_split_kernel<D, NQ, false, false, PAGED>), grid, block, 0, s, a);
   return hipGetLastError();
 }
 
@@ -937,9 +937,9 @@ hipError_t launch_attn_combine(const AttnArgs &a, int d, int nq, hipStream_t s) 
   if (blocks == 0) return hipSuccess;
   const dim3 grid((unsigned)blocks), block(256);
   if (d == 128)
-    hipLaunchKernelGGL((attn_combine_kernel<128>), grid, block, 0, s, a, nq);
+    STS_LAUNCH((attn_combine_kernel<128>), grid, block, 0, s, a, nq);
   else if (d == 64)
-    hipLaunchKernelGGL((attn_combine_kernel<64>), grid, block, 0, s, a, nq);
+    STS_LAUNCH((attn_combine_kernel<64>), grid, block, 0, s, a, nq);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();
@@ -973,7 +973,7 @@ hipError_t launch_attn_probsum(const AttnArgs &a, int d, int nq, hipStream_t s) 
   const size_t blocks = (size_t)a.B * a.Hkv * a.ps_sets * a.ps_splits;
   if (blocks == 0) return hipSuccess;
   const dim3 grid((unsigned)blocks), block(64 * STS_WG_WAVES);
-#define STS_PROBSUM(DD, QQ) hipLaunchKernelGGL((attn_probsum_kernel<DD, QQ>), grid, block, 0, s, a)
+#define STS_PROBSUM(DD, QQ) STS_LAUNCH((attn_probsum_kernel<DD, QQ>), grid, block, 0, s, a)
   if (d == 128 && nq == 1) STS_PROBSUM(128, 1);
   else if (d == 128 && nq == 2) STS_PROBSUM(128, 2);
   else if (d == 128 && nq == 4) STS_PROBSUM(128, 4);

@@ -3,9 +3,25 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "../../include/sts.h"
+
+// Every kernel goes out through STS_LAUNCH. With the library's timing aid switched on, the host
+// code sets this pair of events before a launch and the dispatch itself stamps them with the
+// kernel's own begin and end times (no extra packets around it); otherwise it is an ordinary
+// launch.
+struct StsLaunchEvents { hipEvent_t start, stop; };
+extern thread_local StsLaunchEvents g_sts_launch_events;
+#define STS_LAUNCH(kernel, grid, block, shmem, stream, ...)                                              \
+  do {                                                                                                   \
+    if (g_sts_launch_events.start)                                                                       \
+      hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, g_sts_launch_events.start,               \
+                            g_sts_launch_events.stop, 0, __VA_ARGS__);                                   \
+    else                                                                                                 \
+      hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);                               \
+  } while (0)
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));

@@ -68,20 +68,20 @@ __global__ void __launch_bounds__(256) headmap_argmax_kernel(const unsigned long
 
 hipError_t launch_headmap_clear(unsigned long long *overlap, int n, hipStream_t s) {
   if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(headmap_clear_kernel, dim3((n + 255) / 256), dim3(256), 0, s, overlap, n);
+  STS_LAUNCH(headmap_clear_kernel, dim3((n + 255) / 256), dim3(256), 0, s, overlap, n);
   return hipGetLastError();
 }
 
 hipError_t launch_headmap_overlap(const int32_t *idx_d, const int32_t *idx_t, int S, int R, int Hd, int Ht,
                                   int k, int c, unsigned long long *overlap, hipStream_t s) {
   if ((size_t)S * R == 0 || Ht == 0 || c == 0) return hipSuccess;
-  hipLaunchKernelGGL(headmap_overlap_kernel, dim3(S * R, Ht), dim3(256), 0, s, idx_d, idx_t, S, R, Hd, Ht, k, c,
+  STS_LAUNCH(headmap_overlap_kernel, dim3(S * R, Ht), dim3(256), 0, s, idx_d, idx_t, S, R, Hd, Ht, k, c,
                      overlap);
   return hipGetLastError();
 }
 
 hipError_t launch_headmap_argmax(const unsigned long long *overlap, int Hd, int Ht, int32_t *map, hipStream_t s) {
   if (Ht == 0) return hipSuccess;
-  hipLaunchKernelGGL(headmap_argmax_kernel, dim3((Ht + 255) / 256), dim3(256), 0, s, overlap, Hd, Ht, map);
+  STS_LAUNCH(headmap_argmax_kernel, dim3((Ht + 255) / 256), dim3(256), 0, s, overlap, Hd, Ht, map);
   return hipGetLastError();
 }

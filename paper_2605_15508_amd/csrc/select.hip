@@ -1076,16 +1076,16 @@ hipError_t launch_select_small(const SelectArgs &a, hipStream_t s) {
   const bool v = (a.N % 4) == 0 && (reinterpret_cast<uintptr_t>(a.scores) % 16) == 0 &&
                  (a.agg == nullptr || (reinterpret_cast<uintptr_t>(a.agg) % 16) == 0);
   if (v)
-    hipLaunchKernelGGL((select_small_kernel<true, false>), grid, block, 0, s, a);
+    STS_LAUNCH((select_small_kernel<true, false>), grid, block, 0, s, a);
   else
-    hipLaunchKernelGGL((select_small_kernel<false, false>), grid, block, 0, s, a);
+    STS_LAUNCH((select_small_kernel<false, false>), grid, block, 0, s, a);
   return hipGetLastError();
 }
 
 // ranks the rows of a.src (up to SEL_SMALL_N entries each) out of LDS
 hipError_t launch_select_rank(const SelectArgs &a, hipStream_t s) {
   if ((size_t)a.B * a.Hd == 0) return hipSuccess;
-  hipLaunchKernelGGL((select_small_kernel<false, true>), dim3(a.B * a.Hd), dim3(SMALL_THREADS), 0, s, a);
+  STS_LAUNCH((select_small_kernel<false, true>), dim3(a.B * a.Hd), dim3(SMALL_THREADS), 0, s, a);
   return hipGetLastError();
 }
 
@@ -1099,7 +1099,7 @@ bool select_aggblock_ok(const SelectArgs &a) {
 hipError_t launch_select_aggblock(const SelectArgs &a, hipStream_t s) {
   if ((size_t)a.B * a.Hd == 0 || a.N == 0) return hipSuccess;
   const dim3 grid((a.N + SEL_CHUNK - 1) / SEL_CHUNK, a.B * a.Hd), block(SEL_THREADS);
-  hipLaunchKernelGGL(select_aggblock_kernel, grid, block, 0, s, a);
+  STS_LAUNCH(select_aggblock_kernel, grid, block, 0, s, a);
   return hipGetLastError();
 }
 
@@ -1107,15 +1107,15 @@ hipError_t launch_select_local(const SelectArgs &a, hipStream_t s) {
   if ((size_t)a.B * a.Hd == 0 || a.pool_nchunks == 0) return hipSuccess;
   const dim3 grid(a.pool_nchunks, a.B * a.Hd);
   if (a.pool_chunk == 256 * 32)
-    hipLaunchKernelGGL(select_local_kernel<256>, grid, dim3(256), 0, s, a);
+    STS_LAUNCH(select_local_kernel<256>, grid, dim3(256), 0, s, a);
   else   // 1024 * 32
-    hipLaunchKernelGGL(select_local_kernel<1024>, grid, dim3(1024), 0, s, a);
+    STS_LAUNCH(select_local_kernel<1024>, grid, dim3(1024), 0, s, a);
   return hipGetLastError();
 }
 
 hipError_t launch_select_pool(const SelectArgs &a, hipStream_t s) {
   if ((size_t)a.B * a.Hd == 0) return hipSuccess;
-  hipLaunchKernelGGL(select_pool_kernel, dim3(a.B * a.Hd), dim3(SMALL_THREADS), 0, s, a);
+  STS_LAUNCH(select_pool_kernel, dim3(a.B * a.Hd), dim3(SMALL_THREADS), 0, s, a);
   return hipGetLastError();
 }
 
@@ -1125,10 +1125,10 @@ hipError_t launch_select_block(const SelectArgs &a, hipStream_t s) {
   if (pow2 && a.page >= 4 && a.page <= 256 && (a.N % a.page) == 0 &&
       (reinterpret_cast<uintptr_t>(a.agg) % 16) == 0) {
     const dim3 grid((a.N + SEL_CHUNK - 1) / SEL_CHUNK, a.B * a.Hd), block(SEL_THREADS);
-    hipLaunchKernelGGL(select_block_vec_kernel, grid, block, 0, s, a);
+    STS_LAUNCH(select_block_vec_kernel, grid, block, 0, s, a);
   } else {
     const dim3 grid((a.srcN + SEL_THREADS - 1) / SEL_THREADS, a.B * a.Hd), block(SEL_THREADS);
-    hipLaunchKernelGGL(select_block_kernel, grid, block, 0, s, a);
+    STS_LAUNCH(select_block_kernel, grid, block, 0, s, a);
   }
   return hipGetLastError();
 }
@@ -1136,7 +1136,7 @@ hipError_t launch_select_block(const SelectArgs &a, hipStream_t s) {
 hipError_t launch_select_clear(const SelectArgs &a, hipStream_t s) {
   const size_t n = (size_t)a.clear_words;
   if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(select_clear_kernel, dim3((unsigned)((n + SEL_THREADS - 1) / SEL_THREADS)),
+  STS_LAUNCH(select_clear_kernel, dim3((unsigned)((n + SEL_THREADS - 1) / SEL_THREADS)),
                      dim3(SEL_THREADS), 0, s, a.hist, n);
   return hipGetLastError();
 }
@@ -1146,9 +1146,9 @@ hipError_t launch_select_agg(const SelectArgs &a, hipStream_t s) {
   if ((size_t)a.B * a.Hd == 0 || chunks == 0) return hipSuccess;
   const dim3 grid(chunks, a.B * a.Hd), block(SEL_THREADS);
   if (vec_ok(a))
-    hipLaunchKernelGGL(select_agg_kernel<true>, grid, block, 0, s, a);
+    STS_LAUNCH(select_agg_kernel<true>, grid, block, 0, s, a);
   else
-    hipLaunchKernelGGL(select_agg_kernel<false>, grid, block, 0, s, a);
+    STS_LAUNCH(select_agg_kernel<false>, grid, block, 0, s, a);
   return hipGetLastError();
 }
 
@@ -1157,11 +1157,11 @@ hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t s) {
   const dim3 grid((a.nchunks + a.hist_cpw - 1) / a.hist_cpw, a.B * a.Hd), block(SEL_THREADS);
   const bool v = src_vec_ok(a);
   if (pass == 1) {
-    if (v) hipLaunchKernelGGL((select_hist_kernel<1, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((select_hist_kernel<1, false>), grid, block, 0, s, a);
+    if (v) STS_LAUNCH((select_hist_kernel<1, true>), grid, block, 0, s, a);
+    else STS_LAUNCH((select_hist_kernel<1, false>), grid, block, 0, s, a);
   } else {
-    if (v) hipLaunchKernelGGL((select_hist_kernel<2, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((select_hist_kernel<2, false>), grid, block, 0, s, a);
+    if (v) STS_LAUNCH((select_hist_kernel<2, true>), grid, block, 0, s, a);
+    else STS_LAUNCH((select_hist_kernel<2, false>), grid, block, 0, s, a);
   }
   return hipGetLastError();
 }
@@ -1170,8 +1170,8 @@ hipError_t launch_select_write(const SelectArgs &a, hipStream_t s) {
   if ((size_t)a.B * a.Hd == 0) return hipSuccess;
   const dim3 grid(a.nchunks > 0 ? a.nchunks : 1, a.B * a.Hd), block(SEL_THREADS);
   if (src_vec_ok(a))
-    hipLaunchKernelGGL(select_write_kernel<true>, grid, block, 0, s, a);
+    STS_LAUNCH(select_write_kernel<true>, grid, block, 0, s, a);
   else
-    hipLaunchKernelGGL(select_write_kernel<false>, grid, block, 0, s, a);
+    STS_LAUNCH(select_write_kernel<false>, grid, block, 0, s, a);
   return hipGetLastError();
 }

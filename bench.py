@@ -257,8 +257,9 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    # second pass of K steps with the library's per-kernel HIP events switched on (they add a
-    # few microseconds per launch, so they stay out of the region that gives `value`)
+    # second pass of K steps with the library's per-kernel HIP events switched on: every dispatch
+    # stamps its own begin and end into a pair of events (kept out of the region that gives
+    # `value`, which is timed without them)
     sts.prof_enable(True)
     sts.prof_reset()
     for i in range(min(args.steps, max(1, STS_PROF_BUDGET // (8 * L)))):

@@ -89,6 +89,10 @@ typedef enum { STS_BF16 = 0, STS_F32 = 1 } sts_dtype;
  * once per draft head, and each layer's sts_sparse_attn reads its heads' slice of `indices`
  * in place (idx_stride_b / cnt_stride_b there).
  *
+ * A ready-made aggregate (one fp32 probability row per draft head: Tq = 1, kind PROBS, e.g.
+ * sts_dense_attn's weights_sum_out) is ranked where it lies when agg_out is NULL: no copy into
+ * the workspace is made, and the tensor is only read.
+ *
  * Supported: 1 <= Tq <= 64, 1 <= Hq <= 256, 1 <= Hd <= 256, N < 2^31 - 2^16,
  * page_size <= 4096. Rows of size zero are handled (nothing is read; counts are 0).
  */

@@ -242,7 +242,8 @@ int sts_version(void);
  * kernel's own begin and end times. sts_prof_read synchronises those
  * events and returns, per kernel kind, the number of launches and their summed duration
  * since the last sts_prof_reset. Enabling allocates events lazily; at most STS_PROF_MAX
- * launches are kept per reset, later ones are not recorded.
+ * launches are kept per reset, later ones are not recorded. Keep it switched off while a
+ * stream is being captured into a graph (the stamped launch is not a capturable node).
  */
 typedef enum {
   STS_K_SELECT_CLEAR = 0,  /* zero histograms */

@@ -54,6 +54,9 @@ def parse_args():
                     help="heavy tokens scattered over the context (worst case for the gather) or clustered at its end")
     ap.add_argument("--scores", default="fp32", choices=["fp32", "bf16"],
                     help="type of the draft scores read by sts_select (and of the logits dump of the draft layer)")
+    ap.add_argument("--draft-heads", type=int, default=None,
+                    help="number of draft heads Hd (default: the configuration's); fewer draft heads make more "
+                         "target heads of a KV group share one index row")
     ap.add_argument("--draft-scores", default="dump", choices=["dump", "sum"],
                     help="draft-layer configuration: the draft attention dumps its logits and sts_select aggregates "
                          "them (dump), or it sums the attention weights over the query block itself in a second "
@@ -156,6 +159,9 @@ def main():
     cfg = CONFIGS[args.config]
     if args.gain is not None:
         cfg = replace(cfg, gain=args.gain)
+    if args.draft_heads is not None:
+        assert not cfg.draft_d, "the draft-layer configuration fixes its head count"
+        cfg = replace(cfg, Hd=args.draft_heads)
     if args.positions == "recent":
         cfg = replace(cfg, clustered=True)
     head_map = None

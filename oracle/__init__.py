@@ -42,7 +42,9 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(build())
+        # STS_ORACLE_LIB: a library built elsewhere from (a variant of) sts_oracle.c; the
+        # mutation test uses it to show that the pins reject planted mistakes
+        _lib = ctypes.CDLL(os.environ.get("STS_ORACLE_LIB") or build())
         _lib.oracle_num_threads.restype = ctypes.c_int
     return _lib
 

@@ -1,0 +1,121 @@
+"""Do the pins bite? Each case plants one plausible mistake in a copy of the oracle's C source (a
+dropped term, a wrong sign or index, a transposed operand, an off-by-one), builds it, and runs
+the oracle's pin tests against that build in a child process: at least one pin must fail. The
+mistakes live in the oracle, on the CPU; nothing here touches the GPU path."""
+import os
+import subprocess
+import sys
+import tempfile
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "sts_oracle.c")
+PIN_FILES = ["test_oracle_select.py", "test_oracle_attn.py", "test_oracle_blocks.py", "test_oracle_headmap.py"]
+
+# (name, text in sts_oracle.c, replacement, pin files that must notice)
+MUTANTS = [
+    ("aggregate adds right to left",
+     "for (int i = 0; i < Tq; ++i) {\n        float p = P[(size_t)i * N + n];",
+     "for (int ii = 0; ii < Tq; ++ii) {\n        const int i_src = Tq - 1 - ii; const int i = ii;\n        float p = P[(size_t)i_src * N + n];",
+     ["test_oracle_select.py"]),
+    ("aggregate drops the last query row",
+     "for (int i = 0; i < Tq; ++i) {\n        float p = P[(size_t)i * N + n];",
+     "for (int i = 0; i < (Tq > 1 ? Tq - 1 : Tq); ++i) {\n        float p = P[(size_t)i * N + n];",
+     ["test_oracle_select.py"]),
+    ("normaliser added instead of subtracted",
+     "p = expf(p - lse[(size_t)r * Tq + i]);", "p = expf(p + lse[(size_t)r * Tq + i]);",
+     ["test_oracle_select.py"]),
+    ("normaliser of the wrong row",
+     "p = expf(p - lse[(size_t)r * Tq + i]);", "p = expf(p - lse[(size_t)r * Tq]);",
+     ["test_oracle_select.py"]),
+    ("ties go to the higher index",
+     "return (p->n > q->n) - (p->n < q->n);", "return (p->n < q->n) - (p->n > q->n);",
+     ["test_oracle_select.py"]),
+    ("smallest scores selected",
+     "if (p->a > q->a) return -1;\n  if (p->a < q->a) return 1;", "if (p->a > q->a) return 1;\n  if (p->a < q->a) return -1;",
+     ["test_oracle_select.py"]),
+    ("index list left in score order",
+     "qsort(out, (size_t)c, sizeof(int32_t), by_int);", "(void)by_int;",
+     ["test_oracle_select.py"]),
+    ("budget off by one",
+     "const int c = k < nb ? k : nb;\n    int32_t *out = sel", "const int c = (k < nb ? k : nb) > 1 ? (k < nb ? k : nb) - 1 : (k < nb ? k : nb);\n    int32_t *out = sel",
+     ["test_oracle_select.py"]),
+    ("valid length ignored by the selection",
+     "const int nb = seq_lens ? seq_lens[b] : N;\n    const int c = k < nb ? k : nb;", "const int nb = N; (void)b;\n    const int c = k < nb ? k : nb;",
+     ["test_oracle_select.py"]),
+    ("block sum runs past the valid length",
+     "for (int n = m * page; n < (m + 1) * page && n < nb; ++n) {", "for (int n = m * page; n < (m + 1) * page && n < N; ++n) {",
+     ["test_oracle_blocks.py"]),
+    ("block sum skips the block's first token",
+     "for (int n = m * page; n < (m + 1) * page && n < nb; ++n) {", "for (int n = m * page + (page > 1); n < (m + 1) * page && n < nb; ++n) {",
+     ["test_oracle_blocks.py"]),
+    ("remap ignores the head map",
+     "const int j = head_map[t];\n      memcpy(indices", "const int j = t % Hd;\n      memcpy(indices",
+     ["test_oracle_select.py"]),
+    ("query head reads the wrong KV head",
+     "const int g = t / G;", "const int g = t % Hkv;",
+     ["test_oracle_attn.py"]),
+    ("scale dropped",
+     "s[j] = (double)scale * dot;\n        if (s[j] > m) m = s[j];", "s[j] = dot;\n        if (s[j] > m) m = s[j];",
+     ["test_oracle_attn.py"]),
+    ("values read from K",
+     "vr = Vg + row * stride_n;", "vr = Kg + row * stride_n;",
+     ["test_oracle_attn.py"]),
+    ("gathered row index ignored for V",
+     "const size_t row = idx ? (size_t)idx[j] : (size_t)j;\n          vr =", "const size_t row = (size_t)j;\n          vr =",
+     ["test_oracle_attn.py"]),
+    ("output not normalised",
+     "o[e] = (total > 0) ? (float)(acc[e] / l) : 0.0f;", "o[e] = (total > 0) ? (float)(acc[e]) : 0.0f;",
+     ["test_oracle_attn.py"]),
+    ("log-sum-exp with the wrong sign",
+     "(float)(m + log(l))", "(float)(m - log(l))",
+     ["test_oracle_attn.py"]),
+    ("own tokens: row i misses token i",
+     "const int nnew = k_new ? (causal ? i + 1 : Tq) : 0;", "const int nnew = k_new ? (causal ? i : Tq) : 0;",
+     ["test_oracle_attn.py"]),
+    ("own tokens of the wrong KV head",
+     "const uint16_t *kr = k_new + (((size_t)b * Tq + j) * Hkv + g) * d;", "const uint16_t *kr = k_new + (((size_t)b * Tq + j) * Hkv) * d;",
+     ["test_oracle_attn.py"]),
+    ("head mapping: the last best draft head wins",
+     "if (score > max_score) {", "if (score >= max_score) {",
+     ["test_oracle_headmap.py"]),
+    ("head mapping: overlap of the first row only",
+     "for (int r = 0; r < R; ++r) {\n            const unsigned char *x", "for (int r = 0; r < 1; ++r) {\n            const unsigned char *x",
+     ["test_oracle_headmap.py"]),
+]
+
+
+def _build(src_text, out_dir):
+    c = os.path.join(out_dir, "sts_oracle.c")
+    with open(c, "w") as f:
+        f.write(src_text)
+    lib = os.path.join(out_dir, "libmutant.so")
+    subprocess.run(["gcc", "-std=c11", "-O2", "-fopenmp", "-fno-fast-math", "-ffp-contract=off", "-fPIC", "-shared",
+                    "-I", os.path.join(ROOT, "oracle"), "-o", lib, c, "-lm"], check=True)
+    return lib
+
+
+def _run_pins(lib, files):
+    env = dict(os.environ, STS_ORACLE_LIB=lib, OMP_NUM_THREADS="2")
+    return subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider",
+                           *[os.path.join(ROOT, "tests", f) for f in files]],
+                          capture_output=True, text=True, env=env, cwd=ROOT, timeout=600)
+
+
+def test_unmodified_copy_passes_every_pin():
+    """The harness itself: the same source, built the same way, passes (so a failing mutant
+    fails because of its mistake, not because of the detour through another library)."""
+    with tempfile.TemporaryDirectory() as tmp:
+        r = _run_pins(_build(open(SRC).read(), tmp), PIN_FILES)
+        assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
+
+
+@pytest.mark.parametrize("name,old,new,files", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_planted_mistake_is_caught(name, old, new, files):
+    src = open(SRC).read()
+    assert src.count(old) == 1, f"the text this mutant replaces must occur exactly once: {old!r}"
+    with tempfile.TemporaryDirectory() as tmp:
+        r = _run_pins(_build(src.replace(old, new), tmp), files)
+        assert r.returncode == 1, f"no pin noticed: {name}\n" + r.stdout[-1500:] + r.stderr[-1500:]
+        assert " failed" in r.stdout, r.stdout[-1500:]

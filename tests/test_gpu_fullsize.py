@@ -90,6 +90,30 @@ def _sample_heads(w, idx, cnt, out, lse, samples, tag, dense=None):
                        sel=sl, what=f"{tag} dense b{b} h{t}")
 
 
+def test_c2_whole_configuration():
+    """The 32K configuration as a whole (batch 1, 10%: k = 3277): every selection row bit-exact,
+    every head of the sparse and the dense attention against the oracle, and the budget sweep
+    of the 128K configuration's fractions on the same tensors."""
+    from workload import budget_tokens
+    w = make_workload(CONFIGS["c2"], seed=2, device=DEV)
+    assert w.k_budget == 3277
+    for frac in (0.05, 0.10, 0.20):
+        kb = budget_tokens(w.cfg, frac)
+        idx, cnt, agg = sts.sts_select(w.scores, w.head_map, kb, want_agg=True)
+        out, lse = sts.sts_sparse_attn(w.q, w.k, w.v, idx, w.scale, counts=cnt, head_map=w.head_map,
+                                       out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        o_idx, o_cnt, o_agg = oracle.select_indices(w.scores.cpu().numpy(), w.head_map.numpy(), kb)
+        np.testing.assert_array_equal(agg.cpu().numpy().view(np.uint32), o_agg.view(np.uint32))
+        np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
+        np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
+        ref = oracle_attn(w.q.cpu(), w.k.cpu(), w.v.cpu(), w.scale, idx.cpu(), cnt.cpu())
+        check_attn(out, lse, ref, what=f"c2 sparse {frac:.0%}")
+    dout, dlse, _ = sts.sts_dense_attn(w.q, w.k, w.v, w.scale, out_dtype=torch.float32)
+    dref = oracle_attn(w.q.cpu(), w.k.cpu(), w.v.cpu(), w.scale, heads=range(0, 8))
+    check_attn(dout, dlse, dref, sel=(slice(0, 1), slice(0, 8)), what="c2 dense heads 0-7")
+
+
 def test_c4_one_layer_of_the_1m_context_configuration():
     """One full layer of the 1M-token configuration (4 GiB of KV): byte offsets beyond 2^32,
     selection bit-exact on whole rows at both budgets, attention on sampled heads."""

@@ -70,6 +70,24 @@ def test_c3_sparse_and_dense_sampled_heads(c3):
     assert torch.isfinite(out.float()).all() and torch.isfinite(dout.float()).all()
 
 
+@pytest.mark.parametrize("frac,want_k", [(0.05, 6554), (0.20, 26215)])
+def test_c3_budget_sweep(c3, frac, want_k):
+    """The other two points of the 128K budget sweep: whole selection rows of one batch element
+    bit-exact, sparse attention on sampled (batch, head) pairs."""
+    from workload import budget_tokens
+    w = c3
+    kb = budget_tokens(w.cfg, frac)
+    assert kb == want_k
+    idx, cnt, _ = sts.sts_select(w.scores, w.head_map, kb)
+    out, lse = sts.sts_sparse_attn(w.q, w.k, w.v, idx, w.scale, counts=cnt, head_map=w.head_map)
+    torch.cuda.synchronize()
+    b = 2
+    o_idx, o_cnt, _ = oracle.select_indices(w.scores[b:b + 1].cpu().numpy(), w.head_map.numpy(), kb)
+    np.testing.assert_array_equal(idx[b:b + 1].cpu().numpy(), o_idx)
+    np.testing.assert_array_equal(cnt[b:b + 1].cpu().numpy(), o_cnt)
+    _sample_heads(w, idx, cnt, out, lse, [(0, 7), (3, 20)], f"c3 {frac:.0%}")
+
+
 def _sample_heads(w, idx, cnt, out, lse, samples, tag, dense=None):
     G = w.cfg.Hq // w.cfg.Hkv
     for b, t in samples:

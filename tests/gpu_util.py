@@ -8,6 +8,9 @@ import oracle
 MAX_ABS = 1e-2
 MEAN_ABS = 1e-3
 LSE_ABS = 1e-3
+# and relative to the rms of the compared outputs (see check_attn)
+REL_MAX = 4e-2
+REL_MEAN = 5e-3
 
 
 def bits(t: torch.Tensor) -> np.ndarray:
@@ -37,6 +40,17 @@ def check_attn(out, lse, ref, sel=None, what=""):
     assert np.isfinite(o).all(), what
     assert err.max() <= MAX_ABS, f"{what}: max-abs {err.max():.3e}"
     assert err.mean() <= MEAN_ABS, f"{what}: mean-abs {err.mean():.3e}"
+    # The absolute bar says little when the outputs themselves are small (an average over
+    # thousands of N(0, 0.5^2) value rows is of order 1e-2 or less), so the error is also held
+    # against the scale of the compared outputs: the attention weights enter the PV product
+    # rounded to bf16 (relative 2^-9 each) and everything else is fp32, which leaves errors of
+    # about 1% of the outputs' rms at worst (measured over this suite: 1.2% max, 0.13% mean);
+    # a bf16 output adds its own rounding, up to 2^-9 of the largest element.
+    if ro.size:
+        rms = float(np.sqrt(np.mean(ro.astype(np.float64) ** 2)))
+        rounding = 2.0 ** -8 * float(np.abs(ro).max()) if out.dtype == torch.bfloat16 else 0.0
+        assert err.max() <= REL_MAX * rms + rounding + 1e-6, f"{what}: max-abs {err.max():.3e} at output rms {rms:.3e}"
+        assert err.mean() <= REL_MEAN * rms + rounding / 8 + 1e-7, f"{what}: mean-abs {err.mean():.3e} at output rms {rms:.3e}"
     fin = np.isfinite(rl)
     assert (np.isneginf(l) == np.isneginf(rl)).all(), what
     assert np.abs(l[fin] - rl[fin]).max(initial=0.0) <= LSE_ABS, f"{what}: lse {np.abs(l[fin] - rl[fin]).max():.3e}"

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import paper_2605_15508_amd as sts
-from gpu_util import check_attn, oracle_attn
+from gpu_util import check_attn, check_logits, oracle_attn
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -124,7 +124,7 @@ def test_dense_seq_lens_strided_cache_and_logits():
     check_attn(out, lse, ref, what="dense seq_lens strided")
     lg, rl = logits.cpu().numpy(), ref["logits"]
     for b, n in enumerate(lens.tolist()):
-        assert np.abs(lg[b, :, :, :n] - rl[b, :, :, :n]).max(initial=0.0) < 2e-3
+        check_logits(lg[b, :, :, :n], rl[b, :, :, :n], what=f"batch {b}")
     assert (out[2] == 0).all() and torch.isneginf(lse[2]).all()
 
 
@@ -134,7 +134,7 @@ def test_logits_dump_head_dim_64_unaligned_n():
     out, lse, logits = sts.sts_dense_attn(q, k, v, 0.125, out_dtype=torch.float32, want_logits=True)
     ref = oracle_attn(q, k, v, 0.125, want_logits=True)
     check_attn(out, lse, ref, what="dense d64 logits")
-    assert np.abs(logits.cpu().numpy() - ref["logits"]).max() < 2e-3
+    check_logits(logits.cpu().numpy(), ref["logits"])
 
 
 @pytest.mark.parametrize("d,N", [(128, 640), (64, 301), (128, 4099)])
@@ -303,7 +303,7 @@ def test_weights_summed_over_the_query_block(B, Tq, Hq, Hkv, d, N):
     for b, n in enumerate(lens.tolist()):
         assert torch.equal(A[b, :, :n], agg_d[b, :, :n])
         assert (A[b, :, n:] == 0).all()
-        assert (np.abs(got[b, :, :n] - ref_A[b, :, :n]) <= 5e-3 * ref_A[b, :, :n] + 1e-7).all()
+        assert (np.abs(got[b, :, :n] - ref_A[b, :, :n]) <= 3e-5 * ref_A[b, :, :n] + 1e-10).all()
         # each row's weights sum to one, so the aggregate sums to Tq
         assert np.allclose(got[b, :, :n].sum(-1, dtype=np.float64), Tq, atol=2e-3)
     # without a caller's lse buffer the normalisers live in the workspace (no dump: the first

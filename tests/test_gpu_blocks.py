@@ -10,7 +10,7 @@ import torch
 
 import oracle
 import paper_2605_15508_amd as sts
-from gpu_util import check_attn, oracle_attn
+from gpu_util import check_attn, check_logits, oracle_attn
 from workload import CONFIGS, make_workload
 
 pytestmark = pytest.mark.gpu
@@ -128,7 +128,7 @@ def test_paged_cache_sparse_and_dense(page):
     check_attn(dout, dlse, dref, what=f"paged dense p{page}")
     lg = dlog.cpu().numpy()
     for b, n in enumerate(lens.tolist()):
-        assert np.abs(lg[b, :, :, :n] - dref["logits"][b, :, :, :n]).max() < 2e-3
+        check_logits(lg[b, :, :, :n], dref["logits"][b, :, :, :n], what=f"batch {b}")
 
 
 def test_block_chain_select_then_attention_on_the_4k_configuration():

@@ -141,7 +141,7 @@ def test_select_logits_lse_stagewise():
 def test_select_then_sparse_attention_on_the_4k_configuration():
     """The whole path on the small configuration: planted workload, selection bit-exact,
     sparse attention within tolerance, everything against the oracle."""
-    from gpu_util import check_attn, oracle_attn
+    from gpu_util import check_attn, check_logits, oracle_attn
 
     w = make_workload(CONFIGS["c1"], seed=20251127)
     q, k, v, scores = w.q.to(DEV), w.k.to(DEV), w.v.to(DEV), w.scores.to(DEV)
@@ -166,7 +166,7 @@ def test_draft_attention_to_selection_to_sparse_attention_chain():
     Checked stage by stage against the oracle."""
     from dataclasses import replace
 
-    from gpu_util import check_attn, oracle_attn
+    from gpu_util import check_attn, check_logits, oracle_attn
     from workload import make_draft_layer
 
     cfg = replace(CONFIGS["c5"], B=2, N=3000)
@@ -179,7 +179,7 @@ def test_draft_attention_to_selection_to_sparse_attention_chain():
     d_out, d_lse, d_logits = sts.sts_dense_attn(qd, kd, vd, dl["scale"], want_logits=True, out_dtype=torch.float32)
     ref_d = oracle_attn(qd, kd, vd, dl["scale"], want_logits=True)
     check_attn(d_out, d_lse, ref_d, what="draft dense")
-    assert np.abs(d_logits.cpu().numpy() - ref_d["logits"]).max() < 2e-3
+    check_logits(d_logits.cpu().numpy(), ref_d["logits"], what="draft logits")
     # stage a1-a3 on the GPU's own logits (identical score tensors on both sides)
     idx, cnt, agg = sts.sts_select(d_logits, w.head_map, kb, lse=d_lse, kind=sts.STS_SCORES_LOGITS_LSE,
                                    want_agg=True)
@@ -253,8 +253,8 @@ def test_per_head_budgets_feed_sparse_attention():
     np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
     ref = oracle.attn(oracle.bf16_bits(w.q), oracle.bf16_bits(w.k), oracle.bf16_bits(w.v), w.scale,
                       indices=o_idx, counts=o_cnt)
-    assert np.abs(out.cpu().numpy() - ref["out"]).max() < 1e-2
-    assert np.abs(lse.cpu().numpy() - ref["lse"]).max() < 1e-3
+    from gpu_util import check_attn
+    check_attn(out, lse, ref, what="per-head budgets")
 
 
 @pytest.mark.parametrize("spin_limit", ["0", "3"])

@@ -220,4 +220,4 @@ def test_random_summed_weights_case(seed):
         assert (A[b, :, n:] == 0).all(), what
         if n > 0:
             ref_A = oracle.aggregate(ref["logits"][b:b + 1, :, :, :n].copy(), ref["lse"][b:b + 1], kind=oracle.LOGITS_LSE)[0]
-            assert (np.abs(got[b, :, :n] - ref_A) <= 5e-3 * ref_A + 1e-7).all(), what
+            assert (np.abs(got[b, :, :n] - ref_A) <= 3e-5 * ref_A + 1e-10).all(), what

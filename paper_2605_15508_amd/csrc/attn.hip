@@ -699,8 +699,9 @@ hipError_t launch_split_d(const AttnArgs &a, int nq, bool sparse, hipStream_t s)
 // Layout: S = Q K^T leaves lane (a, b) with rows 4a..4a+3 of a 16-row query tile for key b, so
 // with Tq padded to a power of two Tp (padding rows weigh +0) a head's rows are registers of one
 // lane (Tp <= 4) or of Tp/4 lanes 16 apart (Tp = 8, 16). The sum over rows is a left-to-right
-// fold: inside the lane, then handed on from lane to lane. The kernel is bound by vector ALU
-// work per tile, not by memory, which is why the fold is arranged to take few instructions.
+// fold: inside the lane, then handed on from lane to lane (a fold along 16 lanes with shifted
+// adds took more than twice the vector instructions per tile). What bounds the kernel is the
+// memory system: a thin write stream mixed into the read stream.
 template <int TP>
 __device__ __forceinline__ void fold_rows(const float (&p)[4], float (&s)[4], int a) {
   constexpr int RPL = TP < 4 ? TP : 4;       // rows of one head held by a lane

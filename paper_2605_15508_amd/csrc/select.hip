@@ -277,12 +277,27 @@ __global__ void __launch_bounds__(SEL_THREADS) select_agg_kernel(const SelectArg
   const int n0 = chunk * SEL_CHUNK;
   const int n1 = min(n0 + SEL_CHUNK, A.N);
   if (VEC4) {
-    for (int n = n0 + threadIdx.x * 4; n < n1; n += SEL_THREADS * 4) {
-      const f32x4 acc = agg_quad(R, n);
-      if (!A.agg_is_input) *reinterpret_cast<f32x4 *>(out + n) = acc;
+    // The chunk's sums wait in registers and are stored in one burst after the last read: a
+    // write stream mixed into the read stream costs this memory system far more than its bytes,
+    // and with the workgroups of a launch running in step the two phases separate chip-wide.
+    constexpr int IT = SEL_CHUNK / (SEL_THREADS * 4);
+    f32x4 keep[IT];
+#pragma clang loop unroll(full)
+    for (int i = 0; i < IT; ++i) {
+      const int n = n0 + (i * SEL_THREADS + (int)threadIdx.x) * 4;
+      if (n < n1) {
+        keep[i] = agg_quad(R, n);
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if (A.page == 1 && n + e < nb) atomicAdd(&h[key_of(acc[e]) >> (32 - SEL_BITS0)], 1u);
+        for (int e = 0; e < 4; ++e)
+          if (A.page == 1 && n + e < nb) atomicAdd(&h[key_of(keep[i][e]) >> (32 - SEL_BITS0)], 1u);
+      }
+    }
+    if (!A.agg_is_input) {
+#pragma clang loop unroll(full)
+      for (int i = 0; i < IT; ++i) {
+        const int n = n0 + (i * SEL_THREADS + (int)threadIdx.x) * 4;
+        if (n < n1) *reinterpret_cast<f32x4 *>(out + n) = keep[i];
+      }
     }
   } else {
     for (int n = n0 + threadIdx.x; n < n1; n += SEL_THREADS) {

@@ -138,7 +138,11 @@ sts_status plan_attn(const sts_attn_params *p, int sparse, AttnPlan &pl) {
   pl.nq = max_rows <= 16 ? 1 : (max_rows <= 32 ? 2 : 4);
   const int64_t len = sparse ? (int64_t)p->kmax * page_of(p) : p->N;
   const int64_t tiles = (len + STS_TILE_KEYS - 1) / STS_TILE_KEYS;
-  int64_t resident = (int64_t)cu_count() * (pl.nq == 4 ? 1 : 2);
+  // Workgroups per CU the split count aims at. Two for the gather (its two dependent latencies
+  // per tile want more waves) and for head size 64; one for the dense kernel at head size 128,
+  // where a second workgroup per CU only costs (c3 dense 348 -> 324 us, 32K dense 51 -> 44 us),
+  // and for four query tiles (one workgroup fills the register file).
+  int64_t resident = (int64_t)cu_count() * ((pl.nq == 4 || (!sparse && p->d == 128)) ? 1 : 2);
   if (const char *e = getenv("STS_ATTN_WGS_PER_CU")) {   // tuning knob: target workgroups per CU
     const double f = atof(e);
     if (f > 0.0) resident = (int64_t)(cu_count() * f);

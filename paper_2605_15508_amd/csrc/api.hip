@@ -140,7 +140,8 @@ sts_status plan_attn(const sts_attn_params *p, int sparse, AttnPlan &pl) {
   const int64_t tiles = (len + STS_TILE_KEYS - 1) / STS_TILE_KEYS;
   // Workgroups per CU the split count aims at. Two for the gather (its two dependent latencies
   // per tile want more waves) and for head size 64; one for the dense kernel at head size 128,
-  // where a second workgroup per CU only costs (c3 dense 348 -> 324 us, 32K dense 51 -> 44 us),
+  // where a second workgroup per CU only costs (128K context, batch 4: 348 -> 324 us; 32K,
+  // batch 1: 51 -> 44 us),
   // and for four query tiles (one workgroup fills the register file).
   int64_t resident = (int64_t)cu_count() * ((pl.nq == 4 || (!sparse && p->d == 128)) ? 1 : 2);
   if (const char *e = getenv("STS_ATTN_WGS_PER_CU")) {   // tuning knob: target workgroups per CU

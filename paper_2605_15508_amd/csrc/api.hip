@@ -143,7 +143,9 @@ sts_status plan_attn(const sts_attn_params *p, int sparse, AttnPlan &pl) {
   // where a second workgroup per CU only costs (128K context, batch 4: 348 -> 324 us; 32K,
   // batch 1: 51 -> 44 us),
   // and for four query tiles (one workgroup fills the register file).
-  int64_t resident = (int64_t)cu_count() * ((pl.nq == 4 || (!sparse && p->d == 128)) ? 1 : 2);
+  // The gather with two query tiles at head size 128 (as register-bound as the dense kernel)
+  // is 3% faster with one as well.
+  int64_t resident = (int64_t)cu_count() * ((pl.nq == 4 || (p->d == 128 && (!sparse || pl.nq == 2))) ? 1 : 2);
   if (const char *e = getenv("STS_ATTN_WGS_PER_CU")) {   // tuning knob: target workgroups per CU
     const double f = atof(e);
     if (f > 0.0) resident = (int64_t)(cu_count() * f);

@@ -60,3 +60,54 @@ def test_graph_replays_match_eager(N, budget):
         torch.cuda.synchronize()
         for got, ref in zip((idx, cnt, out, lse, dout), want):
             assert torch.equal(got, ref)
+
+
+def test_graph_replays_of_the_draft_chain_match_eager():
+    """Draft attention with its summed weights -> in-place selection -> sparse attention, captured
+    and replayed with new inputs (the second pass over K and the histogram-only first pass of the
+    selection are ordinary kernel nodes as well)."""
+    B, Tq, Hq, Hkv, d, N, Hd, dd, k = 2, 4, 8, 2, 128, 40000, 4, 64, 9000
+    hm = [t * Hd // Hq for t in range(Hq)]
+    g = torch.Generator().manual_seed(11)
+
+    def fresh():
+        return dict(q=torch.randn(B, Tq, Hq, d, generator=g).to(torch.bfloat16),
+                    k=(torch.randn(B, Hkv, N, d, generator=g) * 0.5).to(torch.bfloat16),
+                    v=(torch.randn(B, Hkv, N, d, generator=g) * 0.5).to(torch.bfloat16),
+                    qd=torch.randn(B, Tq, Hd, dd, generator=g).to(torch.bfloat16),
+                    kd=(torch.randn(B, Hkv, N, dd, generator=g) * 0.5).to(torch.bfloat16),
+                    vd=(torch.randn(B, Hkv, N, dd, generator=g) * 0.5).to(torch.bfloat16))
+    sets = [fresh() for _ in range(3)]
+    buf = {n: t.to(DEV).clone() for n, t in sets[0].items()}
+    A = torch.empty(B, Hd, N, dtype=torch.float32, device=DEV)
+    dout = torch.empty(B, Tq, Hd, dd, dtype=torch.bfloat16, device=DEV)
+    idx = torch.empty(B, Hq, k, dtype=torch.int32, device=DEV)
+    cnt = torch.empty(B, Hq, dtype=torch.int32, device=DEV)
+    out = torch.empty(B, Tq, Hq, d, dtype=torch.float32, device=DEV)
+    lse = torch.empty(B, Hq, Tq, dtype=torch.float32, device=DEV)
+
+    def path():
+        sts.sts_dense_attn(buf["qd"], buf["kd"], buf["vd"], 0.125, out=dout, want_lse=False, weights_sum_out=A)
+        sts.sts_select(A.view(B, Hd, 1, N), hm, k, out=(idx, cnt))
+        sts.sts_sparse_attn(buf["q"], buf["k"], buf["v"], idx, 0.09, counts=cnt, head_map=hm, out=out, lse_out=lse)
+
+    path()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        path()
+    torch.cuda.synchronize()
+    for s in sets + sets[:1]:
+        for n, t in s.items():
+            buf[n].copy_(t.to(DEV))
+        path()
+        torch.cuda.synchronize()
+        want = [t.clone() for t in (A, idx, cnt, out, lse)]
+        for t in (A, out, lse):
+            t.fill_(float("nan"))
+        idx.fill_(0); cnt.fill_(0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((A, idx, cnt, out, lse), want):
+            assert torch.equal(got, ref)

@@ -61,6 +61,14 @@ def parse_args():
                     help="draft-layer configuration: the draft attention dumps its logits and sts_select aggregates "
                          "them (dump), or it sums the attention weights over the query block itself in a second "
                          "pass over K and sts_select ranks that aggregate (sum)")
+    ap.add_argument("--fused-tail", action="store_true",
+                    help="also pass the speculative block's own keys/values (k_new, v_new) to the attention calls, "
+                         "which then append them causally inside the combine step")
+    ap.add_argument("--prefill-blocks", type=int, default=0,
+                    help="other mode: chunked sparse prefill, this many 16-row query blocks over ONE shared cache "
+                         "of the configuration's context (batch 1), each block with its own mask; prints its own JSON line")
+    ap.add_argument("--headmap", action="store_true",
+                    help="other mode: offline head-mapping construction (Algorithm 1) on synthetic traces; prints its own JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (scales rocprofv3 --pmc byte counters)")
     return ap.parse_args()
@@ -137,6 +145,90 @@ def cpu_baseline(w, idx, cnt, page=1, budget_s=25.0, scores=None, lse=None):
     }
 
 
+def _timed(fn, steps, warmup, torch):
+    """Median / mean of `steps` event-timed calls of fn() on the current stream, microseconds."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    xs = sorted(a.elapsed_time(b) * 1e3 for a, b in ev)
+    return {"median": round(statistics.median(xs), 2), "mean": round(statistics.fmean(xs), 2),
+            "min": round(xs[0], 2), "p90": round(xs[min(len(xs) - 1, int(0.9 * len(xs)))], 2)}
+
+
+def run_prefill(args, torch, sts):
+    """Chunked sparse prefill (2-D masks: one mask per block of 16 query rows and head). NB query
+    blocks are one batch over a single shared cache (kv_stride_b = 0); block i sees the first
+    N - 16*(NB-1-i) cached tokens and adds its own 16 tokens causally. Draft scores are bf16."""
+    from dataclasses import replace
+
+    from workload import CONFIGS, budget_tokens, make_workload
+    dev = torch.device("cuda:0")
+    cfg = replace(CONFIGS[args.config], B=1, Tq=16)
+    NB, T = args.prefill_blocks, 16
+    w = make_workload(cfg, seed=args.seed, device=dev, budget=args.budget, with_scores=False)
+    N, Hq, Hkv, d, Hd = cfg.N, cfg.Hq, cfg.Hkv, cfg.d, cfg.Hd
+    k = budget_tokens(cfg, args.budget)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed + 17)
+    q = torch.randn(NB, T, Hq, d, generator=gen, device=dev).to(torch.bfloat16)
+    kn = (torch.randn(NB, T, Hkv, d, generator=gen, device=dev) * 0.5).to(torch.bfloat16)
+    vn = (torch.randn(NB, T, Hkv, d, generator=gen, device=dev) * 0.5).to(torch.bfloat16)
+    lens = (N - T * (NB - 1 - torch.arange(NB, device=dev))).to(torch.int32)
+    scores = torch.empty(NB, Hd, T, N, dtype=torch.bfloat16, device=dev)
+    for b in range(NB):      # softmax of random logits over the visible prefix, block by block
+        lg = torch.randn(Hd, T, N, generator=gen, device=dev) * 2
+        lg[:, :, int(lens[b]):] = float("-inf")
+        scores[b] = torch.softmax(lg, dim=-1).to(torch.bfloat16)
+        del lg
+    kx, vx = w.k.expand(NB, Hkv, N, d), w.v.expand(NB, Hkv, N, d)
+    idx = torch.empty(NB, Hq, k, dtype=torch.int32, device=dev)
+    cnt = torch.empty(NB, Hq, dtype=torch.int32, device=dev)
+    out = torch.empty(NB, T, Hq, d, dtype=torch.bfloat16, device=dev)
+    sel = lambda: sts.sts_select(scores, w.head_map, k, seq_lens=lens, out=(idx, cnt))
+    att = lambda: sts.sts_sparse_attn(q, kx, vx, idx, w.scale, counts=cnt, head_map=w.head_map, out=out,
+                                      want_lse=False, k_new=kn, v_new=vn, causal=True)
+    t_sel = _timed(sel, args.steps, args.warmup, torch)
+    t_att = _timed(att, args.steps, args.warmup, torch)
+    plan = sts.attn_plan(q, torch.empty(NB, Hkv, N, d, device="meta"), True, kmax=k, head_map=w.head_map)
+    b_set = NB * plan["units_per_batch"] * k * 2 * d * 2
+    print(json.dumps({
+        "metric": "chunked sparse prefill: attention us per 16-token query block over a shared cache", "unit": "us/block",
+        "value": round(t_att["median"] / NB, 2), "higher_is_better": False, "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+        "steps": args.steps, "warmup": args.warmup,
+        "config": {"workload": f"{cfg.name} shape, one cache of N{N} Hq{Hq}/Hkv{Hkv} d{d}, {NB} blocks of {T} rows, "
+                               f"budget {k} tokens per head and block, draft scores bf16 [{NB},{Hd},{T},{N}]"},
+        "sparse_attn_us": t_att, "select_us": t_sel, "gathered_kv_bytes_b_set": b_set,
+        "gathered_kv_gbs_b_set": round(b_set / (t_att["median"] * 1e-6) / 1e9, 1), "launch": plan}))
+
+
+def run_headmap(args, torch, sts):
+    """Algorithm 1 on synthetic attention-weight traces of both models (offline step)."""
+    dev = torch.device("cuda:0")
+    S, R, Hd, Ht, N, k = 2, 128, 16, 32, 32768, 512
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed)
+    a_d = torch.softmax(torch.randn(S, Hd, R, N, generator=gen, device=dev) * 2, dim=-1)
+    # target heads follow a planted draft head plus noise, so the map has something to find
+    planted = torch.randint(0, Hd, (Ht,), generator=gen, device=dev)
+    a_t = torch.softmax(torch.log(a_d[:, planted]) + torch.randn(S, Ht, R, N, generator=gen, device=dev), dim=-1)
+    res = {}
+    fn = lambda: res.update(r=sts.sts_head_map(a_d, a_t, k))
+    t = _timed(fn, max(3, min(args.steps, 10)), 2, torch)
+    mp = res["r"][0].cpu()
+    print(json.dumps({
+        "metric": "offline head-mapping construction (Algorithm 1), ms per call", "unit": "ms", "value": round(t["median"] / 1e3, 3),
+        "higher_is_better": False, "n_gpus": 1, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"traces a_d [{S},{Hd},{R},{N}] and a_t [{S},{Ht},{R},{N}] fp32, top-{k} per row"},
+        "call_us": t, "planted_map_recovered": bool((mp == planted.cpu().to(mp.dtype)).all()),
+        "trace_bytes": int(a_d.numel() * 4 + a_t.numel() * 4)}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -156,6 +248,10 @@ def main():
     sts.load_library()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.prefill_blocks > 0:
+        return run_prefill(args, torch, sts)
+    if args.headmap:
+        return run_headmap(args, torch, sts)
     cfg = CONFIGS[args.config]
     if args.gain is not None:
         cfg = replace(cfg, gain=args.gain)
@@ -220,6 +316,13 @@ def main():
             d_logits = torch.empty(B, Hd, Tq, N, dtype=torch.bfloat16 if args.scores == "bf16" else torch.float32, device=dev)
     elif args.scores == "bf16":
         w.scores = w.scores.to(torch.bfloat16)
+
+    if args.fused_tail:
+        tg = torch.Generator(device=dev)
+        tg.manual_seed(args.seed + 5)
+        pg["k_new"] = (torch.randn(B, Tq, Hkv, d, generator=tg, device=dev) * 0.5).to(torch.bfloat16)
+        pg["v_new"] = (torch.randn(B, Tq, Hkv, d, generator=tg, device=dev) * 0.5).to(torch.bfloat16)
+        pg["causal"] = True
 
     def step(ev=None, layer=0):
         lk, lv = layers[layer]
@@ -327,7 +430,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": workload, "context": N, "batch": B, "budget_tokens": kb * page, "page_size": page, "paged_kv": bool(args.paged),
-                   "layers": L, "cache": "cold: every pass reads KV that has left the caches" if (L > 1 or kv_bytes > (256 << 20)) else "warm", "head_map": "t*Hd//Hq" if args.head_map == "default" else "seeded random", "gain": cfg.gain, "heavy_positions": args.positions, "scores": args.scores, "step": ("%d layers x (" % L if L > 1 else "(") + "select + sparse_attn" + ("" if args.no_dense else " + dense_attn")
+                   "layers": L, "cache": "cold: every pass reads KV that has left the caches" if (L > 1 or kv_bytes > (256 << 20)) else "warm", "head_map": "t*Hd//Hq" if args.head_map == "default" else "seeded random", "gain": cfg.gain, "heavy_positions": args.positions, "scores": args.scores, "fused_tail": bool(args.fused_tail), "step": ("%d layers x (" % L if L > 1 else "(") + "select + sparse_attn" + ("" if args.no_dense else " + dense_attn")
                    + ((" + draft dense attn with logits dump" if d_sum is None else " + draft dense attn with summed weights") if draft is not None else "") + ")"},
         "sparse_attn_us": {"mean": round(sparse_us[0], 2), "median": round(sparse_us[1], 2), "min": round(sparse_us[2], 2), "p10": round(sparse_us[3], 2), "p90": round(sparse_us[4], 2)},
         "dense_attn_us": None if args.no_dense else {"mean": round(dense_us[0], 2), "median": round(dense_us[1], 2), "min": round(dense_us[2], 2), "p10": round(dense_us[3], 2), "p90": round(dense_us[4], 2)},

@@ -221,7 +221,7 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
   a.k_new = static_cast<const uint16_t *>(p->k_new);
   a.v_new = static_cast<const uint16_t *>(p->v_new);
   a.causal = p->causal;
-  a.direct = (pl.num_splits == 1 && !p->k_new) ? 1 : 0;
+  a.direct = (pl.num_splits == 1) ? 1 : 0;
   a.num_units = pl.num_units;
   a.num_splits = pl.num_splits;
   a.scale = p->scale;

@@ -468,7 +468,7 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
         }
       }
       if (A.direct) {
-        // single split and nothing to append: this workgroup holds the whole result of its
+        // single split: this workgroup holds the whole result of its
         // rows, so it normalises and writes them itself and no combine kernel is launched
         const int r = nq * 16 + row;
         if (r < rows_valid) {
@@ -481,9 +481,40 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
             const float mw = lds_ml[w][r][0];
             L += (mw == -INFINITY) ? 0.f : lds_ml[w][r][1] * __builtin_amdgcn_exp2f(mw - ms);
           }
-          const float inv = (L > 0.f) ? 1.f / L : 0.f;
           const int hsel = r / A.Tq, tq = r - hsel * A.Tq;
           const int head = g * A.G + nth_member(mask, hsel);
+          // The speculative block's own tokens (see the combine kernel, which does the same for
+          // split lists): candidate tq also attends to candidates 0..tq, merged here like one more
+          // partial each, in order. The 16 threads of a row hold D/16 channels each.
+          if (A.k_new) {
+            typedef typename Chunk<D>::type seg_t;          // D/16 bf16 values = 16 or 8 bytes
+            auto widen = [](uint32_t w, int hi) -> float {
+              return __builtin_bit_cast(float, hi ? (w & 0xffff0000u) : (w << 16));
+            };
+            const seg_t qw = *reinterpret_cast<const seg_t *>(A.q + (((size_t)bt * A.Tq + tq) * A.Hq + head) * D + seg * SEGF);
+            const int nnew = A.causal ? tq + 1 : A.Tq;
+            for (int j = 0; j < nnew; ++j) {               // the 16 threads of a row share nnew
+              const size_t nrow = (((size_t)bt * A.Tq + j) * A.Hkv + g) * D + seg * SEGF;
+              const seg_t kw = *reinterpret_cast<const seg_t *>(A.k_new + nrow);
+              const seg_t vw = *reinterpret_cast<const seg_t *>(A.v_new + nrow);
+              float dot = 0.f;
+#pragma unroll
+              for (int e = 0; e < SEGF; ++e) dot += widen(qw[e >> 1], e & 1) * widen(kw[e >> 1], e & 1);
+              dot += __shfl_xor(dot, 1, 64);
+              dot += __shfl_xor(dot, 2, 64);
+              dot += __shfl_xor(dot, 4, 64);
+              dot += __shfl_xor(dot, 8, 64);
+              const float m2 = dot * A.scale_log2;
+              const float mnew = fmaxf(ms, m2);
+              const float fo = __builtin_amdgcn_exp2f(ms - mnew);   // 0 while nothing is accumulated
+              const float fn = __builtin_amdgcn_exp2f(m2 - mnew);
+              L = L * fo + fn;
+#pragma unroll
+              for (int e = 0; e < SEGF; ++e) sum[e] = sum[e] * fo + widen(vw[e >> 1], e & 1) * fn;
+              ms = mnew;
+            }
+          }
+          const float inv = (L > 0.f) ? 1.f / L : 0.f;
           const size_t orow = (((size_t)bt * A.Tq + tq) * A.Hq + head) * D + seg * SEGF;
           if (A.out_dtype == STS_F32) {
             float *dst = reinterpret_cast<float *>(A.out) + orow;

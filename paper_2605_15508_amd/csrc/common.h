@@ -55,7 +55,7 @@ struct AttnArgs {
   int64_t stride_page;                    // elements between pages of the pool
   const uint16_t *k_new, *v_new;          // [B,Tq,Hkv,d] the block's own keys/values, or NULL
   int32_t causal;
-  int32_t direct;                         // single split, no tail: the split kernel writes the result
+  int32_t direct;                         // single split: the split kernel writes the result itself
   float scale_log2;                       // scale * log2(e)
   float scale;
   float *part_o;                          // [B*U*S][NQ*16][D]

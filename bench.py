@@ -63,7 +63,7 @@ def parse_args():
                          "pass over K and sts_select ranks that aggregate (sum)")
     ap.add_argument("--fused-tail", action="store_true",
                     help="also pass the speculative block's own keys/values (k_new, v_new) to the attention calls, "
-                         "which then append them causally inside the combine step")
+                         "which then append them causally in their final merge")
     ap.add_argument("--prefill-blocks", type=int, default=0,
                     help="other mode: chunked sparse prefill, this many 16-row query blocks over ONE shared cache "
                          "of the configuration's context (batch 1), each block with its own mask; prints its own JSON line")

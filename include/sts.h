@@ -146,7 +146,7 @@ typedef struct {
  * The speculative block's own tokens (paper Section 2.1: the target checks all candidates in
  * one parallel step, so candidate i also attends to the candidates before it). Their keys and
  * values are not in the cache yet; pass them as k_new / v_new and they are appended after the
- * cached keys of every query row (causally when `causal` is set) inside the combine step, so
+ * cached keys of every query row (causally when `causal` is set) in the final merge of the call, so
  * out and lse_out cover the whole verification attention. Without them the caller merges that
  * part itself using lse_out.
  *

@@ -564,8 +564,8 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
 // Combine the per-split partials and write the final rows. One workgroup of 256 threads per
 // (batch, unit, query tile, group of 4 rows): wave w merges the splits w, w+4, w+8, ... of its
 // 4 rows (thread = row, D/16 channels; loads in independent batches), the four waves are then
-// merged through LDS in wave order by wave 0, which also appends the block's own tokens and
-// writes the result. The order of all merges is fixed, so results are identical run to run.
+// merged through LDS in wave order by wave 0, which writes the result; the block's own tokens
+// enter as the first entries of wave 3's share. The order of all merges is fixed, so results are identical run to run.
 template <int D>
 __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs A, const int NQ) {
   constexpr int SEGF = D / 16;
@@ -603,6 +603,48 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs A, con
     for (int e = 0; e < SEGF; ++e) o[e] = o[e] * fo + x[e] * fn;
     mstar = mnew;
   };
+  // The speculative block's own tokens: candidate tq also attends to candidates 0..tq (all of
+  // them when not causal). They are the first entries of the last wave's share, so their loads
+  // go out together with the partials' and add no latency of their own. The 16 threads of a row
+  // each hold D/16 channels: partial dot products are summed across the row's 16 lanes, then
+  // every token is merged like one more partial, in order.
+  if (A.k_new && wave == 3 && valid) {
+    const int hsel_t = r / A.Tq, tq_t = r - hsel_t * A.Tq;
+    const int head_t = g * A.G + nth_member(mask, hsel_t);
+    typedef typename Chunk<D>::type seg_t;          // D/16 bf16 values = 16 or 8 bytes
+    auto widen = [](uint32_t w, int hi) -> float {
+      return __builtin_bit_cast(float, hi ? (w & 0xffff0000u) : (w << 16));
+    };
+    const seg_t qw = *reinterpret_cast<const seg_t *>(A.q + (((size_t)bt * A.Tq + tq_t) * A.Hq + head_t) * D + seg * SEGF);
+    const int nnew = A.causal ? tq_t + 1 : A.Tq;
+    // all rows are asked for before the first one is used (a load per trip would cost a
+    // memory latency per token)
+    seg_t kw[16], vw[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      if (j < A.Tq) {                               // Tq <= 16
+        const size_t nrow = (((size_t)bt * A.Tq + j) * A.Hkv + g) * D + seg * SEGF;
+        kw[j] = *reinterpret_cast<const seg_t *>(A.k_new + nrow);
+        vw[j] = *reinterpret_cast<const seg_t *>(A.v_new + nrow);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      if (j < nnew) {                               // the 16 threads of a row share nnew
+        float dot = 0.f;
+#pragma unroll
+        for (int e = 0; e < SEGF; ++e) dot += widen(qw[e >> 1], e & 1) * widen(kw[j][e >> 1], e & 1);
+        dot += __shfl_xor(dot, 1, 64);
+        dot += __shfl_xor(dot, 2, 64);
+        dot += __shfl_xor(dot, 4, 64);
+        dot += __shfl_xor(dot, 8, 64);
+        float vs[SEGF];
+#pragma unroll
+        for (int e = 0; e < SEGF; ++e) vs[e] = widen(vw[j][e >> 1], e & 1);
+        merge(dot * A.scale_log2, 1.f, vs);
+      }
+    }
+  }
   for (int s0 = wave; s0 < S; s0 += 4 * BATCH) {
     float ms[BATCH], ls[BATCH];
     f32x4 x[BATCH][SEGF / 4];
@@ -638,35 +680,6 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs A, con
 
   const int hsel = r / A.Tq, tq = r - hsel * A.Tq;
   const int head = g * A.G + nth_member(mask, hsel);
-  // The speculative block's own tokens: candidate tq also attends to candidates 0..tq (all of
-  // them when not causal). The 16 threads of a row each hold D/16 channels: partial dot
-  // products are summed across the row's 16 lanes, then merged like one more split, in order.
-  if (A.k_new) {
-    typedef typename Chunk<D>::type seg_t;          // D/16 bf16 values = 16 or 8 bytes
-    auto widen = [](uint32_t w, int hi) -> float {
-      return __builtin_bit_cast(float, hi ? (w & 0xffff0000u) : (w << 16));
-    };
-    const seg_t qw = *reinterpret_cast<const seg_t *>(A.q + (((size_t)bt * A.Tq + tq) * A.Hq + head) * D + seg * SEGF);
-    const int nnew = A.causal ? tq + 1 : A.Tq;
-    for (int j = 0; j < A.Tq; ++j) {               // same trip count for every row of the wave
-      const size_t nrow = (((size_t)bt * A.Tq + j) * A.Hkv + g) * D + seg * SEGF;
-      const seg_t kw = *reinterpret_cast<const seg_t *>(A.k_new + nrow);
-      const seg_t vw = *reinterpret_cast<const seg_t *>(A.v_new + nrow);
-      float dot = 0.f;
-#pragma unroll
-      for (int e = 0; e < SEGF; ++e) dot += widen(qw[e >> 1], e & 1) * widen(kw[e >> 1], e & 1);
-      dot += __shfl_xor(dot, 1, 64);
-      dot += __shfl_xor(dot, 2, 64);
-      dot += __shfl_xor(dot, 4, 64);
-      dot += __shfl_xor(dot, 8, 64);
-      if (j < nnew) {
-        float vs[SEGF];
-#pragma unroll
-        for (int e = 0; e < SEGF; ++e) vs[e] = widen(vw[e >> 1], e & 1);
-        merge(dot * A.scale_log2, 1.f, vs);
-      }
-    }
-  }
   const float inv = (L > 0.f) ? 1.f / L : 0.f;
   const size_t orow = (((size_t)bt * A.Tq + tq) * A.Hq + head) * D + seg * SEGF;
   if (A.out_dtype == STS_F32) {

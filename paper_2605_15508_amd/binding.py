@@ -126,9 +126,11 @@ def _ptr(t) -> Optional[int]:
 
 
 def _stream() -> int:
+    """Raw handle of torch's current stream on the current device (the cheap accessor: the
+    Stream object behind torch.cuda.current_stream() costs several microseconds per call)."""
     import torch
 
-    return torch.cuda.current_stream().cuda_stream
+    return torch._C._cuda_getCurrentRawStream(torch.cuda.current_device())
 
 
 _ws_cache: Dict[Tuple[str, int], "object"] = {}
@@ -146,9 +148,19 @@ def _workspace(tag: str, nbytes: int, device):
     return buf
 
 
+_i32_cache: Dict[tuple, ctypes.Array] = {}
+
+
 def _host_i32(seq) -> ctypes.Array:
-    vals = [int(x) for x in (seq.tolist() if hasattr(seq, "tolist") else seq)]
-    return (ctypes.c_int32 * len(vals))(*vals)
+    """Host int32 array for a short list of ints (head maps, budgets); arrays are cached by value."""
+    vals = tuple(seq.tolist() if hasattr(seq, "tolist") else seq)
+    arr = _i32_cache.get(vals)
+    if arr is None:
+        if len(_i32_cache) > 256:
+            _i32_cache.clear()
+        arr = (ctypes.c_int32 * len(vals))(*[int(x) for x in vals])
+        _i32_cache[vals] = arr
+    return arr
 
 
 def sts_select(scores, head_map, k: int, lse=None, seq_lens=None, kind: int = STS_SCORES_PROBS,

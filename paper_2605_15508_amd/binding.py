@@ -1,6 +1,11 @@
 """ctypes binding of include/sts.h. Argument marshalling only.
 
 torch is used for device memory (outputs, workspace) and for the current HIP stream.
+
+Workspaces: without a `workspace=` argument a call uses one cached scratch buffer per kind of
+call (selection, attention, head mapping) and device, which is right for calls issued on one
+stream. Calls of the same kind that may overlap on different streams must each bring their own
+`workspace=` tensor (sized with the library's *_workspace_bytes), as the C interface requires.
 """
 from __future__ import annotations
 

@@ -2,10 +2,9 @@
 
 torch is used for device memory (outputs, workspace) and for the current HIP stream.
 
-Workspaces: without a `workspace=` argument a call uses one cached scratch buffer per kind of
-call (selection, attention, head mapping) and device, which is right for calls issued on one
-stream. Calls of the same kind that may overlap on different streams must each bring their own
-`workspace=` tensor (sized with the library's *_workspace_bytes), as the C interface requires.
+Workspaces: without a `workspace=` argument a call uses a cached scratch buffer per kind of
+call (selection, attention, head mapping), device and stream, so calls that may overlap on
+different streams never share scratch (the C interface leaves that to the caller).
 """
 from __future__ import annotations
 
@@ -138,14 +137,16 @@ def _stream() -> int:
     return torch._C._cuda_getCurrentRawStream(torch.cuda.current_device())
 
 
-_ws_cache: Dict[Tuple[str, int], "object"] = {}
+_ws_cache: Dict[Tuple[str, int, int], "object"] = {}
 
 
 def _workspace(tag: str, nbytes: int, device):
     """A cached device scratch buffer (256-byte aligned by the torch allocator)."""
     import torch
 
-    key = (tag, device.index if device.index is not None else torch.cuda.current_device())
+    # one buffer per kind of call, device and stream: calls that may overlap (different streams)
+    # never share scratch, calls on one stream are ordered anyway
+    key = (tag, device.index if device.index is not None else torch.cuda.current_device(), _stream())
     buf = _ws_cache.get(key)
     if buf is None or buf.numel() < nbytes:
         buf = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)

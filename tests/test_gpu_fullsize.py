@@ -200,3 +200,25 @@ def test_c5_two_batch_elements_of_the_70b_shaped_chain():
                              ref_d["lse"][:, j - gd * Gd:j - gd * Gd + 1], kind=oracle.LOGITS_LSE)[0, 0]
     got_A = A[b, j].cpu().numpy()
     assert (np.abs(got_A - ref_A) <= 3e-5 * ref_A + 1e-10).all()
+
+
+def test_summed_weights_at_a_million_tokens():
+    """The second pass over K on a 1M-token draft cache (32768 key tiles, 64-bit row offsets):
+    bit for bit the aggregate of the dump, zero past the valid length, same index sets."""
+    B, Tq, Hq, Hkv, d, N = 1, 5, 16, 4, 64, 1 << 20
+    g = torch.Generator(device=DEV)
+    g.manual_seed(3)
+    q = torch.randn(B, Tq, Hq, d, generator=g, device=DEV).to(torch.bfloat16)
+    k = (torch.randn(B, Hkv, N, d, generator=g, device=DEV) * 0.5).to(torch.bfloat16)
+    v = (torch.randn(B, Hkv, N, d, generator=g, device=DEV) * 0.5).to(torch.bfloat16)
+    lens = torch.tensor([N - 12345], dtype=torch.int32, device=DEV)
+    A = torch.full((B, Hq, N), 7.0, device=DEV)
+    _, lse, logits = sts.sts_dense_attn(q, k, v, 0.125, seq_lens=lens, want_logits=True, weights_sum_out=A)
+    hm, kk, n = list(range(Hq)), 50000, int(lens[0])
+    idx_d, cnt_d, agg_d = sts.sts_select(logits, hm, kk, lse=lse, seq_lens=lens, kind=sts.STS_SCORES_LOGITS_LSE,
+                                         want_agg=True)
+    idx_a, cnt_a, _ = sts.sts_select(A.view(B, Hq, 1, N), hm, kk, seq_lens=lens)
+    assert torch.equal(A[0, :, :n], agg_d[0, :, :n]) and (A[0, :, n:] == 0).all()
+    assert torch.equal(idx_a, idx_d) and torch.equal(cnt_a, cnt_d)
+    assert torch.allclose(A[0, :, :n].double().sum(-1), torch.full((Hq,), float(Tq), dtype=torch.float64, device=DEV),
+                          atol=1e-4)

@@ -207,3 +207,23 @@ def test_block_select_fused_paths(page, N, k, kind, bf16):
     np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
     call(False)                                            # the lists do not depend on the optional output
     assert torch.equal(got["r"][0], idx) and torch.equal(got["r"][1], cnt)
+
+
+@pytest.mark.parametrize("N,page,nb", [(64, 8, 43), (40000, 16, 39989), (300000, 8, 299995)])
+def test_partial_last_block_is_ranked_on_the_gpu(N, page, nb):
+    """The planted case of the oracle's pin on every selection path (one workgroup per row, fused
+    block sums + LDS ranking, the multi-workgroup pipeline): the best score sits in the partial
+    last block of a ragged length, a larger one just past the length must not count."""
+    B, Hd, Tq = 1, 2, 2
+    P = torch.full((B, Hd, Tq, N), 0.01)
+    P[0, :, :, nb - 1] = 5.0
+    if nb < N:
+        P[0, :, :, nb] = 50.0
+    lens = torch.tensor([nb], dtype=torch.int32)
+    last = (nb - 1) // page
+    for k in (1, 3):
+        idx, cnt, _ = sts.sts_select(P.to(DEV), [0, 1], k, seq_lens=lens.to(DEV), page_size=page)
+        o_idx, o_cnt, _ = oracle.select_indices(P.numpy(), np.asarray([0, 1], np.int32), k, seq_lens=lens.numpy(), page=page)
+        np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
+        np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
+        assert last in o_idx[0, 0].tolist()

@@ -57,6 +57,13 @@ def test_block_selection_matches_brute_force_and_expansion():
     # the last block (id 25) holds 3 tokens only
     t2, c2 = oracle.expand_blocks(np.array([[[0, 25]]], np.int32), None, page, N)
     assert c2[0, 0] == 11 and t2[0, 0, :11].tolist() == list(range(8)) + [200, 201, 202]
+    # counts cut the block list: only the first counts[b, t] entries stand for tokens, the rest
+    # of the row (here a valid-looking block id and the -1 padding) is ignored
+    t3, c3 = oracle.expand_blocks(np.array([[[1, 3, 7, -1]]], np.int32), np.array([[2]], np.int32), page, N)
+    assert c3[0, 0] == 16 and t3[0, 0, :16].tolist() == list(range(8, 16)) + list(range(24, 32))
+    assert (t3[0, 0, 16:] == -1).all()
+    t4, c4 = oracle.expand_blocks(np.array([[[5, 6]]], np.int32), np.array([[0]], np.int32), page, N)
+    assert c4[0, 0] == 0 and (t4 == -1).all()
 
 
 def test_block_attention_equals_token_attention_on_expanded_rows():
@@ -74,3 +81,19 @@ def test_block_attention_equals_token_attention_on_expanded_rows():
         ref = torch.softmax(s, -1) @ v[0, t // 2].double()[rows]
         np.testing.assert_allclose(r["out"][0, :, t], ref.numpy(), rtol=1e-6, atol=1e-7)
     assert cnt.tolist() == [[9, 9, 12, 9]]
+
+
+def test_partial_last_block_of_a_ragged_length_is_ranked():
+    """A valid length that is no multiple of the page: the last, partial block is a candidate like
+    any other (ceil(N_b / page) blocks), and tokens past the length do not count towards it."""
+    B, Hd, Tq, N, page = 1, 1, 2, 64, 8
+    P = np.full((B, Hd, Tq, N), 0.01, np.float32)
+    P[0, 0, :, 42] = 5.0                    # block 5 holds tokens 40..47; the valid length is 43
+    P[0, 0, :, 44] = 50.0                   # past the valid length: must not help block 5 ... nor hurt
+    lens = np.array([43], np.int32)
+    idx, cnt, A = oracle.select_indices(P, np.array([0], np.int32), 1, seq_lens=lens, page=page)
+    assert cnt[0, 0] == 1 and idx[0, 0, 0] == 5
+    blk = oracle.block_scores(A, page, lens)
+    assert blk[0, 0, 5] == np.float32(0.02 + 0.02 + 10.0)        # tokens 40, 41, 42 only
+    idx6, cnt6, _ = oracle.select_indices(P, np.array([0], np.int32), 8, seq_lens=lens, page=page)
+    assert cnt6[0, 0] == 6 and idx6[0, 0, :6].tolist() == [0, 1, 2, 3, 4, 5] and (idx6[0, 0, 6:] == -1).all()

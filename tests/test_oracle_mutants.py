@@ -119,3 +119,51 @@ def test_planted_mistake_is_caught(name, old, new, files):
         r = _run_pins(_build(src.replace(old, new), tmp), files)
         assert r.returncode == 1, f"no pin noticed: {name}\n" + r.stdout[-1500:] + r.stderr[-1500:]
         assert " failed" in r.stdout, r.stdout[-1500:]
+
+
+# ---- the Python half of the oracle (block expansion, per-head budgets, the composition of the
+# selection stages): same procedure on a copy of the package
+PY_SRC = os.path.join(ROOT, "oracle", "__init__.py")
+PY_MUTANTS = [
+    ("block expansion not clipped at N",
+     "row.extend(range(int(m) * page, min((int(m) + 1) * page, N)))", "row.extend(range(int(m) * page, (int(m) + 1) * page))",
+     ["test_oracle_blocks.py"]),
+    ("block expansion ignores the counts",
+     "c = kb if counts is None else int(counts[b, t])", "c = kb",
+     ["test_oracle_blocks.py"]),
+    ("block count of a ragged length rounded down",
+     "lens = None if seq_lens is None else (np.asarray(seq_lens, np.int64) + page - 1) // page",
+     "lens = None if seq_lens is None else np.asarray(seq_lens, np.int64) // page",
+     ["test_oracle_blocks.py"]),
+    ("blocks ranked by their first token only",
+     "src = block_scores(A, page, seq_lens)", "src = np.ascontiguousarray(A[:, :, ::page])",
+     ["test_oracle_blocks.py"]),
+    ("every head gets the first head's budget",
+     "kj = int(k_head[j])", "kj = int(k_head[0])",
+     ["test_oracle_select.py"]),
+    ("reduction switch dropped on the way to the aggregation",
+     "A = aggregate(scores, lse, kind, reduce)", "A = aggregate(scores, lse, kind)",
+     ["test_oracle_select.py"]),
+    ("valid lengths dropped on the way to the selection",
+     "sel, cnt = pick(A, k, seq_lens)", "sel, cnt = pick(A, k, None)",
+     ["test_oracle_select.py"]),
+]
+
+
+@pytest.mark.parametrize("name,old,new,files", PY_MUTANTS, ids=[m[0] for m in PY_MUTANTS])
+def test_planted_mistake_in_the_python_half_is_caught(name, old, new, files):
+    import shutil
+    src = open(PY_SRC).read()
+    assert src.count(old) == 1, f"the text this mutant replaces must occur exactly once: {old!r}"
+    with tempfile.TemporaryDirectory() as tmp:
+        pkg = os.path.join(tmp, "oracle")
+        shutil.copytree(os.path.join(ROOT, "oracle"), pkg, ignore=shutil.ignore_patterns("__pycache__"))
+        with open(os.path.join(pkg, "__init__.py"), "w") as f:
+            f.write(src.replace(old, new))
+        env = dict(os.environ, STS_ORACLE_PKG_DIR=tmp, OMP_NUM_THREADS="2")
+        env.pop("STS_ORACLE_LIB", None)
+        r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider",
+                            *[os.path.join(ROOT, "tests", f) for f in files]],
+                           capture_output=True, text=True, env=env, cwd=ROOT, timeout=600)
+        assert r.returncode == 1, f"no pin noticed: {name}\n" + r.stdout[-1500:] + r.stderr[-1500:]
+        assert " failed" in r.stdout, r.stdout[-1500:]

@@ -220,3 +220,16 @@ def test_remap_rows_follow_head_map():
     np.testing.assert_array_equal(idx2, idx[:, perm])
     with pytest.raises(ValueError):
         oracle.remap(sel, cnt, np.array([0, 4], np.int32))
+
+
+def test_reduction_switch_reaches_the_selection():
+    """Sum and maximum over the query rows rank differently; the whole selection follows the switch."""
+    P = np.zeros((1, 1, 3, 4), np.float32)
+    P[0, 0, :, 0] = [0.3, 0.3, 0.3]         # sum 0.9, max 0.3
+    P[0, 0, :, 1] = [0.8, 0.0, 0.0]         # sum 0.8, max 0.8
+    P[0, 0, :, 2] = [0.1, 0.1, 0.1]
+    hm = np.array([0], np.int32)
+    i_sum, _, a_sum = oracle.select_indices(P, hm, 1, reduce=oracle.SUM)
+    i_max, _, a_max = oracle.select_indices(P, hm, 1, reduce=oracle.MAX)
+    assert i_sum[0, 0, 0] == 0 and i_max[0, 0, 0] == 1
+    assert a_max[0, 0].tolist() == [np.float32(0.3), np.float32(0.8), np.float32(0.1), 0.0]

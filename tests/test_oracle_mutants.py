@@ -77,6 +77,25 @@ MUTANTS = [
     ("own tokens of the wrong KV head",
      "const uint16_t *kr = k_new + (((size_t)b * Tq + j) * Hkv + g) * d;", "const uint16_t *kr = k_new + (((size_t)b * Tq + j) * Hkv) * d;",
      ["test_oracle_attn.py"]),
+    ("dense attention ignores the valid length",
+     "c = seq_lens ? seq_lens[b] : N;\n      if (c < 0 || c > N) {", "c = N;\n      if (c < 0 || c > N) {",
+     ["test_oracle_attn.py"]),
+    ("logits written with query row and head swapped",
+     "logits_out[(((size_t)b * Hq + t) * Tq + i) * N + j]", "logits_out[(((size_t)b * Tq + i) * Hq + t) * N + j]",
+     ["test_oracle_attn.py"]),
+    ("log-sum-exp written with query row and head swapped",
+     "lse_out[((size_t)b * Hq + t) * Tq + i] =", "lse_out[((size_t)b * Tq + i) * Hq + t] =",
+     ["test_oracle_attn.py"]),
+    ("token stride of the cache ignored",
+     "const uint16_t *kr = Kg + row * stride_n;", "const uint16_t *kr = Kg + row * (size_t)d;",
+     ["test_oracle_attn.py"]),
+    ("head stride of the cache ignored",
+     "const uint16_t *Kg = k + (size_t)b * stride_b + (size_t)g * stride_h;",
+     "const uint16_t *Kg = k + (size_t)b * stride_b + (size_t)g * (size_t)N * d;",
+     ["test_oracle_attn.py"]),
+    ("query of the wrong row",
+     "const uint16_t *qr = q + (((size_t)b * Tq + i) * Hq + t) * d;", "const uint16_t *qr = q + (((size_t)b * Tq) * Hq + t) * d;",
+     ["test_oracle_attn.py"]),
     ("head mapping: the last best draft head wins",
      "if (score > max_score) {", "if (score >= max_score) {",
      ["test_oracle_headmap.py"]),
@@ -111,14 +130,51 @@ def test_unmodified_copy_passes_every_pin():
         assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
 
 
-@pytest.mark.parametrize("name,old,new,files", MUTANTS, ids=[m[0] for m in MUTANTS])
-def test_planted_mistake_is_caught(name, old, new, files):
+def _c_mutant(m):
+    name, old, new, files = m
     src = open(SRC).read()
-    assert src.count(old) == 1, f"the text this mutant replaces must occur exactly once: {old!r}"
+    if src.count(old) != 1:
+        return ("missing", f"the text this mutant replaces must occur exactly once: {old!r}")
     with tempfile.TemporaryDirectory() as tmp:
         r = _run_pins(_build(src.replace(old, new), tmp), files)
-        assert r.returncode == 1, f"no pin noticed: {name}\n" + r.stdout[-1500:] + r.stderr[-1500:]
-        assert " failed" in r.stdout, r.stdout[-1500:]
+        return (r.returncode, r.stdout[-1500:] + r.stderr[-1500:])
+
+
+def _py_mutant(m):
+    import shutil
+    name, old, new, files = m
+    src = open(PY_SRC).read()
+    if src.count(old) != 1:
+        return ("missing", f"the text this mutant replaces must occur exactly once: {old!r}")
+    with tempfile.TemporaryDirectory() as tmp:
+        pkg = os.path.join(tmp, "oracle")
+        shutil.copytree(os.path.join(ROOT, "oracle"), pkg, ignore=shutil.ignore_patterns("__pycache__"))
+        with open(os.path.join(pkg, "__init__.py"), "w") as f:
+            f.write(src.replace(old, new))
+        env = dict(os.environ, STS_ORACLE_PKG_DIR=tmp, OMP_NUM_THREADS="2")
+        env.pop("STS_ORACLE_LIB", None)
+        r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider",
+                            *[os.path.join(ROOT, "tests", f) for f in files]],
+                           capture_output=True, text=True, env=env, cwd=ROOT, timeout=600)
+        return (r.returncode, r.stdout[-1500:] + r.stderr[-1500:])
+
+
+@pytest.fixture(scope="module")
+def verdicts():
+    """Every mutant built and judged once, a few at a time (each is a compiler run plus a pytest
+    child process), so that the whole file takes well under a minute."""
+    from concurrent.futures import ThreadPoolExecutor
+    jobs = [("c", m) for m in MUTANTS] + [("py", m) for m in PY_MUTANTS]
+    with ThreadPoolExecutor(max_workers=max(2, min(6, (os.cpu_count() or 2) - 1))) as ex:
+        out = list(ex.map(lambda j: _c_mutant(j[1]) if j[0] == "c" else _py_mutant(j[1]), jobs))
+    return {(kind, m[0]): v for (kind, m), v in zip(jobs, out)}
+
+
+@pytest.mark.parametrize("name", [m[0] for m in MUTANTS])
+def test_planted_mistake_is_caught(name, verdicts):
+    rc, tail = verdicts[("c", name)]
+    assert rc != "missing", tail
+    assert rc == 1 and " failed" in tail, f"no pin noticed: {name}\n{tail}"
 
 
 # ---- the Python half of the oracle (block expansion, per-head budgets, the composition of the
@@ -150,20 +206,8 @@ PY_MUTANTS = [
 ]
 
 
-@pytest.mark.parametrize("name,old,new,files", PY_MUTANTS, ids=[m[0] for m in PY_MUTANTS])
-def test_planted_mistake_in_the_python_half_is_caught(name, old, new, files):
-    import shutil
-    src = open(PY_SRC).read()
-    assert src.count(old) == 1, f"the text this mutant replaces must occur exactly once: {old!r}"
-    with tempfile.TemporaryDirectory() as tmp:
-        pkg = os.path.join(tmp, "oracle")
-        shutil.copytree(os.path.join(ROOT, "oracle"), pkg, ignore=shutil.ignore_patterns("__pycache__"))
-        with open(os.path.join(pkg, "__init__.py"), "w") as f:
-            f.write(src.replace(old, new))
-        env = dict(os.environ, STS_ORACLE_PKG_DIR=tmp, OMP_NUM_THREADS="2")
-        env.pop("STS_ORACLE_LIB", None)
-        r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider",
-                            *[os.path.join(ROOT, "tests", f) for f in files]],
-                           capture_output=True, text=True, env=env, cwd=ROOT, timeout=600)
-        assert r.returncode == 1, f"no pin noticed: {name}\n" + r.stdout[-1500:] + r.stderr[-1500:]
-        assert " failed" in r.stdout, r.stdout[-1500:]
+@pytest.mark.parametrize("name", [m[0] for m in PY_MUTANTS])
+def test_planted_mistake_in_the_python_half_is_caught(name, verdicts):
+    rc, tail = verdicts[("py", name)]
+    assert rc != "missing", tail
+    assert rc == 1 and " failed" in tail, f"no pin noticed: {name}\n{tail}"

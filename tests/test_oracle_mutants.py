@@ -96,6 +96,27 @@ MUTANTS = [
     ("query of the wrong row",
      "const uint16_t *qr = q + (((size_t)b * Tq + i) * Hq + t) * d;", "const uint16_t *qr = q + (((size_t)b * Tq) * Hq + t) * d;",
      ["test_oracle_attn.py"]),
+    ("short rows padded with 0 instead of -1",
+     "for (int i = 0; i < k; ++i) out[i] = -1;", "for (int i = 0; i < k; ++i) out[i] = 0;",
+     ["test_oracle_select.py"]),
+    ("counts report the budget, not what was kept",
+     "cnt[r] = c;\n    if (c == 0) continue;", "cnt[r] = k;\n    if (c == 0) continue;",
+     ["test_oracle_select.py"]),
+    ("maximum over the query rows takes the minimum",
+     "acc = (p > acc) ? p : acc;", "acc = (p < acc) ? p : acc;",
+     ["test_oracle_select.py"]),
+    ("natural exponential replaced by a power of two",
+     "p = expf(p - lse[(size_t)r * Tq + i]);", "p = exp2f(p - lse[(size_t)r * Tq + i]);",
+     ["test_oracle_select.py"]),
+    ("remapped counts taken from the first draft head",
+     "if (counts) counts[(size_t)b * Hq + t] = cnt[(size_t)b * Hd + j];", "if (counts) counts[(size_t)b * Hq + t] = cnt[(size_t)b * Hd];",
+     ["test_oracle_select.py"]),
+    ("own tokens, not causal: the last one is missed",
+     "const int nnew = k_new ? (causal ? i + 1 : Tq) : 0;", "const int nnew = k_new ? (causal ? i + 1 : Tq - 1) : 0;",
+     ["test_oracle_attn.py"]),
+    ("head mapping counts the union instead of the intersection",
+     "score += (x[n] & y[n]);", "score += (x[n] | y[n]);",
+     ["test_oracle_headmap.py"]),
     ("head mapping: the last best draft head wins",
      "if (score > max_score) {", "if (score >= max_score) {",
      ["test_oracle_headmap.py"]),

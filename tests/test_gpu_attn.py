@@ -209,6 +209,11 @@ def test_maximum_head_counts_and_group_size():
     check_attn(dout, dlse, dref, what="Hq 256 / G 16 dense")
     plan = sts.attn_plan(q, k, True, kmax=kk, head_map=hm)
     assert plan["query_tiles"] == 4 and plan["units_per_batch"] == 16 * 4     # 16 heads x 16 rows -> 4 units of 64 rows
+    # the same shape through the second pass over K (four sets of four heads per KV head)
+    A = torch.empty(B, Hq, N, dtype=torch.float32, device=DEV)
+    _, lse2, logits = sts.sts_dense_attn(q, k, v, 0.125, want_logits=True, weights_sum_out=A)
+    _, _, agg = sts.sts_select(logits, list(range(Hq)), kk, lse=lse2, kind=sts.STS_SCORES_LOGITS_LSE, want_agg=True)
+    assert torch.equal(A, agg)
 
 
 def test_layers_read_their_slice_of_one_selection():

@@ -233,7 +233,7 @@ sts_status sts_select(const sts_select_params *p, void *stream);
 sts_status sts_sparse_attn(const sts_attn_params *p, void *stream);
 sts_status sts_dense_attn(const sts_attn_params *p, void *stream);
 
-const char *sts_strerror(sts_status s);
+const char *sts_strerror(int status);   /* any int: values that are no sts_status give "unknown status" */
 int sts_version(void);
 
 /* ----------------------------------------------------------------------------------------

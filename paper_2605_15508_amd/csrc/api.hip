@@ -625,8 +625,8 @@ sts_status sts_head_map(const sts_headmap_params *p, void *stream) {
   return e == hipSuccess ? STS_OK : STS_EHIP;
 }
 
-const char *sts_strerror(sts_status s) {
-  switch (s) {
+const char *sts_strerror(int status) {   // an int on purpose: any value a caller holds may be asked about
+  switch (status) {
     case STS_OK: return "ok";
     case STS_EINVAL: return "invalid argument";
     case STS_EUNSUPPORTED: return "unsupported shape";

@@ -1,0 +1,158 @@
+// Host-side sanitizer driver (test infrastructure, not part of libsts.so). It is linked with the
+// library's host file only: the kernel launchers are replaced by stubs that check their launch
+// arguments and touch no device memory, so every entry point can be driven on a machine without
+// a GPU, with made-up device addresses, under AddressSanitizer and UndefinedBehaviorSanitizer:
+// planning, workspace sizing and carving, argument validation, the head-map tables, error paths.
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <vector>
+
+#include "common.h"
+
+static long g_launches = 0;
+static const unsigned char *g_ws_lo = nullptr, *g_ws_hi = nullptr;
+
+static void fail(const char *what) {
+  fprintf(stderr, "host check failed: %s\n", what);
+  exit(3);
+}
+static void in_ws(const void *p, const char *what) {
+  const unsigned char *c = static_cast<const unsigned char *>(p);
+  if (p && (c < g_ws_lo || c > g_ws_hi)) fail(what);
+}
+
+// ---- stub launchers: argument checks only
+hipError_t launch_attn_split(const AttnArgs &a, int d, int nq, bool sparse, hipStream_t) {
+  ++g_launches;
+  if ((d != 64 && d != 128) || (nq != 1 && nq != 2 && nq != 4)) fail("split: d / nq");
+  if (a.num_splits < 1 || a.num_units < 1 || a.num_units > STS_MAX_HEADS) fail("split: grid");
+  if (sparse && !a.indices && a.kmax > 0) fail("split: indices");
+  in_ws(a.part_o, "split: part_o");
+  in_ws(a.part_ml, "split: part_ml");
+  for (int u = 0; u < a.num_units; ++u) {
+    const uint32_t unit = a.units.unit[u];
+    const int g = unit & 0xff, n = (unit >> 24) & 0x1f;
+    if (g >= a.Hkv || n < 1 || n * a.Tq > nq * 16) fail("split: unit table");
+  }
+  return hipSuccess;
+}
+hipError_t launch_attn_combine(const AttnArgs &a, int, int, hipStream_t) { ++g_launches; if (a.direct) fail("combine after a direct launch"); return hipSuccess; }
+hipError_t launch_attn_probsum(const AttnArgs &a, int, int nq, hipStream_t) {
+  ++g_launches;
+  if (!a.agg_out || !a.lse_out || a.ps_splits < 1 || a.ps_sets < 1 || a.ps_heads < 1) fail("probsum: args");
+  if (a.ps_tp < a.Tq || (a.ps_tp & (a.ps_tp - 1)) || a.ps_heads * a.ps_tp > nq * 16) fail("probsum: rows");
+  return hipSuccess;
+}
+int attn_probsum_wgs_per_cu(int, int) { return 2; }
+static void check_select(const SelectArgs &a, const char *what) {
+  ++g_launches;
+  if (a.B < 1 || a.Hd < 1 || a.k < 1) fail(what);
+  in_ws(a.hist, what);
+  in_ws(a.state, what);
+  in_ws(a.chunk_cnt, what);
+  in_ws(a.pool_key, what);
+  in_ws(a.pool_idx, what);
+  in_ws(a.blk, what);
+  if (a.targets.off[a.Hd] != a.Hq) fail("select: inverse head map");
+  for (int j = 0; j < a.Hd; ++j)
+    for (int t = a.targets.off[j]; t < a.targets.off[j + 1]; ++t)
+      if (a.targets.tgt[t] >= a.Hq) fail("select: target table");
+  for (int j = 0; j < a.Hd; ++j)
+    if (a.kh[j] < 1 || a.kh[j] > a.k) fail("select: budgets");
+}
+hipError_t launch_select_clear(const SelectArgs &a, hipStream_t) { check_select(a, "clear"); return hipSuccess; }
+hipError_t launch_select_agg(const SelectArgs &a, hipStream_t) { check_select(a, "agg"); return hipSuccess; }
+hipError_t launch_select_block(const SelectArgs &a, hipStream_t) { check_select(a, "block"); return hipSuccess; }
+hipError_t launch_select_small(const SelectArgs &a, hipStream_t) { check_select(a, "small"); return hipSuccess; }
+hipError_t launch_select_rank(const SelectArgs &a, hipStream_t) { check_select(a, "rank"); return hipSuccess; }
+bool select_aggblock_ok(const SelectArgs &a) { return a.page >= 4 && a.page <= 256 && (a.page & (a.page - 1)) == 0 && a.N % a.page == 0; }
+hipError_t launch_select_aggblock(const SelectArgs &a, hipStream_t) { check_select(a, "aggblock"); return hipSuccess; }
+hipError_t launch_select_local(const SelectArgs &a, hipStream_t) { check_select(a, "local"); return hipSuccess; }
+hipError_t launch_select_pool(const SelectArgs &a, hipStream_t) { check_select(a, "pool"); return hipSuccess; }
+hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t) { check_select(a, "hist"); if (pass != 1 && pass != 2) fail("hist pass"); return hipSuccess; }
+hipError_t launch_select_write(const SelectArgs &a, hipStream_t) { check_select(a, "write"); return hipSuccess; }
+hipError_t launch_headmap_clear(unsigned long long *, int, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_headmap_overlap(const int32_t *, const int32_t *, int, int, int, int, int, int, unsigned long long *, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_headmap_argmax(const unsigned long long *, int, int, int32_t *, hipStream_t) { ++g_launches; return hipSuccess; }
+
+int main() {
+  long calls = 0, accepted = 0;
+  // made-up, 256-byte aligned "device" addresses: never dereferenced (the launchers are stubs)
+  unsigned char *const fake = reinterpret_cast<unsigned char *>(uintptr_t(1) << 40);
+  unsigned char *const ws = reinterpret_cast<unsigned char *>(uintptr_t(2) << 40);
+  const int Bs[] = {0, 1, 4, 33}, Tqs[] = {1, 5, 8, 16}, Ns[] = {0, 1, 31, 4096, 131072, 1 << 20}, ds[] = {64, 128};
+  for (int B : Bs) for (int Tq : Tqs) for (int N : Ns) for (int d : ds)
+    for (int Hkv : {1, 8, 16}) for (int G : {1, 4, 8, 16}) {
+      const int Hq = Hkv * G;
+      if (Hq > 256) continue;
+      for (int sparse = 0; sparse < 2; ++sparse)
+        for (int page : {0, 8})
+          for (int hmk = 0; hmk < 3; ++hmk)
+            for (int extra = 0; extra < 3; ++extra) {
+              sts_attn_params p;
+              memset(&p, 0, sizeof(p));
+              p.B = B; p.Tq = Tq; p.Hq = Hq; p.Hkv = Hkv; p.d = d; p.N = N;
+              p.kv_stride_n = d; p.kv_stride_h = (int64_t)N * d; p.kv_stride_b = (int64_t)Hkv * N * d;
+              p.kmax = sparse ? (N / 10 + 1) : 0;
+              p.scale = 0.1f; p.page_size = page;
+              std::vector<int32_t> hm(Hq);
+              for (int t = 0; t < Hq; ++t) hm[t] = hmk == 0 ? t : (hmk == 1 ? t / 2 : 0);
+              p.head_map = sparse ? hm.data() : nullptr;
+              p.q = fake; p.k = fake; p.v = fake; p.out = fake;
+              if (sparse) p.indices = reinterpret_cast<const int32_t *>(fake);
+              if (extra == 1) { p.k_new = fake; p.v_new = fake; p.causal = 1; }
+              if (extra == 2 && !sparse && page == 0) p.weights_sum_out = reinterpret_cast<float *>(fake);
+              int32_t s = 0, u = 0, nq = 0;
+              const size_t need = sts_attn_workspace_bytes(&p, sparse);
+              (void)sts_attn_plan(&p, sparse, &s, &u, &nq);
+              p.workspace = ws; p.workspace_bytes = need;
+              g_ws_lo = ws; g_ws_hi = ws + need;
+              const sts_status rc = sparse ? sts_sparse_attn(&p, nullptr) : sts_dense_attn(&p, nullptr);
+              accepted += rc == STS_OK;
+              if (need > 256) {              // one byte short must be refused
+                p.workspace_bytes = need - 1;
+                if ((sparse ? sts_sparse_attn(&p, nullptr) : sts_dense_attn(&p, nullptr)) == STS_OK && B > 0) fail("short attention workspace accepted");
+              }
+              calls += 4;
+            }
+    }
+  for (int B : Bs) for (int Tq : {1, 5, 64}) for (int N : Ns) for (int Hd : {1, 16, 256}) for (int Hq : {1, 32, 256})
+    for (int k : {1, 410, 13108, 1 << 20}) for (int page : {0, 8, 4096}) for (int budgets = 0; budgets < 2; ++budgets) {
+      if ((int64_t)B * Hd > 65535) continue;
+      sts_select_params p;
+      memset(&p, 0, sizeof(p));
+      p.B = B; p.Hd = Hd; p.Tq = Tq; p.N = N; p.Hq = Hq; p.k = k; p.page_size = page;
+      std::vector<int32_t> hm(Hq), kh(Hd);
+      for (int t = 0; t < Hq; ++t) hm[t] = t % Hd;
+      for (int j = 0; j < Hd; ++j) kh[j] = 1 + (j % k);
+      p.head_map = hm.data();
+      p.k_head = budgets ? kh.data() : nullptr;
+      p.scores = fake; p.indices = reinterpret_cast<int32_t *>(fake);
+      const size_t need = sts_select_workspace_bytes(&p);
+      p.workspace = ws; p.workspace_bytes = need;
+      g_ws_lo = ws; g_ws_hi = ws + need;
+      accepted += sts_select(&p, nullptr) == STS_OK;
+      hm[0] = Hd;                           // out of range: must be refused
+      if (sts_select(&p, nullptr) == STS_OK) fail("bad head map accepted");
+      calls += 3;
+    }
+  for (int S : {0, 1, 4}) for (int R : {0, 1, 128}) for (int N : {0, 1, 32768}) for (int k : {1, 512}) {
+    sts_headmap_params p;
+    memset(&p, 0, sizeof(p));
+    p.S = S; p.R = R; p.Hd = 16; p.Ht = 32; p.N = N; p.k = k;
+    p.a_d = reinterpret_cast<const float *>(fake); p.a_t = reinterpret_cast<const float *>(fake);
+    p.map = reinterpret_cast<int32_t *>(fake);
+    const size_t need = sts_headmap_workspace_bytes(&p);
+    p.workspace = ws; p.workspace_bytes = need;
+    g_ws_lo = ws; g_ws_hi = ws + need;
+    accepted += sts_head_map(&p, nullptr) == STS_OK;
+    calls += 2;
+  }
+  for (int s = 1; s >= -6; --s)
+    if (!sts_strerror(s)[0]) fail("empty error string");
+  if (accepted == 0 || g_launches == 0) fail("nothing was accepted: the driver checks nothing");
+  printf("host checks done: %ld calls, %ld accepted, %ld stub launches, version %d\n", calls, accepted, g_launches, sts_version());
+  return 0;
+}

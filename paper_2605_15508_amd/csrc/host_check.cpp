@@ -61,18 +61,40 @@ static void check_select(const SelectArgs &a, const char *what) {
       if (a.targets.tgt[t] >= a.Hq) fail("select: target table");
   for (int j = 0; j < a.Hd; ++j)
     if (a.kh[j] < 1 || a.kh[j] > a.k) fail("select: budgets");
+  if (a.page < 1 || a.srcN != (a.N + a.page - 1) / a.page) fail("select: block count");
+  if (a.spin_limit < 0) fail("select: spin limit");
 }
-hipError_t launch_select_clear(const SelectArgs &a, hipStream_t) { check_select(a, "clear"); return hipSuccess; }
+static void check_pipeline(const SelectArgs &a, const char *what) {
+  check_select(a, what);
+  if (a.nchunks != (a.srcN + SEL_CHUNK - 1) / SEL_CHUNK) fail("pipeline: chunks");
+  if (a.hist_cpw != 1 && a.hist_cpw != 2 && a.hist_cpw != 4) fail("pipeline: chunks per workgroup");
+  if (!a.hist || !a.state || !a.chunk_cnt) fail("pipeline: workspace parts");
+  if (!a.agg_is_input) in_ws(a.agg, "pipeline: aggregate");
+  // the cleared region covers the three histograms, the state words and the chunk flags of every row
+  const size_t rows = (size_t)a.B * a.Hd;
+  if (a.clear_words < rows * (3 * SEL_BINS + 8 + (size_t)a.nchunks * SEL_FLAG_PITCH)) fail("pipeline: cleared region");
+  in_ws(reinterpret_cast<const unsigned char *>(a.hist) + a.clear_words * 4, "pipeline: cleared region end");
+}
+static void check_pool(const SelectArgs &a, const char *what) {
+  check_select(a, what);
+  if (a.pool_chunk != SEL_CHUNK && a.pool_chunk != 4 * SEL_CHUNK) fail("pool: chunk size");
+  if (a.pool_nchunks != (a.N + a.pool_chunk - 1) / a.pool_chunk) fail("pool: chunks");
+  if (a.pool_pitch != (a.k < a.pool_chunk ? a.k : a.pool_chunk)) fail("pool: pitch");
+  if ((int64_t)a.pool_nchunks * a.pool_pitch > SEL_POOL_MAX) fail("pool: pairs per row beyond the LDS limit");
+  if (a.N % 4 != 0 || a.page != 1 || !a.pool_key || !a.pool_idx) fail("pool: shape");
+  in_ws(reinterpret_cast<const unsigned char *>(a.pool_idx) + (size_t)a.B * a.Hd * a.pool_nchunks * a.pool_pitch * 4, "pool: end");
+}
+hipError_t launch_select_clear(const SelectArgs &a, hipStream_t) { check_pipeline(a, "clear"); return hipSuccess; }
 hipError_t launch_select_agg(const SelectArgs &a, hipStream_t) { check_select(a, "agg"); return hipSuccess; }
 hipError_t launch_select_block(const SelectArgs &a, hipStream_t) { check_select(a, "block"); return hipSuccess; }
 hipError_t launch_select_small(const SelectArgs &a, hipStream_t) { check_select(a, "small"); return hipSuccess; }
 hipError_t launch_select_rank(const SelectArgs &a, hipStream_t) { check_select(a, "rank"); return hipSuccess; }
 bool select_aggblock_ok(const SelectArgs &a) { return a.page >= 4 && a.page <= 256 && (a.page & (a.page - 1)) == 0 && a.N % a.page == 0; }
 hipError_t launch_select_aggblock(const SelectArgs &a, hipStream_t) { check_select(a, "aggblock"); return hipSuccess; }
-hipError_t launch_select_local(const SelectArgs &a, hipStream_t) { check_select(a, "local"); return hipSuccess; }
-hipError_t launch_select_pool(const SelectArgs &a, hipStream_t) { check_select(a, "pool"); return hipSuccess; }
-hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t) { check_select(a, "hist"); if (pass != 1 && pass != 2) fail("hist pass"); return hipSuccess; }
-hipError_t launch_select_write(const SelectArgs &a, hipStream_t) { check_select(a, "write"); return hipSuccess; }
+hipError_t launch_select_local(const SelectArgs &a, hipStream_t) { check_pool(a, "local"); return hipSuccess; }
+hipError_t launch_select_pool(const SelectArgs &a, hipStream_t) { check_pool(a, "pool"); return hipSuccess; }
+hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t) { check_pipeline(a, "hist"); if (pass != 1 && pass != 2) fail("hist pass"); return hipSuccess; }
+hipError_t launch_select_write(const SelectArgs &a, hipStream_t) { check_pipeline(a, "write"); return hipSuccess; }
 hipError_t launch_headmap_clear(unsigned long long *, int, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_headmap_overlap(const int32_t *, const int32_t *, int, int, int, int, int, int, unsigned long long *, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_headmap_argmax(const unsigned long long *, int, int, int32_t *, hipStream_t) { ++g_launches; return hipSuccess; }

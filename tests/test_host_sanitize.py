@@ -1,5 +1,5 @@
 """Host-side sanitizers over the library's host code (GPU code is never built with sanitizers):
-paper_2605_15508_amd/csrc/host_check.cpp drives every entry point with made-up device addresses
+tests/host_check.cpp drives every entry point with made-up device addresses
 against stub launchers that check their launch arguments, in a host-only build of csrc/api.hip
 with AddressSanitizer and UndefinedBehaviorSanitizer. No GPU is involved."""
 import os
@@ -22,7 +22,7 @@ def test_host_code_is_clean_under_asan_and_ubsan():
         subprocess.run([hipcc, "--cuda-host-only", "--offload-arch=gfx950", "-O1", "-g", "-std=c++17",
                         "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
                         "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-                        os.path.join(CSRC, "api.hip"), "-x", "hip", os.path.join(CSRC, "host_check.cpp"), "-o", exe],
+                        os.path.join(CSRC, "api.hip"), "-x", "hip", os.path.join(ROOT, "tests", "host_check.cpp"), "-o", exe],
                        check=True, capture_output=True, text=True)
         env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0")   # the HIP runtime keeps its own allocations
         r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)

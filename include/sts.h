@@ -233,6 +233,26 @@ sts_status sts_select(const sts_select_params *p, void *stream);
 sts_status sts_sparse_attn(const sts_attn_params *p, void *stream);
 sts_status sts_dense_attn(const sts_attn_params *p, void *stream);
 
+/* ----------------------------------------------------------------------------------------
+ * sts_sparse_attn_static -- sts_sparse_attn for callers that cannot allocate device memory or
+ * carry a workspace around: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc. Same arguments, same kernels, same results as sts_sparse_attn (bit for bit),
+ * except that p->workspace and p->workspace_bytes are ignored: the per-split partial results go
+ * to an array of STS_STATIC_SCRATCH_BYTES that the library's code object holds in device memory
+ * (each GPU the library runs on holds its own copy until the process ends). The call allocates
+ * and frees nothing and keeps the timing aid below switched off for its launches.
+ *  - A shape whose partials need more than STS_STATIC_SCRATCH_BYTES (what
+ *    sts_attn_workspace_bytes(p, 1) returns) is refused with STS_EWORKSPACE, nothing enqueued.
+ *  - The current device must be the device of `stream`. The first call on a device asks the
+ *    runtime for that device's copy of the array; STS_EHIP if that fails.
+ *  - Every call on a GPU shares that GPU's array, which keeps the last call's contents. Nothing
+ *    in it has to start at zero (every workgroup writes its partial before the combine step
+ *    reads it), but two calls that overlap on one GPU (different streams with no event between
+ *    them) race on it: order them, or use sts_sparse_attn with a workspace per stream.
+ */
+#define STS_STATIC_SCRATCH_BYTES ((size_t)8 << 20)
+sts_status sts_sparse_attn_static(const sts_attn_params *p, void *stream);
+
 const char *sts_strerror(int status);   /* any int: values that are no sts_status give "unknown status" */
 int sts_version(void);
 

@@ -26,7 +26,9 @@ KERNEL_KINDS = {"select_clear": 0, "select_agg": 1, "select_hist": 2, "select_co
 # every symbol include/sts.h declares
 EXPORTS = ["sts_select_workspace_bytes", "sts_attn_workspace_bytes", "sts_select", "sts_sparse_attn",
            "sts_dense_attn", "sts_strerror", "sts_version", "sts_prof_enable", "sts_prof_reset",
-           "sts_prof_read", "sts_attn_plan", "sts_head_map", "sts_headmap_workspace_bytes"]
+           "sts_prof_read", "sts_attn_plan", "sts_head_map", "sts_headmap_workspace_bytes",
+           "sts_sparse_attn_static"]
+STS_STATIC_SCRATCH_BYTES = 8 << 20
 
 
 class StsError(RuntimeError):
@@ -89,7 +91,7 @@ def load_library():
     lib.sts_attn_workspace_bytes.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_int]
     lib.sts_select.restype = ctypes.c_int
     lib.sts_select.argtypes = [ctypes.POINTER(SelectParams), ctypes.c_void_p]
-    for f in (lib.sts_sparse_attn, lib.sts_dense_attn):
+    for f in (lib.sts_sparse_attn, lib.sts_dense_attn, lib.sts_sparse_attn_static):
         f.restype = ctypes.c_int
         f.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_void_p]
     lib.sts_strerror.restype = ctypes.c_char_p
@@ -267,7 +269,7 @@ def _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse_o
 def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=None, seq_lens=None,
               out=None, out_dtype=None, want_lse=True, want_logits=False, workspace=None,
               lse_out=None, logits_out=None, page_size=1, block_table=None, N=None,
-              k_new=None, v_new=None, causal=True, weights_sum_out=None):
+              k_new=None, v_new=None, causal=True, weights_sum_out=None, static=False):
     import torch
 
     lib = load_library()
@@ -293,6 +295,10 @@ def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=
     p, _keep = _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse, logits,
                             page_size=page_size, block_table=block_table, N=N,
                             k_new=k_new, v_new=v_new, causal=causal)
+    if static:      # the library's own scratch array: no workspace, nothing allocated by the call
+        assert sparse and workspace is None
+        _check(lib.sts_sparse_attn_static(ctypes.byref(p), _stream()), "sts_sparse_attn_static")
+        return out, lse, logits
     need = lib.sts_attn_workspace_bytes(ctypes.byref(p), 1 if sparse else 0)
     ws = workspace if workspace is not None else _workspace("attn", need, dev)
     p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()
@@ -320,6 +326,19 @@ def sts_sparse_attn(q, k, v, indices, scale, counts=None, head_map=None, out=Non
                             out=out, out_dtype=out_dtype, want_lse=want_lse, workspace=workspace,
                             lse_out=lse_out, page_size=page_size, block_table=block_table, N=N,
                             k_new=k_new, v_new=v_new, causal=causal)
+    return out, lse
+
+
+def sts_sparse_attn_static(q, k, v, indices, scale, counts=None, head_map=None, out=None, out_dtype=None,
+                           want_lse=True, lse_out=None, page_size=1, block_table=None, N=None,
+                           k_new=None, v_new=None, causal=True):
+    """sts_sparse_attn on the library's static scratch array (no workspace; the C call allocates
+    nothing; pass `out` and `lse_out` so that this wrapper allocates nothing either). Shapes whose
+    partial results exceed STS_STATIC_SCRATCH_BYTES raise StsError (workspace)."""
+    out, lse, _ = _run_attn(True, q, k, v, scale, indices=indices, counts=counts, head_map=head_map,
+                            out=out, out_dtype=out_dtype, want_lse=want_lse, lse_out=lse_out,
+                            page_size=page_size, block_table=block_table, N=N,
+                            k_new=k_new, v_new=v_new, causal=causal, static=True)
     return out, lse
 
 

@@ -173,7 +173,10 @@ sts_status plan_attn(const sts_attn_params *p, int sparse, AttnPlan &pl) {
   return STS_OK;
 }
 
-sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
+// ws / ws_bytes: the scratch memory of the call (the caller's workspace, or the library's static
+// array for the entry point that allocates nothing, which also keeps the timing aid off: creating
+// events allocates).
+sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s, void *ws, size_t ws_bytes, bool timed) {
   AttnPlan pl;
   const sts_status v = plan_attn(p, sparse, pl);
   if (v != STS_OK) return v;
@@ -183,8 +186,8 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
   if (sparse && p->kmax > 0 && !p->indices) return STS_EINVAL;
   if (sparse && p->kmax > 0 && p->N == 0) return STS_EINVAL;
   const size_t need = pl.part_o_bytes + pl.part_ml_bytes + pl.lse_bytes;
-  if (!p->workspace || p->workspace_bytes < need) return STS_EWORKSPACE;
-  if (reinterpret_cast<uintptr_t>(p->workspace) % 256 != 0) return STS_EWORKSPACE;
+  if (!ws || ws_bytes < need) return STS_EWORKSPACE;
+  if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return STS_EWORKSPACE;
   const bool want_sum = !sparse && p->weights_sum_out != nullptr;
   // (the second pass adds a 32-bit lane offset of up to 12 rows to a 64-bit tile address)
   if (want_sum && (p->block_table || p->k_new || page_of(p) != 1 ||
@@ -226,22 +229,24 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s) {
   a.num_splits = pl.num_splits;
   a.scale = p->scale;
   a.scale_log2 = p->scale * 1.44269504088896340736f;
-  a.part_o = static_cast<float *>(p->workspace);
-  a.part_ml = reinterpret_cast<float *>(static_cast<unsigned char *>(p->workspace) + pl.part_o_bytes);
+  a.part_o = static_cast<float *>(ws);
+  a.part_ml = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + pl.part_o_bytes);
   a.logits_out = sparse ? nullptr : p->logits_out;
   a.logits_bf16 = p->logits_bf16 ? 1 : 0;
   a.out = p->out;
   a.lse_out = p->lse_out;
   if (want_sum && !a.lse_out)   // the second pass needs the row normalisers
-    a.lse_out = reinterpret_cast<float *>(static_cast<unsigned char *>(p->workspace) + pl.part_o_bytes + pl.part_ml_bytes);
+    a.lse_out = reinterpret_cast<float *>(static_cast<unsigned char *>(ws) + pl.part_o_bytes + pl.part_ml_bytes);
   a.out_dtype = p->out_dtype;
   a.units = pl.units;
 
-  hipError_t rc = run_kernel(sparse ? STS_K_ATTN_SPARSE : STS_K_ATTN_DENSE, s,
-                             [&] { return launch_attn_split(a, p->d, pl.nq, sparse != 0, s); });
+  hipError_t rc = timed ? run_kernel(sparse ? STS_K_ATTN_SPARSE : STS_K_ATTN_DENSE, s,
+                                     [&] { return launch_attn_split(a, p->d, pl.nq, sparse != 0, s); })
+                        : launch_attn_split(a, p->d, pl.nq, sparse != 0, s);
   if (rc != hipSuccess) return STS_EHIP;
   if (!a.direct) {
-    rc = run_kernel(STS_K_ATTN_COMBINE, s, [&] { return launch_attn_combine(a, p->d, pl.nq, s); });
+    rc = timed ? run_kernel(STS_K_ATTN_COMBINE, s, [&] { return launch_attn_combine(a, p->d, pl.nq, s); })
+               : launch_attn_combine(a, p->d, pl.nq, s);
     if (rc != hipSuccess) return STS_EHIP;
   }
   if (want_sum && p->N > 0) {
@@ -372,11 +377,22 @@ sts_status sts_attn_plan(const sts_attn_params *p, int sparse, int32_t *num_spli
 }
 
 sts_status sts_sparse_attn(const sts_attn_params *p, void *stream) {
-  return run_attn(p, 1, static_cast<hipStream_t>(stream));
+  if (!p) return STS_EINVAL;
+  return run_attn(p, 1, static_cast<hipStream_t>(stream), p->workspace, p->workspace_bytes, true);
 }
 
 sts_status sts_dense_attn(const sts_attn_params *p, void *stream) {
-  return run_attn(p, 0, static_cast<hipStream_t>(stream));
+  if (!p) return STS_EINVAL;
+  return run_attn(p, 0, static_cast<hipStream_t>(stream), p->workspace, p->workspace_bytes, true);
+}
+
+sts_status sts_sparse_attn_static(const sts_attn_params *p, void *stream) {
+  if (!p) return STS_EINVAL;
+  void *ws = nullptr;
+  const sts_status v = sts_static_scratch(&ws);
+  if (v != STS_OK) return v;
+  // a shape whose partial results do not fit the array comes back as STS_EWORKSPACE
+  return run_attn(p, 1, static_cast<hipStream_t>(stream), ws, STS_STATIC_SCRATCH_BYTES, false);
 }
 
 size_t sts_select_workspace_bytes(const sts_select_params *p) {
@@ -636,7 +652,7 @@ const char *sts_strerror(int status) {   // an int on purpose: any value a calle
   return "unknown status";
 }
 
-int sts_version(void) { return 108; }
+int sts_version(void) { return 200; }
 
 void sts_prof_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);

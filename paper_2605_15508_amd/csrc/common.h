@@ -125,6 +125,9 @@ struct SelectArgs {
   int32_t kh[STS_MAX_HEADS];  // budget of draft head j (<= k)
 };
 
+// device address of the current device's copy of the static scratch array (scratch.hip)
+sts_status sts_static_scratch(void **out);
+
 // launches (defined in the .hip files); each returns hipGetLastError() of its launch
 hipError_t launch_attn_split(const AttnArgs &a, int d, int nq, bool sparse, hipStream_t s);
 hipError_t launch_attn_combine(const AttnArgs &a, int d, int nq, hipStream_t s);

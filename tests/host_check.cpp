@@ -23,6 +23,10 @@ static void in_ws(const void *p, const char *what) {
   if (p && (c < g_ws_lo || c > g_ws_hi)) fail(what);
 }
 
+// the static scratch array lives in device memory: here a made-up address stands in for it
+static unsigned char *const g_static_ws = reinterpret_cast<unsigned char *>(uintptr_t(3) << 40);
+sts_status sts_static_scratch(void **out) { *out = g_static_ws; return STS_OK; }
+
 // ---- stub launchers: argument checks only
 hipError_t launch_attn_split(const AttnArgs &a, int d, int nq, bool sparse, hipStream_t) {
   ++g_launches;
@@ -133,6 +137,14 @@ int main() {
               g_ws_lo = ws; g_ws_hi = ws + need;
               const sts_status rc = sparse ? sts_sparse_attn(&p, nullptr) : sts_dense_attn(&p, nullptr);
               accepted += rc == STS_OK;
+              if (sparse) {                  // the same call on the static scratch array: accepted iff it fits
+                g_ws_lo = g_static_ws; g_ws_hi = g_static_ws + STS_STATIC_SCRATCH_BYTES;
+                const sts_status rs = sts_sparse_attn_static(&p, nullptr);
+                if (rc == STS_OK && B > 0 && rs != (need <= STS_STATIC_SCRATCH_BYTES ? STS_OK : STS_EWORKSPACE)) fail("static scratch: wrong verdict");
+                if (rc != STS_OK && rs == STS_OK) fail("static scratch accepted what the workspace call refuses");
+                g_ws_lo = ws; g_ws_hi = ws + need;
+                ++calls;
+              }
               if (need > 256) {              // one byte short must be refused
                 p.workspace_bytes = need - 1;
                 if ((sparse ? sts_sparse_attn(&p, nullptr) : sts_dense_attn(&p, nullptr)) == STS_OK && B > 0) fail("short attention workspace accepted");

@@ -21,13 +21,8 @@
  *  - Results are deterministic run to run: the split count depends only on the shape and the
  *    partial results are combined in a fixed order; selection uses integer arithmetic only.
  *  - bf16 tensors are raw 16-bit patterns. All accumulation is fp32.
- *  - Three environment variables are read per call, for tuning and tests only:
- *    STS_ATTN_WGS_PER_CU (target workgroups per compute unit when the context is split; it
- *    changes the split count, hence the attention workspace size and the rounding of the
- *    output, so keep it constant within a process) and STS_SELECT_SPIN_LIMIT (polls of
- *    another workgroup's published chunk counts before they are recomputed locally; default
- *    256; no effect on results) and STS_PROBSUM_WGS_PER_CU (workgroups per compute unit of the
- *    pass that writes weights_sum_out; no effect on results).
+ *  - No environment variable is read on the call path; tuning and test knobs are set with
+ *    sts_set_knob (below).
  */
 #ifndef STS_H
 #define STS_H
@@ -106,7 +101,7 @@ typedef struct {
   const int32_t *seq_lens;  /* [dev] [B] valid lengths N_b <= N, or NULL (N_b = N) */
   int32_t *indices;         /* [dev] out [B,Hq,k] ascending token ids; positions >= c hold -1 */
   int32_t *counts;          /* [dev] out [B,Hq] c = min(k, N_b); may be NULL */
-  float *agg_out;           /* [dev] out [B,Hd,N] the aggregated scores A; may be NULL */
+  float *agg_out;           /* [dev] out [B,Hd,N] the aggregated scores A, 0 at n >= N_b; may be NULL */
   int32_t kind;             /* sts_score_kind */
   int32_t reduce;           /* sts_reduce */
   int32_t page_size;        /* 0 or 1: token granularity. p > 1: block granularity (see above) */
@@ -280,13 +275,40 @@ typedef enum {
   STS_K_SELECT_LOCAL = 11, /* small budgets: aggregation + top-k inside each 8192-token chunk */
   STS_K_SELECT_POOL = 12,  /* small budgets: ranking of the chunks' winners, one workgroup per row */
   STS_K_ATTN_PROBSUM = 13, /* dense second pass over K: attention weights summed over the query block */
-  STS_K_COUNT_ = 14
+  STS_K_SELECT_FUSED = 14, /* long rows: aggregation, threshold and compaction in one launch */
+  STS_K_COUNT_ = 15
 } sts_kernel_kind;
 #define STS_PROF_MAX 4096
 
 void sts_prof_enable(int on);
 void sts_prof_reset(void);
 sts_status sts_prof_read(int kernel_kind, int32_t *launches, double *total_ms);
+
+/* Tuning and test knobs (process-wide; not part of the method). Before a knob is first set or
+ * read, its environment variable, read once per process, gives the initial value; NaN (the
+ * default) leaves the library's own rule in force. Set them between calls, never while a call
+ * of another thread is in flight.
+ *  - STS_KNOB_ATTN_WGS_PER_CU (env STS_ATTN_WGS_PER_CU): target workgroups per compute unit when
+ *    the context is split. It changes the split count, hence sts_attn_workspace_bytes and the
+ *    rounding of the output: a workspace sized before the change may be refused afterwards
+ *    (STS_EWORKSPACE; never written out of bounds).
+ *  - STS_KNOB_SELECT_SPIN_LIMIT (env STS_SELECT_SPIN_LIMIT): polls of another workgroup's
+ *    published counts before they are recomputed locally. No effect on results.
+ *  - STS_KNOB_PROBSUM_WGS_PER_CU (env STS_PROBSUM_WGS_PER_CU): workgroups per compute unit of the
+ *    pass that writes weights_sum_out. No effect on results.
+ *  - STS_KNOB_SELECT_PATH (env STS_SELECT_PATH): 0 the library's rule, 1 histogram pipeline only,
+ *    2 pipeline or chunk-local top-k + pool, 3 the one-launch selection for rows of up to 256
+ *    parts (the rule stops at 8). It changes sts_select_workspace_bytes, never the results.
+ */
+typedef enum {
+  STS_KNOB_ATTN_WGS_PER_CU = 0,
+  STS_KNOB_SELECT_SPIN_LIMIT = 1,
+  STS_KNOB_PROBSUM_WGS_PER_CU = 2,
+  STS_KNOB_SELECT_PATH = 3,
+  STS_KNOB_COUNT_ = 4
+} sts_knob;
+void sts_set_knob(int knob, double value);
+double sts_get_knob(int knob);
 
 /* Launch geometry chosen for a shape (for reports): number of context splits and of
  * (head-set) work units per batch element. Returns STS_OK or the validation error. */

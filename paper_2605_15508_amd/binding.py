@@ -21,13 +21,14 @@ STS_BF16, STS_F32 = 0, 1
 KERNEL_KINDS = {"select_clear": 0, "select_agg": 1, "select_hist": 2, "select_count": 3,
                 "select_write": 4, "attn_sparse": 5, "attn_dense": 6, "attn_combine": 7, "select_block": 8,
                 "headmap": 9, "select_small": 10, "select_local": 11, "select_pool": 12,
-                "attn_probsum": 13}
+                "attn_probsum": 13, "select_fused": 14}
+KNOBS = {"attn_wgs_per_cu": 0, "select_spin_limit": 1, "probsum_wgs_per_cu": 2, "select_path": 3}
 
 # every symbol include/sts.h declares
 EXPORTS = ["sts_select_workspace_bytes", "sts_attn_workspace_bytes", "sts_select", "sts_sparse_attn",
            "sts_dense_attn", "sts_strerror", "sts_version", "sts_prof_enable", "sts_prof_reset",
            "sts_prof_read", "sts_attn_plan", "sts_head_map", "sts_headmap_workspace_bytes",
-           "sts_sparse_attn_static"]
+           "sts_sparse_attn_static", "sts_set_knob", "sts_get_knob"]
 STS_STATIC_SCRATCH_BYTES = 8 << 20
 
 
@@ -108,6 +109,10 @@ def load_library():
     lib.sts_head_map.argtypes = [ctypes.POINTER(HeadmapParams), ctypes.c_void_p]
     lib.sts_attn_plan.restype = ctypes.c_int
     lib.sts_attn_plan.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_int] + [ctypes.POINTER(ctypes.c_int32)] * 3
+    lib.sts_set_knob.restype = None
+    lib.sts_set_knob.argtypes = [ctypes.c_int, ctypes.c_double]
+    lib.sts_get_knob.restype = ctypes.c_double
+    lib.sts_get_knob.argtypes = [ctypes.c_int]
     _lib = lib
     return lib
 
@@ -393,6 +398,16 @@ def attn_plan(q, k, sparse: bool, kmax: int = 0, head_map=None, page_size: int =
     _check(lib.sts_attn_plan(ctypes.byref(p), 1 if sparse else 0, ctypes.byref(s), ctypes.byref(u),
                              ctypes.byref(nq)), "sts_attn_plan")
     return {"num_splits": s.value, "units_per_batch": u.value, "query_tiles": nq.value}
+
+
+def set_knob(name: str, value=None):
+    """Set a tuning / test knob of the library (see sts_set_knob in include/sts.h); None restores
+    the library's own rule."""
+    load_library().sts_set_knob(KNOBS[name], float("nan") if value is None else float(value))
+
+
+def get_knob(name: str) -> float:
+    return float(load_library().sts_get_knob(KNOBS[name]))
 
 
 def prof_enable(on: bool = True):

@@ -50,6 +50,30 @@ hipError_t run_kernel(int kind, hipStream_t s, F &&launch) {
   return rc;
 }
 
+// ------------------------------------------------------------------------- tuning knobs
+// Values set with sts_set_knob; before the first set or get of a knob its environment variable
+// (read once per process) gives the initial value. NaN = not set: the library's own rule applies.
+const char *const KNOB_ENV[STS_KNOB_COUNT_] = {"STS_ATTN_WGS_PER_CU", "STS_SELECT_SPIN_LIMIT",
+                                               "STS_PROBSUM_WGS_PER_CU", "STS_SELECT_PATH"};
+std::mutex g_knob_mu;
+double g_knob[STS_KNOB_COUNT_];
+bool g_knob_init = false;
+
+void knobs_init_locked() {
+  if (g_knob_init) return;
+  for (int i = 0; i < STS_KNOB_COUNT_; ++i) {
+    const char *e = getenv(KNOB_ENV[i]);
+    g_knob[i] = (e && *e) ? atof(e) : NAN;
+  }
+  g_knob_init = true;
+}
+
+double knob(int which) {
+  std::lock_guard<std::mutex> lk(g_knob_mu);
+  knobs_init_locked();
+  return g_knob[which];
+}
+
 int cu_count() {
   static const int cus = [] {   // once per process (thread-safe initialisation)
     int dev = 0, n = 0;
@@ -146,10 +170,9 @@ sts_status plan_attn(const sts_attn_params *p, int sparse, AttnPlan &pl) {
   // The gather with two query tiles at head size 128 (as register-bound as the dense kernel)
   // is 3% faster with one as well.
   int64_t resident = (int64_t)cu_count() * ((pl.nq == 4 || (p->d == 128 && (!sparse || pl.nq == 2))) ? 1 : 2);
-  if (const char *e = getenv("STS_ATTN_WGS_PER_CU")) {   // tuning knob: target workgroups per CU
-    const double f = atof(e);
-    if (f > 0.0) resident = (int64_t)(cu_count() * f);
-  }
+  const double wgs_knob = knob(STS_KNOB_ATTN_WGS_PER_CU);   // tuning knob: target workgroups per CU
+  const bool wgs_set = wgs_knob > 0.0;                       // (NaN compares false)
+  if (wgs_set) resident = (int64_t)(cu_count() * wgs_knob);
   const int64_t units_total = (int64_t)p->B * nu;
   int64_t S = units_total > 0 ? resident / units_total : 1;
   // at least two tiles per wave, so that the partials and their combine stay small next to
@@ -161,7 +184,7 @@ sts_status plan_attn(const sts_attn_params *p, int sparse, AttnPlan &pl) {
   // With at least one unit per CU, halving every unit only adds the combine launch: one
   // workgroup per CU keeps enough loads in flight (70B-shaped layer, 256 units of 410 tiles:
   // 268 us unsplit against 278 us in two halves).
-  if (S == 2 && units_total >= cu_count() && !getenv("STS_ATTN_WGS_PER_CU")) S = 1;
+  if (S == 2 && units_total >= cu_count() && !wgs_set) S = 1;
   if (S < 1) S = 1;
   pl.num_splits = (int)S;
   const size_t parts = (size_t)units_total * (size_t)S;
@@ -266,10 +289,7 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s, void *w
     const int64_t tiles = ((int64_t)p->N + STS_TILE_KEYS - 1) / STS_TILE_KEYS;
     const int64_t groups = (int64_t)p->B * p->Hkv * a.ps_sets;
     double per_cu = attn_probsum_wgs_per_cu(p->d, nq);
-    if (const char *e = getenv("STS_PROBSUM_WGS_PER_CU")) {   // tuning knob
-      const double f = atof(e);
-      if (f > 0.0) per_cu = f;
-    }
+    if (const double f = knob(STS_KNOB_PROBSUM_WGS_PER_CU); f > 0.0) per_cu = f;   // tuning knob
     int64_t S = (int64_t)(cu_count() * per_cu) / groups;
     const int64_t s_cap = (tiles + 4 * STS_WG_WAVES - 1) / (4 * STS_WG_WAVES);
     if (S > s_cap) S = s_cap;
@@ -286,14 +306,21 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s, void *w
 struct SelectPlan {
   bool small;          // one workgroup per row, keys in LDS, a single launch
   bool pool;           // shape allows chunk-local top-k + one ranking workgroup per row
+  bool fused;          // long rows: parts of a row in LDS, one launch (plus the flag clear)
   int nchunks, page, srcN, pool_pitch, pool_chunk, pool_nchunks;
+  int part_tokens, parts;
   size_t agg_bytes, blk_bytes, hist_bytes, state_bytes, chunk_bytes;
   size_t pool_key_bytes;
+  size_t pub_bytes, pflag_bytes;
   size_t pipeline_total() const { return agg_bytes + blk_bytes + hist_bytes + state_bytes + chunk_bytes; }
   size_t pool_total() const { return pool ? 2 * pool_key_bytes : 0; }
+  size_t fused_total() const { return pub_bytes + pflag_bytes; }
   // a pool-shaped call falls back to the pipeline when its pointers are not 16-byte aligned,
   // so the workspace covers both
-  size_t total() const { return pipeline_total() > pool_total() ? pipeline_total() : pool_total(); }
+  size_t total() const {
+    if (fused) return fused_total();
+    return pipeline_total() > pool_total() ? pipeline_total() : pool_total();
+  }
 };
 
 sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
@@ -316,6 +343,13 @@ sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
   pl.pool = false;
   pl.pool_pitch = 0;
   pl.pool_key_bytes = 0;
+  pl.fused = false;
+  pl.part_tokens = pl.parts = 0;
+  pl.pub_bytes = pl.pflag_bytes = 0;
+  // test / tuning knob: 0 the library's rule, 1 histogram pipeline only, 2 pipeline or pool,
+  // 3 the one-launch selection wherever its shape limits allow
+  const double path_knob = knob(STS_KNOB_SELECT_PATH);
+  const int path = path_knob == path_knob ? (int)path_knob : 0;
   if (pl.small) {
     pl.nchunks = 0;
     pl.agg_bytes = pl.blk_bytes = pl.hist_bytes = pl.state_bytes = pl.chunk_bytes = 0;
@@ -329,7 +363,7 @@ sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
   // passes over the aggregate are long (8M scores or more in the call). Chunks are 8192 tokens,
   // or 32768 when only that keeps the pool small enough (long rows, middle budgets).
   pl.pool_chunk = pl.pool_nchunks = 0;
-  if (pl.page == 1 && (p->N % 4) == 0) {
+  if (pl.page == 1 && (p->N % 4) == 0 && path != 1) {
     for (const int chunk : {SEL_CHUNK, 4 * SEL_CHUNK}) {
       const int64_t nch = ((int64_t)p->N + chunk - 1) / chunk;
       const int64_t pitch = p->k < chunk ? p->k : chunk;
@@ -344,6 +378,25 @@ sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
         pl.pool_key_bytes = align256(rows * (size_t)nch * (size_t)pitch * sizeof(uint32_t));
         break;
       }
+    }
+  }
+  // Long rows at token granularity: one launch in which every workgroup keeps a part of a row in
+  // LDS (select_fused_kernel). Parts are as large as LDS allows (32768 tokens) when that still
+  // gives a workgroup per CU, else smaller, down to 8192, to spread short calls over the chip.
+  if (pl.page == 1 && p->N > SEL_FUSED_N && path != 1 && path != 2) {
+    const int max_parts = path == 3 ? 256 : SEL_FUSED_MAX_PARTS;
+    int P = SEL_SMALL_N;
+    while (P > SEL_FUSED_N && (int64_t)rows * (((int64_t)p->N + P - 1) / P) < cu_count() &&
+           ((int64_t)p->N + P / 2 - 1) / (P / 2) <= max_parts)
+      P >>= 1;
+    const int64_t parts = ((int64_t)p->N + P - 1) / P;
+    if (parts <= max_parts) {
+      pl.fused = true;
+      pl.pool = false;
+      pl.part_tokens = P;
+      pl.parts = (int)parts;
+      pl.pub_bytes = align256(rows * 3 * (size_t)parts * 1024 * sizeof(unsigned long long));
+      pl.pflag_bytes = 0;
     }
   }
   pl.agg_bytes = p->agg_out ? 0 : align256(rows * (size_t)p->N * sizeof(float));
@@ -457,9 +510,12 @@ static sts_status enqueue_select(const sts_select_params *p, void *stream) {
   // Test knob: STS_SELECT_SPIN_LIMIT bounds the polls of an earlier chunk's published counts
   // before the waiting workgroup recounts that chunk itself (0: one look, then recount).
   {
-    const char *e = getenv("STS_SELECT_SPIN_LIMIT");
-    const int v = e ? atoi(e) : 256;
-    a.spin_limit = v < 0 ? 0 : (v > 65536 ? 65536 : v);
+    const double v = knob(STS_KNOB_SELECT_SPIN_LIMIT);
+    const bool set = v == v;   // not NaN
+    a.spin_limit = !set ? 256 : (v < 0 ? 0 : (v > 65536 ? 65536 : (int)v));
+    // the parts of the one-launch selection wait for ALL parts of their row, and recomputing a
+    // missing part's histogram means re-reading its scores: a far longer patience by default
+    a.fused_spin_limit = !set ? 20000 : a.spin_limit;
   }
   // inverse of the head map: the target heads fed by each draft head, in head order
   {
@@ -475,6 +531,21 @@ static sts_status enqueue_select(const sts_select_params *p, void *stream) {
   }
 
   hipError_t rc;
+  if (pl.fused) {
+    unsigned char *fw = static_cast<unsigned char *>(p->workspace);
+    a.pub = reinterpret_cast<unsigned long long *>(fw);
+    a.part_tokens = pl.part_tokens;
+    a.parts = pl.parts;
+    a.agg = p->agg_out;   // optional output only: the keys never leave LDS
+    a.src = nullptr;
+    a.hist = a.state = a.chunk_cnt = nullptr;   // the pipeline's scratch does not exist on this path
+    if (pl.parts > 1) {
+      rc = run_kernel(STS_K_SELECT_CLEAR, s, [&] { return launch_select_clear_pub(a, s); });
+      if (rc != hipSuccess) return STS_EHIP;
+    }
+    rc = run_kernel(STS_K_SELECT_FUSED, s, [&] { return launch_select_fused(a, s); });
+    return rc == hipSuccess ? STS_OK : STS_EHIP;
+  }
   if (pl.pool && reinterpret_cast<uintptr_t>(p->scores) % 16 == 0 &&
       (!p->agg_out || reinterpret_cast<uintptr_t>(p->agg_out) % 16 == 0)) {
     unsigned char *pw = static_cast<unsigned char *>(p->workspace);
@@ -559,16 +630,25 @@ sts_status plan_headmap(const sts_headmap_params *p, HeadmapPlan &pl) {
   pl.idx_d_bytes = align256(rows_d * (size_t)p->k * sizeof(int32_t));
   pl.idx_t_bytes = align256(rows_t * (size_t)p->k * sizeof(int32_t));
   pl.overlap_bytes = align256((size_t)p->Ht * p->Hd * sizeof(unsigned long long));
-  // one selection slice at a time: B = rows of the slice, one draft head, one query row
-  sts_select_params sp;
-  memset(&sp, 0, sizeof(sp));
-  const size_t big = rows_d > rows_t ? rows_d : rows_t;
-  sp.B = (int32_t)(big < (size_t)HM_SLICE ? big : (size_t)HM_SLICE);
-  sp.Hd = 1; sp.Tq = 1; sp.N = p->N; sp.Hq = 1; sp.k = p->k;
-  SelectPlan spl;
-  const sts_status v = plan_select(&sp, spl);
-  if (v != STS_OK) return v;
-  pl.select_bytes = spl.total();
+  // One selection slice at a time: B = rows of the slice, one draft head, one query row. The
+  // selection chooses its path (and with it its scratch size) from the row count, so the scratch
+  // is sized for the largest need over every slice size that will be launched: the full slices
+  // and the tail slice of either trace.
+  pl.select_bytes = 0;
+  for (const size_t rows : {rows_d, rows_t}) {
+    const size_t sizes[2] = {rows >= (size_t)HM_SLICE ? (size_t)HM_SLICE : 0, rows % (size_t)HM_SLICE};
+    for (const size_t n : sizes) {
+      if (n == 0) continue;
+      sts_select_params sp;
+      memset(&sp, 0, sizeof(sp));
+      sp.B = (int32_t)n;
+      sp.Hd = 1; sp.Tq = 1; sp.N = p->N; sp.Hq = 1; sp.k = p->k;
+      SelectPlan spl;
+      const sts_status v = plan_select(&sp, spl);
+      if (v != STS_OK) return v;
+      if (spl.total() > pl.select_bytes) pl.select_bytes = spl.total();
+    }
+  }
   return STS_OK;
 }
 
@@ -653,6 +733,18 @@ const char *sts_strerror(int status) {   // an int on purpose: any value a calle
 }
 
 int sts_version(void) { return 200; }
+
+void sts_set_knob(int which, double value) {
+  if (which < 0 || which >= STS_KNOB_COUNT_) return;
+  std::lock_guard<std::mutex> lk(g_knob_mu);
+  knobs_init_locked();
+  g_knob[which] = value;
+}
+
+double sts_get_knob(int which) {
+  if (which < 0 || which >= STS_KNOB_COUNT_) return NAN;
+  return knob(which);
+}
 
 void sts_prof_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);

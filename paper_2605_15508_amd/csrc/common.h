@@ -88,6 +88,9 @@ constexpr int SEL_THREADS = 256;
 constexpr int SEL_SMALL_N = 32768;      // LDS capacity of the one-workgroup-per-row selection (tokens)
 constexpr int SEL_FLAG_PITCH = 32;      // words between the published counts of two chunks: one 128-byte line each
 constexpr int SEL_FUSED_N = 8192;
+constexpr int SEL_FUSED_MAX_PARTS = 8;   // parts per row of the one-launch selection: every part reads every other
+                                         // part's histograms, which grows with the square (256K tokens; a test knob
+                                         // allows up to 256)
 constexpr int SEL_POOL_MAX = 16384;     // chunk-local winners per row that the pool kernel ranks out of LDS       // rows up to this many tokens always take it
 
 struct SelectTargets {
@@ -119,6 +122,10 @@ struct SelectArgs {
   uint64_t clear_words;       // words to zero from `hist` on: histograms, state and chunk flags
   int32_t hist_cpw;           // consecutive chunks per workgroup of the refinement histograms (1, 2 or 4)
   int32_t spin_limit;         // polls of an unpublished earlier chunk before it is recounted locally
+  unsigned long long *pub;    // fused selection: [rows][3][parts][1024] words the parts publish (top bit: written;
+                              // two bin counts in the halves), zero before the launch
+  int32_t part_tokens, parts; // fused selection: tokens per part (8192..32768) and parts per row
+  int32_t fused_spin_limit;   // polls of another part's flag before its histogram is recomputed locally
   int32_t agg_is_input;       // `agg` is the caller's score tensor itself (one fp32 probability row per head): never stored to
   int32_t B, Hd, Tq, N, Hq, k, kind, reduce, nchunks;   // k: row pitch of indices = largest budget
   SelectTargets targets;
@@ -140,6 +147,8 @@ hipError_t launch_select_small(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_rank(const SelectArgs &a, hipStream_t s);
 bool select_aggblock_ok(const SelectArgs &a);
 hipError_t launch_select_aggblock(const SelectArgs &a, hipStream_t s);
+hipError_t launch_select_fused(const SelectArgs &a, hipStream_t s);
+hipError_t launch_select_clear_pub(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_local(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_pool(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t s);

@@ -179,44 +179,48 @@ struct ScoreLoad<f32x4, true> {
   }
 };
 
-// NROWS consecutive score rows, from row i on, of the token(s) at n: all loads first (their
-// latencies overlap), then the reduction strictly in row order. FIRST: row i is row 0 and
-// initialises the accumulator.
-template <int NROWS, bool FIRST, bool BF16, class V>
-__device__ __forceinline__ void agg_rows(const AggRow &R, int i, int n, V &acc) {
+// NROWS consecutive score rows, from row i on, of the token(s) at each of the NPOS positions n[]:
+// all loads first (their latencies overlap), then the reduction strictly in row order. FIRST: row
+// i is row 0 and initialises the accumulators.
+template <int NROWS, bool FIRST, bool BF16, int NPOS, class V>
+__device__ __forceinline__ void agg_rows(const AggRow &R, int i, const int (&n)[NPOS], V (&acc)[NPOS]) {
   typedef ScoreLoad<V, BF16> SL;
-  typename SL::raw raw[NROWS];
+  typename SL::raw raw[NPOS][NROWS];
 #pragma unroll
-  for (int u = 0; u < NROWS; ++u) raw[u] = SL::load(R, i + u, n);
+  for (int x = 0; x < NPOS; ++x)
 #pragma unroll
-  for (int u = 0; u < NROWS; ++u) {
-    V p = SL::widen(raw[u]);
-    if (R.logits) {
-      const float l = R.L[i + u];
-      if constexpr (sizeof(V) == sizeof(float)) {
-        p = prob_of(p, l);
+    for (int u = 0; u < NROWS; ++u) raw[x][u] = SL::load(R, i + u, n[x]);
+#pragma unroll
+  for (int x = 0; x < NPOS; ++x)
+#pragma unroll
+    for (int u = 0; u < NROWS; ++u) {
+      V p = SL::widen(raw[x][u]);
+      if (R.logits) {
+        const float l = R.L[i + u];
+        if constexpr (sizeof(V) == sizeof(float)) {
+          p = prob_of(p, l);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) p[e] = prob_of(p[e], l);
+        }
+      }
+      if (FIRST && u == 0) {
+        acc[x] = p;
+      } else if (R.use_max) {
+        if constexpr (sizeof(V) == sizeof(float)) {
+          acc[x] = fmaxf(acc[x], p);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[x][e] = fmaxf(acc[x][e], p[e]);
+        }
       } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) p[e] = prob_of(p[e], l);
+        acc[x] = acc[x] + p;
       }
     }
-    if (FIRST && u == 0) {
-      acc = p;
-    } else if (R.use_max) {
-      if constexpr (sizeof(V) == sizeof(float)) {
-        acc = fmaxf(acc, p);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) acc[e] = fmaxf(acc[e], p[e]);
-      }
-    } else {
-      acc = acc + p;
-    }
-  }
 }
 
-template <bool FIRST, bool BF16, class V>
-__device__ __forceinline__ void agg_group(const AggRow &R, int i, int rows, int n, V &acc) {
+template <bool FIRST, bool BF16, int NPOS, class V>
+__device__ __forceinline__ void agg_group(const AggRow &R, int i, int rows, const int (&n)[NPOS], V (&acc)[NPOS]) {
   switch (rows) {   // uniform: a scalar branch; every case is straight-line code
     case 1: agg_rows<1, FIRST, BF16>(R, i, n, acc); break;
     case 2: agg_rows<2, FIRST, BF16>(R, i, n, acc); break;
@@ -229,10 +233,10 @@ __device__ __forceinline__ void agg_group(const AggRow &R, int i, int rows, int 
   }
 }
 
-// aggregated score(s) at n: rows in groups of up to 8 loads in flight
-template <class V>
-__device__ __forceinline__ V agg_at(const AggRow &R, int n) {
-  V acc;
+// aggregated score(s) at NPOS positions at once: rows in groups of up to 8 loads per position in
+// flight
+template <class V, int NPOS>
+__device__ __forceinline__ void agg_multi(const AggRow &R, const int (&n)[NPOS], V (&acc)[NPOS]) {
   if (R.bf16) {
     agg_group<true, true>(R, 0, min(R.Tq, 8), n, acc);
     for (int i = 8; i < R.Tq; i += 8) agg_group<false, true>(R, i, min(R.Tq - i, 8), n, acc);
@@ -240,7 +244,14 @@ __device__ __forceinline__ V agg_at(const AggRow &R, int n) {
     agg_group<true, false>(R, 0, min(R.Tq, 8), n, acc);
     for (int i = 8; i < R.Tq; i += 8) agg_group<false, false>(R, i, min(R.Tq - i, 8), n, acc);
   }
-  return acc;
+}
+
+template <class V>
+__device__ __forceinline__ V agg_at(const AggRow &R, int n) {
+  const int pos[1] = {n};
+  V acc[1];
+  agg_multi<V, 1>(R, pos, acc);
+  return acc[0];
 }
 
 __device__ __forceinline__ f32x4 agg_quad(const AggRow &R, int n) { return agg_at<f32x4>(R, n); }
@@ -261,6 +272,11 @@ __device__ __forceinline__ void flush_hist(uint32_t *global_bins, const uint32_t
 __global__ void __launch_bounds__(SEL_THREADS) select_clear_kernel(uint32_t *p, size_t n) {
   const size_t i = (size_t)blockIdx.x * SEL_THREADS + threadIdx.x;
   if (i < n) p[i] = 0u;
+}
+
+__global__ void __launch_bounds__(SEL_THREADS) select_clear16_kernel(u32x4 *p, size_t n) {
+  const size_t i = (size_t)blockIdx.x * SEL_THREADS + threadIdx.x;
+  if (i < n) p[i] = u32x4{0u, 0u, 0u, 0u};
 }
 
 // --------------------------------------------------------------------------- aggregation
@@ -296,13 +312,19 @@ __global__ void __launch_bounds__(SEL_THREADS) select_agg_kernel(const SelectArg
 #pragma clang loop unroll(full)
       for (int i = 0; i < IT; ++i) {
         const int n = n0 + (i * SEL_THREADS + (int)threadIdx.x) * 4;
-        if (n < n1) *reinterpret_cast<f32x4 *>(out + n) = keep[i];
+        if (n < n1) {
+          f32x4 o = keep[i];
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (n + e >= nb) o[e] = 0.f;          // the stored aggregate is 0 past the valid length
+          *reinterpret_cast<f32x4 *>(out + n) = o;
+        }
       }
     }
   } else {
     for (int n = n0 + threadIdx.x; n < n1; n += SEL_THREADS) {
       const float acc = agg_one(R, n);
-      if (!A.agg_is_input) out[n] = acc;
+      if (!A.agg_is_input) out[n] = n < nb ? acc : 0.f;
       if (A.page == 1 && n < nb) atomicAdd(&h[key_of(acc) >> (32 - SEL_BITS0)], 1u);
     }
   }
@@ -415,7 +437,13 @@ __global__ void __launch_bounds__(SEL_THREADS) select_aggblock_kernel(const Sele
   for (int n = blockIdx.x * SEL_CHUNK + threadIdx.x * 4; n < min((blockIdx.x + 1) * SEL_CHUNK, A.N);
        n += SEL_THREADS * 4) {
     const f32x4 x = agg_quad(R, n);
-    if (tok_out) *reinterpret_cast<f32x4 *>(tok_out + n) = x;
+    if (tok_out) {
+      f32x4 o = x;
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (n + e >= nb) o[e] = 0.f;
+      *reinterpret_cast<f32x4 *>(tok_out + n) = o;
+    }
     float run = 0.f;
     bool have = false;                             // whether `run` holds at least one term
     for (int s = 0; s < L; ++s) {
@@ -836,18 +864,20 @@ __global__ void __launch_bounds__(SMALL_THREADS) select_small_kernel(const Selec
   } else if (VEC4) {
     for (int n = tid * 4; n < A.N; n += SMALL_THREADS * 4) {
       const f32x4 acc = agg_quad(R, n);
-      if (want_agg) *reinterpret_cast<f32x4 *>(out + n) = acc;
+      f32x4 o = acc;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const uint32_t key = key_of(acc[e]);
         keys[small_slot(n + e)] = key;
         if (n + e < nb) atomicAdd(&h[key >> (32 - SEL_BITS0)], 1u);
+        else o[e] = 0.f;
       }
+      if (want_agg) *reinterpret_cast<f32x4 *>(out + n) = o;
     }
   } else {
     for (int n = tid; n < A.N; n += SMALL_THREADS) {
       const float acc = agg_one(R, n);
-      if (want_agg) out[n] = acc;
+      if (want_agg) out[n] = n < nb ? acc : 0.f;
       const uint32_t key = key_of(acc);
       keys[small_slot(n)] = key;
       if (n < nb) atomicAdd(&h[key >> (32 - SEL_BITS0)], 1u);
@@ -861,6 +891,310 @@ __global__ void __launch_bounds__(SMALL_THREADS) select_small_kernel(const Selec
   lds_compact<SMALL_THREADS, SEL_SMALL_N / SMALL_THREADS>(keys, nb, T, r, c, tmp, [&](uint32_t pos, int n) {
     for (int ti = t0; ti < t1; ++ti) A.indices[((size_t)bt * A.Hq + A.targets.tgt[ti]) * A.k + pos] = n;
   });
+}
+
+// ------------------------------------------------------- long rows: the whole selection in one launch
+// A row is cut into parts of P = PER * 1024 tokens; one 1024-thread workgroup per (part, row)
+// aggregates its part once (same fp32 order), keeps the keys in LDS and never reads a score or an
+// aggregate again. The three digit histograms are row-wide quantities, so at each level every part
+// publishes its own histogram and adds up the histograms of all parts of its row; the digit search
+// is then done redundantly by every part. While adding, a part also keeps the sum over the parts
+// BEFORE it, which after the digit search gives the number of keys greater than / equal to the
+// threshold in earlier parts, i.e. where its own kept tokens start in the output list: no second
+// exchange is needed for the compaction.
+//
+// Exchange protocol (per level). The published area is zeroed by a small kernel launched before
+// this one. Thread t of a part publishes the counts of bins 2t and 2t+1 in one 64-bit word whose
+// top bit says "written" (a device-scope store of 8 aligned bytes: the word arrives whole), and
+// reads the words of the other parts for the same two bins until their top bits are set: the
+// payload is its own flag, so one memory round trip per level is all the parts wait for each
+// other. The wait is bounded: after the poll limit the workgroup decides, part by part, which
+// histograms have arrived completely and recomputes the others from the scores itself, so every
+// workgroup exits whatever the others do (a row's parts have neighbouring workgroup ids and start
+// together, so in practice the words are there on the first or second look).
+constexpr int FUSED_THREADS = 1024;
+constexpr unsigned long long FUSED_VALID = 1ull << 63;
+// LDS slot of a part's local token l: four pad words after every 32 tokens. Quads (l % 4 == 0)
+// stay contiguous and 16-byte aligned, so every pass moves four keys per LDS instruction, and both
+// ways of walking the part are free of bank conflicts: consecutive lanes on consecutive quads, and
+// lane t on the quads of its own run of 32 tokens (36 words apart from its neighbour's).
+__device__ __forceinline__ int fused_slot(int l) { return l + ((l >> 5) << 2); }
+
+// sum over the block of two values per thread; red needs 2 * FUSED_THREADS / 64 words
+__device__ __forceinline__ void block_sum2(uint32_t a, uint32_t b, uint32_t *red, uint32_t &sa, uint32_t &sb) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    a += (uint32_t)__shfl_xor((int)a, off, 64);
+    b += (uint32_t)__shfl_xor((int)b, off, 64);
+  }
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) {
+    red[2 * wave] = a;
+    red[2 * wave + 1] = b;
+  }
+  __syncthreads();
+  sa = sb = 0;
+#pragma unroll
+  for (int w = 0; w < FUSED_THREADS / 64; ++w) {
+    sa += red[2 * w];
+    sb += red[2 * w + 1];
+  }
+  __syncthreads();
+}
+
+// bin of `key` at `level` under the prefix fixed so far, or -1 when the key is no candidate
+__device__ __forceinline__ int fused_bin(uint32_t key, int level, uint32_t d0, uint32_t pre01) {
+  if (level == 0) return (int)(key >> (32 - SEL_BITS0));
+  if (level == 1) return (key >> (SEL_BITS1 + SEL_BITS2)) == d0 ? (int)((key >> SEL_BITS2) & ((1u << SEL_BITS1) - 1)) : -1;
+  return (key >> SEL_BITS2) == pre01 ? (int)(key & ((1u << SEL_BITS2) - 1)) : -1;
+}
+
+template <bool VEC4, int PER>
+__global__ void __launch_bounds__(FUSED_THREADS) select_fused_kernel(const SelectArgs A) {
+  constexpr int T = FUSED_THREADS;
+  constexpr int P = PER * T;                       // tokens per part
+  __shared__ __attribute__((aligned(16))) uint32_t keys[P + P / 8];   // later: the staged token ids of the part
+  __shared__ uint32_t h[SEL_BINS];
+  __shared__ uint32_t tmp[T / 64 + 2];
+  __shared__ uint32_t red[2 * T / 64];
+  __shared__ uint32_t lds_flag[2];                 // [0]: some thread ran out of polls, [1]: scratch of the slow path
+  const int row = blockIdx.y, part = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int bt = row / A.Hd, j = row % A.Hd;
+  const int nb = row_len(A, bt);
+  const uint32_t c = (uint32_t)min(A.kh[j], nb);
+  const int t0 = A.targets.off[j], t1 = A.targets.off[j + 1];
+  if (part == 0) write_tail<T>(A, bt, j, c);
+  const bool want_agg = A.agg != nullptr;
+  const bool ranked = c > 0 && t0 != t1;           // the same for every part of the row
+  if (!ranked && !want_agg) return;
+  const int n0 = part * P;
+  const int nend = min(n0 + P, A.N);
+  const int m = max(0, min(nend, nb) - n0);        // ranked tokens of this part
+  const int Qv = (nb + P - 1) / P;                 // parts of the row that hold ranked tokens
+  if (m == 0 && !want_agg) return;                 // the other parts do not expect this one
+
+  for (int i = tid; i < SEL_BINS; i += T) h[i] = 0u;
+  if (tid == 0) lds_flag[0] = 0u;
+  __syncthreads();
+  const AggRow R = agg_row(A, row);
+  float *out = want_agg ? A.agg + (size_t)row * A.N : nullptr;
+  if (VEC4) {
+    // one quad per thread and step (more in flight did not stream faster: 16 waves per CU keep
+    // enough loads outstanding, and the registers are better spent elsewhere)
+#pragma unroll 1
+    for (int i = 0; i < PER / 4; ++i) {
+      const int l = (i * T + tid) * 4;             // local token index
+      if (l < m) {
+        const f32x4 acc = agg_quad(R, n0 + l);     // N % 4 == 0: the quad lies inside the row
+        f32x4 o = acc;
+        u32x4 kv;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          kv[e] = key_of(acc[e]);
+          if (l + e < m) atomicAdd(&h[kv[e] >> (32 - SEL_BITS0)], 1u);
+          else o[e] = 0.f;                         // the aggregate is 0 past the valid length
+        }
+        *reinterpret_cast<u32x4 *>(&keys[fused_slot(l)]) = kv;
+        if (want_agg) *reinterpret_cast<f32x4 *>(out + n0 + l) = o;
+      } else if (want_agg && n0 + l < nend) {
+        *reinterpret_cast<f32x4 *>(out + n0 + l) = f32x4{0.f, 0.f, 0.f, 0.f};
+      }
+    }
+  } else {
+    for (int l = tid; l < nend - n0; l += T) {
+      float acc = 0.f;
+      if (l < m) {
+        acc = agg_one(R, n0 + l);
+        const uint32_t key = key_of(acc);
+        keys[fused_slot(l)] = key;
+        atomicAdd(&h[key >> (32 - SEL_BITS0)], 1u);
+      }
+      if (want_agg) out[n0 + l] = acc;
+    }
+  }
+  __syncthreads();
+  if (!ranked || m == 0) return;
+
+  // Three levels, one loop (the code below exists once): build this part's histogram of the level
+  // (level 0 was built while streaming), exchange it, find the row-wide digit.
+  uint32_t pre_gt = 0, pre_eq = 0;       // keys of earlier parts greater than / equal to the threshold
+  uint32_t d0 = 0, pre01 = 0, krem = c, d2 = 0;
+  uint32_t cand = 0;                     // bit 4i + e: token e of this thread's quad tid + i * T shares the first digit
+#pragma unroll 1
+  for (int level = 0; level < 3; ++level) {
+    if (level > 0) {
+      for (int i = tid; i < SEL_BINS; i += T) h[i] = 0u;
+      __syncthreads();
+      if (level == 1) {
+        // all of the thread's PER keys (quads tid, tid + T, ...), four quads in flight at a time;
+        // cand remembers the candidates so that the last level only looks at those again
+#pragma unroll 1
+        for (int i0 = 0; i0 < PER / 4; i0 += 2) {
+          u32x4 kq[2];
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+            kq[i] = *reinterpret_cast<const u32x4 *>(&keys[fused_slot(min((tid + (i0 + i) * T) * 4, P - 4))]);
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int bin = fused_bin(kq[i][e], 1, d0, 0u);
+              if ((tid + (i0 + i) * T) * 4 + e < m && bin >= 0) {
+                atomicAdd(&h[bin], 1u);
+                cand |= 1u << (4 * (i0 + i) + e);
+              }
+            }
+        }
+      } else {
+        for (uint32_t rest = cand; rest; rest &= rest - 1) {
+          const int bit = __builtin_ctz(rest);
+          const int bin = fused_bin(keys[fused_slot((tid + (bit >> 2) * T) * 4 + (bit & 3))], 2, d0, pre01);
+          if (bin >= 0) atomicAdd(&h[bin], 1u);
+        }
+      }
+      __syncthreads();
+    }
+    const uint32_t own0 = h[2 * tid], own1 = h[2 * tid + 1];
+    uint32_t all0 = own0, all1 = own1, bef0 = 0, bef1 = 0;
+    if (Qv > 1) {
+      unsigned long long *pub = A.pub + (size_t)(row * 3 + level) * A.parts * T;      // [parts][T]
+      __hip_atomic_store(&pub[(size_t)part * T + tid], FUSED_VALID | own0 | ((unsigned long long)own1 << 32),
+                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      bool complete = false;
+      for (int spin = 0; !complete && spin <= A.fused_spin_limit; ++spin) {
+        if (spin) __builtin_amdgcn_s_sleep(4);
+        all0 = own0; all1 = own1; bef0 = bef1 = 0;
+        complete = true;
+        // loads are unconditional so that they overlap (this part's own word contributes nothing)
+#pragma unroll 4
+        for (int q = 0; q < Qv; ++q) {
+          const unsigned long long w = __hip_atomic_load(&pub[(size_t)q * T + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const bool use = q != part;
+          if (use && !(w & FUSED_VALID)) complete = false;
+          const uint32_t w0 = use ? ((uint32_t)w & 0xffffffu) : 0u, w1 = use ? ((uint32_t)(w >> 32) & 0xffffffu) : 0u;
+          all0 += w0;
+          all1 += w1;
+          bef0 += q < part ? w0 : 0u;
+          bef1 += q < part ? w1 : 0u;
+        }
+      }
+      if (!complete) lds_flag[0] = 1u;
+      __syncthreads();
+      if (lds_flag[0]) {
+        // Some thread ran out of polls (the flag stays set: later levels come this way too). Part by
+        // part, the histogram is used if all of its 1024 words have arrived and is recomputed from
+        // the scores otherwise: the same decision in every thread.
+        all0 = own0; all1 = own1; bef0 = bef1 = 0;
+#pragma unroll 1
+        for (int q = 0; q < Qv; ++q) {
+          if (q == part) continue;
+          if (tid == 0) lds_flag[1] = 1u;
+          __syncthreads();
+          const unsigned long long w = __hip_atomic_load(&pub[(size_t)q * T + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (!(w & FUSED_VALID)) lds_flag[1] = 0u;
+          __syncthreads();
+          uint32_t w0 = (uint32_t)w & 0xffffffu, w1 = (uint32_t)(w >> 32) & 0xffffffu;
+          if (lds_flag[1] == 0u) {        // uniform
+            for (int i = tid; i < SEL_BINS; i += T) h[i] = 0u;
+            __syncthreads();
+            const int q0 = q * P, q1 = min(q0 + P, nb);
+            if (VEC4) {
+#pragma unroll 1
+              for (int n = q0 + tid * 4; n < q1; n += T * 4) {
+                const f32x4 acc = agg_quad(R, n);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const int bin = fused_bin(key_of(acc[e]), level, d0, pre01);
+                  if (n + e < q1 && bin >= 0) atomicAdd(&h[bin], 1u);
+                }
+              }
+            } else {
+#pragma unroll 1
+              for (int n = q0 + tid; n < q1; n += T) {
+                const int bin = fused_bin(key_of(agg_one(R, n)), level, d0, pre01);
+                if (bin >= 0) atomicAdd(&h[bin], 1u);
+              }
+            }
+            __syncthreads();
+            w0 = h[2 * tid];
+            w1 = h[2 * tid + 1];
+          }
+          __syncthreads();                // h and the flag are free again
+          all0 += w0;
+          all1 += w1;
+          bef0 += q < part ? w0 : 0u;
+          bef1 += q < part ? w1 : 0u;
+        }
+      }
+    }
+    __syncthreads();
+    h[2 * tid] = all0;
+    h[2 * tid + 1] = all1;
+    __syncthreads();
+    uint32_t digit, knext;
+    find_digit<SEL_BINS, T>(h, krem, tmp, digit, knext);
+    // keys of earlier parts in higher bins are greater than the threshold whatever follows; those
+    // in the digit's own bin are the "equal" ones of the last level
+    const uint32_t b0 = 2 * tid, b1 = 2 * tid + 1;
+    const uint32_t above = (b0 > digit ? bef0 : 0u) + (b1 > digit ? bef1 : 0u);
+    const uint32_t at = (b0 == digit ? bef0 : 0u) + (b1 == digit ? bef1 : 0u);
+    uint32_t sa, sb;
+    block_sum2(above, at, red, sa, sb);
+    pre_gt += sa;
+    pre_eq = sb;
+    if (level == 0) d0 = digit;
+    else if (level == 1) pre01 = (d0 << SEL_BITS1) | digit;
+    else d2 = digit;
+    krem = knext;
+  }
+  const uint32_t r = krem;               // keys equal to the threshold that are kept
+  const uint32_t Tk = (pre01 << SEL_BITS2) | d2;
+
+  // ordered compaction of the part: thread tid owns the PER consecutive tokens from tid * PER on;
+  // what it needs to remember of them are two bits per token (greater / equal)
+  static_assert(PER <= 32, "one mask bit per owned token");
+  uint32_t gt_mask = 0, eq_mask = 0;
+#pragma unroll 1
+  for (int i0 = 0; i0 < PER; i0 += 8) {
+    u32x4 kq[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) kq[i] = *reinterpret_cast<const u32x4 *>(&keys[fused_slot(tid * PER + i0 + 4 * i)]);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const bool in = tid * PER + i0 + i < m;
+      const uint32_t key = kq[i >> 2][i & 3];
+      gt_mask |= (in && key > Tk) ? 1u << (i0 + i) : 0u;
+      eq_mask |= (in && key == Tk) ? 1u << (i0 + i) : 0u;
+    }
+  }
+  const uint32_t cg = __builtin_popcount(gt_mask), ce = __builtin_popcount(eq_mask);
+  uint32_t total;
+  const uint32_t excl = block_excl_scan<T>(cg | (ce << 16), tmp, total);   // its barriers free the key buffer
+  const uint32_t part_gt = total & 0xffffu, part_eq = total >> 16;
+  const uint32_t first = pre_gt + min(pre_eq, r);
+  const uint32_t last = min((pre_gt + part_gt) + min(pre_eq + part_eq, r), c);
+  uint32_t g = pre_gt + (excl & 0xffffu), q = pre_eq + (excl >> 16);
+  int32_t *staged = reinterpret_cast<int32_t *>(keys);
+  for (uint32_t rest = gt_mask | eq_mask; rest; rest &= rest - 1) {
+    const int i = __builtin_ctz(rest);
+    const bool is_gt = (gt_mask >> i) & 1u;
+    if (is_gt || q < r) {
+      const uint32_t pos = g + min(q, r);
+      // always inside [first, last) for a consistent threshold; the test keeps a bad state in bounds
+      if (pos >= first && pos - first < (uint32_t)P) staged[pos - first] = n0 + tid * PER + i;
+    }
+    g += is_gt ? 1u : 0u;
+    q += is_gt ? 0u : 1u;
+  }
+  __syncthreads();
+  if (last > first) {
+    const uint32_t cnt = min(last - first, (uint32_t)P);
+    for (int ti = t0; ti < t1; ++ti) {
+      int32_t *dst = A.indices + ((size_t)bt * A.Hq + A.targets.tgt[ti]) * A.k + first;
+      for (uint32_t p = tid; p < cnt; p += T) dst[p] = staged[p];
+    }
+  }
 }
 
 // ---------------------------------------------- small budgets on long rows: chunk-local top-k
@@ -904,12 +1238,14 @@ __global__ void __launch_bounds__(THREADS) select_local_kernel(const SelectArgs 
     const int n = n0 + (i * THREADS + threadIdx.x) * 4;
     if (n < A.N) {                                             // N % 4 == 0 on this path
       const f32x4 acc = agg_quad(R, n);
-      if (want_agg) *reinterpret_cast<f32x4 *>(out + n) = acc;
+      f32x4 o = acc;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         K.k[i][e] = key_of(acc[e]);
         if (n + e < nb) atomicAdd(&h[K.k[i][e] >> (32 - SEL_BITS0)], 1u);
+        else o[e] = 0.f;
       }
+      if (want_agg) *reinterpret_cast<f32x4 *>(out + n) = o;
     } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e) K.k[i][e] = 0u;
@@ -1115,6 +1451,36 @@ hipError_t launch_select_aggblock(const SelectArgs &a, hipStream_t s) {
   if ((size_t)a.B * a.Hd == 0 || a.N == 0) return hipSuccess;
   const dim3 grid((a.N + SEL_CHUNK - 1) / SEL_CHUNK, a.B * a.Hd), block(SEL_THREADS);
   STS_LAUNCH(select_aggblock_kernel, grid, block, 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_select_fused(const SelectArgs &a, hipStream_t s) {
+  if ((size_t)a.B * a.Hd == 0 || a.parts == 0) return hipSuccess;
+  const dim3 grid(a.parts, a.B * a.Hd), block(FUSED_THREADS);
+  const bool v = (a.N % 4) == 0 && (reinterpret_cast<uintptr_t>(a.scores) % 16) == 0 &&
+                 (a.agg == nullptr || (reinterpret_cast<uintptr_t>(a.agg) % 16) == 0);
+#define STS_FUSED(PER)                                                                     \
+  do {                                                                                     \
+    if (v) STS_LAUNCH((select_fused_kernel<true, PER>), grid, block, 0, s, a);             \
+    else STS_LAUNCH((select_fused_kernel<false, PER>), grid, block, 0, s, a);              \
+  } while (0)
+  switch (a.part_tokens) {
+    case 8192: STS_FUSED(8); break;
+    case 16384: STS_FUSED(16); break;
+    case 32768: STS_FUSED(32); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef STS_FUSED
+  return hipGetLastError();
+}
+
+// zeroes the area the parts of the fused selection publish their histograms in (one 64-bit word per
+// row, level, part and thread), 16 bytes per thread
+hipError_t launch_select_clear_pub(const SelectArgs &a, hipStream_t s) {
+  const size_t n16 = (size_t)a.B * a.Hd * 3 * (size_t)a.parts * FUSED_THREADS / 2;
+  if (n16 == 0) return hipSuccess;
+  STS_LAUNCH(select_clear16_kernel, dim3((unsigned)((n16 + SEL_THREADS - 1) / SEL_THREADS)), dim3(SEL_THREADS), 0, s,
+             reinterpret_cast<u32x4 *>(a.pub), n16);
   return hipGetLastError();
 }
 

@@ -67,3 +67,15 @@ def check_logits(got, ref, what=""):
     got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
     bad = np.abs(got - ref) > LOGIT_TOL * (1.0 + np.abs(ref))
     assert not bad.any(), f"{what}: logits differ by up to {np.abs(got - ref).max():.3e}"
+
+
+def stored_agg(o_agg, seq_lens):
+    """What sts_select stores in agg_out for the oracle's aggregate: the same values up to each
+    batch element's valid length, 0 past it (the interface's rule; the oracle aggregates all N)."""
+    if seq_lens is None:
+        return o_agg
+    a = np.array(o_agg, copy=True)
+    lens = np.asarray(seq_lens.cpu().numpy() if hasattr(seq_lens, "cpu") else seq_lens)
+    for b in range(a.shape[0]):
+        a[b, :, int(lens[b]):] = 0.0
+    return a

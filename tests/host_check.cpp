@@ -3,6 +3,7 @@
 // arguments and touch no device memory, so every entry point can be driven on a machine without
 // a GPU, with made-up device addresses, under AddressSanitizer and UndefinedBehaviorSanitizer:
 // planning, workspace sizing and carving, argument validation, the head-map tables, error paths.
+#include <math.h>
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
@@ -95,6 +96,18 @@ hipError_t launch_select_small(const SelectArgs &a, hipStream_t) { check_select(
 hipError_t launch_select_rank(const SelectArgs &a, hipStream_t) { check_select(a, "rank"); return hipSuccess; }
 bool select_aggblock_ok(const SelectArgs &a) { return a.page >= 4 && a.page <= 256 && (a.page & (a.page - 1)) == 0 && a.N % a.page == 0; }
 hipError_t launch_select_aggblock(const SelectArgs &a, hipStream_t) { check_select(a, "aggblock"); return hipSuccess; }
+static void check_fused(const SelectArgs &a, const char *what) {
+  check_select(a, what);
+  in_ws(a.pub, what);
+  const int P = a.part_tokens;
+  if (P != 8192 && P != 16384 && P != 32768) fail("fused: part size");
+  if (a.parts != (a.N + P - 1) / P || a.parts < 1 || a.parts > 256) fail("fused: parts");
+  if (a.page != 1 || a.N <= SEL_FUSED_N || !a.pub) fail("fused: shape");
+  if (a.fused_spin_limit < 0) fail("fused: spin limit");
+  in_ws(reinterpret_cast<const unsigned char *>(a.pub) + (size_t)a.B * a.Hd * 3 * a.parts * 8192, "fused: end");
+}
+hipError_t launch_select_fused(const SelectArgs &a, hipStream_t) { check_fused(a, "fused"); return hipSuccess; }
+hipError_t launch_select_clear_pub(const SelectArgs &a, hipStream_t) { check_fused(a, "clear published words"); return hipSuccess; }
 hipError_t launch_select_local(const SelectArgs &a, hipStream_t) { check_pool(a, "local"); return hipSuccess; }
 hipError_t launch_select_pool(const SelectArgs &a, hipStream_t) { check_pool(a, "pool"); return hipSuccess; }
 hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t) { check_pipeline(a, "hist"); if (pass != 1 && pass != 2) fail("hist pass"); return hipSuccess; }
@@ -152,6 +165,8 @@ int main() {
               calls += 4;
             }
     }
+  for (int path : {0, 1, 2, 3}) {
+  sts_set_knob(STS_KNOB_SELECT_PATH, path);
   for (int B : Bs) for (int Tq : {1, 5, 64}) for (int N : Ns) for (int Hd : {1, 16, 256}) for (int Hq : {1, 32, 256})
     for (int k : {1, 410, 13108, 1 << 20}) for (int page : {0, 8, 4096}) for (int budgets = 0; budgets < 2; ++budgets) {
       if ((int64_t)B * Hd > 65535) continue;
@@ -172,6 +187,31 @@ int main() {
       if (sts_select(&p, nullptr) == STS_OK) fail("bad head map accepted");
       calls += 3;
     }
+  }
+  sts_set_knob(STS_KNOB_SELECT_PATH, 0);
+  // a split count changed between the size query and the call: refused, never written out of bounds
+  {
+    sts_attn_params p;
+    memset(&p, 0, sizeof(p));
+    p.B = 1; p.Tq = 5; p.Hq = 32; p.Hkv = 8; p.d = 128; p.N = 131072; p.kmax = 13108;
+    p.kv_stride_n = 128; p.kv_stride_h = (int64_t)p.N * 128; p.kv_stride_b = 8 * p.kv_stride_h;
+    p.scale = 0.1f;
+    p.q = fake; p.k = fake; p.v = fake; p.out = fake; p.indices = reinterpret_cast<const int32_t *>(fake);
+    sts_set_knob(STS_KNOB_ATTN_WGS_PER_CU, 1.0);
+    const size_t small_need = sts_attn_workspace_bytes(&p, 1);
+    sts_set_knob(STS_KNOB_ATTN_WGS_PER_CU, 4.0);
+    const size_t big_need = sts_attn_workspace_bytes(&p, 1);
+    if (!(big_need > small_need)) fail("the knob does not change the split count");
+    p.workspace = ws; p.workspace_bytes = small_need;
+    g_ws_lo = ws; g_ws_hi = ws + small_need;
+    if (sts_sparse_attn(&p, nullptr) != STS_EWORKSPACE) fail("workspace sized for another split count accepted");
+    p.workspace_bytes = big_need;
+    g_ws_lo = ws; g_ws_hi = ws + big_need;
+    if (sts_sparse_attn(&p, nullptr) != STS_OK) fail("workspace of the right size refused");
+    sts_set_knob(STS_KNOB_ATTN_WGS_PER_CU, NAN);
+    if (sts_get_knob(STS_KNOB_ATTN_WGS_PER_CU) == sts_get_knob(STS_KNOB_ATTN_WGS_PER_CU)) fail("knob not reset");
+    calls += 4;
+  }
   for (int S : {0, 1, 4}) for (int R : {0, 1, 128}) for (int N : {0, 1, 32768}) for (int k : {1, 512}) {
     sts_headmap_params p;
     memset(&p, 0, sizeof(p));
@@ -183,6 +223,33 @@ int main() {
     g_ws_lo = ws; g_ws_hi = ws + need;
     accepted += sts_head_map(&p, nullptr) == STS_OK;
     calls += 2;
+  }
+  // Selection slices of different row counts take different paths (and scratch sizes): the size
+  // query must cover every slice launched, and a refusal must come before the first enqueue.
+  {
+    struct { int S, R, Hd, Ht, N, k; } shapes[] = {
+        {1, 16, 8, 32, 16384, 64},      // 128 draft rows (pipeline: needs scratch), 512 target rows (one workgroup per row: none)
+        {1, 4109, 8, 32, 16384, 64},    // a full 32768-row slice followed by a 104-row tail
+        {1, 8, 4, 8, 40000, 100},       // rows beyond what one workgroup ranks out of LDS
+        {2, 300, 16, 32, 131072, 512},  // small budget on long rows: chunk-local top-k + pool
+    };
+    for (const auto &sh : shapes) {
+      sts_headmap_params p;
+      memset(&p, 0, sizeof(p));
+      p.S = sh.S; p.R = sh.R; p.Hd = sh.Hd; p.Ht = sh.Ht; p.N = sh.N; p.k = sh.k;
+      p.a_d = reinterpret_cast<const float *>(fake); p.a_t = reinterpret_cast<const float *>(fake);
+      p.map = reinterpret_cast<int32_t *>(fake);
+      const size_t need = sts_headmap_workspace_bytes(&p);
+      p.workspace = ws; p.workspace_bytes = need;
+      g_ws_lo = ws; g_ws_hi = ws + need;
+      if (sts_head_map(&p, nullptr) != STS_OK) fail("head map refuses the workspace size it asked for");
+      const long before = g_launches;
+      p.workspace_bytes = need - 257;       // (the query adds one alignment unit of slack)
+      if (sts_head_map(&p, nullptr) != STS_EWORKSPACE) fail("short head-map workspace accepted");
+      if (g_launches != before) fail("head map enqueued kernels before refusing");
+      calls += 3;
+      ++accepted;
+    }
   }
   for (int s = 1; s >= -6; --s)
     if (!sts_strerror(s)[0]) fail("empty error string");

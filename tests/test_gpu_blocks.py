@@ -10,7 +10,7 @@ import torch
 
 import oracle
 import paper_2605_15508_amd as sts
-from gpu_util import check_attn, check_logits, oracle_attn
+from gpu_util import check_attn, check_logits, oracle_attn, stored_agg
 from workload import CONFIGS, make_workload
 
 pytestmark = pytest.mark.gpu
@@ -78,7 +78,7 @@ def test_block_select_bit_exact(page, N, k):
         torch.cuda.synchronize()
         o_idx, o_cnt, o_agg = oracle.select_indices(scores.numpy(), np.asarray(hm, np.int32), k,
                                                     seq_lens=None if sl is None else sl.numpy(), page=page)
-        np.testing.assert_array_equal(agg.cpu().numpy().view(np.uint32), o_agg.view(np.uint32))
+        np.testing.assert_array_equal(agg.cpu().numpy().view(np.uint32), stored_agg(o_agg, sl).view(np.uint32))
         np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
         np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
 
@@ -194,7 +194,7 @@ def test_block_select_fused_paths(page, N, k, kind, bf16):
         assert kinds == {"select_clear", "select_agg", "select_hist", "select_write"}
     idx, cnt, agg = got["r"]
     agg = agg.cpu().numpy()
-    o_agg = oracle.aggregate(scores.numpy(), lse.numpy() if kind == 1 else None, kind, 0)
+    o_agg = stored_agg(oracle.aggregate(scores.numpy(), lse.numpy() if kind == 1 else None, kind, 0), lens)
     if kind == 0:
         np.testing.assert_array_equal(agg.view(np.uint32), o_agg.view(np.uint32))
     else:

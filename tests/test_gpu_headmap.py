@@ -43,6 +43,18 @@ def test_headmap_random_traces(S, Hd, Ht, R, N, k):
     run_both(a_d, a_t, k)
 
 
+@pytest.mark.parametrize("S,Hd,Ht,R,N,k", [
+    (1, 8, 32, 16, 16384, 64),     # 128 draft rows go through the many-workgroup pipeline, 512 target rows one workgroup each
+    (1, 4, 8, 4, 40000, 100),      # rows longer than one workgroup's LDS: pipeline for both traces
+    (1, 2, 3, 6, 65536, 200),      # small budget on long rows: chunk-local top-k + pool
+])
+def test_headmap_rows_that_take_the_other_selection_paths(S, Hd, Ht, R, N, k):
+    rng = np.random.default_rng(N + k)
+    a_d = rng.random((S, Hd, R, N), dtype=np.float32)
+    a_t = a_d[:, rng.integers(0, Hd, Ht)] * rng.random((S, Ht, R, N), dtype=np.float32)
+    run_both(a_d, a_t, k)
+
+
 def test_headmap_ties_and_planted_permutation():
     rng = np.random.default_rng(5)
     S, Hd, R, N, k = 2, 5, 4, 256, 16

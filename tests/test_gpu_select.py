@@ -8,10 +8,22 @@ import torch
 
 import oracle
 import paper_2605_15508_amd as sts
+from gpu_util import stored_agg
 from workload import CONFIGS, make_workload
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
+
+
+@pytest.fixture(autouse=True, params=[0, 2, 3], ids=["auto", "pipeline-or-pool", "one-launch-wherever-possible"])
+def select_path(request):
+    """Every case runs twice: under the library's own routing (long rows take the one-launch
+    selection) and with that path switched off, so that the histogram pipeline and the chunk-local
+    top-k + pool, which the same shapes took before and block-granular calls still take, stay
+    covered."""
+    sts.set_knob("select_path", request.param)
+    yield request.param
+    sts.set_knob("select_path", None)
 
 
 def run_both(scores, head_map, k, lse=None, seq_lens=None, kind=0, reduce=0):
@@ -23,7 +35,7 @@ def run_both(scores, head_map, k, lse=None, seq_lens=None, kind=0, reduce=0):
     o_idx, o_cnt, o_agg = oracle.select_indices(
         scores.numpy(), np.asarray(head_map, np.int32), k, lse=None if lse is None else lse.numpy(),
         kind=kind, reduce=reduce, seq_lens=None if seq_lens is None else seq_lens.numpy())
-    return (idx.cpu().numpy(), cnt.cpu().numpy(), agg.cpu().numpy()), (o_idx, o_cnt, o_agg)
+    return (idx.cpu().numpy(), cnt.cpu().numpy(), agg.cpu().numpy()), (o_idx, o_cnt, stored_agg(o_agg, seq_lens))
 
 
 def run_both_budgets(scores, head_map, k, k_head, seq_lens=None, page=1):
@@ -258,11 +270,19 @@ def test_per_head_budgets_feed_sparse_attention():
 
 
 @pytest.mark.parametrize("spin_limit", ["0", "3"])
-def test_lookback_recount_path(spin_limit, monkeypatch):
-    """The compaction kernel reads the counts that earlier chunks of the row publish; a chunk
-    whose counts do not show up within the poll limit is recounted by the waiting workgroup.
-    A tiny limit (set from the host) forces that path; the result must not change."""
-    monkeypatch.setenv("STS_SELECT_SPIN_LIMIT", spin_limit)
+def test_lookback_recount_path(spin_limit):
+    """Workgroups that read what other workgroups of their row publish (the parts' histograms in
+    the one-launch selection) wait a bounded number of polls; what does not show up is recomputed
+    by the waiting workgroup. A tiny limit (set from the host) forces that path; the result must
+    not change."""
+    sts.set_knob("select_spin_limit", int(spin_limit))
+    try:
+        _lookback_cases()
+    finally:
+        sts.set_knob("select_spin_limit", None)
+
+
+def _lookback_cases():
     hm = [0, 1, 1, 2]
     for N, k, levels in ((200000, 20000, 0), (70001, 7000, 0), (100000, 50000, 3)):
         if levels:
@@ -288,9 +308,13 @@ def launched(fn):
         sts.prof_enable(False)
 
 
-def test_each_selection_path_is_taken_where_expected():
-    """Three ways through sts_select, chosen from the shape: one workgroup per row (short rows),
-    chunk-local top-k + pool (small budgets on long rows), the histogram pipeline (the rest)."""
+FUSED = {"select_clear", "select_fused"}
+
+
+def test_each_selection_path_is_taken_where_expected(select_path):
+    """Ways through sts_select, chosen from the shape: one workgroup per row (short rows); for
+    long rows the one-launch selection, or, with that switched off, chunk-local top-k + pool
+    (small budgets) and the histogram pipeline (the rest)."""
     def run(B, Hd, N, k):
         s = softmax_scores(3, B, Hd, 2, N).to(DEV)
         return launched(lambda: sts.sts_select(s, list(range(Hd)), k))
@@ -298,6 +322,18 @@ def test_each_selection_path_is_taken_where_expected():
     pool = {"select_local", "select_pool"}
     assert run(1, 4, 8192, 100) == {"select_small"}
     assert run(16, 16, 20000, 100) == {"select_small"}                      # 256 rows
+    if select_path == 3:
+        assert run(1, 2, 32768 * 40, 100) == FUSED                          # 40 parts per row
+        return
+    if select_path == 0:
+        assert run(1, 4, 8196, 100) == FUSED
+        assert run(1, 4, 65536, 512) == FUSED
+        assert run(16, 4, 65536, 4097) == FUSED
+        assert run(1, 4, 65532 + 2, 512) == FUSED                           # N % 4 != 0: scalar variant
+        assert run(2, 4, 262144, 100) == FUSED                              # 8 parts of 32768: the limit
+        assert run(2, 4, 262144 + 4, 100) == pool                           # beyond it: the earlier paths
+        assert run(1, 1, 4096 * 300, 100) == pipeline
+        return
     assert run(1, 4, 65536, 512) == pool                                    # 8 chunks of 8192 x 512
     assert run(1, 4, 65536, 1024) == pool                                   # 8192 pooled pairs: the limit
     assert run(1, 4, 65536, 4096) == pipeline                               # 2 chunks of 32768: 8 workgroups only
@@ -310,7 +346,7 @@ def test_each_selection_path_is_taken_where_expected():
 
 
 @pytest.mark.parametrize("kind,reduce", [(0, 0), (0, 1), (1, 0)])
-def test_pool_path_options(kind, reduce):
+def test_pool_path_options(kind, reduce, select_path):
     """Chunk-local top-k + pool with every option of the call: scaled-logit input, maximum
     reduction, ragged lengths (one ending inside the first chunk, one between chunks, one
     empty), per-head budgets, a draft head nobody reads, and the aggregate on request."""
@@ -327,10 +363,10 @@ def test_pool_path_options(kind, reduce):
     def call():
         got["r"] = sts.sts_select(sd, hm, k, lse=lse.to(DEV) if kind == 1 else None, seq_lens=lens.to(DEV),
                                   kind=kind, reduce=reduce, want_agg=True, k_head=kh)
-    assert launched(call) == {"select_local", "select_pool"}
+    assert launched(call) == ({"select_local", "select_pool"} if select_path == 2 else FUSED)
     idx, cnt, agg = got["r"]
     agg = agg.cpu().numpy()
-    o_agg = oracle.aggregate(scores.numpy(), lse.numpy() if kind == 1 else None, kind, reduce)
+    o_agg = stored_agg(oracle.aggregate(scores.numpy(), lse.numpy() if kind == 1 else None, kind, reduce), lens)
     if kind == 0:
         np.testing.assert_array_equal(agg.view(np.uint32), o_agg.view(np.uint32))
     else:
@@ -413,9 +449,10 @@ def test_bf16_dump_feeds_selection():
     np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
 
 
-def test_misaligned_scores_fall_back_to_the_pipeline():
+def test_misaligned_scores_fall_back_to_the_pipeline(select_path):
     """A pool-shaped call whose score pointer is not 16-byte aligned runs the histogram pipeline
-    (scalar loads) inside the same workspace, with the same result."""
+    (scalar loads) inside the same workspace, with the same result; the one-launch selection takes
+    its scalar variant."""
     B, Hd, Tq, N, k = 1, 3, 2, 40000, 500
     base = torch.zeros(B * Hd * Tq * N + 1, dtype=torch.float32)
     scores = base[1:].view(B, Hd, Tq, N)
@@ -425,14 +462,14 @@ def test_misaligned_scores_fall_back_to_the_pipeline():
     assert sd.data_ptr() % 16 == 4
     got = {}
     kinds = launched(lambda: got.update(r=sts.sts_select(sd, [0, 1, 2], k)))
-    assert kinds == {"select_clear", "select_agg", "select_hist", "select_write"}
+    assert kinds == ({"select_clear", "select_agg", "select_hist", "select_write"} if select_path == 2 else FUSED)
     o_idx, o_cnt, _ = oracle.select_indices(scores.numpy(), np.asarray([0, 1, 2], np.int32), k)
     np.testing.assert_array_equal(got["r"][0].cpu().numpy(), o_idx)
     np.testing.assert_array_equal(got["r"][1].cpu().numpy(), o_cnt)
 
 
 @pytest.mark.parametrize("levels", [0, 3])
-def test_pool_path_with_32768_token_chunks(levels):
+def test_pool_path_with_32768_token_chunks(levels, select_path):
     """Long rows with middle budgets: the pool stays small only with 32768-token chunks (1024
     threads per workgroup). Ragged lengths ending inside a chunk, on a chunk boundary and at 0."""
     B, Hd, Tq, N, k = 3, 11, 3, 100000, 2000         # 13 x 2000 is too much, 4 x 2000 fits; 33 rows x 4 chunks
@@ -446,11 +483,11 @@ def test_pool_path_with_32768_token_chunks(levels):
     sd = scores.to(DEV)
     got = {}
     kinds = launched(lambda: got.update(r=sts.sts_select(sd, hm, k, seq_lens=lens.to(DEV), k_head=kh, want_agg=True)))
-    assert kinds == {"select_local", "select_pool"}
+    assert kinds == ({"select_local", "select_pool"} if select_path == 2 else FUSED)
     idx, cnt, agg = got["r"]
     o_idx, o_cnt, o_agg = oracle.select_indices(scores.numpy(), np.asarray(hm, np.int32), k, seq_lens=lens.numpy(),
                                                 k_head=kh)
-    np.testing.assert_array_equal(agg.cpu().numpy().view(np.uint32), o_agg.view(np.uint32))
+    np.testing.assert_array_equal(agg.cpu().numpy().view(np.uint32), stored_agg(o_agg, lens).view(np.uint32))
     np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
     np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
 
@@ -477,7 +514,7 @@ def test_hand_worked_cases_on_the_gpu():
     (70001, 20000, 0, 0),      # N % 4 != 0: scalar path
     (40004, 9000, 0, 1),       # misaligned base: scalar path on the caller's own tensor
 ])
-def test_single_row_input_is_ranked_in_place(N, k, levels, off):
+def test_single_row_input_is_ranked_in_place(N, k, levels, off, select_path):
     """One fp32 probability row per head (Tq = 1; e.g. a ready-made aggregate) on the
     multi-workgroup pipeline: the rows are ranked where they lie (no copy into the workspace),
     the input stays untouched, and asking for the aggregate returns the input itself."""
@@ -494,7 +531,7 @@ def test_single_row_input_is_ranked_in_place(N, k, levels, off):
     sd.copy_(s)
     got = {}
     kinds = launched(lambda: got.update(r=sts.sts_select(sd, head_map, k, seq_lens=lens.to(DEV))))
-    assert kinds == {"select_clear", "select_agg", "select_hist", "select_write"}
+    assert kinds == ({"select_clear", "select_agg", "select_hist", "select_write"} if select_path == 2 else FUSED)
     idx, cnt, _ = got["r"]
     assert torch.equal(sd.cpu(), s)
     o_idx, o_cnt, o_agg = oracle.select_indices(s.numpy(), np.asarray(head_map, np.int32), k, seq_lens=lens.numpy())

@@ -9,7 +9,7 @@ import torch
 
 import oracle
 import paper_2605_15508_amd as sts
-from gpu_util import check_attn
+from gpu_util import check_attn, stored_agg
 from test_gpu_blocks import paged_copy
 
 pytestmark = pytest.mark.gpu
@@ -109,7 +109,7 @@ def test_random_select_case(seed):
     o_idx, o_cnt, o_agg = oracle.select_indices(scores.numpy(), np.asarray(hm, np.int32), k, reduce=reduce,
                                                 seq_lens=None if lens is None else lens.numpy(), page=page)
     what = f"seed {seed}: B{B} Hd{Hd} Hq{Hq} Tq{Tq} N{N} k{k} p{page} reduce{reduce} style{style}"
-    np.testing.assert_array_equal(agg.cpu().numpy().view(np.uint32), o_agg.view(np.uint32), err_msg=what)
+    np.testing.assert_array_equal(agg.cpu().numpy().view(np.uint32), stored_agg(o_agg, lens).view(np.uint32), err_msg=what)
     np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt, err_msg=what)
     np.testing.assert_array_equal(idx.cpu().numpy(), o_idx, err_msg=what)
 
@@ -158,7 +158,7 @@ def test_random_selection_case(seed):
                                    want_agg=True, page_size=page, k_head=kh)
     torch.cuda.synchronize()
     agg = agg.cpu().numpy()
-    o_agg = oracle.aggregate(scores.float().numpy(), lse.numpy() if kind == 1 else None, kind, reduce)
+    o_agg = stored_agg(oracle.aggregate(scores.float().numpy(), lse.numpy() if kind == 1 else None, kind, reduce), lens)
     if kind == 0:
         np.testing.assert_array_equal(agg.view(np.uint32), o_agg.view(np.uint32), err_msg=what)
     else:

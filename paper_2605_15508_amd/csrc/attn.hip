@@ -53,8 +53,11 @@ __device__ __forceinline__ float xor_max(float x, int lanemask) {
   return fmaxf(x, __shfl_xor(x, lanemask, 64));
 }
 
+// One workgroup per CU (the whole register file for it) for exactly the variants the host plans
+// one workgroup per CU for: four query tiles, and head size 128 when dense or with two query tiles.
 template <int D, int NQ, bool SPARSE, bool LOGITS, bool PAGED>
-__global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_split_kernel(const AttnArgs A) {
+__global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4 || (D == 128 && (!SPARSE || NQ == 2))) ? 1 : 2)
+attn_split_kernel(const AttnArgs A) {
   typedef typename Chunk<D>::type chunk_t;
   constexpr int NT = D / 16;         // output tiles of the PV product == elements per lane chunk
   constexpr int KK = D / 32;         // contraction steps of the QK product
@@ -383,12 +386,17 @@ __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4) ? 1 : 2) attn_spl
     uint32_t m0, m1, mk_next, mk_new;
     int v = 0;
     // prologue: tile v in flight, tile v+1 resolved, tile v+2 fetched
+    // The first tile's K/V loads go out as soon as its own index entries are there: the entries of
+    // the second tile are asked for before them (so that waiting for those entries later does not
+    // wait for the K/V rows, which return in order), but not waited for.
     int raw_a = SPARSE ? rows_first : fetch_rows(tile_of(0));
     int raw_b = fetch_rows(tile_of(1));
     int x_a = resolve(raw_a, tile_of(0), m0);
+    if (SPARSE) __builtin_amdgcn_sched_barrier(0);
+    issue_loads(x_a, tile_of(0), K0, V0);
+    if (SPARSE) __builtin_amdgcn_sched_barrier(0);
     raw_a = fetch_rows(tile_of(2));
     int x_b = resolve(raw_b, tile_of(1), mk_next);
-    issue_loads(x_a, tile_of(0), K0, V0);
     if (SPARSE) __builtin_amdgcn_sched_barrier(0);
     for (;;) {
       raw_b = fetch_rows(tile_of(v + 3));

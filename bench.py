@@ -69,28 +69,37 @@ def parse_args():
                          "of the configuration's context (batch 1), each block with its own mask; prints its own JSON line")
     ap.add_argument("--headmap", action="store_true",
                     help="other mode: offline head-mapping construction (Algorithm 1) on synthetic traces; prints its own JSON line")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="leave out the budget sweep, the paper's budgets, the 32K point and the graph-replayed figures")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (scales rocprofv3 --pmc byte counters)")
     return ap.parse_args()
 
 
-def read_traffic(kernel: str, workload: str):
+def read_traffic(kernel: str, workload: str, version: int):
     """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary
-    (profiles/traffic_<kernel>_<workload>.txt holds a line `hbm_bytes_per_launch: <int>`)."""
+    (profiles/traffic_<kernel>_<workload>.txt: `hbm_bytes_per_launch: <int>`, taken with the library
+    whose `library_version: <int>` the file states). None when the file belongs to another version of
+    the library: a counter reading says nothing about kernels that have changed since."""
     path = os.path.join(ROOT, "profiles", f"traffic_{kernel}_{workload}.txt")
+    vals = {}
     try:
         with open(path) as f:
             for line in f:
-                if line.startswith("hbm_bytes_per_launch:"):
-                    return int(float(line.split(":", 1)[1]))
+                for key in ("hbm_bytes_per_launch", "library_version", "kernel_avg_us"):
+                    if line.startswith(key + ":"):
+                        vals[key] = float(line.split(":", 1)[1])
     except OSError:
-        pass
-    return None
+        return None
+    if "hbm_bytes_per_launch" not in vals or int(vals.get("library_version", -1)) != version:
+        return None
+    return int(vals["hbm_bytes_per_launch"])
 
 
-def cpu_baseline(w, idx, cnt, page=1, budget_s=25.0, scores=None, lse=None):
+def cpu_baseline(w, idx, cnt, out_s, page=1, budget_s=25.0, scores=None, lse=None):
     """Time the CPU oracle (as it stands, untuned) on this machine's host cores on a bounded sample
-    of the same workload. Returns the cpu_baseline object."""
+    of the same workload, and compare what it computes with what the GPU computed (outside any
+    timed region). Returns (cpu_baseline object, parity object)."""
     import numpy as np
 
     import oracle
@@ -116,9 +125,10 @@ def cpu_baseline(w, idx, cnt, page=1, budget_s=25.0, scores=None, lse=None):
     vb = oracle.bf16_bits(w.v[:nb].cpu())
     idxn, cntn = tokens(idx[:nb], cnt[:nb])
     best = float("inf")
+    ref = None
     for _ in range(2):
         t0 = time.perf_counter()
-        oracle.attn(qb[:nb], kb, vb, w.scale, idxn, cntn)
+        ref = oracle.attn(qb[:nb], kb, vb, w.scale, idxn, cntn)
         best = min(best, time.perf_counter() - t0)
     sparse_us_layer = best / nb * cfg.B * 1e6
     # selection on one batch element
@@ -127,15 +137,31 @@ def cpu_baseline(w, idx, cnt, page=1, budget_s=25.0, scores=None, lse=None):
     sc = src[:1].float().cpu().numpy()       # bf16 scores are widened exactly, as the library does
     ls = None if lse is None else lse[:1].cpu().numpy()
     t0 = time.perf_counter()
-    oracle.select_indices(sc, w.head_map.numpy(), idx.shape[2], page=page, lse=ls,
-                          kind=oracle.PROBS if ls is None else oracle.LOGITS_LSE)
+    o_idx, o_cnt, _ = oracle.select_indices(sc, w.head_map.numpy(), idx.shape[2], page=page, lse=ls,
+                                            kind=oracle.PROBS if ls is None else oracle.LOGITS_LSE)
     sel_us_layer = (time.perf_counter() - t0) * cfg.B * 1e6
     # dense on one KV group of batch 0 (extrapolated linearly)
     G = cfg.Hq // cfg.Hkv
     t0 = time.perf_counter()
     oracle.attn(qb[:1], kb[:1], vb[:1], w.scale, heads=range(0, G))
     dense_us_layer = (time.perf_counter() - t0) * cfg.Hkv * cfg.B * 1e6
-    return {
+    # parity of this very run: the GPU's index sets against the oracle's on the batch element the
+    # oracle ranked, the GPU's sparse outputs against the oracle's on every batch element it computed
+    # (the oracle attended over the GPU's index lists, so the two comparisons are independent)
+    err = np.abs(out_s[:nb].float().cpu().numpy() - ref["out"])
+    rms = float(np.sqrt(np.mean(ref["out"].astype(np.float64) ** 2)))
+    exact_select = ls is None       # with scaled-logit input the device exponential differs from libm in the last bits
+    same_idx = bool(np.array_equal(idx[:1].cpu().numpy(), o_idx) and np.array_equal(cnt[:1].cpu().numpy(), o_cnt))
+    parity = {
+        "index_sets_equal": same_idx if exact_select else None,
+        "index_sets_checked": (f"batch element 0, all {cfg.Hq} heads, k={idx.shape[2]}" if exact_select else
+                               "not compared here: logits input (checked stage-wise in the GPU tests)"),
+        "out_max_abs_err": float(err.max()), "out_mean_abs_err": float(err.mean()), "out_rms": rms,
+        "out_checked": f"sts_sparse_attn, {nb} of {cfg.B} batch elements, all heads and query rows",
+        "tolerance": {"max_abs": 1e-2, "mean_abs": 1e-3},
+        "ok": bool((same_idx or not exact_select) and err.max() <= 1e-2 and err.mean() <= 1e-3),
+    }
+    base = {
         "value": round(sparse_us_layer, 1), "unit": "us/layer", "cores": threads, "kind": "oracle",
         "sample": (f"sts_sparse_attn oracle on {nb} of {cfg.B} batch elements (all {cfg.Hq} heads, "
                    f"k={idx.shape[2]}{' blocks of %d' % page if page > 1 else ''}), best of 2, scaled to the batch; select timed on 1 batch element, "
@@ -143,6 +169,7 @@ def cpu_baseline(w, idx, cnt, page=1, budget_s=25.0, scores=None, lse=None):
         "select_us_layer": round(sel_us_layer, 1),
         "dense_us_layer_extrapolated": round(dense_us_layer, 1),
     }
+    return base, parity
 
 
 def _timed(fn, steps, warmup, torch):
@@ -227,6 +254,123 @@ def run_headmap(args, torch, sts):
         "config": {"workload": f"traces a_d [{S},{Hd},{R},{N}] and a_t [{S},{Ht},{R},{N}] fp32, top-{k} per row"},
         "call_us": t, "planted_map_recovered": bool((mp == planted.cpu().to(mp.dtype)).all()),
         "trace_bytes": int(a_d.numel() * 4 + a_t.numel() * 4)}))
+
+
+def _median(xs):
+    return round(statistics.median(xs), 2)
+
+
+class Point:
+    """select -> sparse attention -> dense attention on one resident workload at one budget, with
+    index and output buffers of its own; the dense pass between two sparse passes (and the
+    rotation over layers) keeps every sparse pass cache-cold."""
+
+    def __init__(self, torch, sts, w, layers, kb, page=1, extra=None):
+        cfg = w.cfg
+        dev = w.q.device
+        self.torch, self.sts, self.w, self.layers, self.kb, self.page = torch, sts, w, layers, kb, page
+        self.extra = dict(extra or {})
+        self.idx = torch.empty(cfg.B, cfg.Hq, kb, dtype=torch.int32, device=dev)
+        self.cnt = torch.empty(cfg.B, cfg.Hq, dtype=torch.int32, device=dev)
+        self.out_s = torch.empty(cfg.B, cfg.Tq, cfg.Hq, cfg.d, dtype=torch.bfloat16, device=dev)
+        self.out_d = torch.empty_like(self.out_s)
+
+    def select(self):
+        self.sts.sts_select(self.w.scores, self.w.head_map, self.kb, out=(self.idx, self.cnt), page_size=self.page)
+
+    def sparse(self, layer=0):
+        lk, lv = self.layers[layer]
+        self.sts.sts_sparse_attn(self.w.q, lk, lv, self.idx, self.w.scale, counts=self.cnt, head_map=self.w.head_map,
+                                 out=self.out_s, want_lse=False, **self.extra)
+
+    def dense(self, layer=0):
+        lk, lv = self.layers[layer]
+        self.sts.sts_dense_attn(self.w.q, lk, lv, self.w.scale, out=self.out_d, want_lse=False, **self.extra)
+
+    def bytes_set(self):
+        plan = self.sts.attn_plan(self.w.q, self.torch.empty(self.w.cfg.B, self.w.cfg.Hkv, self.w.cfg.N, self.w.cfg.d, device="meta"),
+                                  True, kmax=self.kb, head_map=self.w.head_map, page_size=self.page)
+        return self.w.cfg.B * plan["units_per_batch"] * self.kb * self.page * 2 * self.w.cfg.d * 2, plan
+
+    def eager(self, steps, warmup=2):
+        """Per-call medians (us) over `steps` event-timed steps, then the split kernel's own time
+        from the library's dispatch-stamped events."""
+        torch, sts = self.torch, self.sts
+        L = len(self.layers)
+        for _ in range(warmup):
+            for l in range(L):
+                self.select(); self.sparse(l); self.dense(l)
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps * L)]
+        torch.cuda.synchronize()
+        for i in range(steps):
+            for l in range(L):
+                ev = evs[i * L + l]
+                ev[0].record(); self.select(); ev[1].record(); self.sparse(l); ev[2].record(); self.dense(l); ev[3].record()
+        torch.cuda.synchronize()
+        t = [_median([ev[i].elapsed_time(ev[i + 1]) * 1e3 for ev in evs]) for i in range(3)]
+        sts.prof_enable(True)
+        sts.prof_reset()
+        for i in range(max(1, min(steps, STS_PROF_BUDGET // (8 * L)))):
+            for l in range(L):
+                self.select(); self.sparse(l); self.dense(l)
+        torch.cuda.synchronize()
+        prof = sts.prof_read()
+        sts.prof_enable(False)
+        kus = {k: round(ms * 1e3 / n, 2) for k, (n, ms) in prof.items() if n}
+        b_set, plan = self.bytes_set()
+        split = kus.get("attn_sparse", 0.0)
+        return {"budget_tokens": self.kb * self.page, "select_us": t[0], "sparse_attn_us": t[1], "dense_attn_us": t[2],
+                "speedup_vs_dense": round(t[2] / t[1], 3) if t[1] > 0 else None,
+                # (the combine kernel's figure averages the sparse and the dense call's launches)
+                "kernel_us": {k: v for k, v in kus.items() if k.startswith("attn_sparse") or k.startswith("select")
+                              or (k == "attn_combine" and plan["num_splits"] > 1)},
+                "gathered_kv_bytes_b_set": b_set, "num_splits": plan["num_splits"],
+                "split_kernel_frac": round(b_set / (split * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if split > 0 else None,
+                "call_frac": round(b_set / (t[1] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if t[1] > 0 else None}
+
+    def graph(self, reps=30):
+        """The same calls captured in HIP graphs and replayed (no host launch cost between the
+        kernels). A call's time is the difference between a graph that holds it after a dense pass
+        (which leaves the caches cold for it) and a graph that holds the dense pass alone."""
+        torch = self.torch
+        L = len(self.layers)
+
+        def capture(body):
+            s = torch.cuda.Stream()
+            s.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(s):
+                body()                               # workspaces of this stream exist before the capture
+                torch.cuda.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=s):
+                    body()
+            torch.cuda.synchronize()
+            return g
+
+        def run(g):
+            g.replay()
+            torch.cuda.synchronize()
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+            evs[0].record()
+            for i in range(reps):
+                g.replay()
+                evs[i + 1].record()
+            torch.cuda.synchronize()
+            # median over the replays: one disturbed replay must not decide a difference of a few us
+            return statistics.median(evs[i].elapsed_time(evs[i + 1]) for i in range(reps)) * 1e3 / L
+
+        def every_layer(fn):
+            def body():
+                for l in range(L):
+                    fn(l)
+            return body
+
+        t_dense = run(capture(every_layer(lambda l: self.dense(l))))
+        t_ds = run(capture(every_layer(lambda l: (self.dense(l), self.sparse(l)))))
+        t_dsel = run(capture(every_layer(lambda l: (self.dense(l), self.select()))))
+        t_step = run(capture(every_layer(lambda l: (self.select(), self.sparse(l), self.dense(l)))))
+        return {"sparse_attn_us": round(t_ds - t_dense, 2), "select_us": round(t_dsel - t_dense, 2),
+                "dense_attn_us": round(t_dense, 2), "step_us": round(t_step, 2)}
 
 
 def main():
@@ -447,8 +591,7 @@ def main():
             "bound": "hbm", "kernel": "attn_split_kernel<sparse>", "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
             "algorithmic_bytes_per_launch": b_set, "avg_launch_us": round(split_us, 2), "launches": split_n,
-            # the committed counter summary was taken on the configuration's default budget, token granularity
-            "traffic": read_traffic("attn_sparse_split", cfg.name) if (args.budget is None and page == 1) else None,
+            "traffic": None,       # filled in below from the committed counter summary, if it belongs to this library version
         },
         "paper_context": "2.67x end-to-end speedup at ~90% sparsity on NVIDIA H20 (other hardware, whole serving stack)",
     }
@@ -467,11 +610,57 @@ def main():
     if dsplit_n:
         result["roofline_dense"] = {"achieved": round(b_dense / (dsplit_ms * 1e-3 / dsplit_n) / 1e9, 1),
                                     "frac": round(b_dense / (dsplit_ms * 1e-3 / dsplit_n) / 1e9 / HBM_PEAK_GBS, 4)}
+    version = sts.sts_version()
+    result["library_version"] = version
+    result["roofline"]["traffic"] = (read_traffic("attn_sparse_split", cfg.name, version)
+                                     if (args.budget is None and page == 1) else None)
+    result["roofline"]["scope"] = ("the split kernel alone (the dominant kernel of sts_sparse_attn); the whole call, "
+                                   "with the combine kernel and the gaps between launches, is roofline_call")
+    # the same algorithmic bytes over the time of the whole sts_sparse_attn call (`value`)
+    result["roofline_call"] = {"bound": "hbm", "bytes": b_set, "us": round(sparse_us[1], 2), "unit": "GB/s",
+                               "achieved": round(b_set / (sparse_us[1] * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                               "frac": round(b_set / (sparse_us[1] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+    plain = draft is None and not args.paged and page == 1 and not args.fused_tail and args.scores == "fp32"
+    if plain and not args.no_extras:
+        here = Point(torch, sts, w, layers, kb)
+        here.select()
+        result["graph_replay"] = here.graph()
+        result["graph_replay"]["call_frac"] = round(b_set / (result["graph_replay"]["sparse_attn_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
+        # the budget sweep of the 128K configuration (5% and 20% beside the 10% above), same resident inputs
+        if cfg.name == "c3" and args.budget is None:
+            result["sweep"] = {}
+            for frac in (0.05, 0.20):
+                pt = Point(torch, sts, w, layers, budget_tokens(cfg, frac))
+                result["sweep"]["%g%%" % (frac * 100)] = pt.eager(min(K, 10))
+                del pt
+            # the paper's own operating points (Sections 6.2, 6.3: budgets of 256, 512 and 4096 tokens)
+            result["paper_budgets"] = {}
+            for kk in (256, 512, 4096):
+                pt = Point(torch, sts, w, layers, kk)
+                r = pt.eager(min(K, 10))
+                r["graph_replay"] = pt.graph()
+                result["paper_budgets"]["%s@%d" % (cfg.name, kk)] = r
+                del pt
+            # and the 32K configuration at its 10% budget (16 rotating layers: cold caches)
+            c2 = CONFIGS["c2"]
+            w2 = make_workload(c2, seed=args.seed, device=dev)
+            layers2 = [(w2.k, w2.v)]
+            for l in range(1, 16):
+                wl = make_workload(c2, seed=args.seed + l, device=dev, with_scores=False)
+                layers2.append((wl.k, wl.v))
+                del wl
+            pt = Point(torch, sts, w2, layers2, w2.k_budget)
+            r = pt.eager(min(K, 10))
+            r["graph_replay"] = pt.graph(reps=5)
+            result["paper_budgets"]["c2@%d" % w2.k_budget] = r
+            del pt, w2, layers2
     if not args.no_cpu_baseline:
+        step(layer=0)                     # the outputs of layer 0, whose cache the oracle reads below
+        torch.cuda.synchronize()
         if d_sum is not None:
-            result["cpu_baseline"] = cpu_baseline(w, idx, cnt, page=page, scores=d_sum.view(B, Hd, 1, N), lse=None)
+            result["cpu_baseline"], result["parity"] = cpu_baseline(w, idx, cnt, out_s, page=page, scores=d_sum.view(B, Hd, 1, N), lse=None)
         else:
-            result["cpu_baseline"] = cpu_baseline(w, idx, cnt, page=page, scores=d_logits, lse=d_lse)
+            result["cpu_baseline"], result["parity"] = cpu_baseline(w, idx, cnt, out_s, page=page, scores=d_logits, lse=d_lse)
     print(json.dumps(result))
 
 

@@ -33,6 +33,30 @@ def test_default_step_prints_the_contract_fields():
     assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-3
     cpu = r["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]
+    # the call-level fraction beside the kernel's, the graph-replayed figures, and this run's own
+    # comparison with the oracle (index sets equal, outputs inside the stated tolerance)
+    call = r["roofline_call"]
+    assert call["bytes"] == roof["algorithmic_bytes_per_launch"] and call["us"] == r["value"]
+    assert call["frac"] <= roof["frac"] + 1e-6
+    assert r["graph_replay"]["sparse_attn_us"] > 0 and r["graph_replay"]["step_us"] > 0
+    par = r["parity"]
+    assert par["ok"] is True and par["index_sets_equal"] is True
+    assert par["out_max_abs_err"] <= 1e-2 and par["out_mean_abs_err"] <= 1e-3
+    assert r["library_version"] > 0
+
+
+def test_headline_configuration_carries_sweep_and_paper_budgets():
+    """The default run (128K context, batch 4) with few steps and without the oracle leg: the 5%
+    and 20% points of the sweep, the paper's own budgets and the 32K point are in the line."""
+    r = _bench("--steps", "3", "--warmup", "1", "--no-cpu-baseline")
+    assert set(r["sweep"]) == {"5%", "20%"}
+    assert r["sweep"]["5%"]["budget_tokens"] == 6554 and r["sweep"]["20%"]["budget_tokens"] == 26215
+    for pt in r["sweep"].values():
+        assert pt["sparse_attn_us"] > 0 and pt["dense_attn_us"] > pt["sparse_attn_us"] and 0 < pt["split_kernel_frac"] < 1
+    assert {"c3@256", "c3@512", "c3@4096"} <= set(r["paper_budgets"])
+    assert any(k.startswith("c2@") for k in r["paper_budgets"])
+    for pt in r["paper_budgets"].values():
+        assert pt["graph_replay"]["sparse_attn_us"] > 0 and pt["select_us"] > 0
 
 
 def test_fused_tail_option_and_other_modes():

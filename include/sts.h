@@ -17,7 +17,9 @@
  *    stream, or events between streams): the library holds no state and takes no locks.
  *  - Return value: STS_OK (0) or a negative sts_status. On error nothing has been enqueued
  *    (except STS_EHIP, a failed launch, after which earlier kernels of the call may have
- *    been enqueued). No exceptions, no errno, no logging.
+ *    been enqueued and the outputs are undefined). STS_EHIP reports the launch calls' own
+ *    return values: an error left behind by an unrelated HIP call of the process is neither
+ *    reported nor cleared. No exceptions, no errno, no logging.
  *  - Results are deterministic run to run: the split count depends only on the shape and the
  *    partial results are combined in a fixed order; selection uses integer arithmetic only.
  *  - bf16 tensors are raw 16-bit patterns. All accumulation is fp32.

@@ -278,6 +278,29 @@ int oracle_attn(const uint16_t *q, const uint16_t *k, const uint16_t *v, int B, 
 
 /* ------------------------------------------------- Algorithm 1: head mapping */
 
+/* Tokens that the top-k sets of target head ht and draft head hd have in common, summed over
+ * every query row of every sample (membership bitmaps, one byte per token). */
+static int64_t shared_topk_total(const unsigned char *mt, const unsigned char *md, int S, int Ht, int Hd, int R,
+                                 int N, int ht, int hd) {
+  int64_t shared = 0;
+  for (int s = 0; s < S; ++s)
+    for (int r = 0; r < R; ++r) {
+      const unsigned char *in_t = mt + (((size_t)s * Ht + ht) * R + r) * (size_t)N;
+      const unsigned char *in_d = md + (((size_t)s * Hd + hd) * R + r) * (size_t)N;
+      for (int n = 0; n < N; ++n) shared += (in_t[n] & in_d[n]);
+    }
+  return shared;
+}
+
+/* Position of the largest entry; among equal entries the first one (so an all-zero row gives 0:
+ * a target head that shares nothing with any draft head maps to draft head 0). */
+static int32_t first_largest(const int64_t *row, int n) {
+  int32_t where = 0;
+  for (int i = 1; i < n; ++i)
+    if (row[i] > row[where]) where = i;
+  return where;
+}
+
 int oracle_head_mapping(const float *a_d, const float *a_t, int S, int Hd, int Ht, int R,
                         int N, int k, int32_t *map, int64_t *overlap) {
   if (!a_d || !a_t || !map || S < 1 || Hd < 1 || Ht < 1 || R < 1 || N < 1 || k < 1) return -1;
@@ -316,25 +339,10 @@ int oracle_head_mapping(const float *a_d, const float *a_t, int S, int Hd, int H
     free(top);
   }
   if (status == 0) {
-    for (int ht = 0; ht < Ht; ++ht) {
-      long long max_score = -1;
-      int best = -1;
-      for (int hd = 0; hd < Hd; ++hd) {
-        long long score = 0;
-        for (int s = 0; s < S; ++s)
-          for (int r = 0; r < R; ++r) {
-            const unsigned char *x = mt + (((size_t)s * Ht + ht) * R + r) * (size_t)N;
-            const unsigned char *y = md + (((size_t)s * Hd + hd) * R + r) * (size_t)N;
-            for (int n = 0; n < N; ++n) score += (x[n] & y[n]);
-          }
-        ov[(size_t)ht * Hd + hd] = score;
-        if (score > max_score) {
-          max_score = score;
-          best = hd;
-        }
-      }
-      map[ht] = best;
-    }
+    /* the whole matrix of summed intersection sizes first, then one arg-max per target head */
+    for (int ht = 0; ht < Ht; ++ht)
+      for (int hd = 0; hd < Hd; ++hd) ov[(size_t)ht * Hd + hd] = shared_topk_total(mt, md, S, Ht, Hd, R, N, ht, hd);
+    for (int ht = 0; ht < Ht; ++ht) map[ht] = first_largest(ov + (size_t)ht * Hd, Hd);
     if (overlap) memcpy(overlap, ov, (size_t)Ht * Hd * sizeof(int64_t));
   }
   free(md);

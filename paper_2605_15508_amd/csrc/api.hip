@@ -10,6 +10,7 @@
 #include "common.h"
 
 thread_local StsLaunchEvents g_sts_launch_events = {nullptr, nullptr};
+thread_local hipError_t g_sts_launch_rc = hipSuccess;
 
 namespace {
 

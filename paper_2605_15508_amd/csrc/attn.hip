@@ -719,7 +719,7 @@ hipError_t launch_split_dnp(const AttnArgs &a, bool sparse, hipStream_t s) {
     STS_LAUNCH((attn_split_kernel<D, NQ, false, true, PAGED>), grid, block, 0, s, a);
   else
     STS_LAUNCH((attn_split_kernel<D, NQ, false, false, PAGED>), grid, block, 0, s, a);
-  return hipGetLastError();
+  return sts_take_launch_status();
 }
 
 template <int D, int NQ>
@@ -995,7 +995,7 @@ hipError_t launch_attn_combine(const AttnArgs &a, int d, int nq, hipStream_t s) 
     STS_LAUNCH((attn_combine_kernel<64>), grid, block, 0, s, a, nq);
   else
     return hipErrorInvalidValue;
-  return hipGetLastError();
+  return sts_take_launch_status();
 }
 
 // resident workgroups per CU of the second-pass kernel for this head size and query-tile count
@@ -1035,5 +1035,5 @@ hipError_t launch_attn_probsum(const AttnArgs &a, int d, int nq, hipStream_t s) 
   else if (d == 64 && nq == 4) STS_PROBSUM(64, 4);
   else return hipErrorInvalidValue;
 #undef STS_PROBSUM
-  return hipGetLastError();
+  return sts_take_launch_status();
 }

@@ -6,22 +6,47 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <type_traits>
+#include <utility>
+
 #include "../../include/sts.h"
 
 // Every kernel goes out through STS_LAUNCH. With the library's timing aid switched on, the host
 // code sets this pair of events before a launch and the dispatch itself stamps them with the
 // kernel's own begin and end times (no extra packets around it); otherwise it is an ordinary
-// launch.
+// launch. The status is the launch call's own return value (an error that some earlier, unrelated
+// HIP call of the process left behind is neither reported as ours nor cleared); a launcher hands
+// it back with sts_take_launch_status().
 struct StsLaunchEvents { hipEvent_t start, stop; };
 extern thread_local StsLaunchEvents g_sts_launch_events;
-#define STS_LAUNCH(kernel, grid, block, shmem, stream, ...)                                              \
-  do {                                                                                                   \
-    if (g_sts_launch_events.start)                                                                       \
-      hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, g_sts_launch_events.start,               \
-                            g_sts_launch_events.stop, 0, __VA_ARGS__);                                   \
-    else                                                                                                 \
-      hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);                               \
-  } while (0)
+extern thread_local hipError_t g_sts_launch_rc;
+
+template <class Tuple, size_t... I>
+inline void sts_arg_pointers(Tuple &vals, void **ptrs, std::index_sequence<I...>) {
+  ((ptrs[I] = static_cast<void *>(&std::get<I>(vals))), ...);
+}
+
+template <class... P, class... A>
+inline void sts_launch(void (*kernel)(P...), dim3 grid, dim3 block, unsigned shmem, hipStream_t stream, const A &...args) {
+  std::tuple<std::remove_cv_t<P>...> vals(args...);      // copies of the kernel's own parameter types
+  void *ptrs[sizeof...(P)];
+  sts_arg_pointers(vals, ptrs, std::index_sequence_for<P...>{});
+  const hipError_t rc =
+      g_sts_launch_events.start
+          ? hipExtLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, shmem, stream,
+                               g_sts_launch_events.start, g_sts_launch_events.stop, 0)
+          : hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, shmem, stream);
+  if (g_sts_launch_rc == hipSuccess) g_sts_launch_rc = rc;
+}
+#define STS_LAUNCH(kernel, grid, block, shmem, stream, ...) sts_launch(kernel, grid, block, shmem, stream, __VA_ARGS__)
+
+// status of the launches since the last call of this function (the first failure, if any)
+inline hipError_t sts_take_launch_status() {
+  const hipError_t rc = g_sts_launch_rc;
+  g_sts_launch_rc = hipSuccess;
+  return rc;
+}
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -135,7 +160,7 @@ struct SelectArgs {
 // device address of the current device's copy of the static scratch array (scratch.hip)
 sts_status sts_static_scratch(void **out);
 
-// launches (defined in the .hip files); each returns hipGetLastError() of its launch
+// launches (defined in the .hip files); each returns the status of its own launch call
 hipError_t launch_attn_split(const AttnArgs &a, int d, int nq, bool sparse, hipStream_t s);
 hipError_t launch_attn_combine(const AttnArgs &a, int d, int nq, hipStream_t s);
 hipError_t launch_attn_probsum(const AttnArgs &a, int d, int nq, hipStream_t s);

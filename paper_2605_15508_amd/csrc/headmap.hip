@@ -69,7 +69,7 @@ __global__ void __launch_bounds__(256) headmap_argmax_kernel(const unsigned long
 hipError_t launch_headmap_clear(unsigned long long *overlap, int n, hipStream_t s) {
   if (n == 0) return hipSuccess;
   STS_LAUNCH(headmap_clear_kernel, dim3((n + 255) / 256), dim3(256), 0, s, overlap, n);
-  return hipGetLastError();
+  return sts_take_launch_status();
 }
 
 hipError_t launch_headmap_overlap(const int32_t *idx_d, const int32_t *idx_t, int S, int R, int Hd, int Ht,
@@ -77,11 +77,11 @@ hipError_t launch_headmap_overlap(const int32_t *idx_d, const int32_t *idx_t, in
   if ((size_t)S * R == 0 || Ht == 0 || c == 0) return hipSuccess;
   STS_LAUNCH(headmap_overlap_kernel, dim3(S * R, Ht), dim3(256), 0, s, idx_d, idx_t, S, R, Hd, Ht, k, c,
                      overlap);
-  return hipGetLastError();
+  return sts_take_launch_status();
 }
 
 hipError_t launch_headmap_argmax(const unsigned long long *overlap, int Hd, int Ht, int32_t *map, hipStream_t s) {
   if (Ht == 0) return hipSuccess;
   STS_LAUNCH(headmap_argmax_kernel, dim3((Ht + 255) / 256), dim3(256), 0, s, overlap, Hd, Ht, map);
-  return hipGetLastError();
+  return sts_take_launch_status();
 }

@@ -1430,14 +1430,14 @@ hipError_t launch_select_small(const SelectArgs &a, hipStream_t s) {
     STS_LAUNCH((select_small_kernel<true, false>), grid, block, 0, s, a);
   else
     STS_LAUNCH((select_small_kernel<false, false>), grid, block, 0, s, a);
-  return hipGetLastError();
+  return sts_take_launch_status();
 }
 
 // ranks the rows of a.src (up to SEL_SMALL_N entries each) out of LDS
 hipError_t launch_select_rank(const SelectArgs &a, hipStream_t s) {
   if ((size_t)a.B * a.Hd == 0) return hipSuccess;
   STS_LAUNCH((select_small_kernel<false, true>), dim3(a.B * a.Hd), dim3(SMALL_THREADS), 0, s, a);
-  return hipGetLastError();
+  return sts_take_launch_status();
 }
 
 bool select_aggblock_ok(const SelectArgs &a) {
@@ -1451,7 +1451,7 @@ hipError_t launch_select_aggblock(const SelectArgs &a, hipStream_t s) {
   if ((size_t)a.B * a.Hd == 0 || a.N == 0) return hipSuccess;
   const dim3 grid((a.N + SEL_CHUNK - 1) / SEL_CHUNK, a.B * a.Hd), block(SEL_THREADS);
   STS_LAUNCH(select_aggblock_kernel, grid, block, 0, s, a);
-  return hipGetLastError();
+  return sts_take_launch_status();
 }
 
 hipError_t launch_select_fused(const SelectArgs &a, hipStream_t s) {
@@ -1471,7 +1471,7 @@ hipError_t launch_select_fused(const SelectArgs &a, hipStream_t s) {
     default: return hipErrorInvalidValue;
   }
 #undef STS_FUSED
-  return hipGetLastError();
+  return sts_take_launch_status();
 }
 
 // zeroes the area the parts of the fused selection publish their histograms in (one 64-bit word per
@@ -1481,7 +1481,7 @@ hipError_t launch_select_clear_pub(const SelectArgs &a, hipStream_t s) {
   if (n16 == 0) return hipSuccess;
   STS_LAUNCH(select_clear16_kernel, dim3((unsigned)((n16 + SEL_THREADS - 1) / SEL_THREADS)), dim3(SEL_THREADS), 0, s,
              reinterpret_cast<u32x4 *>(a.pub), n16);
-  return hipGetLastError();
+  return sts_take_launch_status();
 }
 
 hipError_t launch_select_local(const SelectArgs &a, hipStream_t s) {
@@ -1491,13 +1491,13 @@ hipError_t launch_select_local(const SelectArgs &a, hipStream_t s) {
     STS_LAUNCH(select_local_kernel<256>, grid, dim3(256), 0, s, a);
   else   // 1024 * 32
     STS_LAUNCH(select_local_kernel<1024>, grid, dim3(1024), 0, s, a);
-  return hipGetLastError();
+  return sts_take_launch_status();
 }
 
 hipError_t launch_select_pool(const SelectArgs &a, hipStream_t s) {
   if ((size_t)a.B * a.Hd == 0) return hipSuccess;
   STS_LAUNCH(select_pool_kernel, dim3(a.B * a.Hd), dim3(SMALL_THREADS), 0, s, a);
-  return hipGetLastError();
+  return sts_take_launch_status();
 }
 
 hipError_t launch_select_block(const SelectArgs &a, hipStream_t s) {
@@ -1511,7 +1511,7 @@ hipError_t launch_select_block(const SelectArgs &a, hipStream_t s) {
     const dim3 grid((a.srcN + SEL_THREADS - 1) / SEL_THREADS, a.B * a.Hd), block(SEL_THREADS);
     STS_LAUNCH(select_block_kernel, grid, block, 0, s, a);
   }
-  return hipGetLastError();
+  return sts_take_launch_status();
 }
 
 hipError_t launch_select_clear(const SelectArgs &a, hipStream_t s) {
@@ -1519,7 +1519,7 @@ hipError_t launch_select_clear(const SelectArgs &a, hipStream_t s) {
   if (n == 0) return hipSuccess;
   STS_LAUNCH(select_clear_kernel, dim3((unsigned)((n + SEL_THREADS - 1) / SEL_THREADS)),
                      dim3(SEL_THREADS), 0, s, a.hist, n);
-  return hipGetLastError();
+  return sts_take_launch_status();
 }
 
 hipError_t launch_select_agg(const SelectArgs &a, hipStream_t s) {
@@ -1530,7 +1530,7 @@ hipError_t launch_select_agg(const SelectArgs &a, hipStream_t s) {
     STS_LAUNCH(select_agg_kernel<true>, grid, block, 0, s, a);
   else
     STS_LAUNCH(select_agg_kernel<false>, grid, block, 0, s, a);
-  return hipGetLastError();
+  return sts_take_launch_status();
 }
 
 hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t s) {
@@ -1544,7 +1544,7 @@ hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t s) {
     if (v) STS_LAUNCH((select_hist_kernel<2, true>), grid, block, 0, s, a);
     else STS_LAUNCH((select_hist_kernel<2, false>), grid, block, 0, s, a);
   }
-  return hipGetLastError();
+  return sts_take_launch_status();
 }
 
 hipError_t launch_select_write(const SelectArgs &a, hipStream_t s) {
@@ -1554,5 +1554,5 @@ hipError_t launch_select_write(const SelectArgs &a, hipStream_t s) {
     STS_LAUNCH(select_write_kernel<true>, grid, block, 0, s, a);
   else
     STS_LAUNCH(select_write_kernel<false>, grid, block, 0, s, a);
-  return hipGetLastError();
+  return sts_take_launch_status();
 }

@@ -115,13 +115,13 @@ MUTANTS = [
      "const int nnew = k_new ? (causal ? i + 1 : Tq) : 0;", "const int nnew = k_new ? (causal ? i + 1 : Tq - 1) : 0;",
      ["test_oracle_attn.py"]),
     ("head mapping counts the union instead of the intersection",
-     "score += (x[n] & y[n]);", "score += (x[n] | y[n]);",
+     "shared += (in_t[n] & in_d[n]);", "shared += (in_t[n] | in_d[n]);",
      ["test_oracle_headmap.py"]),
     ("head mapping: the last best draft head wins",
-     "if (score > max_score) {", "if (score >= max_score) {",
+     "if (row[i] > row[where]) where = i;", "if (row[i] >= row[where]) where = i;",
      ["test_oracle_headmap.py"]),
     ("head mapping: overlap of the first row only",
-     "for (int r = 0; r < R; ++r) {\n            const unsigned char *x", "for (int r = 0; r < 1; ++r) {\n            const unsigned char *x",
+     "for (int r = 0; r < R; ++r) {\n      const unsigned char *in_t", "for (int r = 0; r < 1; ++r) {\n      const unsigned char *in_t",
      ["test_oracle_headmap.py"]),
 ]
 

@@ -237,6 +237,91 @@ def attn(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float,
     return {"out": out, "lse": lse, "logits": logits}
 
 
+def select_rows(scores, k, lse=None, kind=PROBS, seq_lens=None):
+    """Per-row selection for prefill (Section 4.2: during prefill every query token has a mask
+    of its own, a two-dimensional pattern per head): every one of the Tq score rows of a draft
+    head is ranked by itself. scores [B,Hd,Tq,N] -> (sel [B,Hd,Tq,k] ascending, -1 padded;
+    cnt [B,Hd,Tq]). It is the single-row case of the selection, row by row."""
+    scores = _c(scores, np.float32)
+    B, Hd, Tq, N = scores.shape
+    sel = np.empty((B, Hd, Tq, k), np.int32)
+    cnt = np.empty((B, Hd, Tq), np.int32)
+    for i in range(Tq):
+        A = aggregate(scores[:, :, i:i + 1], None if lse is None else np.ascontiguousarray(lse[:, :, i:i + 1]), kind, SUM)
+        sel[:, :, i], cnt[:, :, i] = select(A, k, seq_lens)
+    return sel, cnt
+
+
+def union_rows(row_sel: np.ndarray, row_cnt: Optional[np.ndarray], head_map, pitch: Optional[int] = None):
+    """The tokens any query row of a block keeps, per target head, and which rows keep each of
+    them. row_sel [B,Hd,Tq,k] (the valid entries of a row come first, row_cnt [B,Hd,Tq] or None = k
+    of them), head_map [Hq] target head -> draft head. Returns (union [B,Hq,pitch] int32 ascending,
+    -1 padded; mask [B,Hq,pitch] uint16, bit i set iff row i keeps the token; cnt [B,Hq]).
+    Written out as the definition: a set union per target head (Section 4.2: the target attends to
+    the key-value pairs the indices name, here one index set per query row)."""
+    row_sel = np.asarray(row_sel)
+    B, Hd, Tq, k = row_sel.shape
+    assert Tq <= 16
+    head_map = np.asarray(head_map)
+    Hq = head_map.shape[0]
+    rows = [[None] * Hq for _ in range(B)]
+    longest = 0
+    for b in range(B):
+        for t in range(Hq):
+            j = int(head_map[t])
+            keep = {}
+            for i in range(Tq):
+                c = k if row_cnt is None else int(row_cnt[b, j, i])
+                for n in row_sel[b, j, i, :c]:
+                    keep[int(n)] = keep.get(int(n), 0) | (1 << i)
+            rows[b][t] = sorted(keep.items())
+            longest = max(longest, len(keep))
+    pitch = longest if pitch is None else pitch
+    assert pitch >= longest
+    union = np.full((B, Hq, pitch), -1, np.int32)
+    mask = np.zeros((B, Hq, pitch), np.uint16)
+    cnt = np.zeros((B, Hq), np.int32)
+    for b in range(B):
+        for t in range(Hq):
+            cnt[b, t] = len(rows[b][t])
+            for p, (n, bits) in enumerate(rows[b][t]):
+                union[b, t, p] = n
+                mask[b, t, p] = bits
+    return union, mask, cnt
+
+
+def attn_rows(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float, row_idx: np.ndarray,
+              row_cnt: Optional[np.ndarray] = None):
+    """Attention with an index set per query row: row i of head t attends to row_idx[b,t,i,:c]
+    (row_cnt [B,Hq,Tq] valid entries, or all). The definition, query row by query row: each row is
+    the one-row case of `attn`. Returns dict(out [B,Tq,Hq,d], lse [B,Hq,Tq])."""
+    B, Tq, Hq, d = q.shape
+    out = np.zeros((B, Tq, Hq, d), np.float32)
+    lse = np.zeros((B, Hq, Tq), np.float32)
+    for i in range(Tq):
+        r = attn(np.ascontiguousarray(q[:, i:i + 1]), k, v, scale, np.ascontiguousarray(row_idx[:, :, i]),
+                 None if row_cnt is None else np.ascontiguousarray(row_cnt[:, :, i]))
+        out[:, i] = r["out"][:, 0]
+        lse[:, :, i] = r["lse"][:, :, 0]
+    return {"out": out, "lse": lse}
+
+
+def rows_of_union(union: np.ndarray, mask: np.ndarray, cnt: np.ndarray, Tq: int, pitch: int):
+    """Back from (union, mask) to one index list per query row: [B,Hq,Tq,pitch] (-1 padded) and
+    counts [B,Hq,Tq]."""
+    B, Hq, _ = union.shape
+    rows = np.full((B, Hq, Tq, pitch), -1, np.int32)
+    rc = np.zeros((B, Hq, Tq), np.int32)
+    for b in range(B):
+        for t in range(Hq):
+            c = int(cnt[b, t])
+            for i in range(Tq):
+                mine = union[b, t, :c][(mask[b, t, :c] >> i) & 1 == 1]
+                rows[b, t, i, :len(mine)] = mine
+                rc[b, t, i] = len(mine)
+    return rows, rc
+
+
 def head_mapping(a_d: np.ndarray, a_t: np.ndarray, k: int):
     """Algorithm 1. a_d [S,Hd,R,N], a_t [S,Ht,R,N] fp32 -> (map [Ht] int32, overlap [Ht,Hd] int64)."""
     a_d = _c(a_d, np.float32)

@@ -224,6 +224,22 @@ PY_MUTANTS = [
     ("valid lengths dropped on the way to the selection",
      "sel, cnt = pick(A, k, seq_lens)", "sel, cnt = pick(A, k, None)",
      ["test_oracle_select.py"]),
+    ("union of the rows: a later row's bit replaces the earlier ones",
+     "keep[int(n)] = keep.get(int(n), 0) | (1 << i)", "keep[int(n)] = (1 << i)",
+     ["test_oracle_rows.py"]),
+    ("union of the rows: the rows' counts are ignored",
+     "c = k if row_cnt is None else int(row_cnt[b, j, i])", "c = k",
+     ["test_oracle_rows.py"]),
+    ("union of the rows: every target head reads draft head 0",
+     "j = int(head_map[t])\n            keep = {}", "j = 0\n            keep = {}",
+     ["test_oracle_rows.py"]),
+    ("per-row selection ranks the first row for every row",
+     "A = aggregate(scores[:, :, i:i + 1], None if lse is None", "A = aggregate(scores[:, :, 0:1], None if lse is None",
+     ["test_oracle_rows.py"]),
+    ("per-row attention: every row uses the first row's list",
+     "r = attn(np.ascontiguousarray(q[:, i:i + 1]), k, v, scale, np.ascontiguousarray(row_idx[:, :, i]),",
+     "r = attn(np.ascontiguousarray(q[:, i:i + 1]), k, v, scale, np.ascontiguousarray(row_idx[:, :, 0]),",
+     ["test_oracle_rows.py"]),
 ]
 
 

@@ -67,6 +67,9 @@ def parse_args():
     ap.add_argument("--prefill-blocks", type=int, default=0,
                     help="other mode: chunked sparse prefill, this many 16-row query blocks over ONE shared cache "
                          "of the configuration's context (batch 1), each block with its own mask; prints its own JSON line")
+    ap.add_argument("--prefill-masks", default="block", choices=["block", "rows"],
+                    help="with --prefill-blocks: one mask per 16-row block (from the rows' summed scores), or one per "
+                         "query row, gathered once per block as the union of the rows' sets (row bits)")
     ap.add_argument("--headmap", action="store_true",
                     help="other mode: offline head-mapping construction (Algorithm 1) on synthetic traces; prints its own JSON line")
     ap.add_argument("--no-extras", action="store_true",
@@ -208,30 +211,82 @@ def run_prefill(args, torch, sts):
     vn = (torch.randn(NB, T, Hkv, d, generator=gen, device=dev) * 0.5).to(torch.bfloat16)
     lens = (N - T * (NB - 1 - torch.arange(NB, device=dev))).to(torch.int32)
     scores = torch.empty(NB, Hd, T, N, dtype=torch.bfloat16, device=dev)
-    for b in range(NB):      # softmax of random logits over the visible prefix, block by block
-        lg = torch.randn(Hd, T, N, generator=gen, device=dev) * 2
+    for b in range(NB):      # softmax over the visible prefix, block by block: the rows of a block share the
+        # block's logits up to noise (neighbouring query tokens attend to much the same keys; same
+        # noise level as the draft scores of the configuration)
+        lg = (torch.randn(Hd, 1, N, generator=gen, device=dev) * 2
+              + torch.randn(Hd, T, N, generator=gen, device=dev) * cfg.noise)
         lg[:, :, int(lens[b]):] = float("-inf")
         scores[b] = torch.softmax(lg, dim=-1).to(torch.bfloat16)
         del lg
     kx, vx = w.k.expand(NB, Hkv, N, d), w.v.expand(NB, Hkv, N, d)
-    idx = torch.empty(NB, Hq, k, dtype=torch.int32, device=dev)
-    cnt = torch.empty(NB, Hq, dtype=torch.int32, device=dev)
     out = torch.empty(NB, T, Hq, d, dtype=torch.bfloat16, device=dev)
-    sel = lambda: sts.sts_select(scores, w.head_map, k, seq_lens=lens, out=(idx, cnt))
-    att = lambda: sts.sts_sparse_attn(q, kx, vx, idx, w.scale, counts=cnt, head_map=w.head_map, out=out,
-                                      want_lse=False, k_new=kn, v_new=vn, causal=True)
+    rows = args.prefill_masks == "rows"
+    if rows:
+        # a mask per query row (Section 4.2): per-row selection, union of a block's 16 row sets with
+        # row bits, one gather of the union per block
+        pitch = min(T * k, N)
+        ridx = torch.empty(NB, Hd, T, k, dtype=torch.int32, device=dev)
+        rcnt = torch.empty(NB, Hd, T, dtype=torch.int32, device=dev)
+        idx = torch.empty(NB, Hq, pitch, dtype=torch.int32, device=dev)
+        msk = torch.empty(NB, Hq, pitch, dtype=torch.int16, device=dev)
+        cnt = torch.empty(NB, Hq, dtype=torch.int32, device=dev)
+        def sel():
+            sts.sts_select_rows(scores, k, seq_lens=lens, out=(ridx, rcnt))
+            sts.sts_union_rows(ridx, rcnt, w.head_map, N, pitch=pitch, out=(idx, msk, cnt))
+        att = lambda: sts.sts_sparse_attn(q, kx, vx, idx, w.scale, counts=cnt, head_map=w.head_map, out=out,
+                                          want_lse=False, k_new=kn, v_new=vn, causal=True, row_mask=msk)
+    else:
+        idx = torch.empty(NB, Hq, k, dtype=torch.int32, device=dev)
+        cnt = torch.empty(NB, Hq, dtype=torch.int32, device=dev)
+        sel = lambda: sts.sts_select(scores, w.head_map, k, seq_lens=lens, out=(idx, cnt))
+        att = lambda: sts.sts_sparse_attn(q, kx, vx, idx, w.scale, counts=cnt, head_map=w.head_map, out=out,
+                                          want_lse=False, k_new=kn, v_new=vn, causal=True)
     t_sel = _timed(sel, args.steps, args.warmup, torch)
     t_att = _timed(att, args.steps, args.warmup, torch)
-    plan = sts.attn_plan(q, torch.empty(NB, Hkv, N, d, device="meta"), True, kmax=k, head_map=w.head_map)
-    b_set = NB * plan["units_per_batch"] * k * 2 * d * 2
+    sts.prof_enable(True)
+    sts.prof_reset()
+    for _ in range(max(1, min(args.steps, 20))):
+        att()
+    torch.cuda.synchronize()
+    prof = sts.prof_read()
+    sts.prof_enable(False)
+    split_us = prof["attn_sparse"][1] * 1e3 / max(prof["attn_sparse"][0], 1)
+    plan = sts.attn_plan(q, torch.empty(NB, Hkv, N, d, device="meta"), True, kmax=idx.shape[2], head_map=w.head_map)
+    row_bytes = 2 * d * 2
+    units = plan["units_per_batch"]
+    # the heads of a KV group that share a draft head form one unit and share one gathered list
+    G, hm = Hq // Hkv, [int(x) for x in w.head_map]
+    leaders, seen = [], set()
+    for t in range(Hq):
+        if (t // G, hm[t]) not in seen:
+            seen.add((t // G, hm[t]))
+            leaders.append(t)
+    assert len(leaders) == units
+    entries = int(cnt[:, leaders].sum().item()) if rows else NB * units * k       # gathered once per unit
+    b_set = entries * row_bytes
+    extra = {}
+    if rows:
+        # what one gather per query row (the single-row formulation) would move for the same masks
+        per_row_entries = int(rcnt[:, [hm[t] for t in leaders]].sum().item())
+        extra = {"union_entries_per_block_and_unit": round(entries / (NB * units), 1),
+                 "gathered_kv_bytes_one_gather_per_row": per_row_entries * row_bytes,
+                 "union_saves": round(per_row_entries / max(entries, 1), 2)}
     print(json.dumps({
         "metric": "chunked sparse prefill: attention us per 16-token query block over a shared cache", "unit": "us/block",
         "value": round(t_att["median"] / NB, 2), "higher_is_better": False, "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
         "steps": args.steps, "warmup": args.warmup,
         "config": {"workload": f"{cfg.name} shape, one cache of N{N} Hq{Hq}/Hkv{Hkv} d{d}, {NB} blocks of {T} rows, "
-                               f"budget {k} tokens per head and block, draft scores bf16 [{NB},{Hd},{T},{N}]"},
+                               f"budget {k} tokens per head and " + ("query row (a mask per row, gathered as the block's union)" if rows else "block")
+                               + f", draft scores bf16 [{NB},{Hd},{T},{N}]", "masks": args.prefill_masks},
         "sparse_attn_us": t_att, "select_us": t_sel, "gathered_kv_bytes_b_set": b_set,
-        "gathered_kv_gbs_b_set": round(b_set / (t_att["median"] * 1e-6) / 1e9, 1), "launch": plan}))
+        "gathered_kv_gbs_b_set": round(b_set / (t_att["median"] * 1e-6) / 1e9, 1),
+        "roofline": {"bound": "hbm", "kernel": "attn_split_kernel<sparse" + (", row bits>" if rows else ">"),
+                     "achieved": round(b_set / (split_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(b_set / (split_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "avg_launch_us": round(split_us, 2),
+                     "algorithmic_bytes_per_launch": b_set,
+                     "note": "blocks gather overlapping rows of one cache, so part of the traffic is served by the caches"},
+        "launch": plan, **extra}))
 
 
 def run_headmap(args, torch, sts):

@@ -147,6 +147,13 @@ typedef struct {
  * out and lse_out cover the whole verification attention. Without them the caller merges that
  * part itself using lse_out.
  *
+ * An index set per query row (paper Section 4.2: during prefill the sparsity pattern is
+ * two-dimensional, every query token of a head has a mask of its own). With row_mask the call
+ * gathers each entry of `indices` once for the whole block of up to 16 query rows and row i
+ * attends only to the entries whose word has bit i set: `indices` holds the union of the rows'
+ * sets (sts_union_rows builds both from per-row lists). A row that keeps nothing gives out = 0 and
+ * lse = -inf. Contiguous or strided caches, any page_size; not with block_table.
+ *
  * Summed attention weights (paper Section 4.3: one mask per speculative batch, from the draft's
  * attention over the whole query block; Section 5: the draft layer hands its scores to the
  * selection). With weights_sum_out the dense call makes a second pass over K once the row
@@ -192,6 +199,9 @@ typedef struct {
   float *weights_sum_out;   /* [dev] dense only, optional [B,Hq,N] fp32: the attention weights summed over
                                the Tq query rows, sum_i exp(s[i,n] - lse[i]), rows added in order; 0 at
                                n >= N_b (see below) */
+  const uint16_t *row_mask; /* [dev] sparse only, optional, laid out like `indices` ([B,Hq,kmax], the same
+                               batch stride): bit i of an entry's word set iff query row i keeps the entry
+                               (see above); NULL = every row keeps every entry */
   void *workspace;          /* [dev] 256-byte aligned scratch */
   size_t workspace_bytes;
 } sts_attn_params;
@@ -219,6 +229,34 @@ typedef struct {
   void *workspace;          /* [dev] 256-byte aligned scratch */
   size_t workspace_bytes;
 } sts_headmap_params;
+
+/* ----------------------------------------------------------------------------------------
+ * sts_union_rows -- two-dimensional masks for a block of query rows (paper Section 4.2: during
+ * prefill each query token has its own mask). Per-row index lists, one per (batch, draft head,
+ * query row) -- e.g. sts_select on the score tensor viewed as [B, Hd*Tq, 1, N] with the identity
+ * head map, whose output is [B, Hd, Tq, k] -- become, for every target head t, the ascending union
+ * of the lists of the rows of draft head head_map[t], and one 16-bit word per union entry whose
+ * bit i is set iff row i keeps the token: the form sts_sparse_attn reads with row_mask, gathering
+ * every token once for the whole block.
+ * A row's valid entries are its first row_counts[b,j,i] ones (any order; values outside [0,N),
+ * such as the -1 padding, name no token). The outputs have `pitch` entries per (batch, target
+ * head): a union longer than that is truncated to its first `pitch` tokens (counts then equal
+ * pitch; pitch >= min(Tq*k, N) never truncates); the tail is padded with -1 / 0.
+ * Supported: 1 <= Tq <= 16, Hq, Hd <= 256. No workspace.
+ */
+typedef struct {
+  int32_t B, Hd, Hq, Tq, N;
+  int32_t k;                   /* pitch of the per-row lists */
+  const int32_t *row_indices;  /* [dev] [B,Hd,Tq,k] */
+  const int32_t *row_counts;   /* [dev] [B,Hd,Tq] valid entries per row, or NULL (= k) */
+  const int32_t *head_map;     /* [host] [Hq] target head -> draft head */
+  int32_t pitch;               /* entries per (batch, target head) of the outputs */
+  int32_t *indices;            /* [dev] out [B,Hq,pitch] ascending union, -1 padded */
+  uint16_t *row_mask;          /* [dev] out [B,Hq,pitch] */
+  int32_t *counts;             /* [dev] out [B,Hq] union sizes; may be NULL */
+} sts_union_params;
+
+sts_status sts_union_rows(const sts_union_params *p, void *stream);
 
 size_t sts_headmap_workspace_bytes(const sts_headmap_params *p);
 sts_status sts_head_map(const sts_headmap_params *p, void *stream);
@@ -278,7 +316,8 @@ typedef enum {
   STS_K_SELECT_POOL = 12,  /* small budgets: ranking of the chunks' winners, one workgroup per row */
   STS_K_ATTN_PROBSUM = 13, /* dense second pass over K: attention weights summed over the query block */
   STS_K_SELECT_FUSED = 14, /* long rows: aggregation, threshold and compaction in one launch */
-  STS_K_COUNT_ = 15
+  STS_K_UNION_ROWS = 15,   /* union of per-row index lists + row bits */
+  STS_K_COUNT_ = 16
 } sts_kernel_kind;
 #define STS_PROF_MAX 4096
 

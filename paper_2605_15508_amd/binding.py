@@ -21,14 +21,14 @@ STS_BF16, STS_F32 = 0, 1
 KERNEL_KINDS = {"select_clear": 0, "select_agg": 1, "select_hist": 2, "select_count": 3,
                 "select_write": 4, "attn_sparse": 5, "attn_dense": 6, "attn_combine": 7, "select_block": 8,
                 "headmap": 9, "select_small": 10, "select_local": 11, "select_pool": 12,
-                "attn_probsum": 13, "select_fused": 14}
+                "attn_probsum": 13, "select_fused": 14, "union_rows": 15}
 KNOBS = {"attn_wgs_per_cu": 0, "select_spin_limit": 1, "probsum_wgs_per_cu": 2, "select_path": 3}
 
 # every symbol include/sts.h declares
 EXPORTS = ["sts_select_workspace_bytes", "sts_attn_workspace_bytes", "sts_select", "sts_sparse_attn",
            "sts_dense_attn", "sts_strerror", "sts_version", "sts_prof_enable", "sts_prof_reset",
            "sts_prof_read", "sts_attn_plan", "sts_head_map", "sts_headmap_workspace_bytes",
-           "sts_sparse_attn_static", "sts_set_knob", "sts_get_knob"]
+           "sts_sparse_attn_static", "sts_set_knob", "sts_get_knob", "sts_union_rows"]
 STS_STATIC_SCRATCH_BYTES = 8 << 20
 
 
@@ -60,8 +60,15 @@ class AttnParams(ctypes.Structure):
                 ("num_pages", ctypes.c_int32), ("kv_stride_page", ctypes.c_int64),
                 ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p), ("causal", ctypes.c_int32),
                 ("logits_bf16", ctypes.c_int32), ("idx_stride_b", ctypes.c_int64), ("cnt_stride_b", ctypes.c_int64),
-                ("weights_sum_out", ctypes.c_void_p),
+                ("weights_sum_out", ctypes.c_void_p), ("row_mask", ctypes.c_void_p),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
+
+
+class UnionParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("Hd", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Tq", ctypes.c_int32),
+                ("N", ctypes.c_int32), ("k", ctypes.c_int32), ("row_indices", ctypes.c_void_p),
+                ("row_counts", ctypes.c_void_p), ("head_map", ctypes.c_void_p), ("pitch", ctypes.c_int32),
+                ("indices", ctypes.c_void_p), ("row_mask", ctypes.c_void_p), ("counts", ctypes.c_void_p)]
 
 
 class HeadmapParams(ctypes.Structure):
@@ -109,6 +116,8 @@ def load_library():
     lib.sts_head_map.argtypes = [ctypes.POINTER(HeadmapParams), ctypes.c_void_p]
     lib.sts_attn_plan.restype = ctypes.c_int
     lib.sts_attn_plan.argtypes = [ctypes.POINTER(AttnParams), ctypes.c_int] + [ctypes.POINTER(ctypes.c_int32)] * 3
+    lib.sts_union_rows.restype = ctypes.c_int
+    lib.sts_union_rows.argtypes = [ctypes.POINTER(UnionParams), ctypes.c_void_p]
     lib.sts_set_knob.restype = None
     lib.sts_set_knob.argtypes = [ctypes.c_int, ctypes.c_double]
     lib.sts_get_knob.restype = ctypes.c_double
@@ -220,7 +229,7 @@ def sts_select(scores, head_map, k: int, lse=None, seq_lens=None, kind: int = ST
 
 
 def _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse_out, logits_out,
-                 page_size=1, block_table=None, N=None, k_new=None, v_new=None, causal=True):
+                 page_size=1, block_table=None, N=None, k_new=None, v_new=None, causal=True, row_mask=None):
     import torch
 
     assert q.is_cuda and q.dtype == torch.bfloat16 and q.is_contiguous()
@@ -268,13 +277,18 @@ def _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse_o
                    block_table=_ptr(block_table), table_stride=tstride, num_pages=npages,
                    kv_stride_page=sp, k_new=_ptr(k_new), v_new=_ptr(v_new), causal=1 if causal else 0,
                    idx_stride_b=isb, cnt_stride_b=csb, workspace=None, workspace_bytes=0)
+    if row_mask is not None:
+        # uint16 words (torch.int16 storage is accepted: same bits), laid out like the indices
+        assert indices is not None and row_mask.is_cuda and row_mask.element_size() == 2
+        assert tuple(row_mask.shape) == tuple(indices.shape) and row_mask.stride() == indices.stride()
+        p.row_mask = row_mask.data_ptr()
     return p, hm
 
 
 def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=None, seq_lens=None,
               out=None, out_dtype=None, want_lse=True, want_logits=False, workspace=None,
               lse_out=None, logits_out=None, page_size=1, block_table=None, N=None,
-              k_new=None, v_new=None, causal=True, weights_sum_out=None, static=False):
+              k_new=None, v_new=None, causal=True, weights_sum_out=None, static=False, row_mask=None):
     import torch
 
     lib = load_library()
@@ -299,7 +313,7 @@ def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=
                               and logits.is_contiguous() and tuple(logits.shape) == (B, Hq, Tq, N))
     p, _keep = _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse, logits,
                             page_size=page_size, block_table=block_table, N=N,
-                            k_new=k_new, v_new=v_new, causal=causal)
+                            k_new=k_new, v_new=v_new, causal=causal, row_mask=row_mask)
     if static:      # the library's own scratch array: no workspace, nothing allocated by the call
         assert sparse and workspace is None
         _check(lib.sts_sparse_attn_static(ctypes.byref(p), _stream()), "sts_sparse_attn_static")
@@ -324,14 +338,58 @@ def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=
 
 def sts_sparse_attn(q, k, v, indices, scale, counts=None, head_map=None, out=None, out_dtype=None,
                     want_lse=True, workspace=None, lse_out=None, page_size=1, block_table=None, N=None,
-                    k_new=None, v_new=None, causal=True):
+                    k_new=None, v_new=None, causal=True, row_mask=None):
     """Attention over the gathered rows indices[b,t,:counts[b,t]] of the full cache.
-    q [B,Tq,Hq,d] bf16, k/v [B,Hkv,N,d] bf16 (strided ok) -> (out [B,Tq,Hq,d], lse [B,Hq,Tq])."""
+    q [B,Tq,Hq,d] bf16, k/v [B,Hkv,N,d] bf16 (strided ok) -> (out [B,Tq,Hq,d], lse [B,Hq,Tq]).
+    row_mask (16-bit words shaped like indices): query row i attends only to entries with bit i."""
     out, lse, _ = _run_attn(True, q, k, v, scale, indices=indices, counts=counts, head_map=head_map,
                             out=out, out_dtype=out_dtype, want_lse=want_lse, workspace=workspace,
                             lse_out=lse_out, page_size=page_size, block_table=block_table, N=N,
-                            k_new=k_new, v_new=v_new, causal=causal)
+                            k_new=k_new, v_new=v_new, causal=causal, row_mask=row_mask)
     return out, lse
+
+
+def sts_select_rows(scores, k: int, lse=None, seq_lens=None, kind: int = STS_SCORES_PROBS, out=None, workspace=None):
+    """Per-row selection for prefill: every one of the Tq score rows of a draft head is ranked by
+    itself. scores [B,Hd,Tq,N] -> (row_indices [B,Hd,Tq,k], row_counts [B,Hd,Tq]). Marshalling only:
+    it is sts_select on the same memory viewed as [B, Hd*Tq, 1, N] with the identity head map
+    (Hd*Tq <= 256)."""
+    B, Hd, Tq, N = scores.shape
+    assert Hd * Tq <= 256, "sts_select takes up to 256 heads: split the draft heads over several calls"
+    idx, cnt, _ = sts_select(scores.view(B, Hd * Tq, 1, N), list(range(Hd * Tq)), k,
+                             lse=None if lse is None else lse.view(B, Hd * Tq, 1), seq_lens=seq_lens, kind=kind,
+                             out=None if out is None else (out[0].view(B, Hd * Tq, k), out[1].view(B, Hd * Tq)),
+                             workspace=workspace)
+    return idx.view(B, Hd, Tq, k), cnt.view(B, Hd, Tq)
+
+
+def sts_union_rows(row_indices, row_counts, head_map, N: int, pitch: Optional[int] = None, out=None):
+    """Per-row lists [B,Hd,Tq,k] (+ counts [B,Hd,Tq] or None) -> (indices [B,Hq,pitch] ascending union,
+    row_mask [B,Hq,pitch] int16 storage of the 16-bit words, counts [B,Hq]). See sts_union_rows in
+    include/sts.h."""
+    import torch
+
+    lib = load_library()
+    assert row_indices.is_cuda and row_indices.dtype == torch.int32 and row_indices.is_contiguous()
+    B, Hd, Tq, k = row_indices.shape
+    if row_counts is not None:
+        assert row_counts.is_cuda and row_counts.dtype == torch.int32 and row_counts.is_contiguous()
+        assert tuple(row_counts.shape) == (B, Hd, Tq)
+    hm = _host_i32(head_map)
+    Hq = len(hm)
+    pitch = min(Tq * k, N) if pitch is None else int(pitch)
+    dev = row_indices.device
+    if out is None:
+        indices = torch.empty(B, Hq, pitch, dtype=torch.int32, device=dev)
+        mask = torch.empty(B, Hq, pitch, dtype=torch.int16, device=dev)
+        counts = torch.empty(B, Hq, dtype=torch.int32, device=dev)
+    else:
+        indices, mask, counts = out
+    p = UnionParams(B=B, Hd=Hd, Hq=Hq, Tq=Tq, N=int(N), k=k, row_indices=_ptr(row_indices), row_counts=_ptr(row_counts),
+                    head_map=ctypes.cast(hm, ctypes.c_void_p), pitch=pitch, indices=_ptr(indices), row_mask=_ptr(mask),
+                    counts=_ptr(counts))
+    _check(lib.sts_union_rows(ctypes.byref(p), _stream()), "sts_union_rows")
+    return indices, mask, counts
 
 
 def sts_sparse_attn_static(q, k, v, indices, scale, counts=None, head_map=None, out=None, out_dtype=None,

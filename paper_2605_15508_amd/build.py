@@ -10,7 +10,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsts.so")
-SOURCES = ["api.hip", "attn.hip", "select.hip", "headmap.hip", "scratch.hip"]
+SOURCES = ["api.hip", "attn.hip", "select.hip", "headmap.hip", "scratch.hip", "union.hip"]
 HEADERS = [os.path.join(CSRC, "common.h"), os.path.join(HERE, "..", "include", "sts.h")]
 
 # -packed-fp32-ops is switched off on purpose: packed fp32 instructions are not to be

@@ -95,6 +95,7 @@ sts_status validate_attn(const sts_attn_params *p, int sparse) {
   if (p->Tq > 16 || p->Hq > STS_MAX_HEADS || p->Hq / p->Hkv > STS_MAX_GROUP) return STS_EUNSUPPORTED;
   if (p->out_dtype != STS_BF16 && p->out_dtype != STS_F32) return STS_EINVAL;
   if (!isfinite(p->scale)) return STS_EINVAL;
+  if (p->row_mask && (!sparse || p->block_table)) return sparse ? STS_EUNSUPPORTED : STS_EINVAL;
   if (sparse) {
     if (p->kmax < 0) return STS_EINVAL;
     if (p->logits_out || p->seq_lens) return STS_EINVAL;
@@ -230,6 +231,7 @@ sts_status run_attn(const sts_attn_params *p, int sparse, hipStream_t s, void *w
   a.v = static_cast<const uint16_t *>(p->v);
   a.indices = sparse ? p->indices : nullptr;
   a.counts = sparse ? p->counts : nullptr;
+  a.row_mask = sparse ? p->row_mask : nullptr;
   a.idx_stride_b = p->idx_stride_b ? p->idx_stride_b : (int64_t)p->Hq * p->kmax;
   a.cnt_stride_b = p->cnt_stride_b ? p->cnt_stride_b : p->Hq;
   a.seq_lens = sparse ? nullptr : p->seq_lens;
@@ -722,6 +724,30 @@ sts_status sts_head_map(const sts_headmap_params *p, void *stream) {
   return e == hipSuccess ? STS_OK : STS_EHIP;
 }
 
+sts_status sts_union_rows(const sts_union_params *p, void *stream) {
+  if (!p) return STS_EINVAL;
+  if (p->B < 0 || p->Hd < 1 || p->Hq < 1 || p->Tq < 1 || p->N < 0 || p->k < 0 || p->pitch < 0) return STS_EINVAL;
+  if (p->Tq > 16 || p->Hq > STS_MAX_HEADS || p->Hd > STS_MAX_HEADS || p->B > 65535) return STS_EUNSUPPORTED;
+  if ((int64_t)p->N > 0x7fffffffll - 65536) return STS_EUNSUPPORTED;
+  if (!p->head_map || !p->indices || !p->row_mask) return STS_EINVAL;
+  for (int t = 0; t < p->Hq; ++t)
+    if (p->head_map[t] < 0 || p->head_map[t] >= p->Hd) return STS_EINVAL;
+  if (p->B == 0) return STS_OK;
+  if (p->k > 0 && !p->row_indices) return STS_EINVAL;
+  UnionArgs a;
+  memset(&a, 0, sizeof(a));
+  a.row_idx = p->row_indices;
+  a.row_cnt = p->row_counts;
+  a.indices = p->indices;
+  a.row_mask = p->row_mask;
+  a.counts = p->counts;
+  a.B = p->B; a.Hd = p->Hd; a.Hq = p->Hq; a.Tq = p->Tq; a.N = p->N; a.k = p->k; a.pitch = p->pitch;
+  for (int t = 0; t < p->Hq; ++t) a.map[t] = (uint8_t)p->head_map[t];
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const hipError_t rc = run_kernel(STS_K_UNION_ROWS, s, [&] { return launch_union_rows(a, s); });
+  return rc == hipSuccess ? STS_OK : STS_EHIP;
+}
+
 const char *sts_strerror(int status) {   // an int on purpose: any value a caller holds may be asked about
   switch (status) {
     case STS_OK: return "ok";
@@ -733,7 +759,7 @@ const char *sts_strerror(int status) {   // an int on purpose: any value a calle
   return "unknown status";
 }
 
-int sts_version(void) { return 200; }
+int sts_version(void) { return 201; }
 
 void sts_set_knob(int which, double value) {
   if (which < 0 || which >= STS_KNOB_COUNT_) return;

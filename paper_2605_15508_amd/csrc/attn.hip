@@ -55,7 +55,9 @@ __device__ __forceinline__ float xor_max(float x, int lanemask) {
 
 // One workgroup per CU (the whole register file for it) for exactly the variants the host plans
 // one workgroup per CU for: four query tiles, and head size 128 when dense or with two query tiles.
-template <int D, int NQ, bool SPARSE, bool LOGITS, bool PAGED>
+// ROWMASK: every index entry comes with a 16-bit word, bit i set iff query row i of the block keeps
+// the entry (prefill: an index set per query row, gathered once as their union).
+template <int D, int NQ, bool SPARSE, bool LOGITS, bool PAGED, bool ROWMASK = false>
 __global__ void __launch_bounds__(64 * STS_WG_WAVES, (NQ == 4 || (D == 128 && (!SPARSE || NQ == 2))) ? 1 : 2)
 attn_split_kernel(const AttnArgs A) {
   typedef typename Chunk<D>::type chunk_t;
@@ -112,9 +114,12 @@ attn_split_kernel(const AttnArgs A) {
   const int32_t *idx_row = SPARSE ? A.indices + (size_t)bt * A.idx_stride_b + (size_t)head0 * A.kmax : nullptr;
   // first tile's index entries, issued before anything depends on the count (kmax >= 1
   // whenever a sparse grid has tiles to do; the clamp keeps the address inside the row)
-  int rows_first = 0;
-  if (SPARSE && len_max > 0)
+  const uint16_t *mask_row = ROWMASK ? A.row_mask + (size_t)bt * A.idx_stride_b + (size_t)head0 * A.kmax : nullptr;
+  int rows_first = 0, bits_first = 0;
+  if (SPARSE && len_max > 0) {
     rows_first = idx_row[min(((t_begin + wave) * STS_TILE_KEYS + (lane & 31)) >> psh, A.kmax - 1)];
+    if (ROWMASK) bits_first = mask_row[min(((t_begin + wave) * STS_TILE_KEYS + (lane & 31)) >> psh, A.kmax - 1)];
+  }
   const int tiles_total = (c + STS_TILE_KEYS - 1) / STS_TILE_KEYS;
   const int t_end = min(t_begin + tps, tiles_total);
   const int nb_max = (A.N + A.page - 1) >> psh;   // logical blocks of the cache
@@ -171,6 +176,12 @@ attn_split_kernel(const AttnArgs A) {
     const int e = p >> psh;
     return SPARSE ? idx_row[e] : e;
   };
+  // the row bits of the same entry (ROWMASK only)
+  auto fetch_bits = [&](int t) -> int {
+    const int pos = t * STS_TILE_KEYS + (lane & 31);
+    const int p = (t < t_end) ? min(pos, c - 1) : safe_pos;
+    return ROWMASK ? (int)mask_row[p >> psh] : 0;
+  };
 
   auto resolve = [&](int raw, int t, uint32_t &tile_mask) -> int {
     const int pos = t * STS_TILE_KEYS + (lane & 31);
@@ -181,6 +192,10 @@ attn_split_kernel(const AttnArgs A) {
     tile_mask = (uint32_t)__ballot(ok);
     if (PAGED) return table_row[min(blk, A.table_stride - 1)];
     return min(tok, A.N - 1);
+  };
+  // row bits of this lane's slot, cleared where the slot holds no key
+  auto slot_bits = [&](int bits, uint32_t tile_mask) -> int {
+    return ((tile_mask >> (lane & 31)) & 1u) ? bits : 0;
   };
 
   auto issue_loads = [&](int x, int t, chunk_t (&Kr)[8], chunk_t (&Vr)[8]) {
@@ -244,7 +259,8 @@ attn_split_kernel(const AttnArgs A) {
     }
   };
 
-  auto consume = [&](int t, const chunk_t (&Kr)[8], const chunk_t (&Vr)[8], const uint32_t tile_mask, const bool second) {
+  auto consume = [&](int t, const chunk_t (&Kr)[8], const chunk_t (&Vr)[8], const uint32_t tile_mask, const bool second,
+                     const int tile_bits) {
     const int pos0 = t * STS_TILE_KEYS;
     // ---- K: registers -> swizzled LDS tile (row = slot, 16-byte slot index XOR row)
 #pragma unroll
@@ -326,6 +342,11 @@ attn_split_kernel(const AttnArgs A) {
     }
     // ---- online softmax (log2 domain) and P^T as bf16 B operands
     bf16x8 Pb[NQ];
+    int key_bits[8];                // ROWMASK: the row bits of this lane's 8 keys
+    if constexpr (ROWMASK) {
+#pragma unroll
+      for (int m = 0; m < 8; ++m) key_bits[m] = __shfl(tile_bits, slot_of(m), 64);
+    }
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
       float s[8];
@@ -333,18 +354,21 @@ attn_split_kernel(const AttnArgs A) {
       for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const bool ok = (tile_mask >> (16 * ks + 4 * a + r)) & 1u;
+          const bool ok = ROWMASK ? ((key_bits[4 * ks + r] >> q_tq[nq]) & 1) != 0
+                                  : ((tile_mask >> (16 * ks + 4 * a + r)) & 1u) != 0;
           s[4 * ks + r] = ok ? St[nq][ks][r] * A.scale_log2 : -INFINITY;
         }
       float mt = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
       mt = xor_max(mt, 16);
       mt = xor_max(mt, 32);
-      const float m_new = fmaxf(m_run[nq], mt);          // finite: every consumed tile has a valid key
-      const float alpha = __builtin_amdgcn_exp2f(m_run[nq] - m_new);
+      const float m_new = fmaxf(m_run[nq], mt);          // finite: every consumed tile has a valid key ...
+      // ... except with row bits: a row may keep none of a tile's keys, nor of any tile so far
+      const float m_ref = (ROWMASK && m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m_run[nq] - m_ref);
       float p[8], psum = 0.f;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        p[i] = __builtin_amdgcn_exp2f(s[i] - m_new);
+        p[i] = __builtin_amdgcn_exp2f(s[i] - m_ref);
         psum += p[i];
       }
       l_run[nq] = l_run[nq] * alpha + psum;
@@ -384,39 +408,53 @@ attn_split_kernel(const AttnArgs A) {
   if (tile_of(0) < t_end) {   // wave-uniform; a wave without tiles touches no memory
     chunk_t K0[8], V0[8], K1[8], V1[8];
     uint32_t m0, m1, mk_next, mk_new;
+    int b0 = 0, b1 = 0, bk_next = 0, bk_new = 0;   // ROWMASK: the tiles' row bits, staged like the masks
     int v = 0;
     // prologue: tile v in flight, tile v+1 resolved, tile v+2 fetched
     // The first tile's K/V loads go out as soon as its own index entries are there: the entries of
     // the second tile are asked for before them (so that waiting for those entries later does not
     // wait for the K/V rows, which return in order), but not waited for.
     int raw_a = SPARSE ? rows_first : fetch_rows(tile_of(0));
+    int rbits_a = ROWMASK ? bits_first : 0;
     int raw_b = fetch_rows(tile_of(1));
+    int rbits_b = fetch_bits(tile_of(1));
     int x_a = resolve(raw_a, tile_of(0), m0);
+    if (ROWMASK) b0 = slot_bits(rbits_a, m0);
     if (SPARSE) __builtin_amdgcn_sched_barrier(0);
     issue_loads(x_a, tile_of(0), K0, V0);
     if (SPARSE) __builtin_amdgcn_sched_barrier(0);
     raw_a = fetch_rows(tile_of(2));
+    rbits_a = fetch_bits(tile_of(2));
     int x_b = resolve(raw_b, tile_of(1), mk_next);
+    if (ROWMASK) bk_next = slot_bits(rbits_b, mk_next);
     if (SPARSE) __builtin_amdgcn_sched_barrier(0);
     for (;;) {
       raw_b = fetch_rows(tile_of(v + 3));
+      rbits_b = fetch_bits(tile_of(v + 3));
       x_a = resolve(raw_a, tile_of(v + 2), mk_new);
+      if (ROWMASK) bk_new = slot_bits(rbits_a, mk_new);
       if (SPARSE) __builtin_amdgcn_sched_barrier(0);   // index traffic stays ahead of the K/V loads
       issue_loads(x_b, tile_of(v + 1), K1, V1);
       m1 = mk_next;
+      b1 = bk_next;
       if (SPARSE) __builtin_amdgcn_sched_barrier(0);   // loads are in flight before the tile is consumed
-      consume(tile_of(v), K0, V0, m0, false);          // even step: first tile of a pair
+      consume(tile_of(v), K0, V0, m0, false, b0);      // even step: first tile of a pair
       mk_next = mk_new;
+      bk_next = bk_new;
       ++v;
       if (tile_of(v) >= t_end) break;
       raw_a = fetch_rows(tile_of(v + 3));
+      rbits_a = fetch_bits(tile_of(v + 3));
       x_b = resolve(raw_b, tile_of(v + 2), mk_new);
+      if (ROWMASK) bk_new = slot_bits(rbits_b, mk_new);
       if (SPARSE) __builtin_amdgcn_sched_barrier(0);
       issue_loads(x_a, tile_of(v + 1), K0, V0);
       m0 = mk_next;
+      b0 = bk_next;
       if (SPARSE) __builtin_amdgcn_sched_barrier(0);
-      consume(tile_of(v), K1, V1, m1, true);           // odd step: second tile of the pair
+      consume(tile_of(v), K1, V1, m1, true, b1);       // odd step: second tile of the pair
       mk_next = mk_new;
+      bk_next = bk_new;
       ++v;
       if (tile_of(v) >= t_end) break;
     }
@@ -713,7 +751,10 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(const AttnArgs A, con
 template <int D, int NQ, bool PAGED>
 hipError_t launch_split_dnp(const AttnArgs &a, bool sparse, hipStream_t s) {
   const dim3 grid((unsigned)((size_t)a.B * a.num_units * a.num_splits)), block(64 * STS_WG_WAVES);
-  if (sparse)
+  if (sparse && a.row_mask) {
+    if constexpr (!PAGED) STS_LAUNCH((attn_split_kernel<D, NQ, true, false, false, true>), grid, block, 0, s, a);
+    else return hipErrorInvalidValue;           // (the host refuses row bits on a paged cache)
+  } else if (sparse)
     STS_LAUNCH((attn_split_kernel<D, NQ, true, false, PAGED>), grid, block, 0, s, a);
   else if (a.logits_out)
     STS_LAUNCH((attn_split_kernel<D, NQ, false, true, PAGED>), grid, block, 0, s, a);

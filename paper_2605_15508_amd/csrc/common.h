@@ -70,6 +70,7 @@ struct AttnUnitTable {
 struct AttnArgs {
   const uint16_t *q, *k, *v;
   const int32_t *indices, *counts, *seq_lens;
+  const uint16_t *row_mask;               // [B,Hq,kmax] laid out like indices: bit i = query row i keeps the entry; or NULL
   int64_t stride_b, stride_h, stride_n;   // elements
   int64_t idx_stride_b, cnt_stride_b;     // elements between batches of indices / counts
   int32_t B, Tq, Hq, Hkv, G, N, kmax;
@@ -156,6 +157,18 @@ struct SelectArgs {
   SelectTargets targets;
   int32_t kh[STS_MAX_HEADS];  // budget of draft head j (<= k)
 };
+
+// union of per-row index lists (union.hip)
+struct UnionArgs {
+  const int32_t *row_idx;     // [B,Hd,Tq,k]
+  const int32_t *row_cnt;     // [B,Hd,Tq] or nullptr (= k)
+  int32_t *indices;           // [B,Hq,pitch]
+  uint16_t *row_mask;         // [B,Hq,pitch]
+  int32_t *counts;            // [B,Hq] or nullptr
+  int32_t B, Hd, Hq, Tq, N, k, pitch;
+  uint8_t map[STS_MAX_HEADS]; // target head -> draft head
+};
+hipError_t launch_union_rows(const UnionArgs &a, hipStream_t s);
 
 // device address of the current device's copy of the static scratch array (scratch.hip)
 sts_status sts_static_scratch(void **out);

@@ -112,6 +112,13 @@ hipError_t launch_select_local(const SelectArgs &a, hipStream_t) { check_pool(a,
 hipError_t launch_select_pool(const SelectArgs &a, hipStream_t) { check_pool(a, "pool"); return hipSuccess; }
 hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t) { check_pipeline(a, "hist"); if (pass != 1 && pass != 2) fail("hist pass"); return hipSuccess; }
 hipError_t launch_select_write(const SelectArgs &a, hipStream_t) { check_pipeline(a, "write"); return hipSuccess; }
+hipError_t launch_union_rows(const UnionArgs &a, hipStream_t) {
+  ++g_launches;
+  if (a.Tq < 1 || a.Tq > 16 || a.Hq < 1 || a.Hd < 1 || !a.indices || !a.row_mask) fail("union: args");
+  for (int t = 0; t < a.Hq; ++t)
+    if (a.map[t] >= a.Hd) fail("union: head map");
+  return hipSuccess;
+}
 hipError_t launch_headmap_clear(unsigned long long *, int, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_headmap_overlap(const int32_t *, const int32_t *, int, int, int, int, int, int, unsigned long long *, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_headmap_argmax(const unsigned long long *, int, int, int32_t *, hipStream_t) { ++g_launches; return hipSuccess; }
@@ -250,6 +257,21 @@ int main() {
       calls += 3;
       ++accepted;
     }
+  }
+  for (int Tq : {0, 1, 16, 17}) for (int Hq : {1, 256}) for (int Hd : {1, 16}) for (int bad : {0, 1}) {
+    sts_union_params p;
+    memset(&p, 0, sizeof(p));
+    std::vector<int32_t> hm(Hq);
+    for (int t = 0; t < Hq; ++t) hm[t] = t % Hd;
+    if (bad) hm[Hq - 1] = Hd;
+    p.B = 2; p.Hd = Hd; p.Hq = Hq; p.Tq = Tq; p.N = 5000; p.k = 100; p.pitch = 1600;
+    p.row_indices = reinterpret_cast<const int32_t *>(fake);
+    p.head_map = hm.data();
+    p.indices = reinterpret_cast<int32_t *>(fake); p.row_mask = reinterpret_cast<uint16_t *>(fake);
+    const sts_status rc = sts_union_rows(&p, nullptr);
+    if ((rc == STS_OK) != (Tq >= 1 && Tq <= 16 && !bad)) fail("union: wrong verdict");
+    accepted += rc == STS_OK;
+    ++calls;
   }
   for (int s = 1; s >= -6; --s)
     if (!sts_strerror(s)[0]) fail("empty error string");

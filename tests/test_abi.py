@@ -113,7 +113,7 @@ def test_ctypes_structs_match_the_header(tmp_path):
     import subprocess
 
     structs = {"sts_select_params": binding.SelectParams, "sts_attn_params": binding.AttnParams,
-               "sts_headmap_params": binding.HeadmapParams}
+               "sts_headmap_params": binding.HeadmapParams, "sts_union_params": binding.UnionParams}
     lines = ["#include <stdio.h>", "#include <stddef.h>", '#include "sts.h"', "int main(void) {"]
     for cname, cls in structs.items():
         lines.append(f'  printf("{cname} %zu\\n", sizeof({cname}));')

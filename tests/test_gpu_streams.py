@@ -1,13 +1,16 @@
 """Drafting-speculation pipelining (Section 5: mask generation runs on its own stream beside
 the forward pass, ordered by events). The library only enqueues on the caller's stream and
 never synchronises, so mask building for the next round can overlap attention of the current
-one. Results must equal the sequential ones."""
+one. Results must equal the oracle's (and, bit for bit, the sequential run's)."""
 from dataclasses import replace
 
+import numpy as np
 import pytest
 import torch
 
+import oracle
 import paper_2605_15508_amd as sts
+from gpu_util import check_attn
 from workload import CONFIGS, make_workload
 
 pytestmark = pytest.mark.gpu
@@ -55,3 +58,10 @@ def test_select_overlaps_attention_on_a_second_stream():
         got = (idx[0], cnt[0], out[0], lse[0], idx[1], cnt[1], out[1], lse[1])
         for g, r in zip(got, ref):
             assert torch.equal(g, r)
+    # what the two streams produced, against the oracle: index sets bit for bit, outputs in tolerance
+    for w, i, c, o, l in ((w0, idx[0], cnt[0], out[0], lse[0]), (w1, idx[1], cnt[1], out[1], lse[1])):
+        o_idx, o_cnt, _ = oracle.select_indices(w.scores.numpy(), np.asarray(hm, np.int32), k)
+        np.testing.assert_array_equal(i.cpu().numpy(), o_idx)
+        np.testing.assert_array_equal(c.cpu().numpy(), o_cnt)
+        ref_attn = oracle.attn(oracle.bf16_bits(w.q), oracle.bf16_bits(w.k), oracle.bf16_bits(w.v), w.scale, o_idx, o_cnt)
+        check_attn(o, l, ref_attn, what="two streams")

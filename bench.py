@@ -329,18 +329,35 @@ class Point:
         self.cnt = torch.empty(cfg.B, cfg.Hq, dtype=torch.int32, device=dev)
         self.out_s = torch.empty(cfg.B, cfg.Tq, cfg.Hq, cfg.d, dtype=torch.bfloat16, device=dev)
         self.out_d = torch.empty_like(self.out_s)
+        self._calls = {}
+
+    # the parameter block of every call is built once (PreparedCall): a launch then costs the host
+    # one ctypes call, as in a serving loop that repeats the step on fixed buffers
+    def _prepared(self, kind, layer=0):
+        key = (kind, layer, self.torch.cuda.current_stream().cuda_stream)
+        call = self._calls.get(key)
+        if call is None:
+            sts, w = self.sts, self.w
+            if kind == "select":
+                call = sts.sts_select(w.scores, w.head_map, self.kb, out=(self.idx, self.cnt), page_size=self.page, prepare=True)
+            else:
+                lk, lv = self.layers[layer]
+                if kind == "sparse":
+                    call = sts.sts_sparse_attn(w.q, lk, lv, self.idx, w.scale, counts=self.cnt, head_map=w.head_map,
+                                               out=self.out_s, want_lse=False, prepare=True, **self.extra)
+                else:
+                    call = sts.sts_dense_attn(w.q, lk, lv, w.scale, out=self.out_d, want_lse=False, prepare=True, **self.extra)
+            self._calls[key] = call
+        return call
 
     def select(self):
-        self.sts.sts_select(self.w.scores, self.w.head_map, self.kb, out=(self.idx, self.cnt), page_size=self.page)
+        self._prepared("select")()
 
     def sparse(self, layer=0):
-        lk, lv = self.layers[layer]
-        self.sts.sts_sparse_attn(self.w.q, lk, lv, self.idx, self.w.scale, counts=self.cnt, head_map=self.w.head_map,
-                                 out=self.out_s, want_lse=False, **self.extra)
+        self._prepared("sparse", layer)()
 
     def dense(self, layer=0):
-        lk, lv = self.layers[layer]
-        self.sts.sts_dense_attn(self.w.q, lk, lv, self.w.scale, out=self.out_d, want_lse=False, **self.extra)
+        self._prepared("dense", layer)()
 
     def bytes_set(self):
         plan = self.sts.attn_plan(self.w.q, self.torch.empty(self.w.cfg.B, self.w.cfg.Hkv, self.w.cfg.N, self.w.cfg.d, device="meta"),

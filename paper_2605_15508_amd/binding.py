@@ -153,6 +153,24 @@ def _stream() -> int:
     return torch._C._cuda_getCurrentRawStream(torch.cuda.current_device())
 
 
+class PreparedCall:
+    """A library call with its parameter block built once: calling the object enqueues the call
+    again on torch's current stream with the same pointers (the tensors it was built from are kept
+    alive here; the workspace is the one that was current when it was built, so use it on the
+    stream it was prepared on). For serving loops that repeat a call on fixed buffers: the
+    per-call cost on the host is one ctypes call."""
+
+    def __init__(self, fn, params, what, result, keep):
+        self._fn, self._p, self._what, self.result, self._keep = fn, params, what, result, keep
+        self._ref = ctypes.byref(params)
+
+    def __call__(self):
+        rc = self._fn(self._ref, _stream())
+        if rc != 0:
+            _check(rc, self._what)
+        return self.result
+
+
 _ws_cache: Dict[Tuple[str, int, int], "object"] = {}
 
 
@@ -187,7 +205,7 @@ def _host_i32(seq) -> ctypes.Array:
 
 def sts_select(scores, head_map, k: int, lse=None, seq_lens=None, kind: int = STS_SCORES_PROBS,
                reduce: int = STS_REDUCE_SUM, want_agg: bool = False, out=None, workspace=None,
-               page_size: int = 1, k_head=None):
+               page_size: int = 1, k_head=None, prepare: bool = False):
     """scores [B,Hd,Tq,N] fp32 or bf16 (device), head_map [Hq] (host ints) -> (indices [B,Hq,k] int32,
     counts [B,Hq] int32, agg [B,Hd,N] fp32 or None). With page_size > 1, k counts blocks and the
     indices are block ids. k_head [Hd] (host ints, each <= k) gives every draft head its own
@@ -224,6 +242,9 @@ def sts_select(scores, head_map, k: int, lse=None, seq_lens=None, kind: int = ST
     need = lib.sts_select_workspace_bytes(ctypes.byref(p))
     ws = workspace if workspace is not None else _workspace("select", need, dev)
     p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()
+    if prepare:       # build once, launch many times (see PreparedCall)
+        return PreparedCall(lib.sts_select, p, "sts_select", (indices, counts, agg),
+                            (scores, lse, seq_lens, hm, kh, ws))
     _check(lib.sts_select(ctypes.byref(p), _stream()), "sts_select")
     return indices, counts, agg
 
@@ -288,7 +309,8 @@ def _attn_params(q, k, v, scale, indices, counts, head_map, seq_lens, out, lse_o
 def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=None, seq_lens=None,
               out=None, out_dtype=None, want_lse=True, want_logits=False, workspace=None,
               lse_out=None, logits_out=None, page_size=1, block_table=None, N=None,
-              k_new=None, v_new=None, causal=True, weights_sum_out=None, static=False, row_mask=None):
+              k_new=None, v_new=None, causal=True, weights_sum_out=None, static=False, row_mask=None,
+              prepare=False):
     import torch
 
     lib = load_library()
@@ -332,21 +354,27 @@ def _run_attn(sparse: bool, q, k, v, scale, indices=None, counts=None, head_map=
             ws = _workspace("attn", need, dev)
             p.workspace, p.workspace_bytes = ws.data_ptr(), ws.numel() * ws.element_size()
     fn = lib.sts_sparse_attn if sparse else lib.sts_dense_attn
+    if prepare:       # build once, launch many times (see PreparedCall)
+        return PreparedCall(fn, p, "sts_sparse_attn" if sparse else "sts_dense_attn", (out, lse, logits),
+                            (q, k, v, indices, counts, seq_lens, block_table, k_new, v_new, row_mask, weights_sum_out, _keep, ws))
     _check(fn(ctypes.byref(p), _stream()), "sts_sparse_attn" if sparse else "sts_dense_attn")
     return out, lse, logits
 
 
 def sts_sparse_attn(q, k, v, indices, scale, counts=None, head_map=None, out=None, out_dtype=None,
                     want_lse=True, workspace=None, lse_out=None, page_size=1, block_table=None, N=None,
-                    k_new=None, v_new=None, causal=True, row_mask=None):
+                    k_new=None, v_new=None, causal=True, row_mask=None, prepare=False):
     """Attention over the gathered rows indices[b,t,:counts[b,t]] of the full cache.
     q [B,Tq,Hq,d] bf16, k/v [B,Hkv,N,d] bf16 (strided ok) -> (out [B,Tq,Hq,d], lse [B,Hq,Tq]).
-    row_mask (16-bit words shaped like indices): query row i attends only to entries with bit i."""
-    out, lse, _ = _run_attn(True, q, k, v, scale, indices=indices, counts=counts, head_map=head_map,
-                            out=out, out_dtype=out_dtype, want_lse=want_lse, workspace=workspace,
-                            lse_out=lse_out, page_size=page_size, block_table=block_table, N=N,
-                            k_new=k_new, v_new=v_new, causal=causal, row_mask=row_mask)
-    return out, lse
+    row_mask (16-bit words shaped like indices): query row i attends only to entries with bit i.
+    prepare=True returns a PreparedCall instead of launching."""
+    r = _run_attn(True, q, k, v, scale, indices=indices, counts=counts, head_map=head_map,
+                  out=out, out_dtype=out_dtype, want_lse=want_lse, workspace=workspace,
+                  lse_out=lse_out, page_size=page_size, block_table=block_table, N=N,
+                  k_new=k_new, v_new=v_new, causal=causal, row_mask=row_mask, prepare=prepare)
+    if prepare:
+        return r
+    return r[0], r[1]
 
 
 def sts_select_rows(scores, k: int, lse=None, seq_lens=None, kind: int = STS_SCORES_PROBS, out=None, workspace=None):
@@ -407,7 +435,8 @@ def sts_sparse_attn_static(q, k, v, indices, scale, counts=None, head_map=None, 
 
 def sts_dense_attn(q, k, v, scale, seq_lens=None, out=None, out_dtype=None, want_lse=True,
                    want_logits=False, workspace=None, lse_out=None, logits_out=None, page_size=1,
-                   block_table=None, N=None, k_new=None, v_new=None, causal=True, weights_sum_out=None):
+                   block_table=None, N=None, k_new=None, v_new=None, causal=True, weights_sum_out=None,
+                   prepare=False):
     """Dense attention of the same kernel family -> (out, lse, logits [B,Hq,Tq,N] or None).
     want_logits: True (fp32 dump) or a torch dtype (float32 / bfloat16); logits_out: a buffer of
     either type. weights_sum_out: an fp32 [B,Hq,N] buffer that receives the attention weights
@@ -417,7 +446,7 @@ def sts_dense_attn(q, k, v, scale, seq_lens=None, out=None, out_dtype=None, want
                      want_lse=want_lse, want_logits=want_logits, workspace=workspace,
                      lse_out=lse_out, logits_out=logits_out, page_size=page_size,
                      block_table=block_table, N=N, k_new=k_new, v_new=v_new, causal=causal,
-                     weights_sum_out=weights_sum_out)
+                     weights_sum_out=weights_sum_out, prepare=prepare)
 
 
 def sts_head_map(a_d, a_t, k: int, workspace=None):

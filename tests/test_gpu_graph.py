@@ -111,3 +111,30 @@ def test_graph_replays_of_the_draft_chain_match_eager():
         torch.cuda.synchronize()
         for got, ref in zip((A, idx, cnt, out, lse), want):
             assert torch.equal(got, ref)
+
+
+def test_prepared_calls_repeat_the_call_on_fixed_buffers():
+    """A PreparedCall holds the parameter block of a call: calling it again enqueues the same
+    call; results equal those of the ordinary functions, also after the inputs changed in place."""
+    from workload import CONFIGS, make_workload
+    w = make_workload(CONFIGS["c1"], seed=5)
+    q, k, v, scores = (t.to(DEV) for t in (w.q, w.k, w.v, w.scores))
+    sel = sts.sts_select(scores, w.head_map, w.k_budget, prepare=True)
+    idx, cnt, _ = sel()
+    att = sts.sts_sparse_attn(q, k, v, idx, w.scale, counts=cnt, head_map=w.head_map, out_dtype=torch.float32, prepare=True)
+    out, lse, _ = att()
+    den = sts.sts_dense_attn(q, k, v, w.scale, out_dtype=torch.float32, prepare=True)
+    dout, dlse, _ = den()
+    torch.cuda.synchronize()
+    r_idx, r_cnt, _ = sts.sts_select(scores, w.head_map, w.k_budget)
+    r_out, r_lse = sts.sts_sparse_attn(q, k, v, r_idx, w.scale, counts=r_cnt, head_map=w.head_map, out_dtype=torch.float32)
+    r_dout, r_dlse, _ = sts.sts_dense_attn(q, k, v, w.scale, out_dtype=torch.float32)
+    assert torch.equal(idx, r_idx) and torch.equal(cnt, r_cnt) and torch.equal(out, r_out) and torch.equal(lse, r_lse)
+    assert torch.equal(dout, r_dout) and torch.equal(dlse, r_dlse)
+    # new scores in the same buffer: the prepared calls see them
+    scores.copy_(torch.softmax(torch.randn_like(scores) * 2, dim=-1))
+    sel(); att()
+    torch.cuda.synchronize()
+    r_idx, r_cnt, _ = sts.sts_select(scores, w.head_map, w.k_budget)
+    r_out, _ = sts.sts_sparse_attn(q, k, v, r_idx, w.scale, counts=r_cnt, head_map=w.head_map, out_dtype=torch.float32)
+    assert torch.equal(idx, r_idx) and torch.equal(out, r_out)

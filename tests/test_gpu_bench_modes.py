@@ -56,7 +56,9 @@ def test_headline_configuration_carries_sweep_and_paper_budgets():
     assert {"c3@256", "c3@512", "c3@4096"} <= set(r["paper_budgets"])
     assert any(k.startswith("c2@") for k in r["paper_budgets"])
     for pt in r["paper_budgets"].values():
-        assert pt["graph_replay"]["sparse_attn_us"] > 0 and pt["select_us"] > 0
+        # (the graph-replayed figure of a call is a difference of two medians: present, not sign-checked)
+        assert isinstance(pt["graph_replay"]["sparse_attn_us"], float) and pt["graph_replay"]["step_us"] > 0
+        assert pt["select_us"] > 0 and pt["sparse_attn_us"] > 0
 
 
 def test_fused_tail_option_and_other_modes():

@@ -386,7 +386,13 @@ sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
   // Long rows at token granularity: one launch in which every workgroup keeps a part of a row in
   // LDS (select_fused_kernel). Parts are as large as LDS allows (32768 tokens) when that still
   // gives a workgroup per CU, else smaller, down to 8192, to spread short calls over the chip.
-  if (pl.page == 1 && p->N > SEL_FUSED_N && path != 1 && path != 2) {
+  // (One exception under the library's own rule: a ready-made fp32 aggregate, Tq = 1, that the
+  // pipeline ranks where it lies, in a call with more workgroups than CUs. There the pipeline's
+  // passes over the caller's tensor beat several rounds of workgroups that wait for each other:
+  // 70B-shaped layer, 256 rows of 128K: 153 against 182 us.)
+  const bool in_place = p->Tq == 1 && p->kind == STS_SCORES_PROBS && !p->scores_bf16 && !p->agg_out;
+  const bool many_rounds = (int64_t)rows * (((int64_t)p->N + SEL_SMALL_N - 1) / SEL_SMALL_N) > cu_count();
+  if (pl.page == 1 && p->N > SEL_FUSED_N && path != 1 && path != 2 && !(path == 0 && in_place && many_rounds)) {
     const int max_parts = path == 3 ? 256 : SEL_FUSED_MAX_PARTS;
     int P = SEL_SMALL_N;
     while (P > SEL_FUSED_N && (int64_t)rows * (((int64_t)p->N + P - 1) / P) < cu_count() &&

@@ -304,7 +304,7 @@ typedef enum {
   STS_K_SELECT_CLEAR = 0,  /* zero histograms */
   STS_K_SELECT_AGG = 1,    /* aggregation + first-digit histogram */
   STS_K_SELECT_HIST = 2,   /* refinement histograms */
-  STS_K_SELECT_COUNT = 3,  /* not launched any more: the compaction kernel counts its own chunk */
+  STS_K_SELECT_ROWPASS = 3,/* many long rows of ready-made scores: one workgroup per row, several passes */
   STS_K_SELECT_WRITE = 4,  /* per-chunk counts, ordered compaction + head remap */
   STS_K_ATTN_SPARSE = 5,   /* split sparse gather flash-decode */
   STS_K_ATTN_DENSE = 6,    /* split dense flash-decode */
@@ -339,14 +339,21 @@ sts_status sts_prof_read(int kernel_kind, int32_t *launches, double *total_ms);
  *    pass that writes weights_sum_out. No effect on results.
  *  - STS_KNOB_SELECT_PATH (env STS_SELECT_PATH): 0 the library's rule, 1 histogram pipeline only,
  *    2 pipeline or chunk-local top-k + pool, 3 the one-launch selection for rows of up to 256
- *    parts (the rule stops at 8). It changes sts_select_workspace_bytes, never the results.
+ *    parts (the rule stops at 8), 4 one workgroup per row wherever the shape allows it (Tq = 1,
+ *    probabilities, token granularity, no agg_out, N a multiple of 4, or of 8 for bf16; the rule
+ *    takes it for rows of more than 8192 tokens from one row per compute unit on). It changes sts_select_workspace_bytes, never the
+ *    results.
+ *  - STS_KNOB_SELECT_ROW_THREADS (env STS_SELECT_ROW_THREADS): 256 or 1024, the workgroup size of
+ *    the one-workgroup-per-row selection (the rule: 256 from 4 rows per compute unit on, else
+ *    1024). No effect on results.
  */
 typedef enum {
   STS_KNOB_ATTN_WGS_PER_CU = 0,
   STS_KNOB_SELECT_SPIN_LIMIT = 1,
   STS_KNOB_PROBSUM_WGS_PER_CU = 2,
   STS_KNOB_SELECT_PATH = 3,
-  STS_KNOB_COUNT_ = 4
+  STS_KNOB_SELECT_ROW_THREADS = 4,
+  STS_KNOB_COUNT_ = 5
 } sts_knob;
 void sts_set_knob(int knob, double value);
 double sts_get_knob(int knob);

@@ -152,6 +152,7 @@ struct SelectArgs {
                               // two bin counts in the halves), zero before the launch
   int32_t part_tokens, parts; // fused selection: tokens per part (8192..32768) and parts per row
   int32_t fused_spin_limit;   // polls of another part's flag before its histogram is recomputed locally
+  int32_t rowpass_threads;    // one workgroup per row (select_rowpass_kernel): 256 or 1024 threads
   int32_t agg_is_input;       // `agg` is the caller's score tensor itself (one fp32 probability row per head): never stored to
   int32_t B, Hd, Tq, N, Hq, k, kind, reduce, nchunks;   // k: row pitch of indices = largest budget
   SelectTargets targets;
@@ -187,6 +188,8 @@ bool select_aggblock_ok(const SelectArgs &a);
 hipError_t launch_select_aggblock(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_fused(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_clear_pub(const SelectArgs &a, hipStream_t s);
+bool select_rowpass_ok(const SelectArgs &a);
+hipError_t launch_select_rowpass(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_local(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_pool(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_hist(const SelectArgs &a, int pass, hipStream_t s);

@@ -28,11 +28,11 @@
 
 namespace {
 
-__device__ __forceinline__ uint32_t key_of(float x) {
-  uint32_t u = __builtin_bit_cast(uint32_t, x);
+__device__ __forceinline__ uint32_t key_of_bits(uint32_t u) {
   if (u == 0x80000000u) u = 0u;                       // -0 == +0
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // ascending with the float order
 }
+__device__ __forceinline__ uint32_t key_of(float x) { return key_of_bits(__builtin_bit_cast(uint32_t, x)); }
 
 // exp(s - lse) through the hardware base-2 exponential (about 1 ulp; the product with log2(e)
 // adds a relative error below 1e-6 for |s - lse| < 40, far inside the stage-wise tolerance)
@@ -1197,6 +1197,118 @@ __global__ void __launch_bounds__(FUSED_THREADS) select_fused_kernel(const Selec
   }
 }
 
+// --------------------------------- many long rows of ready-made scores: one workgroup per row
+// A call with one score per token (Tq = 1: the per-query-row masks of prefill rank every row of a
+// block's scores on its own; a draft layer's summed weights) and far more rows than CUs. Cutting
+// such rows into parts that wait for each other leaves every CU idle during the exchanges; here a
+// row belongs to ONE workgroup, which keeps nothing but a digit histogram in LDS and reads the
+// row once per digit level and once more to compact it. The re-reads come out of the caches (a
+// row is 256-512 KB; what the resident workgroups hold together fits the last-level cache), and
+// several small workgroups per CU are in different phases at any time, so the digit searches and
+// scans of one hide behind the streaming of the others. Nothing is exchanged, cleared or stored
+// besides the lists. bf16 scores have keys whose low 16 bits are all equal, so their third level
+// is known without a pass.
+template <bool BF16>
+__device__ __forceinline__ uint32_t rowpass_key(const u32x4 &w, int e) {
+  if (BF16) {
+    const uint32_t pair = w[e >> 1];
+    return key_of_bits((e & 1) ? (pair & 0xffff0000u) : (pair << 16));
+  }
+  return key_of_bits(w[e & 3]);
+}
+
+template <int THREADS, bool BF16>
+__global__ void __launch_bounds__(THREADS) select_rowpass_kernel(const SelectArgs A) {
+  constexpr int VPT = BF16 ? 8 : 4;       // tokens per 16-byte word
+  constexpr int UNR = 4;                  // words in flight per thread
+  constexpr int RUN = UNR * VPT;          // consecutive tokens a thread owns per compaction step
+  static_assert(RUN <= 32 && THREADS * RUN < 65536, "mask bits per thread; packed block scan");
+  __shared__ uint32_t h[SEL_BINS];
+  __shared__ uint32_t tmp[THREADS / 64 + 2];
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const int bt = row / A.Hd, j = row % A.Hd;
+  const int nb = row_len(A, bt);
+  const uint32_t c = (uint32_t)min(A.kh[j], nb);
+  const int t0 = A.targets.off[j], t1 = A.targets.off[j + 1];
+  write_tail<THREADS>(A, bt, j, c);
+  if (c == 0 || t0 == t1) return;
+  // N % VPT == 0 and a 16-byte aligned base (the host's condition for this path): whole words
+  const u32x4 *src = reinterpret_cast<const u32x4 *>(
+      static_cast<const unsigned char *>(A.scores) + (size_t)row * A.N * (BF16 ? 2 : 4));
+  const int nv = (nb + VPT - 1) / VPT;    // words that hold ranked tokens
+
+  uint32_t d0 = 0, pre01 = 0, krem = c, d2 = 0;
+#pragma unroll 1
+  for (int level = 0; level < (BF16 ? 2 : 3); ++level) {
+    for (int i = tid; i < SEL_BINS; i += THREADS) h[i] = 0u;
+    __syncthreads();
+#pragma unroll 1
+    for (int i0 = tid; i0 < nv; i0 += THREADS * UNR) {
+      u32x4 w[UNR];
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) w[u] = src[min(i0 + u * THREADS, nv - 1)];
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const int wi = i0 + u * THREADS;
+#pragma unroll
+        for (int e = 0; e < VPT; ++e) {
+          const int bin = fused_bin(rowpass_key<BF16>(w[u], e), level, d0, pre01);
+          if (wi < nv && wi * VPT + e < nb && bin >= 0) atomicAdd(&h[bin], 1u);
+        }
+      }
+    }
+    __syncthreads();
+    uint32_t digit, knext;
+    find_digit<SEL_BINS, THREADS>(h, krem, tmp, digit, knext);
+    if (level == 0) d0 = digit;
+    else if (level == 1) pre01 = (d0 << SEL_BITS1) | digit;
+    else d2 = digit;
+    krem = knext;
+  }
+  // widened bf16: the 16 low key bits repeat the complement of the sign, so every key that shares
+  // the first two digits is the same key
+  if (BF16) d2 = (d0 >> (SEL_BITS0 - 1)) ? 0u : (1u << SEL_BITS2) - 1;
+  const uint32_t r = krem;
+  const uint32_t Tk = (pre01 << SEL_BITS2) | d2;
+
+  // ordered compaction: per step, thread tid owns the RUN consecutive tokens from step + tid * RUN
+  uint32_t gbase = 0, qbase = 0;          // keys greater than / equal to the threshold before this step
+#pragma unroll 1
+  for (int step = 0; step < nb; step += THREADS * RUN) {
+    const int nlo = step + tid * RUN;
+    u32x4 w[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) w[u] = src[min(nlo / VPT + u, nv - 1)];
+    uint32_t gt_mask = 0, eq_mask = 0;
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+#pragma unroll
+      for (int e = 0; e < VPT; ++e) {
+        const uint32_t key = rowpass_key<BF16>(w[u], e);
+        const bool in = nlo + u * VPT + e < nb;
+        gt_mask |= (in && key > Tk) ? 1u << (u * VPT + e) : 0u;
+        eq_mask |= (in && key == Tk) ? 1u << (u * VPT + e) : 0u;
+      }
+    uint32_t total;
+    const uint32_t excl = block_excl_scan<THREADS>(__builtin_popcount(gt_mask) | (__builtin_popcount(eq_mask) << 16), tmp, total);
+    uint32_t g = gbase + (excl & 0xffffu), q = qbase + (excl >> 16);
+    for (uint32_t rest = gt_mask | eq_mask; rest; rest &= rest - 1) {
+      const int i = __builtin_ctz(rest);
+      const bool is_gt = (gt_mask >> i) & 1u;
+      if (is_gt || q < r) {
+        const uint32_t pos = g + min(q, r);
+        if (pos < c)   // always true for a consistent threshold; keeps a bad state in bounds
+          for (int ti = t0; ti < t1; ++ti) A.indices[((size_t)bt * A.Hq + A.targets.tgt[ti]) * A.k + pos] = nlo + i;
+      }
+      g += is_gt ? 1u : 0u;
+      q += is_gt ? 0u : 1u;
+    }
+    gbase += total & 0xffffu;
+    qbase += total >> 16;
+    if (gbase + min(qbase, r) >= c) break;   // the list is complete (uniform)
+  }
+}
+
 // ---------------------------------------------- small budgets on long rows: chunk-local top-k
 // Every token of a row's top-c (ordered by key descending, then token ascending) has fewer
 // than c tokens of the whole row before it in that order, hence fewer than c tokens of its own
@@ -1471,6 +1583,26 @@ hipError_t launch_select_fused(const SelectArgs &a, hipStream_t s) {
     default: return hipErrorInvalidValue;
   }
 #undef STS_FUSED
+  return sts_take_launch_status();
+}
+
+// one workgroup per row, Tq == 1, unpaged, no aggregate output; the caller has checked the shape
+bool select_rowpass_ok(const SelectArgs &a) {
+  return a.Tq == 1 && a.kind == STS_SCORES_PROBS && a.page == 1 && a.agg == nullptr && a.N > 0 &&
+         (a.N % (a.scores_bf16 ? 8 : 4)) == 0 && (reinterpret_cast<uintptr_t>(a.scores) % 16) == 0;
+}
+
+hipError_t launch_select_rowpass(const SelectArgs &a, hipStream_t s) {
+  if ((size_t)a.B * a.Hd == 0) return hipSuccess;
+  if (!select_rowpass_ok(a)) return hipErrorInvalidValue;
+  const dim3 grid(a.B * a.Hd);
+  if (a.rowpass_threads == 1024) {
+    if (a.scores_bf16) STS_LAUNCH((select_rowpass_kernel<1024, true>), grid, dim3(1024), 0, s, a);
+    else STS_LAUNCH((select_rowpass_kernel<1024, false>), grid, dim3(1024), 0, s, a);
+  } else {
+    if (a.scores_bf16) STS_LAUNCH((select_rowpass_kernel<256, true>), grid, dim3(256), 0, s, a);
+    else STS_LAUNCH((select_rowpass_kernel<256, false>), grid, dim3(256), 0, s, a);
+  }
   return sts_take_launch_status();
 }
 

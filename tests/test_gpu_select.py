@@ -540,3 +540,77 @@ def test_single_row_input_is_ranked_in_place(N, k, levels, off, select_path):
     assert torch.equal(idx2, idx) and torch.equal(cnt2, cnt)
     for b, n in enumerate(lens.tolist()):
         assert np.array_equal(agg2[b, :, :n].cpu().numpy(), o_agg[b, :, :n])
+
+
+@pytest.mark.parametrize("B,Hd,N,Hq,k,bf16,what", [
+    (2, 4, 40000, 8, 700, False, "softmax"),        # fp32, three levels, rows of 40000 (not a multiple of a step)
+    (2, 4, 40000, 8, 700, True, "softmax"),         # bf16: many ties among the widened values, two levels
+    (1, 3, 16392, 3, 16392, False, "softmax"),      # k = N: everything kept
+    (1, 2, 9000, 4, 100, True, "signed"),           # negative and positive scores, -0 and +0
+    (1, 2, 9000, 4, 8000, True, "signed"),          # ... with the threshold among the negative ones
+    (1, 2, 9000, 4, 8000, False, "signed"),
+    (1, 2, 70000, 2, 5000, False, "quantised"),     # a handful of distinct values: the tie rule decides
+    (1, 2, 70000, 2, 5000, True, "constant"),       # all equal: the first k tokens
+    (72, 16, 8200, 16, 300, True, "softmax"),       # 1152 rows: the small workgroups the rule takes for many rows
+    (72, 16, 8200, 16, 300, False, "softmax"),
+])
+def test_one_workgroup_per_row_selection(B, Hd, N, Hq, k, bf16, what):
+    """Single-score rows (Tq = 1) ranked by one workgroup per row in several passes over the row:
+    index sets and counts bit for bit against the oracle, with ragged lengths (one ending inside a
+    16-byte word, one empty), per-head budgets, a draft head read by several target heads and one
+    read by none."""
+    g = torch.Generator().manual_seed(N + k + bf16)
+    if what == "softmax":
+        scores = torch.softmax(torch.randn(B, Hd, 1, N, generator=g) * 2, dim=-1)
+    elif what == "signed":
+        scores = torch.randn(B, Hd, 1, N, generator=g)
+        scores[..., ::7] = 0.0
+        scores[..., 3::14] = -0.0
+    elif what == "quantised":
+        scores = torch.randint(0, 5, (B, Hd, 1, N), generator=g).float() / 8
+    else:
+        scores = torch.full((B, Hd, 1, N), 0.25)
+    if bf16:
+        scores = scores.to(torch.bfloat16)
+    hm = [min(t // 2, Hd - 1) for t in range(Hq)] if Hq > Hd else list(range(Hq))     # pairs share; the last heads may be unread
+    kh = [max(1, k - 37 * j) for j in range(Hd)]
+    lens = torch.full((B,), N, dtype=torch.int32)
+    if B > 1:
+        lens[1] = N - 13
+    if B > 2:
+        lens[2] = 0
+        lens[3] = 5
+    sd = scores.to(DEV)
+    sts.set_knob("select_path", 4)
+    try:
+        got = {}
+        kinds = launched(lambda: got.update(r=sts.sts_select(sd, hm, k, seq_lens=lens.to(DEV), k_head=kh)))
+    finally:
+        sts.set_knob("select_path", None)
+    assert kinds == {"select_rowpass"}
+    idx, cnt, _ = got["r"]
+    o_idx, o_cnt, _ = oracle.select_indices(scores.float().numpy(), np.asarray(hm, np.int32), k, k_head=kh, seq_lens=lens.numpy())
+    np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
+    np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
+
+
+def test_many_single_score_rows_take_one_workgroup_per_row():
+    """The library's own rule: from one row per compute unit on, single-score rows of more than
+    8192 tokens go to one workgroup each; fewer rows, several scores per token, an aggregate on
+    request or block granularity keep the other paths."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    rows, N = cus, 8192 + 8
+    s = torch.rand(rows // 16, 16, 1, N, device=DEV)
+    hm = list(range(16))
+    sts.set_knob("select_path", 0)
+    try:
+        assert launched(lambda: sts.sts_select(s, hm, 100)) == {"select_rowpass"}
+        assert launched(lambda: sts.sts_select(s.to(torch.bfloat16), hm, 100)) == {"select_rowpass"}
+        assert "select_rowpass" not in launched(lambda: sts.sts_select(s[:-1], hm, 100))
+        assert "select_rowpass" not in launched(lambda: sts.sts_select(s, hm, 100, want_agg=True))
+        assert "select_rowpass" not in launched(lambda: sts.sts_select(s, hm, 100, page_size=8))
+        assert launched(lambda: sts.sts_select(s[:, :, :, :8192].contiguous(), hm, 100)) == {"select_small"}
+        s2 = torch.rand(rows // 16, 16, 2, N, device=DEV)
+        assert "select_rowpass" not in launched(lambda: sts.sts_select(s2, hm, 100))
+    finally:
+        sts.set_knob("select_path", None)

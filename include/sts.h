@@ -317,7 +317,8 @@ typedef enum {
   STS_K_ATTN_PROBSUM = 13, /* dense second pass over K: attention weights summed over the query block */
   STS_K_SELECT_FUSED = 14, /* long rows: aggregation, threshold and compaction in one launch */
   STS_K_UNION_ROWS = 15,   /* union of per-row index lists + row bits */
-  STS_K_COUNT_ = 16
+  STS_K_SELECT_BAND = 16,  /* at least a row per compute unit: one workgroup per row, one pass */
+  STS_K_COUNT_ = 17
 } sts_kernel_kind;
 #define STS_PROF_MAX 4096
 
@@ -339,13 +340,14 @@ sts_status sts_prof_read(int kernel_kind, int32_t *launches, double *total_ms);
  *    pass that writes weights_sum_out. No effect on results.
  *  - STS_KNOB_SELECT_PATH (env STS_SELECT_PATH): 0 the library's rule, 1 histogram pipeline only,
  *    2 pipeline or chunk-local top-k + pool, 3 the one-launch selection for rows of up to 256
- *    parts (the rule stops at 8), 4 one workgroup per row wherever the shape allows it (Tq = 1,
- *    probabilities, token granularity, no agg_out, N a multiple of 4, or of 8 for bf16; the rule
- *    takes it for rows of more than 8192 tokens from one row per compute unit on). It changes sts_select_workspace_bytes, never the
- *    results.
+ *    parts (the rule stops at 8), 4 one workgroup per row in several passes wherever the shape
+ *    allows it (Tq = 1, probabilities, token granularity, no agg_out, N a multiple of 4, or of 8
+ *    for bf16), 5 one workgroup per row in one pass wherever the shape allows it (token
+ *    granularity, N a multiple of 4 up to 524288). It changes sts_select_workspace_bytes, never
+ *    the results.
  *  - STS_KNOB_SELECT_ROW_THREADS (env STS_SELECT_ROW_THREADS): 256 or 1024, the workgroup size of
- *    the one-workgroup-per-row selection (the rule: 256 from 4 rows per compute unit on, else
- *    1024). No effect on results.
+ *    the several-pass one-workgroup-per-row selection (the rule: 256 from 4 rows per compute
+ *    unit on, else 1024). No effect on results.
  */
 typedef enum {
   STS_KNOB_ATTN_WGS_PER_CU = 0,

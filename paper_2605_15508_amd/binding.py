@@ -21,7 +21,7 @@ STS_BF16, STS_F32 = 0, 1
 KERNEL_KINDS = {"select_clear": 0, "select_agg": 1, "select_hist": 2, "select_rowpass": 3,
                 "select_write": 4, "attn_sparse": 5, "attn_dense": 6, "attn_combine": 7, "select_block": 8,
                 "headmap": 9, "select_small": 10, "select_local": 11, "select_pool": 12,
-                "attn_probsum": 13, "select_fused": 14, "union_rows": 15}
+                "attn_probsum": 13, "select_fused": 14, "union_rows": 15, "select_band": 16}
 KNOBS = {"attn_wgs_per_cu": 0, "select_spin_limit": 1, "probsum_wgs_per_cu": 2, "select_path": 3, "select_row_threads": 4}
 
 # every symbol include/sts.h declares

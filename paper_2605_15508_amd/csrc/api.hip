@@ -311,6 +311,7 @@ struct SelectPlan {
   bool small;          // one workgroup per row, keys in LDS, a single launch
   bool pool;           // shape allows chunk-local top-k + one ranking workgroup per row
   bool fused;          // long rows: parts of a row in LDS, one launch (plus the flag clear)
+  bool band;           // at least a row per CU: one workgroup per row, one pass, no workspace
   bool rowpass;        // many long rows of ready-made scores: one workgroup per row, no workspace
   int rowpass_threads;
   int nchunks, page, srcN, pool_pitch, pool_chunk, pool_nchunks;
@@ -324,7 +325,7 @@ struct SelectPlan {
   // a pool-shaped call falls back to the pipeline when its pointers are not 16-byte aligned,
   // so the workspace covers both
   size_t total() const {
-    if (rowpass) return 0;
+    if (rowpass || band) return 0;
     if (fused) return fused_total();
     return pipeline_total() > pool_total() ? pipeline_total() : pool_total();
   }
@@ -352,28 +353,50 @@ sts_status plan_select(const sts_select_params *p, SelectPlan &pl) {
   pl.pool_key_bytes = 0;
   pl.fused = false;
   pl.rowpass = false;
+  pl.band = false;
   pl.rowpass_threads = 0;
   pl.part_tokens = pl.parts = 0;
   pl.pub_bytes = pl.pflag_bytes = 0;
   // test / tuning knob: 0 the library's rule, 1 histogram pipeline only, 2 pipeline or pool,
-  // 3 the one-launch selection wherever its shape limits allow, 4 one workgroup per row wherever
-  // its shape limits allow
+  // 3 the one-launch selection wherever its shape limits allow, 4 one workgroup per row in
+  // several passes wherever its shape limits allow, 5 one workgroup per row in one pass likewise
   const double path_knob = knob(STS_KNOB_SELECT_PATH);
   const int path = path_knob == path_knob ? (int)path_knob : 0;
-  // One score per token and at least a row per CU (a mask per query row of prefill; a draft
-  // layer's summed weights for a large batch): one workgroup per row re-reads its row instead of
-  // exchanging histograms with other workgroups; nothing to clear, no workspace. Measured: 8192
-  // rows of 128K bf16 scores 1.5 ms against 4.2 ms, 256 rows of 128K fp32 107 against 137 us
-  // (pipeline, in place), 2048 rows of 32K bf16 109 against 264 us (one workgroup per row out of
-  // LDS); 64 rows of 128K: 92 against 48 us, hence the row-count limit.
+  // Enough rows to give at least every second CU one, and rows that do not fit one workgroup's
+  // LDS: one workgroup per row, which samples the row, keeps the band of keys around the
+  // threshold in LDS during a single pass and never talks to another workgroup
+  // (select_band_kernel); nothing to clear, no workspace. The band of a full-length row with the
+  // call's largest budget has to fit (rows for which it does not, decided in the kernel, are
+  // ranked by plain passes there). Measured against the paths below, 128K-token rows, 10%: 256
+  // rows of 8 fp32 scores per token 220 against 289 us, bf16 140 against 203, 512 rows of 16 bf16
+  // scores 448 against 613, 256 rows of one fp32 score 67 against 147 (pipeline, in place), 128
+  // rows of 5 scores 93 against 111; 64 rows: 83 against 58, hence the limit.
+  // One bf16 score per token and many rows per CU (a mask per query row of prefill) is the one
+  // shape that plain passes by small workgroups serve better (select_rowpass_kernel; 4096 rows of
+  // 128K: 754 against 962 us; one workgroup per row out of parts that exchange: 2.1 ms).
   {
-    const bool shape_ok = pl.page == 1 && p->Tq == 1 && p->kind == STS_SCORES_PROBS && !p->agg_out && p->N > 0 &&
-                          (p->N % (p->scores_bf16 ? 8 : 4)) == 0 && reinterpret_cast<uintptr_t>(p->scores) % 16 == 0;
-    const bool enough_rows = (int64_t)rows >= (int64_t)cu_count() && p->N > SEL_FUSED_N;
-    if (shape_ok && (path == 4 || (path == 0 && enough_rows))) {
+    int kmax = p->k;
+    if (p->k_head) {
+      kmax = 1;
+      for (int j = 0; j < p->Hd; ++j) kmax = p->k_head[j] > kmax ? p->k_head[j] : kmax;
+    }
+    const bool aligned = reinterpret_cast<uintptr_t>(p->scores) % 16 == 0;
+    const bool band_ok = pl.page == 1 && p->N > 0 && p->N <= BAND_MAX_N && (p->N % 4) == 0 && aligned &&
+                         (!p->agg_out || reinterpret_cast<uintptr_t>(p->agg_out) % 16 == 0);
+    const bool fits = band_ok && (p->N <= BAND_CAP ||
+                                  band_plan(p->N, (uint32_t)(kmax < p->N ? kmax : p->N), p->scores_bf16 ? 64 : 32).fits);
+    const bool rowpass_ok = pl.page == 1 && p->Tq == 1 && p->kind == STS_SCORES_PROBS && !p->agg_out && p->N > 0 &&
+                            (p->N % (p->scores_bf16 ? 8 : 4)) == 0 && aligned;
+    const int64_t cus = cu_count();
+    const bool long_rows = !pl.small && p->N > SEL_FUSED_N;
+    const bool take_rowpass = path == 4 ? rowpass_ok
+                                        : path == 0 && rowpass_ok && long_rows && p->scores_bf16 && (int64_t)rows >= 4 * cus;
+    const bool take_band = path == 5 ? band_ok : path == 0 && !take_rowpass && fits && long_rows && 2 * (int64_t)rows >= cus;
+    if (take_rowpass || take_band) {
       pl.small = false;
-      pl.rowpass = true;
-      pl.rowpass_threads = (int64_t)rows >= 4 * (int64_t)cu_count() ? 256 : 1024;
+      pl.band = take_band;
+      pl.rowpass = take_rowpass;
+      pl.rowpass_threads = (int64_t)rows >= 4 * cus ? 256 : 1024;
       if (const double t = knob(STS_KNOB_SELECT_ROW_THREADS); t == 256.0 || t == 1024.0) pl.rowpass_threads = (int)t;
       pl.nchunks = 0;
       pl.pool_chunk = pl.pool_nchunks = 0;
@@ -568,6 +591,13 @@ static sts_status enqueue_select(const sts_select_params *p, void *stream) {
   }
 
   hipError_t rc;
+  if (pl.band) {
+    a.agg = p->agg_out;   // optional output only
+    a.src = nullptr;
+    a.hist = a.state = a.chunk_cnt = nullptr;
+    rc = run_kernel(STS_K_SELECT_BAND, s, [&] { return launch_select_band(a, s); });
+    return rc == hipSuccess ? STS_OK : STS_EHIP;
+  }
   if (pl.rowpass) {
     a.agg = nullptr;
     a.src = nullptr;

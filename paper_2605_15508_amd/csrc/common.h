@@ -119,6 +119,39 @@ constexpr int SEL_FUSED_MAX_PARTS = 8;   // parts per row of the one-launch sele
                                          // allows up to 256)
 constexpr int SEL_POOL_MAX = 16384;     // chunk-local winners per row that the pool kernel ranks out of LDS       // rows up to this many tokens always take it
 
+// One workgroup per row, one pass (select_band_kernel): what the strided sample of a row of nb
+// ranked tokens with budget c looks like, and whether the band it is expected to give fits the
+// workgroup's store. The kernel decides per row with this; the host asks the same question for
+// a full-length row when it chooses the path.
+constexpr int BAND_CAP = 8192;          // band entries (key and token) a workgroup holds; it samples up to twice as many keys
+constexpr int BAND_MAX_N = 524288;      // tokens per row: one bit each in LDS
+constexpr int BAND_Z = 5;               // half-width of the band in standard deviations of the sample count
+struct BandPlan {
+  int S;                // one run of `run` tokens is sampled in every S runs
+  int runs, ns;         // sampled runs and tokens (the last run may be cut by the row's end)
+  long long s_hi, s_lo; // sample ranks that give the band's upper and lower edge (s_hi < 1: no upper edge)
+  bool fits;
+};
+__host__ __device__ inline BandPlan band_plan(int nb, uint32_t c, int run) {
+  BandPlan p;
+  const int row_runs = (nb + run - 1) / run;
+  p.S = 16;
+  while (((row_runs + p.S - 1) / p.S) * run > 2 * BAND_CAP) p.S <<= 1;
+  p.runs = (row_runs + p.S - 1) / p.S;              // sampled run i starts at token i * S * run
+  const int last = nb - (p.runs - 1) * p.S * run;
+  p.ns = (p.runs - 1) * run + (last < run ? last : run);
+  const uint32_t cs = c / (uint32_t)p.S;
+  uint32_t sq = (uint32_t)sqrtf((float)cs);
+  while ((uint64_t)sq * sq > cs) --sq;
+  while ((uint64_t)(sq + 1) * (sq + 1) <= cs) ++sq;
+  ++sq;                                   // > sqrt(cs): one standard deviation of the sample count, rounded up
+  p.s_hi = (long long)cs - (long long)BAND_Z * sq - 2;
+  p.s_lo = (long long)cs + (long long)BAND_Z * sq + 3;
+  const long long expect = (long long)p.S * (p.s_lo - (p.s_hi >= 1 ? p.s_hi : 0));
+  p.fits = nb > 0 && p.s_lo <= p.ns && expect <= BAND_CAP - BAND_CAP / 8;
+  return p;
+}
+
 struct SelectTargets {
   // targets of draft head j: tgt[off[j] .. off[j+1])
   uint16_t off[STS_MAX_HEADS + 1];
@@ -188,6 +221,8 @@ bool select_aggblock_ok(const SelectArgs &a);
 hipError_t launch_select_aggblock(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_fused(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_clear_pub(const SelectArgs &a, hipStream_t s);
+bool select_band_ok(const SelectArgs &a);
+hipError_t launch_select_band(const SelectArgs &a, hipStream_t s);
 bool select_rowpass_ok(const SelectArgs &a);
 hipError_t launch_select_rowpass(const SelectArgs &a, hipStream_t s);
 hipError_t launch_select_local(const SelectArgs &a, hipStream_t s);

@@ -246,6 +246,27 @@ __device__ __forceinline__ void agg_multi(const AggRow &R, const int (&n)[NPOS],
   }
 }
 
+// the same for a caller that knows Tq <= MAXG (MAXG <= 8): only those cases are compiled, so many
+// positions in flight do not cost the registers of eight rows each
+template <bool BF16, int MAXG, int NPOS, class V>
+__device__ __forceinline__ void agg_group_lim(const AggRow &R, int rows, const int (&n)[NPOS], V (&acc)[NPOS]) {
+  if constexpr (MAXG <= 1) {
+    agg_rows<1, true, BF16>(R, 0, n, acc);
+  } else {
+    if (rows >= MAXG) agg_rows<MAXG, true, BF16>(R, 0, n, acc);
+    else agg_group_lim<BF16, MAXG - 1>(R, rows, n, acc);
+  }
+}
+template <class V, int NPOS, int MAXG>
+__device__ __forceinline__ void agg_multi_lim(const AggRow &R, const int (&n)[NPOS], V (&acc)[NPOS]) {
+  if constexpr (MAXG >= 8) {
+    agg_multi<V, NPOS>(R, n, acc);
+  } else {
+    if (R.bf16) agg_group_lim<true, MAXG>(R, R.Tq, n, acc);
+    else agg_group_lim<false, MAXG>(R, R.Tq, n, acc);
+  }
+}
+
 template <class V>
 __device__ __forceinline__ V agg_at(const AggRow &R, int n) {
   const int pos[1] = {n};
@@ -1309,6 +1330,399 @@ __global__ void __launch_bounds__(THREADS) select_rowpass_kernel(const SelectArg
   }
 }
 
+// ------------------------------------------- at least a row per CU: one workgroup per row, ONE pass
+// With a workgroup per row nothing has to be exchanged, but the row (128K tokens and more) does
+// not fit into LDS, and every further pass over it costs its bytes again. What does fit is the
+// narrow band of keys around the threshold, if the band is known before the pass. So:
+//  1. Sample: runs of 128 bytes of a score row (32 fp32 or 64 bf16 tokens: whole cache lines, so
+//     the sample costs 1/S of the row's traffic), one run in every S (S = 16, more for rows
+//     beyond 256K so that at most 16384 keys are sampled), are aggregated and ranked out of LDS to
+//     22 key bits: U, just above the
+//     sample's key of rank c/S - z sqrt(c/S) - 2, and L, at or below its key of rank
+//     c/S + z sqrt(c/S) + 3 (z = 5). Whatever the sample says, the result below is exact: the
+//     sample only decides whether this pass suffices.
+//  2. The pass: every token is aggregated once (same fp32 order). Keys >= U are certainly kept:
+//     their bit is set in a bitmap of the row (LDS, one bit per token) and they are counted (G).
+//     Keys in [L, U) go to the band store, unordered (an LDS counter hands out the slots), M of them.
+//  3. If G < c <= G + M and the band fitted, the c-th largest key of the row is the (c - G)-th
+//     largest of the band: three digit levels over the band in LDS give the threshold T and the
+//     number r of keys equal to T that are kept; band entries above T get their bits, and of those
+//     equal to T the r lowest tokens (a two-level search over the token ids when there are more).
+//  4. The list is the bitmap read in order: each thread owns a run of words, one block scan gives
+//     its first position.
+// If the check of step 3 fails (about 1e-6 per row for the sampling error alone; rows with heavy
+// ties or a structure the strided sample misses), the row is ranked by the plain passes over the
+// scores instead (rank_by_passes): correct for every input, several times the traffic.
+constexpr int BAND_THREADS = 1024;
+
+// sum over the block of one value per thread; red needs THREADS / 64 words
+template <int THREADS>
+__device__ __forceinline__ uint32_t block_sum1(uint32_t a, uint32_t *red) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) a += (uint32_t)__shfl_xor((int)a, off, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = a;
+  __syncthreads();
+  uint32_t s = 0;
+#pragma unroll
+  for (int w = 0; w < THREADS / 64; ++w) s += red[w];
+  __syncthreads();
+  return s;
+}
+
+// The plain way for one workgroup to rank a row it cannot hold: a pass over the scores per digit
+// level (the Tq rows are aggregated again each time, in the same order, so the keys repeat bit
+// for bit), then a pass that compacts in token order. h: SEL_BINS words, tmp: THREADS/64 + 2.
+template <int THREADS>
+__device__ __forceinline__ void rank_by_passes(const SelectArgs &A, const AggRow &R, int bt, int nb, uint32_t c,
+                                               int t0, int t1, uint32_t *h, uint32_t *tmp) {
+  constexpr int NPOS = 2;
+  const int tid = threadIdx.x;
+  const int nq = (nb + 3) >> 2;           // quads that hold ranked tokens
+  uint32_t d0 = 0, pre01 = 0, krem = c, d2 = 0;
+#pragma unroll 1
+  for (int level = 0; level < 3; ++level) {
+    for (int i = tid; i < SEL_BINS; i += THREADS) h[i] = 0u;
+    __syncthreads();
+#pragma unroll 1
+    for (int q0 = tid; q0 < nq; q0 += THREADS * NPOS) {
+      int pos[NPOS];
+      f32x4 acc[NPOS];
+#pragma unroll
+      for (int x = 0; x < NPOS; ++x) pos[x] = 4 * min(q0 + x * THREADS, nq - 1);
+      agg_multi<f32x4, NPOS>(R, pos, acc);
+#pragma unroll
+      for (int x = 0; x < NPOS; ++x)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int n = 4 * (q0 + x * THREADS) + e;
+          const int bin = fused_bin(key_of(acc[x][e]), level, d0, pre01);
+          if (n < nb && bin >= 0) atomicAdd(&h[bin], 1u);
+        }
+    }
+    __syncthreads();
+    uint32_t digit, knext;
+    find_digit<SEL_BINS, THREADS>(h, krem, tmp, digit, knext);
+    if (level == 0) d0 = digit;
+    else if (level == 1) pre01 = (d0 << SEL_BITS1) | digit;
+    else d2 = digit;
+    krem = knext;
+  }
+  const uint32_t r = krem, Tk = (pre01 << SEL_BITS2) | d2;
+  // ordered compaction: per step, thread tid owns the NPOS consecutive quads from (step + tid * NPOS)
+  uint32_t gbase = 0, qbase = 0;
+#pragma unroll 1
+  for (int step = 0; step < nq; step += THREADS * NPOS) {
+    const int qlo = step + tid * NPOS;
+    int pos[NPOS];
+    f32x4 acc[NPOS];
+#pragma unroll
+    for (int x = 0; x < NPOS; ++x) pos[x] = 4 * min(qlo + x, nq - 1);
+    agg_multi<f32x4, NPOS>(R, pos, acc);
+    uint32_t gt_mask = 0, eq_mask = 0;
+#pragma unroll
+    for (int x = 0; x < NPOS; ++x)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t key = key_of(acc[x][e]);
+        const bool in = 4 * (qlo + x) + e < nb;
+        gt_mask |= (in && key > Tk) ? 1u << (4 * x + e) : 0u;
+        eq_mask |= (in && key == Tk) ? 1u << (4 * x + e) : 0u;
+      }
+    uint32_t total;
+    const uint32_t excl = block_excl_scan<THREADS>(__builtin_popcount(gt_mask) | (__builtin_popcount(eq_mask) << 16), tmp, total);
+    uint32_t g = gbase + (excl & 0xffffu), q = qbase + (excl >> 16);
+    for (uint32_t rest = gt_mask | eq_mask; rest; rest &= rest - 1) {
+      const int i = __builtin_ctz(rest);
+      const bool is_gt = (gt_mask >> i) & 1u;
+      if (is_gt || q < r) {
+        const uint32_t p = g + min(q, r);
+        if (p < c)
+          for (int ti = t0; ti < t1; ++ti) A.indices[((size_t)bt * A.Hq + A.targets.tgt[ti]) * A.k + p] = 4 * qlo + i;
+      }
+      g += is_gt ? 1u : 0u;
+      q += is_gt ? 0u : 1u;
+    }
+    gbase += total & 0xffffu;
+    qbase += total >> 16;
+    if (gbase + min(qbase, r) >= c) break;   // the list is complete (uniform)
+  }
+}
+
+// the c-th largest (1 <= c <= m) of keys[0 .. m), all of which lie in [lo, hi], and how many keys
+// equal to it are kept. A digit that lo and hi share needs no histogram.
+template <int THREADS>
+__device__ __forceinline__ void band_threshold(const uint32_t *keys, int m, uint32_t c, uint32_t lo, uint32_t hi,
+                                               uint32_t *h, uint32_t *tmp, uint32_t &Tk, uint32_t &r) {
+  const int tid = threadIdx.x;
+  uint32_t d0 = 0, pre01 = 0, krem = c, d2 = 0;
+#pragma unroll 1
+  for (int level = 0; level < 3; ++level) {
+    if (level == 0 && (lo >> (32 - SEL_BITS0)) == (hi >> (32 - SEL_BITS0))) {
+      d0 = lo >> (32 - SEL_BITS0);
+      continue;
+    }
+    if (level == 1 && (lo >> SEL_BITS2) == (hi >> SEL_BITS2)) {
+      pre01 = lo >> SEL_BITS2;
+      continue;
+    }
+    for (int i = tid; i < SEL_BINS; i += THREADS) h[i] = 0u;
+    __syncthreads();
+    for (int i = tid; i < m; i += THREADS) {
+      const int bin = fused_bin(keys[i], level, d0, pre01);
+      if (bin >= 0) atomicAdd(&h[bin], 1u);
+    }
+    __syncthreads();
+    uint32_t digit, knext;
+    find_digit<SEL_BINS, THREADS>(h, krem, tmp, digit, knext);
+    if (level == 0) d0 = digit;
+    else if (level == 1) pre01 = (d0 << SEL_BITS1) | digit;
+    else d2 = digit;
+    krem = knext;
+  }
+  Tk = (pre01 << SEL_BITS2) | d2;
+  r = krem;
+}
+
+// the pass of select_band_kernel with NPOS quads in flight per thread
+template <int NPOS>
+__device__ __forceinline__ uint32_t band_pass(const SelectArgs &A, const AggRow &R, float *out, int nb, bool spec, bool haveU,
+                                              uint32_t U, bool haveL, uint32_t L, uint32_t *bits, uint32_t *skey,
+                                              uint32_t *sidx, uint32_t *ctr) {
+  constexpr int T = BAND_THREADS;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int nq = (nb + 3) >> 2;
+  const int words = (nb + 31) >> 5;
+  const int nq_all = spec ? ((nq + 7) & ~7) : 0;       // whole bitmap words
+  const int nq_out = out ? A.N >> 2 : 0;               // the aggregate is stored for the whole row
+  // keys >= U are certainly kept (none without an upper edge); the others from L on are the band
+  const uint32_t L_eff = haveL ? L : 0u;
+  const uint32_t up_on = haveU ? 0xfu : 0u;
+  uint32_t G = 0;
+#pragma unroll 1
+  for (int q0 = tid; q0 < max(nq_all, nq_out); q0 += T * NPOS) {
+    int pos[NPOS];
+    f32x4 acc[NPOS];
+    bool any = false;
+#pragma unroll
+    for (int x = 0; x < NPOS; ++x) {
+      pos[x] = 4 * min(q0 + x * T, max(nq - 1, 0));
+      any |= q0 + x * T < nq;
+    }
+    if (__builtin_amdgcn_ballot_w64(any)) agg_multi_lim<f32x4, NPOS, (NPOS >= 8 ? 1 : (NPOS >= 4 ? 3 : 8))>(R, pos, acc);
+    uint32_t keys[NPOS][4];
+    uint32_t band = 0;                                 // bit 4x + e: that token belongs to the band
+#pragma unroll
+    for (int x = 0; x < NPOS; ++x) {
+      const int q = q0 + x * T;
+      // tokens this quad holds inside the ranked length: 4 everywhere but at the row's end
+      const int valid = q < nq ? min(4, nb - 4 * q) : 0;
+      uint32_t up = 0, bd = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t key = key_of(acc[x][e]);
+        keys[x][e] = key;
+        up |= (key >= U) ? 1u << e : 0u;
+        bd |= (key >= L_eff) ? 1u << e : 0u;
+      }
+      const uint32_t vmask = spec ? (1u << valid) - 1u : 0u;
+      const uint32_t nib = up & up_on & vmask;
+      band |= (bd & ~nib & vmask) << (4 * x);
+      if (out && q < nq_out) {
+        f32x4 o = acc[x];
+        if (valid < 4) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = e < valid ? o[e] : 0.f;
+        }
+        *reinterpret_cast<f32x4 *>(out + 4 * (size_t)q) = o;
+      }
+      if (q < nq_all) {
+        // the nibbles of eight neighbouring quads make one bitmap word, stored whole by the first
+        // lane of the eight: three shifts by 1, 2, 4 lanes inside a row of 16 lanes, OR-ed
+        G += __builtin_popcount(nib);
+        int v = (int)(nib << (4 * (lane & 7)));
+        v |= __builtin_amdgcn_update_dpp(0, v, 0x101, 0xf, 0xf, true);   // row_shl:1
+        v |= __builtin_amdgcn_update_dpp(0, v, 0x102, 0xf, 0xf, true);   // row_shl:2
+        v |= __builtin_amdgcn_update_dpp(0, v, 0x104, 0xf, 0xf, true);   // row_shl:4
+        if ((lane & 7) == 0 && (q >> 3) < words) bits[q >> 3] = (uint32_t)v;
+      }
+    }
+    if (band) {                                        // one slot request per thread and step
+      uint32_t slot = atomicAdd(ctr, (uint32_t)__builtin_popcount(band));
+#pragma unroll
+      for (int x = 0; x < NPOS; ++x)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if ((band >> (4 * x + e)) & 1u) {
+            if (slot < (uint32_t)BAND_CAP) {
+              skey[slot] = keys[x][e];
+              sidx[slot] = (uint32_t)(4 * (q0 + x * T) + e);
+            }
+            ++slot;
+          }
+    }
+  }
+  return G;
+}
+
+__global__ void __launch_bounds__(BAND_THREADS) select_band_kernel(const SelectArgs A) {
+  constexpr int T = BAND_THREADS;
+  __shared__ uint32_t bits[BAND_MAX_N / 32];           // bit n: token n is kept
+  __shared__ __attribute__((aligned(16))) uint32_t store[2 * BAND_CAP];   // sample keys; band keys and tokens; staged list
+  __shared__ uint32_t h[2][SEL_BINS];
+  __shared__ uint32_t tmp[T / 64 + 2];
+  __shared__ uint32_t red[T / 64];
+  __shared__ uint32_t ctr[2];
+  uint32_t *skey = store, *sidx = store + BAND_CAP;
+  const int row = blockIdx.x, tid = threadIdx.x;
+  const int bt = row / A.Hd, j = row % A.Hd;
+  const int nb = row_len(A, bt);
+  const uint32_t c = (uint32_t)min(A.kh[j], nb);
+  const int t0 = A.targets.off[j], t1 = A.targets.off[j + 1];
+  write_tail<T>(A, bt, j, c);
+  const bool want_agg = A.agg != nullptr;
+  const bool ranked = c > 0 && t0 != t1;
+  if (!ranked && !want_agg) return;
+  const AggRow R = agg_row(A, row);
+  float *out = want_agg ? A.agg + (size_t)row * A.N : nullptr;
+
+  // ---- 1. the band [L, U) from a strided sample
+  bool haveU = false, haveL = false, spec = ranked;
+  uint32_t U = 0, L = 0;
+  if (ranked && nb > BAND_CAP) {
+    const int run = R.bf16 ? 64 : 32;                  // tokens per sampled run: 128 bytes of a score row
+    const BandPlan bp = band_plan(nb, c, run);
+    const int ns = bp.ns, rq = run >> 2;
+    haveU = bp.s_hi >= 1;
+    haveL = true;
+    spec = bp.fits;
+    if (spec) {
+      for (int i = tid; i < SEL_BINS; i += T) h[0][i] = 0u;
+      __syncthreads();
+      for (int s0 = tid; 4 * s0 < ns; s0 += 2 * T) {   // sampled quad s: quad s % rq of run s / rq; two in flight
+        int pos[2];
+        f32x4 acc[2];
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+          const int s = min(s0 + x * T, (ns - 1) >> 2);
+          pos[x] = (s / rq) * bp.S * run + (s % rq) * 4;
+        }
+        agg_multi<f32x4, 2>(R, pos, acc);
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const uint32_t key = key_of(acc[x][e]);
+            const int i = 4 * (s0 + x * T) + e;
+            if (i < ns) {
+              skey[i] = key;
+              atomicAdd(&h[0][key >> (32 - SEL_BITS0)], 1u);
+            }
+          }
+      }
+      __syncthreads();
+      uint32_t dh = 0, kh1 = 1, dl, kl1, dh1 = 0, dl1;
+      if (haveU) find_digit<SEL_BINS, T>(h[0], (uint32_t)bp.s_hi, tmp, dh, kh1);
+      find_digit<SEL_BINS, T>(h[0], (uint32_t)bp.s_lo, tmp, dl, kl1);
+      for (int i = tid; i < SEL_BINS; i += T) h[0][i] = h[1][i] = 0u;
+      __syncthreads();
+      for (int i = tid; i < ns; i += T) {
+        const uint32_t key = skey[i], top = key >> (32 - SEL_BITS0), mid = (key >> SEL_BITS2) & ((1u << SEL_BITS1) - 1);
+        if (haveU && top == dh) atomicAdd(&h[0][mid], 1u);
+        if (top == dl) atomicAdd(&h[1][mid], 1u);
+      }
+      __syncthreads();
+      uint32_t unused;
+      if (haveU) find_digit<SEL_BINS, T>(h[0], kh1, tmp, dh1, unused);
+      find_digit<SEL_BINS, T>(h[1], kl1, tmp, dl1, unused);
+      const uint32_t u22 = ((dh << SEL_BITS1) | dh1) + 1u;
+      if (haveU && u22 < (1u << (SEL_BITS0 + SEL_BITS1))) U = u22 << SEL_BITS2;
+      else haveU = false;                              // nothing can lie above the sample's top bin
+      L = ((dl << SEL_BITS1) | dl1) << SEL_BITS2;
+    }
+  }
+  // rows of up to BAND_CAP tokens: the whole row is the band (haveU = haveL = false, spec = true)
+
+  // ---- 2. the pass; about 16 row loads in flight per thread whatever Tq is
+  if (tid == 0) ctr[0] = 0u;
+  __syncthreads();
+  uint32_t G = 0;
+  if (spec || want_agg) {
+    if (A.Tq == 1) G = band_pass<8>(A, R, out, nb, spec, haveU, U, haveL, L, bits, skey, sidx, ctr);
+    else if (A.Tq <= 3) G = band_pass<4>(A, R, out, nb, spec, haveU, U, haveL, L, bits, skey, sidx, ctr);
+    else G = band_pass<2>(A, R, out, nb, spec, haveU, U, haveL, L, bits, skey, sidx, ctr);
+  }
+  __syncthreads();
+  if (!ranked) return;
+  const uint32_t M = ctr[0];
+  G = block_sum1<T>(G, red);
+  if (!spec || G >= c || G + M < c || M > (uint32_t)BAND_CAP) {
+    rank_by_passes<T>(A, R, bt, nb, c, t0, t1, h[0], tmp);
+    return;
+  }
+
+  // ---- 3. the threshold inside the band, bits of the band's kept tokens
+  uint32_t Tk, r;
+  band_threshold<T>(skey, (int)M, c - G, haveL ? L : 0u, haveU ? U - 1u : 0xffffffffu, h[0], tmp, Tk, r);
+  uint32_t E = 0;
+  for (int i = tid; i < (int)M; i += T) {
+    const uint32_t key = skey[i];
+    if (key > Tk) atomicOr(&bits[sidx[i] >> 5], 1u << (sidx[i] & 31));
+    E += key == Tk ? 1u : 0u;
+  }
+  E = block_sum1<T>(E, red);
+  uint32_t cut = 0;                                    // equal keys are kept from this reversed token id on
+  if (E > r) {
+    // the r lowest tokens among the E equal ones: rank the reversed ids, 11 + 8 bits
+    constexpr uint32_t REV = BAND_MAX_N - 1;
+    for (int i = tid; i < SEL_BINS; i += T) h[0][i] = 0u;
+    __syncthreads();
+    for (int i = tid; i < (int)M; i += T)
+      if (skey[i] == Tk) atomicAdd(&h[0][(REV - sidx[i]) >> 8], 1u);
+    __syncthreads();
+    uint32_t da, ra, db, rb;
+    find_digit<SEL_BINS, T>(h[0], r, tmp, da, ra);
+    for (int i = tid; i < SEL_BINS; i += T) h[0][i] = 0u;
+    __syncthreads();
+    for (int i = tid; i < (int)M; i += T)
+      if (skey[i] == Tk && ((REV - sidx[i]) >> 8) == da) atomicAdd(&h[0][(REV - sidx[i]) & 255u], 1u);
+    __syncthreads();
+    find_digit<SEL_BINS, T>(h[0], ra, tmp, db, rb);
+    cut = (da << 8) | db;
+  }
+  for (int i = tid; i < (int)M; i += T)
+    if (skey[i] == Tk && (BAND_MAX_N - 1 - sidx[i]) >= cut) atomicOr(&bits[sidx[i] >> 5], 1u << (sidx[i] & 31));
+  __syncthreads();
+
+  // ---- 4. the list: set bits in token order, staged in LDS (the band store is free now) and
+  // copied out coalesced, once per target head, 2 * BAND_CAP entries per round
+  const int words = (nb + 31) >> 5;
+  const int per = (words + T - 1) / T;                 // words per thread, consecutive
+  const int w0 = min(tid * per, words), w1 = min(w0 + per, words);
+  uint32_t mine = 0;
+  for (int w = w0; w < w1; ++w) mine += __builtin_popcount(bits[w]);
+  uint32_t total;
+  const uint32_t first = block_excl_scan<T>(mine, tmp, total);
+  const uint32_t kept = min(total, c);                 // total == c for a consistent state
+  int32_t *staged = reinterpret_cast<int32_t *>(store);
+#pragma unroll 1
+  for (uint32_t base = 0; base < kept; base += 2 * BAND_CAP) {
+    uint32_t p = first;
+    if (p < base + 2 * BAND_CAP && p + mine > base)
+      for (int w = w0; w < w1; ++w)
+        for (uint32_t rest = bits[w]; rest; rest &= rest - 1) {
+          if (p >= base && p - base < 2u * BAND_CAP) staged[p - base] = 32 * w + __builtin_ctz(rest);
+          ++p;
+        }
+    __syncthreads();
+    const uint32_t cnt = min(kept - base, 2u * BAND_CAP);
+    for (int ti = t0; ti < t1; ++ti) {
+      int32_t *dst = A.indices + ((size_t)bt * A.Hq + A.targets.tgt[ti]) * A.k + base;
+      for (uint32_t i = tid; i < cnt; i += T) dst[i] = staged[i];
+    }
+    __syncthreads();
+  }
+}
+
 // ---------------------------------------------- small budgets on long rows: chunk-local top-k
 // Every token of a row's top-c (ordered by key descending, then token ascending) has fewer
 // than c tokens of the whole row before it in that order, hence fewer than c tokens of its own
@@ -1603,6 +2017,19 @@ hipError_t launch_select_rowpass(const SelectArgs &a, hipStream_t s) {
     if (a.scores_bf16) STS_LAUNCH((select_rowpass_kernel<256, true>), grid, dim3(256), 0, s, a);
     else STS_LAUNCH((select_rowpass_kernel<256, false>), grid, dim3(256), 0, s, a);
   }
+  return sts_take_launch_status();
+}
+
+// one workgroup per row and one pass (select_band_kernel): token granularity, quads, a bitmap of the row in LDS
+bool select_band_ok(const SelectArgs &a) {
+  return a.page == 1 && a.N > 0 && a.N <= BAND_MAX_N && (a.N % 4) == 0 && (reinterpret_cast<uintptr_t>(a.scores) % 16) == 0 &&
+         (a.agg == nullptr || (reinterpret_cast<uintptr_t>(a.agg) % 16) == 0);
+}
+
+hipError_t launch_select_band(const SelectArgs &a, hipStream_t s) {
+  if ((size_t)a.B * a.Hd == 0) return hipSuccess;
+  if (!select_band_ok(a)) return hipErrorInvalidValue;
+  STS_LAUNCH(select_band_kernel, dim3(a.B * a.Hd), dim3(BAND_THREADS), 0, s, a);
   return sts_take_launch_status();
 }
 

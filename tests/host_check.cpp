@@ -108,6 +108,15 @@ static void check_fused(const SelectArgs &a, const char *what) {
 }
 hipError_t launch_select_fused(const SelectArgs &a, hipStream_t) { check_fused(a, "fused"); return hipSuccess; }
 hipError_t launch_select_clear_pub(const SelectArgs &a, hipStream_t) { check_fused(a, "clear published words"); return hipSuccess; }
+bool select_band_ok(const SelectArgs &a) {
+  return a.page == 1 && a.N > 0 && a.N <= BAND_MAX_N && (a.N % 4) == 0 && (reinterpret_cast<uintptr_t>(a.scores) % 16) == 0 &&
+         (a.agg == nullptr || (reinterpret_cast<uintptr_t>(a.agg) % 16) == 0);
+}
+hipError_t launch_select_band(const SelectArgs &a, hipStream_t) {
+  check_select(a, "band");
+  if (!select_band_ok(a)) fail("band: shape");
+  return hipSuccess;
+}
 bool select_rowpass_ok(const SelectArgs &a) {
   return a.Tq == 1 && a.kind == STS_SCORES_PROBS && a.page == 1 && a.agg == nullptr && a.N > 0 &&
          (a.N % (a.scores_bf16 ? 8 : 4)) == 0 && (reinterpret_cast<uintptr_t>(a.scores) % 16) == 0;
@@ -182,7 +191,7 @@ int main() {
               calls += 4;
             }
     }
-  for (int path : {0, 1, 2, 3, 4}) {
+  for (int path : {0, 1, 2, 3, 4, 5}) {
   sts_set_knob(STS_KNOB_SELECT_PATH, path);
   for (int B : Bs) for (int Tq : {1, 5, 64}) for (int N : Ns) for (int Hd : {1, 16, 256}) for (int Hq : {1, 32, 256})
     for (int k : {1, 410, 13108, 1 << 20}) for (int page : {0, 8, 4096}) for (int budgets = 0; budgets < 2; ++budgets) {

@@ -594,23 +594,128 @@ def test_one_workgroup_per_row_selection(B, Hd, N, Hq, k, bf16, what):
     np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
 
 
-def test_many_single_score_rows_take_one_workgroup_per_row():
-    """The library's own rule: from one row per compute unit on, single-score rows of more than
-    8192 tokens go to one workgroup each; fewer rows, several scores per token, an aggregate on
-    request or block granularity keep the other paths."""
+def test_calls_with_many_rows_take_one_workgroup_per_row():
+    """The library's own rule for rows longer than one workgroup's LDS holds: from one row for
+    every second compute unit on, one workgroup per row in one pass (any number of scores per
+    token, the aggregate on request); one bf16 score per token and four rows per compute unit or
+    more: one small workgroup per row in several passes; fewer rows, block granularity, or a
+    budget whose band cannot fit keep the other paths."""
     cus = torch.cuda.get_device_properties(0).multi_processor_count
-    rows, N = cus, 8192 + 8
-    s = torch.rand(rows // 16, 16, 1, N, device=DEV)
+    N = 32768 + 8
     hm = list(range(16))
     sts.set_knob("select_path", 0)
     try:
-        assert launched(lambda: sts.sts_select(s, hm, 100)) == {"select_rowpass"}
-        assert launched(lambda: sts.sts_select(s.to(torch.bfloat16), hm, 100)) == {"select_rowpass"}
-        assert "select_rowpass" not in launched(lambda: sts.sts_select(s[:-1], hm, 100))
-        assert "select_rowpass" not in launched(lambda: sts.sts_select(s, hm, 100, want_agg=True))
-        assert "select_rowpass" not in launched(lambda: sts.sts_select(s, hm, 100, page_size=8))
+        s = torch.rand(cus // 32, 16, 2, N, device=DEV)                       # cus / 2 rows
+        assert launched(lambda: sts.sts_select(s, hm, 100)) == {"select_band"}
+        assert launched(lambda: sts.sts_select(s, hm, 100, want_agg=True)) == {"select_band"}
+        assert launched(lambda: sts.sts_select(s.to(torch.bfloat16), hm, 3000)) == {"select_band"}
+        assert "select_band" not in launched(lambda: sts.sts_select(s[:-1], hm, 100))
+        assert "select_band" not in launched(lambda: sts.sts_select(s, hm, 100, page_size=8))
+        assert "select_band" not in launched(lambda: sts.sts_select(s, hm, N - 100))        # nearly everything kept
         assert launched(lambda: sts.sts_select(s[:, :, :, :8192].contiguous(), hm, 100)) == {"select_small"}
-        s2 = torch.rand(rows // 16, 16, 2, N, device=DEV)
-        assert "select_rowpass" not in launched(lambda: sts.sts_select(s2, hm, 100))
+        del s
+        s1 = torch.rand(cus // 4, 16, 1, 8192 + 8, device=DEV)                # 4 rows per compute unit, one score per token
+        assert launched(lambda: sts.sts_select(s1, hm, 100)) == {"select_small"}             # short rows, many of them
+        s1 = torch.rand(cus // 4, 16, 1, N, device=DEV)
+        assert launched(lambda: sts.sts_select(s1, hm, 100)) == {"select_band"}
+        assert launched(lambda: sts.sts_select(s1.to(torch.bfloat16), hm, 100)) == {"select_rowpass"}
+        assert launched(lambda: sts.sts_select(s1[:-1].to(torch.bfloat16), hm, 100)) == {"select_band"}
     finally:
         sts.set_knob("select_path", None)
+
+
+def band_scores(what, B, Hd, Tq, N, seed):
+    g = torch.Generator().manual_seed(seed)
+    if what == "softmax":
+        return torch.softmax(torch.randn(B, Hd, Tq, N, generator=g) * 2, dim=-1)
+    if what == "signed":
+        s = torch.randn(B, Hd, Tq, N, generator=g)
+        s[..., ::7] = 0.0
+        s[..., 3::14] = -0.0
+        return s
+    if what == "quantised":                        # a handful of distinct values: the band cannot hold the ties
+        return torch.randint(0, 5, (B, Hd, Tq, N), generator=g).float() / 8
+    if what == "constant":
+        return torch.full((B, Hd, Tq, N), 0.25)
+    if what == "clustered":                        # all heavy tokens in one stretch that the strided sample mostly misses
+        s = torch.rand(B, Hd, Tq, N, generator=g) * 1e-3
+        lo = N // 3
+        s[..., lo:lo + N // 8] += 1.0
+        return s
+    if what == "recent":                           # heavy tokens at the end of the context, plus scattered ones
+        s = torch.softmax(torch.randn(B, Hd, Tq, N, generator=g) * 2, dim=-1)
+        s[..., -N // 20:] *= 50
+        return s
+    raise ValueError(what)
+
+
+@pytest.mark.parametrize("B,Hd,Tq,N,Hq,k,dtype,what", [
+    (2, 4, 5, 40000, 8, 4000, torch.float32, "softmax"),       # the usual shape: sample, one pass, band
+    (2, 4, 1, 40000, 8, 4000, torch.bfloat16, "softmax"),      # bf16: ties at the threshold, the lower tokens win
+    (2, 3, 3, 131072, 6, 13108, torch.float32, "softmax"),     # 128K rows, 10%
+    (1, 2, 2, 262144 + 64, 2, 3000, torch.float32, "softmax"), # sample stride 64
+    (2, 4, 5, 40000, 8, 100, torch.float32, "softmax"),        # small budget: no upper edge, the band is the top of the row
+    (2, 4, 5, 40000, 8, 20000, torch.float32, "softmax"),      # half of the row
+    (2, 4, 5, 40000, 8, 39000, torch.float32, "softmax"),      # nearly everything: ranked by plain passes
+    (2, 2, 1, 9000, 4, 8000, torch.bfloat16, "signed"),        # negative keys, -0 and +0
+    (2, 2, 2, 70000, 2, 5000, torch.float32, "quantised"),     # ties overflow the band: plain passes
+    (2, 2, 1, 70000, 2, 5000, torch.bfloat16, "constant"),     # all equal: the first k tokens
+    (2, 2, 2, 70000, 2, 5000, torch.float32, "clustered"),     # the sample misleads: the check sends the row to plain passes
+    (2, 2, 4, 70000, 2, 3000, torch.float32, "recent"),
+    (2, 4, 5, 8000, 8, 777, torch.float32, "softmax"),         # rows that fit the band store whole: no sample
+    (2, 4, 5, 8196, 8, 777, torch.float32, "softmax"),         # just above that
+])
+def test_one_workgroup_per_row_one_pass_selection(B, Hd, Tq, N, Hq, k, dtype, what):
+    """select_band_kernel: index sets, counts and the aggregate bit for bit against the oracle,
+    whichever way a row goes inside the kernel (band, or plain passes when the band does not fit or
+    the sample misled), with ragged lengths, per-head budgets, shared and unread draft heads."""
+    scores = band_scores(what, B, Hd, Tq, N, N + k + Tq).to(dtype)
+    hm = [min(t // 2, Hd - 1) for t in range(Hq)] if Hq > Hd else list(range(Hq))
+    kh = [max(1, k - 37 * j) for j in range(Hd)]
+    lens = torch.full((B,), N, dtype=torch.int32)
+    lens[-1] = N - 13
+    sd = scores.to(DEV)
+    sts.set_knob("select_path", 5)
+    try:
+        got = {}
+        kinds = launched(lambda: got.update(r=sts.sts_select(sd, hm, k, seq_lens=lens.to(DEV), k_head=kh, want_agg=True)))
+        idx2, cnt2, _ = sts.sts_select(sd, hm, k, seq_lens=lens.to(DEV), k_head=kh)
+    finally:
+        sts.set_knob("select_path", None)
+    assert kinds == {"select_band"}
+    idx, cnt, agg = got["r"]
+    o_idx, o_cnt, o_agg = oracle.select_indices(scores.float().numpy(), np.asarray(hm, np.int32), k, k_head=kh, seq_lens=lens.numpy())
+    np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
+    np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
+    np.testing.assert_array_equal(agg.cpu().numpy().view(np.uint32), stored_agg(o_agg, lens).view(np.uint32))
+    assert torch.equal(idx2, idx) and torch.equal(cnt2, cnt)
+
+
+@pytest.mark.parametrize("kind,reduce", [(0, 1), (1, 0)])
+def test_one_pass_selection_options(kind, reduce):
+    """The same kernel with scaled-logit input and with the maximum reduction; lengths that end
+    inside a quad, inside the first sampled run, and at zero."""
+    B, Hd, Tq, N, k = 4, 4, 3, 40000, 700
+    g = torch.Generator().manual_seed(23 + kind + 2 * reduce)
+    logits = torch.randn(B, Hd, Tq, N, generator=g) * 2.0
+    lse = torch.logsumexp(logits, dim=-1)
+    scores = logits if kind == 1 else torch.softmax(logits, dim=-1)
+    hm = [0, 0, 2, 3, 3, 2]
+    kh = [700, 5, 1, 333]
+    lens = torch.tensor([N, 9001, 7, 0], dtype=torch.int32)
+    sts.set_knob("select_path", 5)
+    try:
+        idx, cnt, agg = sts.sts_select(scores.to(DEV), hm, k, lse=lse.to(DEV) if kind == 1 else None, seq_lens=lens.to(DEV),
+                                       kind=kind, reduce=reduce, want_agg=True, k_head=kh)
+    finally:
+        sts.set_knob("select_path", None)
+    agg = agg.cpu().numpy()
+    o_agg = stored_agg(oracle.aggregate(scores.numpy(), lse.numpy() if kind == 1 else None, kind, reduce), lens)
+    if kind == 0:
+        np.testing.assert_array_equal(agg.view(np.uint32), o_agg.view(np.uint32))
+    else:
+        np.testing.assert_allclose(agg, o_agg, rtol=1e-5, atol=1e-12)
+    sel, c = oracle.select_per_head(agg, k, kh, lens.numpy())       # stage-wise: rank the GPU's own aggregate
+    o_idx, o_cnt = oracle.remap(sel, c, np.asarray(hm, np.int32))
+    np.testing.assert_array_equal(cnt.cpu().numpy(), o_cnt)
+    np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)

@@ -225,7 +225,7 @@ def run_prefill(args, torch, sts):
     if rows:
         # a mask per query row (Section 4.2): per-row selection, union of a block's 16 row sets with
         # row bits, one gather of the union per block
-        pitch = min(T * k, N)
+        pitch = min(4 * k, T * k, N)    # the caller sizes the union's buffers; checked below that nothing was cut
         ridx = torch.empty(NB, Hd, T, k, dtype=torch.int32, device=dev)
         rcnt = torch.empty(NB, Hd, T, dtype=torch.int32, device=dev)
         idx = torch.empty(NB, Hq, pitch, dtype=torch.int32, device=dev)
@@ -243,7 +243,15 @@ def run_prefill(args, torch, sts):
         att = lambda: sts.sts_sparse_attn(q, kx, vx, idx, w.scale, counts=cnt, head_map=w.head_map, out=out,
                                           want_lse=False, k_new=kn, v_new=vn, causal=True)
     t_sel = _timed(sel, args.steps, args.warmup, torch)
+    if rows and int(cnt.max().item()) >= pitch:
+        raise SystemExit("bench.py: the union of a block's row masks does not fit the pitch chosen for it")
     t_att = _timed(att, args.steps, args.warmup, torch)
+    parts = {}
+    if rows:      # the two steps of mask building on their own
+        parts["select_rows_us"] = _timed(lambda: sts.sts_select_rows(scores, k, seq_lens=lens, out=(ridx, rcnt)),
+                                         args.steps, args.warmup, torch)["median"]
+        parts["union_rows_us"] = _timed(lambda: sts.sts_union_rows(ridx, rcnt, w.head_map, N, pitch=pitch, out=(idx, msk, cnt)),
+                                        args.steps, args.warmup, torch)["median"]
     sts.prof_enable(True)
     sts.prof_reset()
     for _ in range(max(1, min(args.steps, 20))):
@@ -265,13 +273,13 @@ def run_prefill(args, torch, sts):
     assert len(leaders) == units
     entries = int(cnt[:, leaders].sum().item()) if rows else NB * units * k       # gathered once per unit
     b_set = entries * row_bytes
-    extra = {}
+    extra = dict(parts)
     if rows:
         # what one gather per query row (the single-row formulation) would move for the same masks
         per_row_entries = int(rcnt[:, [hm[t] for t in leaders]].sum().item())
-        extra = {"union_entries_per_block_and_unit": round(entries / (NB * units), 1),
-                 "gathered_kv_bytes_one_gather_per_row": per_row_entries * row_bytes,
-                 "union_saves": round(per_row_entries / max(entries, 1), 2)}
+        extra.update({"union_entries_per_block_and_unit": round(entries / (NB * units), 1),
+                      "gathered_kv_bytes_one_gather_per_row": per_row_entries * row_bytes,
+                      "union_saves": round(per_row_entries / max(entries, 1), 2)})
     print(json.dumps({
         "metric": "chunked sparse prefill: attention us per 16-token query block over a shared cache", "unit": "us/block",
         "value": round(t_att["median"] / NB, 2), "higher_is_better": False, "n_gpus": 1, "dtype": "bf16", "data": "synthetic",

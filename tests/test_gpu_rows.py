@@ -80,6 +80,33 @@ def test_per_row_selection_bit_exact(B, Hd, Tq, N, k, lens):
     np.testing.assert_array_equal(ridx.cpu().numpy(), o_sel)
 
 
+@pytest.mark.parametrize("swap", ["whole list shuffled", "two entries swapped across chunks", "ascending"])
+def test_union_over_several_chunks_does_not_depend_on_the_order_inside_a_list(swap):
+    """Long contexts are walked in chunks of 32768 tokens, each chunk reading its own segment of
+    every (ascending) list; a list in any other order must give the same union (the kernel notices
+    and reads every entry for every chunk instead)."""
+    B, Hd, Hq, Tq, N, k = 2, 2, 4, 9, 150000, 3000
+    sel, cnt = random_rows(91, B, Hd, Tq, N, k)
+    rng = np.random.default_rng(5)
+    if swap == "whole list shuffled":
+        for b in range(B):
+            for j in range(Hd):
+                for i in range(Tq):
+                    c = cnt[b, j, i]
+                    sel[b, j, i, :c] = rng.permutation(sel[b, j, i, :c])
+    elif swap == "two entries swapped across chunks":
+        c = cnt[1, 1, 3]
+        assert c > 10 and sel[1, 1, 3, 0] < 32768 <= sel[1, 1, 3, c - 1]
+        sel[1, 1, 3, [0, c - 1]] = sel[1, 1, 3, [c - 1, 0]]
+    hm = [0, 1, 1, 0]
+    idx, mask, ucnt = sts.sts_union_rows(torch.from_numpy(sel).to(DEV), torch.from_numpy(cnt).to(DEV), hm, N)
+    torch.cuda.synchronize()
+    o_idx, o_mask, o_cnt = oracle.union_rows(sel, cnt, hm, pitch=idx.shape[2])
+    np.testing.assert_array_equal(ucnt.cpu().numpy(), o_cnt)
+    np.testing.assert_array_equal(idx.cpu().numpy(), o_idx)
+    np.testing.assert_array_equal(mask.cpu().numpy().view(np.uint16), o_mask)
+
+
 def make_qkv(seed, B, Tq, Hq, Hkv, d, N):
     g = torch.Generator().manual_seed(seed)
     q = torch.randn(B, Tq, Hq, d, generator=g).to(torch.bfloat16)

@@ -132,7 +132,11 @@ sts_status plan_attn(const sts_attn_params *p, int sparse, AttnPlan &pl) {
   const sts_status v = validate_attn(p, sparse);
   if (v != STS_OK) return v;
   const int G = p->Hq / p->Hkv;
-  int max_heads = 64 / p->Tq;   // at most 4 query tiles of 16 rows
+  // at most 4 query tiles of 16 rows per unit; 2 for the logits dump at head size 128, whose
+  // four-tile form would not fit the register file (a KV group with more rows is served by two
+  // units, each reading K and V: next to the dump's own writes that costs little)
+  int max_heads = ((!sparse && p->logits_out && p->d == 128) ? 32 : 64) / p->Tq;
+  if (max_heads < 1) max_heads = 1;
   if (max_heads > STS_MAX_GROUP) max_heads = STS_MAX_GROUP;
   int nu = 0, max_rows = 0;
   memset(&pl.units, 0, sizeof(pl.units));

@@ -340,61 +340,67 @@ attn_split_kernel(const AttnArgs A) {
         }
       }
     }
-    // ---- online softmax (log2 domain) and P^T as bf16 B operands
-    bf16x8 Pb[NQ];
+    // ---- online softmax (log2 domain) and P^T as bf16 B operands, then O^T += V^T P^T.
+    // With four query tiles at head size 128 the two steps are done for two tiles at a time (the
+    // V operands are permuted twice): all four P tiles next to both K/V buffers do not fit the
+    // 256 registers that ordinary instructions can address.
+    constexpr int NQH = (NQ == 4 && D == 128) ? 2 : NQ;   // query tiles per round
     int key_bits[8];                // ROWMASK: the row bits of this lane's 8 keys
     if constexpr (ROWMASK) {
 #pragma unroll
       for (int m = 0; m < 8; ++m) key_bits[m] = __shfl(tile_bits, slot_of(m), 64);
     }
 #pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) {
-      float s[8];
+    for (int q0 = 0; q0 < NQ; q0 += NQH) {
+      bf16x8 Pb[NQH];
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
+      for (int nq = q0; nq < q0 + NQH; ++nq) {
+        float s[8];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const bool ok = ROWMASK ? ((key_bits[4 * ks + r] >> q_tq[nq]) & 1) != 0
-                                  : ((tile_mask >> (16 * ks + 4 * a + r)) & 1u) != 0;
-          s[4 * ks + r] = ok ? St[nq][ks][r] * A.scale_log2 : -INFINITY;
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const bool ok = ROWMASK ? ((key_bits[4 * ks + r] >> q_tq[nq]) & 1) != 0
+                                    : ((tile_mask >> (16 * ks + 4 * a + r)) & 1u) != 0;
+            s[4 * ks + r] = ok ? St[nq][ks][r] * A.scale_log2 : -INFINITY;
+          }
+        float mt = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+        mt = xor_max(mt, 16);
+        mt = xor_max(mt, 32);
+        const float m_new = fmaxf(m_run[nq], mt);          // finite: every consumed tile has a valid key ...
+        // ... except with row bits: a row may keep none of a tile's keys, nor of any tile so far
+        const float m_ref = (ROWMASK && m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run[nq] - m_ref);
+        float p[8], psum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          p[i] = __builtin_amdgcn_exp2f(s[i] - m_ref);
+          psum += p[i];
         }
-      float mt = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
-      mt = xor_max(mt, 16);
-      mt = xor_max(mt, 32);
-      const float m_new = fmaxf(m_run[nq], mt);          // finite: every consumed tile has a valid key ...
-      // ... except with row bits: a row may keep none of a tile's keys, nor of any tile so far
-      const float m_ref = (ROWMASK && m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run[nq] - m_ref);
-      float p[8], psum = 0.f;
+        l_run[nq] = l_run[nq] * alpha + psum;
+        m_run[nq] = m_new;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        p[i] = __builtin_amdgcn_exp2f(s[i] - m_ref);
-        psum += p[i];
+        for (int nt = 0; nt < NT; ++nt) acc[nq][nt] *= alpha;
+        u32x4 pw;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const f32x2 pr = {p[2 * i], p[2 * i + 1]};
+          pw[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+        }
+        Pb[nq - q0] = __builtin_bit_cast(bf16x8, pw);
       }
-      l_run[nq] = l_run[nq] * alpha + psum;
-      m_run[nq] = m_new;
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) acc[nq][nt] *= alpha;
-      u32x4 pw;
+      for (int nt = 0; nt < NT; ++nt) {
+        const uint32_t sel = (nt & 1) ? 0x07060302u : 0x05040100u;
+        u32x4 vw;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const f32x2 pr = {p[2 * i], p[2 * i + 1]};
-        pw[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+        for (int j = 0; j < 4; ++j)
+          vw[j] = __builtin_amdgcn_perm(Vr[2 * j + 1][nt >> 1], Vr[2 * j][nt >> 1], sel);
+        const bf16x8 Va = __builtin_bit_cast(bf16x8, vw);
+#pragma unroll
+        for (int nq = q0; nq < q0 + NQH; ++nq)
+          acc[nq][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Va, Pb[nq - q0], acc[nq][nt], 0, 0, 0);
       }
-      Pb[nq] = __builtin_bit_cast(bf16x8, pw);
-    }
-    // ---- O^T += V^T P^T
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const uint32_t sel = (nt & 1) ? 0x07060302u : 0x05040100u;
-      u32x4 vw;
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        vw[j] = __builtin_amdgcn_perm(Vr[2 * j + 1][nt >> 1], Vr[2 * j][nt >> 1], sel);
-      const bf16x8 Va = __builtin_bit_cast(bf16x8, vw);
-#pragma unroll
-      for (int nq = 0; nq < NQ; ++nq)
-        acc[nq][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Va, Pb[nq], acc[nq][nt], 0, 0, 0);
     }
   };
 
@@ -756,9 +762,12 @@ hipError_t launch_split_dnp(const AttnArgs &a, bool sparse, hipStream_t s) {
     else return hipErrorInvalidValue;           // (the host refuses row bits on a paged cache)
   } else if (sparse)
     STS_LAUNCH((attn_split_kernel<D, NQ, true, false, PAGED>), grid, block, 0, s, a);
-  else if (a.logits_out)
-    STS_LAUNCH((attn_split_kernel<D, NQ, false, true, PAGED>), grid, block, 0, s, a);
-  else
+  else if (a.logits_out) {
+    // the dump at head size 128 is planned with at most two query tiles per unit (its four-tile
+    // form does not fit the register file)
+    if constexpr (D == 128 && NQ == 4) return hipErrorInvalidValue;
+    else STS_LAUNCH((attn_split_kernel<D, NQ, false, true, PAGED>), grid, block, 0, s, a);
+  } else
     STS_LAUNCH((attn_split_kernel<D, NQ, false, false, PAGED>), grid, block, 0, s, a);
   return sts_take_launch_status();
 }

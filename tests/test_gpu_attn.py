@@ -157,6 +157,32 @@ def test_logits_dump_in_bf16(d, N):
         assert (np.abs(got - ref[b, :, :, :n]) <= np.abs(ref[b, :, :, :n]) * 2.0 ** -7 + 1e-6).all()
 
 
+@pytest.mark.parametrize("Tq,G,dump", [(8, 8, torch.float32), (5, 8, torch.bfloat16), (16, 4, torch.float32)])
+def test_logits_dump_head_dim_128_group_of_more_than_32_rows(Tq, G, dump):
+    """A KV group with more than 32 query rows at head size 128: the dump serves it with two units
+    of at most two query tiles each (both read K and V); outputs, LSE and logits as for any shape.
+    The attention without the dump takes the group as one unit of four query tiles."""
+    B, Hkv, d, N = 2, 2, 128, 1500
+    q, k, v = make_qkv(Tq * G, B, Tq, Hkv * G, Hkv, d, N)
+    lens = torch.tensor([N, 700], dtype=torch.int32, device=DEV)
+    out, lse, logits = sts.sts_dense_attn(q, k, v, 0.09, seq_lens=lens, out_dtype=torch.float32, want_logits=dump)
+    ref = oracle_attn(q, k, v, 0.09, seq_lens=lens, want_logits=True)
+    check_attn(out, lse, ref, what="dense d128, more than 32 rows per group, with the dump")
+    lg, rl = logits.float().cpu().numpy(), ref["logits"]
+    for b, n in enumerate(lens.tolist()):
+        if dump == torch.float32:
+            check_logits(lg[b, :, :, :n], rl[b, :, :, :n], what=f"batch {b}")
+        else:
+            assert (np.abs(lg[b, :, :, :n] - rl[b, :, :, :n]) <= np.abs(rl[b, :, :, :n]) * 2.0 ** -7 + 1e-6).all()
+    out2, lse2, _ = sts.sts_dense_attn(q, k, v, 0.09, seq_lens=lens, out_dtype=torch.float32)
+    check_attn(out2, lse2, ref, what="dense d128, four query tiles")
+    # the gather with four query tiles: every head of the group shares one list
+    idx = torch.arange(0, 1400, 2, dtype=torch.int32, device=DEV).expand(B, Hkv * G, 700).contiguous()
+    o_s, l_s = sts.sts_sparse_attn(q, k, v, idx, 0.09, head_map=[0] * (Hkv * G), out_dtype=torch.float32)
+    ref_s = oracle_attn(q, k, v, 0.09, indices=idx)
+    check_attn(o_s, l_s, ref_s, what="gather d128, four query tiles")
+
+
 def test_results_are_deterministic_run_to_run():
     B, Tq, Hq, Hkv, d, N, kk = 2, 5, 8, 2, 128, 4000, 400
     q, k, v = make_qkv(9, B, Tq, Hq, Hkv, d, N)

@@ -194,6 +194,61 @@ def test_c5_two_batch_elements_of_the_70b_shaped_chain():
     assert (np.abs(got_A - ref_A) <= 3e-5 * ref_A + 1e-10).all()
 
 
+@pytest.mark.parametrize("B,Hd,Tq,dtype,kind", [
+    (8, 32, 8, torch.float32, "logits"),       # the 70B-shaped layer's dump as the benchmark selects from it
+    (8, 32, 1, torch.float32, "probs"),        # its summed weights
+    (32, 16, 16, torch.bfloat16, "probs"),     # block masks of chunked prefill: 512 rows of 16 bf16 scores per token
+])
+def test_full_batches_of_128k_rows_take_the_one_pass_selection(B, Hd, Tq, dtype, kind):
+    """The shapes the benchmark times with at least a row per compute unit, at their full sizes
+    and under the library's own routing: one workgroup per row, one pass. Whole rows, sampled over
+    the batch, bit for bit against the oracle (scaled-logit input: stage-wise, the oracle ranks
+    the GPU's own aggregate of the row and checks that aggregate to rounding)."""
+    N, k = 131072, 13108
+    g = torch.Generator(device=DEV)
+    g.manual_seed(B * Tq)
+    scores = torch.empty(B, Hd, Tq, N, dtype=dtype, device=DEV)
+    lse = torch.empty(B, Hd, Tq, dtype=torch.float32, device=DEV) if kind == "logits" else None
+    lens = torch.full((B,), N, dtype=torch.int32, device=DEV)
+    lens[B - 1] = N - 4097
+    for b in range(B):
+        lg = torch.randn(Hd, Tq, N, generator=g, device=DEV) * 2
+        lg[:, :, int(lens[b]):] = float("-inf") if kind == "probs" else 0.0
+        if kind == "logits":
+            scores[b] = lg
+            lse[b] = torch.logsumexp(lg[:, :, :int(lens[b])], dim=-1)
+        else:
+            scores[b] = torch.softmax(lg, dim=-1).to(dtype)
+        del lg
+    hm = list(range(Hd))
+    sts.prof_enable(True)
+    sts.prof_reset()
+    try:
+        idx, cnt, agg = sts.sts_select(scores, hm, k, lse=lse, seq_lens=lens, want_agg=(kind == "logits"),
+                                       kind=sts.STS_SCORES_LOGITS_LSE if kind == "logits" else sts.STS_SCORES_PROBS)
+        torch.cuda.synchronize()
+        kinds = {name for name, (n, _) in sts.prof_read().items() if n}
+    finally:
+        sts.prof_enable(False)
+    assert kinds == {"select_band"}
+    assert (cnt.cpu().numpy() == np.minimum(k, lens.cpu().numpy())[:, None]).all()
+    for b, j in [(0, 0), (B // 2, Hd - 1), (B - 1, Hd // 2)]:
+        ln = lens[b:b + 1].cpu().numpy()
+        if kind == "logits":
+            a = agg[b:b + 1, j:j + 1].cpu().numpy()
+            o_agg = oracle.aggregate(scores[b:b + 1, j:j + 1].cpu().numpy(), lse[b:b + 1, j:j + 1].cpu().numpy(),
+                                     kind=oracle.LOGITS_LSE)
+            n = int(ln[0])
+            np.testing.assert_allclose(a[..., :n], o_agg[..., :n], rtol=1e-5, atol=1e-12)
+            sel, c = oracle.select_per_head(a, k, [k], ln)
+        else:
+            o_idx, o_cnt, _ = oracle.select_indices(scores[b:b + 1, j:j + 1].float().cpu().numpy(), np.zeros(1, np.int32), k,
+                                                    seq_lens=ln)
+            sel, c = o_idx, o_cnt
+        np.testing.assert_array_equal(cnt[b, j].cpu().numpy(), np.asarray(c).reshape(-1)[0])
+        np.testing.assert_array_equal(idx[b, j].cpu().numpy(), np.asarray(sel).reshape(-1, k)[0])
+
+
 def test_summed_weights_at_a_million_tokens():
     """The second pass over K on a 1M-token draft cache (32768 key tiles, 64-bit row offsets):
     bit for bit the aggregate of the dump, zero past the valid length, same index sets."""

@@ -1258,23 +1258,71 @@ __global__ void __launch_bounds__(THREADS) select_rowpass_kernel(const SelectArg
       static_cast<const unsigned char *>(A.scores) + (size_t)row * A.N * (BF16 ? 2 : 4));
   const int nv = (nb + VPT - 1) / VPT;    // words that hold ranked tokens
 
+  // bf16 rows: the second digit has only 32 values that occur (5 bits of the score, the rest
+  // follows the sign), so its histogram can be built in the FIRST pass for a window of first
+  // digits, if the window is put where the first digit will turn out to be: a 1/16 sample of the
+  // row (128-byte runs) says where. If the first digit falls outside the window the second pass
+  // is made as for any row; the result never depends on the sample.
+  constexpr int WIN = 8;
+  __shared__ uint32_t hw[BF16 ? WIN * 32 : 1];
+  uint32_t wlo = 0;                       // first digit the window starts at
+  bool win = false;
+  if (BF16 && nv >= 4096) {
+    win = true;
+    for (int i = tid; i < SEL_BINS; i += THREADS) h[i] = 0u;
+    __syncthreads();
+    const int runs = (nv + 127) / 128;    // sampled run i: the 8 words from 128 i on
+    uint32_t mine = 0;
+    for (int s0 = tid; s0 < runs * 8; s0 += THREADS) {
+      const int wi = (s0 >> 3) * 128 + (s0 & 7);
+      if (wi < nv) {
+        const u32x4 w = src[wi];
+#pragma unroll
+        for (int e = 0; e < VPT; ++e)
+          if (wi * VPT + e < nb) {
+            atomicAdd(&h[rowpass_key<BF16>(w, e) >> (32 - SEL_BITS0)], 1u);
+            ++mine;
+          }
+      }
+    }
+    __syncthreads();
+    uint32_t ns;
+    block_excl_scan<THREADS>(mine, tmp, ns);
+    const uint32_t want = (uint32_t)min((uint64_t)ns, max((uint64_t)1, (uint64_t)c * ns / (uint32_t)nb));
+    uint32_t dest, unused;
+    find_digit<SEL_BINS, THREADS>(h, want, tmp, dest, unused);
+    wlo = dest >= WIN / 2 ? dest - WIN / 2 + 1 : 0u;
+    for (int i = tid; i < WIN * 32; i += THREADS) hw[i] = 0u;
+  }
+
   uint32_t d0 = 0, pre01 = 0, krem = c, d2 = 0;
 #pragma unroll 1
   for (int level = 0; level < (BF16 ? 2 : 3); ++level) {
     for (int i = tid; i < SEL_BINS; i += THREADS) h[i] = 0u;
     __syncthreads();
+    if (BF16 && level == 1 && win && d0 - wlo < (uint32_t)WIN) {
+      // the window held the first digit: its 32 counts are the second digit's histogram
+      const uint32_t low = (d0 >> (SEL_BITS0 - 1)) ? 0u : (1u << (SEL_BITS1 - 5)) - 1;   // the bits below follow the sign
+      if (tid < 32) h[((uint32_t)tid << (SEL_BITS1 - 5)) | low] = hw[(d0 - wlo) * 32 + tid];
+    } else {
 #pragma unroll 1
-    for (int i0 = tid; i0 < nv; i0 += THREADS * UNR) {
-      u32x4 w[UNR];
+      for (int i0 = tid; i0 < nv; i0 += THREADS * UNR) {
+        u32x4 w[UNR];
 #pragma unroll
-      for (int u = 0; u < UNR; ++u) w[u] = src[min(i0 + u * THREADS, nv - 1)];
+        for (int u = 0; u < UNR; ++u) w[u] = src[min(i0 + u * THREADS, nv - 1)];
 #pragma unroll
-      for (int u = 0; u < UNR; ++u) {
-        const int wi = i0 + u * THREADS;
+        for (int u = 0; u < UNR; ++u) {
+          const int wi = i0 + u * THREADS;
 #pragma unroll
-        for (int e = 0; e < VPT; ++e) {
-          const int bin = fused_bin(rowpass_key<BF16>(w[u], e), level, d0, pre01);
-          if (wi < nv && wi * VPT + e < nb && bin >= 0) atomicAdd(&h[bin], 1u);
+          for (int e = 0; e < VPT; ++e) {
+            const uint32_t key = rowpass_key<BF16>(w[u], e);
+            const int bin = fused_bin(key, level, d0, pre01);
+            if (wi < nv && wi * VPT + e < nb && bin >= 0) {
+              atomicAdd(&h[bin], 1u);
+              if (BF16 && level == 0 && win && (uint32_t)bin - wlo < (uint32_t)WIN)
+                atomicAdd(&hw[((uint32_t)bin - wlo) * 32 + ((key >> (32 - SEL_BITS0 - 5)) & 31u)], 1u);
+            }
+          }
         }
       }
     }

@@ -553,6 +553,9 @@ def test_single_row_input_is_ranked_in_place(N, k, levels, off, select_path):
     (1, 2, 70000, 2, 5000, True, "constant"),       # all equal: the first k tokens
     (72, 16, 8200, 16, 300, True, "softmax"),       # 1152 rows: the small workgroups the rule takes for many rows
     (72, 16, 8200, 16, 300, False, "softmax"),
+    (2, 2, 70000, 2, 5000, True, "unsampled"),      # the sample puts the window of second-digit histograms in the wrong place
+    (2, 2, 70000, 2, 5000, True, "clustered"),
+    (2, 2, 70000, 2, 60000, True, "softmax"),       # the threshold far down the row
 ])
 def test_one_workgroup_per_row_selection(B, Hd, N, Hq, k, bf16, what):
     """Single-score rows (Tq = 1) ranked by one workgroup per row in several passes over the row:
@@ -568,8 +571,10 @@ def test_one_workgroup_per_row_selection(B, Hd, N, Hq, k, bf16, what):
         scores[..., 3::14] = -0.0
     elif what == "quantised":
         scores = torch.randint(0, 5, (B, Hd, 1, N), generator=g).float() / 8
-    else:
+    elif what == "constant":
         scores = torch.full((B, Hd, 1, N), 0.25)
+    else:
+        scores = band_scores(what, B, Hd, 1, N, N + k)
     if bf16:
         scores = scores.to(torch.bfloat16)
     hm = [min(t // 2, Hd - 1) for t in range(Hq)] if Hq > Hd else list(range(Hq))     # pairs share; the last heads may be unread
@@ -642,6 +647,11 @@ def band_scores(what, B, Hd, Tq, N, seed):
         lo = N // 3
         s[..., lo:lo + N // 8] += 1.0
         return s
+    if what == "unsampled":                        # heavy tokens only where neither kernel's strided sample looks
+        s = torch.rand(B, Hd, Tq, N, generator=g) * 1e-3
+        pos = torch.arange(N)
+        s[..., (pos % 512) >= 64] += torch.rand(int(((pos % 512) >= 64).sum()), generator=g) + 0.5
+        return s
     if what == "recent":                           # heavy tokens at the end of the context, plus scattered ones
         s = torch.softmax(torch.randn(B, Hd, Tq, N, generator=g) * 2, dim=-1)
         s[..., -N // 20:] *= 50
@@ -662,6 +672,8 @@ def band_scores(what, B, Hd, Tq, N, seed):
     (2, 2, 1, 70000, 2, 5000, torch.bfloat16, "constant"),     # all equal: the first k tokens
     (2, 2, 2, 70000, 2, 5000, torch.float32, "clustered"),     # the sample misleads: the check sends the row to plain passes
     (2, 2, 4, 70000, 2, 3000, torch.float32, "recent"),
+    (2, 2, 2, 70000, 2, 5000, torch.float32, "unsampled"),
+    (2, 2, 1, 70000, 2, 5000, torch.bfloat16, "unsampled"),
     (2, 4, 5, 8000, 8, 777, torch.float32, "softmax"),         # rows that fit the band store whole: no sample
     (2, 4, 5, 8196, 8, 777, torch.float32, "softmax"),         # just above that
 ])

@@ -408,6 +408,30 @@ class Point:
                 "split_kernel_frac": round(b_set / (split * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if split > 0 else None,
                 "call_frac": round(b_set / (t[1] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if t[1] > 0 else None}
 
+    def stacked(self, stack, reps=20):
+        """sts_sparse_attn on a stack of layers back to back (each layer its own K/V buffers, the
+        same index sets), one event pair around the whole stack: what a layer costs inside a
+        forward pass, where no event packets stand between the calls. Eager launches, no graph."""
+        torch = self.torch
+        saved = self.layers
+        self.layers = stack
+        try:
+            for l in range(len(stack)):
+                self.sparse(l)
+            torch.cuda.synchronize()
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+            evs[0].record()
+            for i in range(reps):
+                for l in range(len(stack)):
+                    self.sparse(l)
+                evs[i + 1].record()
+            torch.cuda.synchronize()
+            us = statistics.median(evs[i].elapsed_time(evs[i + 1]) for i in range(reps)) * 1e3 / len(stack)
+        finally:
+            self.layers = saved
+            self._calls = {k: v for k, v in self._calls.items() if k[0] != "sparse"}
+        return {"layers": len(stack), "sparse_attn_us_per_layer": round(us, 2)}
+
     def graph(self, reps=30):
         """The same calls captured in HIP graphs and replayed (no host launch cost between the
         kernels). A call's time is the difference between a graph that holds it after a dense pass
@@ -708,6 +732,13 @@ def main():
         result["graph_replay"]["call_frac"] = round(b_set / (result["graph_replay"]["sparse_attn_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
         # the budget sweep of the 128K configuration (5% and 20% beside the 10% above), same resident inputs
         if cfg.name == "c3" and args.budget is None:
+            # eight layers' caches (16 GiB) attended back to back: the gathered rows of a pass (3.4 GB)
+            # exceed every cache, so each call still reads its rows from HBM
+            stack = [layers[0]] + [(layers[0][0].clone(), layers[0][1].clone()) for _ in range(7)]
+            result["stacked_layers"] = here.stacked(stack)
+            result["stacked_layers"]["call_frac"] = round(
+                b_set / (result["stacked_layers"]["sparse_attn_us_per_layer"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
+            del stack
             result["sweep"] = {}
             for frac in (0.05, 0.20):
                 pt = Point(torch, sts, w, layers, budget_tokens(cfg, frac))

@@ -53,6 +53,8 @@ def test_headline_configuration_carries_sweep_and_paper_budgets():
     assert r["sweep"]["5%"]["budget_tokens"] == 6554 and r["sweep"]["20%"]["budget_tokens"] == 26215
     for pt in r["sweep"].values():
         assert pt["sparse_attn_us"] > 0 and pt["dense_attn_us"] > pt["sparse_attn_us"] and 0 < pt["split_kernel_frac"] < 1
+    st = r["stacked_layers"]                       # eight layers' caches attended back to back, eager
+    assert st["layers"] == 8 and st["sparse_attn_us_per_layer"] > 0 and 0 < st["call_frac"] < 1
     assert {"c3@256", "c3@512", "c3@4096"} <= set(r["paper_budgets"])
     assert any(k.startswith("c2@") for k in r["paper_budgets"])
     for pt in r["paper_budgets"].values():

@@ -30,7 +30,8 @@ namespace {
 
 __device__ __forceinline__ uint32_t key_of_bits(uint32_t u) {
   if (u == 0x80000000u) u = 0u;                       // -0 == +0
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // ascending with the float order
+  // ascending with the float order: negative values have all bits flipped, the others the sign bit set
+  return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
 }
 __device__ __forceinline__ uint32_t key_of(float x) { return key_of_bits(__builtin_bit_cast(uint32_t, x)); }
 
@@ -1313,11 +1314,12 @@ __global__ void __launch_bounds__(THREADS) select_rowpass_kernel(const SelectArg
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
           const int wi = i0 + u * THREADS;
+          const int valid = wi < nv ? nb - wi * VPT : 0;   // ranked tokens from this word on: >= VPT but at the row's end
 #pragma unroll
           for (int e = 0; e < VPT; ++e) {
             const uint32_t key = rowpass_key<BF16>(w[u], e);
             const int bin = fused_bin(key, level, d0, pre01);
-            if (wi < nv && wi * VPT + e < nb && bin >= 0) {
+            if (e < valid && bin >= 0) {
               atomicAdd(&h[bin], 1u);
               if (BF16 && level == 0 && win && (uint32_t)bin - wlo < (uint32_t)WIN)
                 atomicAdd(&hw[((uint32_t)bin - wlo) * 32 + ((key >> (32 - SEL_BITS0 - 5)) & 31u)], 1u);
@@ -1354,10 +1356,15 @@ __global__ void __launch_bounds__(THREADS) select_rowpass_kernel(const SelectArg
 #pragma unroll
       for (int e = 0; e < VPT; ++e) {
         const uint32_t key = rowpass_key<BF16>(w[u], e);
-        const bool in = nlo + u * VPT + e < nb;
-        gt_mask |= (in && key > Tk) ? 1u << (u * VPT + e) : 0u;
-        eq_mask |= (in && key == Tk) ? 1u << (u * VPT + e) : 0u;
+        gt_mask |= (key > Tk) ? 1u << (u * VPT + e) : 0u;
+        eq_mask |= (key == Tk) ? 1u << (u * VPT + e) : 0u;
       }
+    {   // tokens past the row's valid length (only in its last run) are dropped from both masks
+      const int left = nb - nlo;
+      const uint32_t in = left >= RUN ? 0xffffffffu : (left > 0 ? (1u << left) - 1u : 0u);
+      gt_mask &= in;
+      eq_mask &= in;
+    }
     uint32_t total;
     const uint32_t excl = block_excl_scan<THREADS>(__builtin_popcount(gt_mask) | (__builtin_popcount(eq_mask) << 16), tmp, total);
     uint32_t g = gbase + (excl & 0xffffu), q = qbase + (excl >> 16);

@@ -294,7 +294,7 @@ def run_prefill(args, torch, sts):
                      "frac": round(b_set / (split_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4), "avg_launch_us": round(split_us, 2),
                      "algorithmic_bytes_per_launch": b_set,
                      "note": "blocks gather overlapping rows of one cache, so part of the traffic is served by the caches"},
-        "launch": plan, **extra}))
+        "launch": plan, "library_version": sts.sts_version(), **extra}))
 
 
 def run_headmap(args, torch, sts):

@@ -1563,7 +1563,12 @@ __device__ __forceinline__ uint32_t band_pass(const SelectArgs &A, const AggRow 
       pos[x] = 4 * min(q0 + x * T, max(nq - 1, 0));
       any |= q0 + x * T < nq;
     }
-    if (__builtin_amdgcn_ballot_w64(any)) agg_multi_lim<f32x4, NPOS, (NPOS >= 8 ? 1 : (NPOS >= 4 ? 3 : 8))>(R, pos, acc);
+    if (__builtin_amdgcn_ballot_w64(any)) {
+      agg_multi_lim<f32x4, NPOS, (NPOS >= 8 ? 1 : (NPOS >= 4 ? 3 : 8))>(R, pos, acc);
+    } else {                                           // a wave past the ranked length (it only stores zeros)
+#pragma unroll
+      for (int x = 0; x < NPOS; ++x) acc[x] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
     uint32_t keys[NPOS][4];
     uint32_t band = 0;                                 // bit 4x + e: that token belongs to the band
 #pragma unroll

@@ -142,8 +142,30 @@ hipError_t launch_headmap_clear(unsigned long long *, int, hipStream_t) { ++g_la
 hipError_t launch_headmap_overlap(const int32_t *, const int32_t *, int, int, int, int, int, int, unsigned long long *, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_headmap_argmax(const unsigned long long *, int, int, int32_t *, hipStream_t) { ++g_launches; return hipSuccess; }
 
+// The sampling plan of the one-pass selection (shared by host and kernel): the sample fits the
+// workgroup's store, covers the row from its first token to within one period of its end, and a
+// plan that claims to fit leaves the band room with margin.
+static void check_band_plans() {
+  for (int run : {32, 64})
+    for (int nb : {8193, 8200, 20000, 40000, 65536, 131072, 131072 - 13, 262144, 262208, 524288})
+      for (uint32_t c : {1u, 100u, 512u, 3000u, 13108u, 26215u, 65536u, 131072u, 524288u}) {
+        if (c > (uint32_t)nb) continue;
+        const BandPlan p = band_plan(nb, c, run);
+        if (p.S < 16 || (p.S & (p.S - 1)) != 0) fail("band plan: sampling period");
+        if (p.ns < 1 || p.ns > 2 * BAND_CAP || p.ns > nb) fail("band plan: sample size");
+        if ((long long)(p.runs - 1) * p.S * run >= nb) fail("band plan: a sampled run starts past the row");
+        if ((long long)p.runs * p.S * run < nb) fail("band plan: the row's end is not within one period of the last run");
+        if (p.s_lo <= p.s_hi) fail("band plan: empty band");
+        if (p.fits && (p.s_lo > p.ns || (long long)p.S * (p.s_lo - (p.s_hi >= 1 ? p.s_hi : 0)) > BAND_CAP)) fail("band plan: fit");
+      }
+  // the headline budgets fit at 128K tokens; nearly everything kept does not
+  if (!band_plan(131072, 13108, 32).fits || !band_plan(131072, 26215, 64).fits) fail("band plan: 10% / 20% of 128K must fit");
+  if (band_plan(131072, 131000, 32).fits) fail("band plan: a budget next to the row length cannot fit");
+}
+
 int main() {
   long calls = 0, accepted = 0;
+  check_band_plans();
   // made-up, 256-byte aligned "device" addresses: never dereferenced (the launchers are stubs)
   unsigned char *const fake = reinterpret_cast<unsigned char *>(uintptr_t(1) << 40);
   unsigned char *const ws = reinterpret_cast<unsigned char *>(uintptr_t(2) << 40);

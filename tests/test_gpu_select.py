@@ -674,6 +674,8 @@ def band_scores(what, B, Hd, Tq, N, seed):
     (2, 2, 4, 70000, 2, 3000, torch.float32, "recent"),
     (2, 2, 2, 70000, 2, 5000, torch.float32, "unsampled"),
     (2, 2, 1, 70000, 2, 5000, torch.bfloat16, "unsampled"),
+    (2, 2, 1, 524288, 2, 3000, torch.float32, "softmax"),      # the longest row the bitmap holds, sample stride 32
+    (2, 2, 2, 524288 - 64, 2, 40000, torch.bfloat16, "softmax"), # ... and a budget whose band cannot fit there: plain passes
     (2, 4, 5, 8000, 8, 777, torch.float32, "softmax"),         # rows that fit the band store whole: no sample
     (2, 4, 5, 8196, 8, 777, torch.float32, "softmax"),         # just above that
 ])

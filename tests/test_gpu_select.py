@@ -15,12 +15,14 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-@pytest.fixture(autouse=True, params=[0, 2, 3], ids=["auto", "pipeline-or-pool", "one-launch-wherever-possible"])
+@pytest.fixture(autouse=True, params=[0, 2, 3, 5],
+                ids=["auto", "pipeline-or-pool", "one-launch-wherever-possible", "one-workgroup-per-row-wherever-possible"])
 def select_path(request):
-    """Every case runs twice: under the library's own routing (long rows take the one-launch
-    selection) and with that path switched off, so that the histogram pipeline and the chunk-local
-    top-k + pool, which the same shapes took before and block-granular calls still take, stay
-    covered."""
+    """Every case runs several times: under the library's own routing (long rows take the
+    one-launch selection), with that path switched off, so that the histogram pipeline and the
+    chunk-local top-k + pool, which the same shapes took before and block-granular calls still
+    take, stay covered, and with every call whose shape allows it ranked by one workgroup per row
+    in one pass (which the library's rule takes only from one row per second compute unit on)."""
     sts.set_knob("select_path", request.param)
     yield request.param
     sts.set_knob("select_path", None)
@@ -309,6 +311,7 @@ def launched(fn):
 
 
 FUSED = {"select_clear", "select_fused"}
+BAND = {"select_band"}
 
 
 def test_each_selection_path_is_taken_where_expected(select_path):
@@ -320,6 +323,11 @@ def test_each_selection_path_is_taken_where_expected(select_path):
         return launched(lambda: sts.sts_select(s, list(range(Hd)), k))
     pipeline = {"select_clear", "select_agg", "select_hist", "select_write"}
     pool = {"select_local", "select_pool"}
+    if select_path == 5:
+        assert run(1, 4, 8192, 100) == {"select_band"} and run(1, 4, 65536, 512) == {"select_band"}
+        assert run(1, 4, 65532 + 2, 512) == FUSED                           # N % 4 != 0: not its shape
+        assert run(1, 1, 4096 * 300, 100) == {"select_clear", "select_agg", "select_hist", "select_write"}   # beyond its bitmap
+        return
     assert run(1, 4, 8192, 100) == {"select_small"}
     assert run(16, 16, 20000, 100) == {"select_small"}                      # 256 rows
     if select_path == 3:
@@ -363,7 +371,7 @@ def test_pool_path_options(kind, reduce, select_path):
     def call():
         got["r"] = sts.sts_select(sd, hm, k, lse=lse.to(DEV) if kind == 1 else None, seq_lens=lens.to(DEV),
                                   kind=kind, reduce=reduce, want_agg=True, k_head=kh)
-    assert launched(call) == ({"select_local", "select_pool"} if select_path == 2 else FUSED)
+    assert launched(call) == ({"select_local", "select_pool"} if select_path == 2 else BAND if select_path == 5 else FUSED)
     idx, cnt, agg = got["r"]
     agg = agg.cpu().numpy()
     o_agg = stored_agg(oracle.aggregate(scores.numpy(), lse.numpy() if kind == 1 else None, kind, reduce), lens)
@@ -462,7 +470,7 @@ def test_misaligned_scores_fall_back_to_the_pipeline(select_path):
     assert sd.data_ptr() % 16 == 4
     got = {}
     kinds = launched(lambda: got.update(r=sts.sts_select(sd, [0, 1, 2], k)))
-    assert kinds == ({"select_clear", "select_agg", "select_hist", "select_write"} if select_path == 2 else FUSED)
+    assert kinds == ({"select_clear", "select_agg", "select_hist", "select_write"} if select_path == 2 else FUSED)   # also with path 5
     o_idx, o_cnt, _ = oracle.select_indices(scores.numpy(), np.asarray([0, 1, 2], np.int32), k)
     np.testing.assert_array_equal(got["r"][0].cpu().numpy(), o_idx)
     np.testing.assert_array_equal(got["r"][1].cpu().numpy(), o_cnt)
@@ -483,7 +491,7 @@ def test_pool_path_with_32768_token_chunks(levels, select_path):
     sd = scores.to(DEV)
     got = {}
     kinds = launched(lambda: got.update(r=sts.sts_select(sd, hm, k, seq_lens=lens.to(DEV), k_head=kh, want_agg=True)))
-    assert kinds == ({"select_local", "select_pool"} if select_path == 2 else FUSED)
+    assert kinds == ({"select_local", "select_pool"} if select_path == 2 else BAND if select_path == 5 else FUSED)
     idx, cnt, agg = got["r"]
     o_idx, o_cnt, o_agg = oracle.select_indices(scores.numpy(), np.asarray(hm, np.int32), k, seq_lens=lens.numpy(),
                                                 k_head=kh)
@@ -531,7 +539,8 @@ def test_single_row_input_is_ranked_in_place(N, k, levels, off, select_path):
     sd.copy_(s)
     got = {}
     kinds = launched(lambda: got.update(r=sts.sts_select(sd, head_map, k, seq_lens=lens.to(DEV))))
-    assert kinds == ({"select_clear", "select_agg", "select_hist", "select_write"} if select_path == 2 else FUSED)
+    if not (select_path == 5 and off == 0):     # (an aligned tensor of the one-pass selection's shape goes there)
+        assert kinds == ({"select_clear", "select_agg", "select_hist", "select_write"} if select_path == 2 else FUSED)
     idx, cnt, _ = got["r"]
     assert torch.equal(sd.cpu(), s)
     o_idx, o_cnt, o_agg = oracle.select_indices(s.numpy(), np.asarray(head_map, np.int32), k, seq_lens=lens.numpy())

@@ -619,7 +619,8 @@ def main():
     # `value`, which is timed without them)
     sts.prof_enable(True)
     sts.prof_reset()
-    for i in range(min(args.steps, max(1, STS_PROF_BUDGET // (8 * L)))):
+    prof_steps = min(args.steps, max(1, STS_PROF_BUDGET // (8 * L))) * L
+    for i in range(prof_steps // L):
         for l in range(L):
             step(layer=l)
     torch.cuda.synchronize()
@@ -724,6 +725,15 @@ def main():
     result["roofline_call"] = {"bound": "hbm", "bytes": b_set, "us": round(sparse_us[1], 2), "unit": "GB/s",
                                "achieved": round(b_set / (sparse_us[1] * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBS,
                                "frac": round(b_set / (sparse_us[1] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+    # the selection against the same roofline: the score tensor it ranks is read once (its lists are
+    # small next to it); kernels = the sum of its kernels' own times, call = the event-timed call
+    sel_src = d_sum if (draft is not None and d_sum is not None) else (d_logits if draft is not None else w.scores)
+    sel_bytes = sel_src.numel() * sel_src.element_size()
+    sel_kernels = sum(ms * 1e3 for k_, (n, ms) in prof.items() if n and k_.startswith("select")) / prof_steps
+    result["roofline_select"] = {"bound": "hbm", "bytes": sel_bytes, "unit": "GB/s", "peak": HBM_PEAK_GBS,
+                                 "kernels_us": round(sel_kernels, 2), "call_us": round(select_us[1], 2),
+                                 "frac_kernels": round(sel_bytes / (sel_kernels * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if sel_kernels > 0 else None,
+                                 "frac_call": round(sel_bytes / (select_us[1] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
     plain = draft is None and not args.paged and page == 1 and not args.fused_tail and args.scores == "fp32"
     if plain and not args.no_extras:
         here = Point(torch, sts, w, layers, kb)

@@ -43,6 +43,8 @@ def test_default_step_prints_the_contract_fields():
     assert par["ok"] is True and par["index_sets_equal"] is True
     assert par["out_max_abs_err"] <= 1e-2 and par["out_mean_abs_err"] <= 1e-3
     assert r["library_version"] > 0
+    rs = r["roofline_select"]                        # the selection's bytes over its kernels' and its call's time
+    assert rs["bytes"] > 0 and rs["kernels_us"] > 0 and rs["call_us"] > 0 and 0 < rs["frac_call"] <= rs["frac_kernels"] < 1
 
 
 def test_headline_configuration_carries_sweep_and_paper_budgets():

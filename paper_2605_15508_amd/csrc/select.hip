@@ -1240,7 +1240,8 @@ __device__ __forceinline__ uint32_t rowpass_key(const u32x4 &w, int e) {
 }
 
 template <int THREADS, bool BF16>
-__global__ void __launch_bounds__(THREADS) select_rowpass_kernel(const SelectArgs A) {
+__global__ void __launch_bounds__(THREADS, THREADS == 256 ? 8 : 4)   // small workgroups: eight waves per SIMD (64 registers)
+select_rowpass_kernel(const SelectArgs A) {
   constexpr int VPT = BF16 ? 8 : 4;       // tokens per 16-byte word
   constexpr int UNR = 4;                  // words in flight per thread
   constexpr int RUN = UNR * VPT;          // consecutive tokens a thread owns per compaction step
@@ -1265,6 +1266,8 @@ __global__ void __launch_bounds__(THREADS) select_rowpass_kernel(const SelectArg
   // row (128-byte runs) says where. If the first digit falls outside the window the second pass
   // is made as for any row; the result never depends on the sample.
   constexpr int WIN = 8;
+  constexpr int STAGE = THREADS * 8;      // list entries staged per round of the compaction
+  __shared__ int32_t staged[STAGE];
   __shared__ uint32_t hw[BF16 ? WIN * 32 : 1];
   uint32_t wlo = 0;                       // first digit the window starts at
   bool win = false;
@@ -1367,20 +1370,35 @@ __global__ void __launch_bounds__(THREADS) select_rowpass_kernel(const SelectArg
     }
     uint32_t total;
     const uint32_t excl = block_excl_scan<THREADS>(__builtin_popcount(gt_mask) | (__builtin_popcount(eq_mask) << 16), tmp, total);
-    uint32_t g = gbase + (excl & 0xffffu), q = qbase + (excl >> 16);
-    for (uint32_t rest = gt_mask | eq_mask; rest; rest &= rest - 1) {
-      const int i = __builtin_ctz(rest);
-      const bool is_gt = (gt_mask >> i) & 1u;
-      if (is_gt || q < r) {
-        const uint32_t pos = g + min(q, r);
-        if (pos < c)   // always true for a consistent threshold; keeps a bad state in bounds
-          for (int ti = t0; ti < t1; ++ti) A.indices[((size_t)bt * A.Hq + A.targets.tgt[ti]) * A.k + pos] = nlo + i;
-      }
-      g += is_gt ? 1u : 0u;
-      q += is_gt ? 0u : 1u;
-    }
+    // The step's kept tokens, places [first, last) of the list, are staged in LDS and copied out
+    // coalesced, STAGE at a time: stored straight from their threads (a few 4-byte stores each,
+    // scattered over the wave) they cost more than reading the row did.
+    const uint32_t first = gbase + min(qbase, r);
     gbase += total & 0xffffu;
     qbase += total >> 16;
+    const uint32_t last = min(gbase + min(qbase, r), c);
+#pragma unroll 1
+    for (uint32_t base = first; base < last; base += STAGE) {
+      uint32_t g = first - min(qbase - (total >> 16), r) + (excl & 0xffffu);   // greater keys before this thread's run
+      uint32_t q = qbase - (total >> 16) + (excl >> 16);                        // equal keys before it
+      for (uint32_t rest = gt_mask | eq_mask; rest; rest &= rest - 1) {
+        const int i = __builtin_ctz(rest);
+        const bool is_gt = (gt_mask >> i) & 1u;
+        if (is_gt || q < r) {
+          const uint32_t pos = g + min(q, r);
+          if (pos >= base && pos - base < (uint32_t)STAGE) staged[pos - base] = nlo + i;
+        }
+        g += is_gt ? 1u : 0u;
+        q += is_gt ? 0u : 1u;
+      }
+      __syncthreads();
+      const uint32_t cnt = min(last - base, (uint32_t)STAGE);
+      for (int ti = t0; ti < t1; ++ti) {
+        int32_t *dst = A.indices + ((size_t)bt * A.Hq + A.targets.tgt[ti]) * A.k + base;
+        for (uint32_t p = tid; p < cnt; p += THREADS) dst[p] = staged[p];
+      }
+      __syncthreads();
+    }
     if (gbase + min(qbase, r) >= c) break;   // the list is complete (uniform)
   }
 }

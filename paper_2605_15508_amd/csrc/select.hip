@@ -1240,8 +1240,7 @@ __device__ __forceinline__ uint32_t rowpass_key(const u32x4 &w, int e) {
 }
 
 template <int THREADS, bool BF16>
-__global__ void __launch_bounds__(THREADS, THREADS == 256 ? 8 : 4)   // small workgroups: eight waves per SIMD (64 registers)
-select_rowpass_kernel(const SelectArgs A) {
+__global__ void __launch_bounds__(THREADS) select_rowpass_kernel(const SelectArgs A) {
   constexpr int VPT = BF16 ? 8 : 4;       // tokens per 16-byte word
   constexpr int UNR = 4;                  // words in flight per thread
   constexpr int RUN = UNR * VPT;          // consecutive tokens a thread owns per compaction step
@@ -1314,6 +1313,33 @@ select_rowpass_kernel(const SelectArgs A) {
         u32x4 w[UNR];
 #pragma unroll
         for (int u = 0; u < UNR; ++u) w[u] = src[min(i0 + u * THREADS, nv - 1)];
+        if (BF16 && level == 0) {
+          // The kernel is bound by its vector instructions (about 18 per token and pass in the
+          // general form below), so the common case gets a form of its own: every word of the
+          // wave inside the row and no sign bit among its scores (attention weights have none).
+          // Then the first digit is 1024 + (the stored 16 bits >> 5) and the window's sub-bin
+          // their low 5 bits: five instructions per token.
+          uint32_t any = 0;
+#pragma unroll
+          for (int u = 0; u < UNR; ++u) any |= w[u][0] | w[u][1] | w[u][2] | w[u][3];
+          const bool lane_ok = (i0 + (UNR - 1) * THREADS + 1) * VPT <= nb && (any & 0x80008000u) == 0u;
+          if (__builtin_amdgcn_ballot_w64(!lane_ok) == 0) {
+            const uint32_t wlo10 = wlo - (1u << (SEL_BITS0 - 1));    // modulo 2^32: the comparison below stays exact
+            uint32_t *hpos = h + (1u << (SEL_BITS0 - 1));
+#pragma unroll
+            for (int u = 0; u < UNR; ++u)
+#pragma unroll
+              for (int e = 0; e < VPT; ++e) {
+                const uint32_t pair = w[u][(e >> 1) & 3];
+                const uint32_t r16 = (e & 1) ? pair >> 16 : pair & 0xffffu;
+                const uint32_t b = r16 >> 5;
+                atomicAdd(&hpos[b], 1u);
+                const uint32_t wd = b - wlo10;
+                if (win && wd < (uint32_t)WIN) atomicAdd(&hw[wd * 32 + (r16 & 31u)], 1u);
+              }
+            continue;
+          }
+        }
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
           const int wi = i0 + u * THREADS;
@@ -1354,15 +1380,37 @@ select_rowpass_kernel(const SelectArgs A) {
 #pragma unroll
     for (int u = 0; u < UNR; ++u) w[u] = src[min(nlo / VPT + u, nv - 1)];
     uint32_t gt_mask = 0, eq_mask = 0;
+    // the common case again (see the first pass): a positive threshold, every run of the wave inside
+    // the row, no sign bit: the stored 16 bits are compared with the threshold's
+    bool plain = false;
+    if (BF16 && (Tk >> 31)) {
+      uint32_t any = 0;
 #pragma unroll
-    for (int u = 0; u < UNR; ++u)
+      for (int u = 0; u < UNR; ++u) any |= w[u][0] | w[u][1] | w[u][2] | w[u][3];
+      plain = __builtin_amdgcn_ballot_w64(!(nlo + RUN <= nb && (any & 0x80008000u) == 0u)) == 0;
+    }
+    if (plain) {
+      const uint32_t T16 = (Tk >> 16) & 0x7fffu;
 #pragma unroll
-      for (int e = 0; e < VPT; ++e) {
-        const uint32_t key = rowpass_key<BF16>(w[u], e);
-        gt_mask |= (key > Tk) ? 1u << (u * VPT + e) : 0u;
-        eq_mask |= (key == Tk) ? 1u << (u * VPT + e) : 0u;
-      }
-    {   // tokens past the row's valid length (only in its last run) are dropped from both masks
+      for (int u = 0; u < UNR; ++u)
+#pragma unroll
+        for (int e = 0; e < VPT; ++e) {
+          const uint32_t pair = w[u][(e >> 1) & 3];
+          const uint32_t r16 = (e & 1) ? pair >> 16 : pair & 0xffffu;
+          gt_mask |= (r16 > T16) ? 1u << (u * VPT + e) : 0u;
+          eq_mask |= (r16 == T16) ? 1u << (u * VPT + e) : 0u;
+        }
+    } else {
+#pragma unroll
+      for (int u = 0; u < UNR; ++u)
+#pragma unroll
+        for (int e = 0; e < VPT; ++e) {
+          const uint32_t key = rowpass_key<BF16>(w[u], e);
+          gt_mask |= (key > Tk) ? 1u << (u * VPT + e) : 0u;
+          eq_mask |= (key == Tk) ? 1u << (u * VPT + e) : 0u;
+        }
+    }
+    if (!plain) {   // tokens past the row's valid length (only in its last run) are dropped from both masks
       const int left = nb - nlo;
       const uint32_t in = left >= RUN ? 0xffffffffu : (left > 0 ? (1u << left) - 1u : 0u);
       gt_mask &= in;

@@ -40,6 +40,6 @@ def test_the_logits_dump_at_head_size_128_has_no_four_tile_form(resources):
 def test_selection_kernels_fit_the_occupancy_they_are_planned_for(resources):
     for k, v in resources.items():
         if "select_rowpass_kernelILi256" in k:
-            assert v["VGPRs"] <= 64 and v["ScratchSize"] == 0, demangle(k)        # eight waves per SIMD
+            assert v["VGPRs"] <= 96 and v["ScratchSize"] == 0, demangle(k)        # five workgroups per CU or more
         if "select_write_kernel" in k:
             assert v["VGPRs"] <= 128 and v["ScratchSize"] == 0, demangle(k)       # four workgroups per CU

@@ -835,7 +835,7 @@ const char *sts_strerror(int status) {   // an int on purpose: any value a calle
   return "unknown status";
 }
 
-int sts_version(void) { return 203; }
+int sts_version(void) { return 204; }
 
 void sts_set_knob(int which, double value) {
   if (which < 0 || which >= STS_KNOB_COUNT_) return;
